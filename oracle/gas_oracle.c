@@ -1,0 +1,211 @@
+/*
+ * Plain CPU oracle for the GAS layer step.  TEST INFRASTRUCTURE ONLY: the
+ * tests, the smoke check and the benchmark's cpu_baseline leg call it; the
+ * product never does, and it shares no code with the HIP library.
+ *
+ * Every function is the written-out definition of one operation of the
+ * mini-batch message-passing step with historical embeddings:
+ *   - pull / push: the Pull and Push operations of the paper's Algorithm 1
+ *     (row gather from, and row scatter into, a history table);
+ *   - spmm: the neighbourhood sum of the paper's Eq. (1)/(2) over the rows of
+ *     the batch subgraph, with the edge weights of the GCN, GCNII and GIN
+ *     operators of its operator appendix;
+ *   - spmm_t: the adjoint of that sum (backward aggregation);
+ *   - linear: the dense transform of the same operators;
+ *   - gcn_norm: the coefficient 1/c_{w,v} of the GCN operator.
+ * Arithmetic is double precision; a value is rounded once, at the store into
+ * a buffer whose type the interface fixes (fp32, or bf16 with round-to-
+ * nearest-even).  No blocking, fusion or reordering: loops run in the order
+ * the definitions state.
+ */
+#include <stdint.h>
+#include <string.h>
+#include <math.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { OR_F32 = 0, OR_BF16 = 1 };
+
+/* bf16 = upper 16 bits of an IEEE fp32 */
+static double bf16_to_double(uint16_t h) {
+    uint32_t u = ((uint32_t)h) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* double -> bf16, round to nearest even, decided on the exact double value */
+static uint16_t double_to_bf16(double x) {
+    if (isnan(x)) return 0x7FC0;
+    float f = (float)x;               /* candidate; may itself have rounded */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    /* bracket x between two neighbouring bf16 values (truncate fp32 toward zero) */
+    uint32_t lo_bits = u & 0xFFFF0000u;
+    float lo_f;
+    memcpy(&lo_f, &lo_bits, 4);
+    if (isinf(f)) return (uint16_t)(u >> 16);
+    /* (float)x may have rounded across a bf16 boundary away from zero */
+    if (fabs((double)lo_f) > fabs(x)) {
+        lo_bits -= 0x10000u;
+        memcpy(&lo_f, &lo_bits, 4);
+    }
+    uint32_t hi_bits = lo_bits + 0x10000u;
+    float hi_f;
+    memcpy(&hi_f, &hi_bits, 4);
+    double dl = fabs(x - (double)lo_f), dh = fabs((double)hi_f - x);
+    if (isinf(hi_f)) dh = fabs(ldexp(1.0, 128) * (x < 0 ? -1.0 : 1.0) - x);
+    uint32_t pick;
+    if (dl < dh) pick = lo_bits;
+    else if (dh < dl) pick = hi_bits;
+    else pick = ((lo_bits >> 16) & 1u) ? hi_bits : lo_bits;   /* tie: even mantissa */
+    return (uint16_t)(pick >> 16);
+}
+
+static double load_elem(const void* p, int64_t i, int dt) {
+    return dt == OR_F32 ? (double)((const float*)p)[i] : bf16_to_double(((const uint16_t*)p)[i]);
+}
+
+static void store_elem(void* p, int64_t i, int dt, double v) {
+    if (dt == OR_F32) ((float*)p)[i] = (float)v;
+    else ((uint16_t*)p)[i] = double_to_bf16(v);
+}
+
+uint16_t oracle_round_bf16(double x) { return double_to_bf16(x); }
+
+/* Pull: dst[i, :] = hist[idx[i], :]  (Algorithm 1, Pull^(l) for w in V_b \ B_b) */
+void oracle_pull(const void* hist, int64_t ld_hist, const int32_t* idx, int64_t n,
+                 int32_t F, int32_t elem_bytes, void* dst, int64_t ld_dst) {
+    for (int64_t i = 0; i < n; ++i)
+        memcpy((char*)dst + i * ld_dst * elem_bytes,
+               (const char*)hist + (int64_t)idx[i] * ld_hist * elem_bytes, (size_t)F * elem_bytes);
+}
+
+/* Push: hist[idx[i], :] = src[i, :]  (Algorithm 1, Push^(l) for v in B_b) */
+void oracle_push(const void* src, int64_t ld_src, const int32_t* idx, int64_t n,
+                 int32_t F, int32_t elem_bytes, void* hist, int64_t ld_hist) {
+    for (int64_t i = 0; i < n; ++i)
+        memcpy((char*)hist + (int64_t)idx[i] * ld_hist * elem_bytes,
+               (const char*)src + i * ld_src * elem_bytes, (size_t)F * elem_bytes);
+}
+
+/* 1/c_{w,v} = 1 / (sqrt(deg(w)+1) * sqrt(deg(v)+1)) for every stored entry
+ * (v = row, w = column), degrees taken on the full graph (GCN operator). */
+void oracle_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t n_rows,
+                     const int32_t* n_id, const int32_t* deg, float* val) {
+    for (int64_t v = 0; v < n_rows; ++v)
+        for (int64_t k = ptr[v]; k < ptr[v + 1]; ++k) {
+            double dv = (double)deg[n_id[v]] + 1.0, dw = (double)deg[n_id[ind[k]]] + 1.0;
+            val[k] = (float)(1.0 / (sqrt(dw) * sqrt(dv)));
+        }
+}
+
+/* Z[v,:] = s_agg * sum_{k in row v} val[k] * X[col[k],:] + diag * X[v,:] + s_res * R[v,:]
+ * GCN: val = 1/c, diag = 0 (the self-loop is a stored entry).  GIN: val = 1
+ * (NULL), diag = 1+eps.  GCNII: s_agg = 1-alpha, R = initial embedding, s_res = alpha. */
+void oracle_spmm(const int32_t* rowptr, const int32_t* col, const float* val, double diag,
+                 const void* X, int64_t ldx, int dtx, int32_t F, double s_agg,
+                 const void* R, int64_t ldr, double s_res,
+                 void* Z, int64_t ldz, int dtz, int64_t n_rows) {
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        double* acc = (double*)calloc((size_t)F, sizeof(double));
+        for (int64_t k = rowptr[v]; k < rowptr[v + 1]; ++k) {
+            double a = val ? (double)val[k] : 1.0;
+            int64_t w = col[k];
+            for (int32_t j = 0; j < F; ++j) acc[j] += a * load_elem(X, w * ldx + j, dtx);
+        }
+        for (int32_t j = 0; j < F; ++j) {
+            double z = s_agg * acc[j];
+            if (diag != 0.0) z += diag * load_elem(X, v * ldx + j, dtx);
+            if (R) z += s_res * load_elem(R, v * ldr + j, dtx);
+            store_elem(Z, v * ldz + j, dtz, z);
+        }
+        free(acc);
+    }
+}
+
+/* Adjoint of the aggregation, written from the SAME row-major entries as the
+ * forward: GX[col[k],:] += val[k] * G[v,:] for every stored (v, col[k]), plus
+ * diag * G[u,:] for u < n_rows.  Rows u >= n_out of GX are not produced. */
+void oracle_spmm_t(const int32_t* rowptr, const int32_t* col, const float* val, double diag,
+                   const void* G, int64_t ldg, int dtg, int32_t F, int64_t n_rows,
+                   int64_t n_out, void* GX, int64_t ldgx, int dtgx) {
+    double* acc = (double*)calloc((size_t)n_out * F, sizeof(double));
+    for (int64_t v = 0; v < n_rows; ++v)
+        for (int64_t k = rowptr[v]; k < rowptr[v + 1]; ++k) {
+            int64_t u = col[k];
+            if (u >= n_out) continue;
+            double a = val ? (double)val[k] : 1.0;
+            for (int32_t j = 0; j < F; ++j) acc[u * F + j] += a * load_elem(G, v * ldg + j, dtg);
+        }
+    for (int64_t u = 0; u < n_out; ++u)
+        for (int32_t j = 0; j < F; ++j) {
+            double g = acc[u * F + j];
+            if (diag != 0.0 && u < n_rows) g += diag * load_elem(G, u * ldg + j, dtg);
+            store_elem(GX, u * ldgx + j, dtgx, g);
+        }
+    free(acc);
+}
+
+/* Y = act( c_identity * Z + c_weight * (Z W) + bias ),  W row-major [F_in, F_out].
+ * GCN: c_identity = 0, c_weight = 1.  GCNII: the identity map W <- (1-beta) I + beta W
+ * gives c_identity = 1-beta, c_weight = beta (needs F_in == F_out). */
+void oracle_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                   const void* W, int32_t F_out, const void* bias, int dt,
+                   double c_identity, double c_weight, int relu,
+                   void* Y, int64_t ldy, int dty) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t j = 0; j < F_out; ++j) {
+            double s = 0.0;
+            for (int32_t k = 0; k < F_in; ++k)
+                s += load_elem(Z, i * ldz + k, dt) * load_elem(W, (int64_t)k * F_out + j, dt);
+            double y = c_weight * s;
+            if (c_identity != 0.0) y += c_identity * load_elem(Z, i * ldz + j, dt);
+            if (bias) y += load_elem(bias, j, dt);
+            if (relu && y < 0.0) y = 0.0;
+            store_elem(Y, i * ldy + j, dty, y);
+        }
+}
+
+/* GIN update: Y = act( relu(Z W1 + b1) W2 + b2 ); the hidden activation stays
+ * in double (it is not a buffer of the interface). */
+void oracle_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                 const void* W1, int32_t F_hid, const void* b1,
+                 const void* W2, int32_t F_out, const void* b2, int dt, int relu_out,
+                 void* Y, int64_t ldy, int dty) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double* h = (double*)calloc((size_t)F_hid, sizeof(double));
+        for (int32_t j = 0; j < F_hid; ++j) {
+            double s = 0.0;
+            for (int32_t k = 0; k < F_in; ++k)
+                s += load_elem(Z, i * ldz + k, dt) * load_elem(W1, (int64_t)k * F_hid + j, dt);
+            if (b1) s += load_elem(b1, j, dt);
+            h[j] = s > 0.0 ? s : 0.0;
+        }
+        for (int32_t j = 0; j < F_out; ++j) {
+            double s = 0.0;
+            for (int32_t k = 0; k < F_hid; ++k) s += h[k] * load_elem(W2, (int64_t)k * F_out + j, dt);
+            if (b2) s += load_elem(b2, j, dt);
+            if (relu_out && s < 0.0) s = 0.0;
+            store_elem(Y, i * ldy + j, dty, s);
+        }
+        free(h);
+    }
+}
+
+int oracle_num_threads(void) {
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

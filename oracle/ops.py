@@ -1,0 +1,155 @@
+"""ctypes wrappers around the oracle's C functions (test infrastructure).
+
+Arrays are numpy: float32 for fp32 buffers, uint16 bit patterns for bf16
+buffers, int32 for indices.  Each wrapper allocates its output and returns it;
+`push` updates the history in place.  See gas_oracle.c for the definitions and
+the passages of the paper they follow.
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.oracle_round_bf16.restype = C.c_uint16
+        _lib.oracle_round_bf16.argtypes = [C.c_double]
+        _lib.oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle buffers are float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _np_dtype(dt: int):
+    return np.float32 if dt == F32 else np.uint16
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _rows(a: np.ndarray):
+    """(array, leading dimension in elements) of a 2-D row-major array."""
+    assert a.ndim == 2 and a.strides[1] == a.itemsize, "need row-major 2-D"
+    return a, a.strides[0] // a.itemsize
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.int32
+    return a
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def round_bf16(x: float) -> int:
+    return int(lib().oracle_round_bf16(float(x)))
+
+
+def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def to_f64(a: np.ndarray) -> np.ndarray:
+    return bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+def pull(hist: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    hist, ld = _rows(hist)
+    idx = _i32(idx)
+    out = np.empty((idx.size, hist.shape[1]), dtype=hist.dtype)
+    lib().oracle_pull(_p(hist), C.c_int64(ld), _p(idx), C.c_int64(idx.size), C.c_int32(hist.shape[1]),
+                      C.c_int32(hist.itemsize), _p(out), C.c_int64(hist.shape[1]))
+    return out
+
+
+def push(src: np.ndarray, idx: np.ndarray, hist: np.ndarray) -> None:
+    src, lds = _rows(src)
+    hist, ldh = _rows(hist)
+    idx = _i32(idx)
+    assert src.dtype == hist.dtype and src.shape == (idx.size, hist.shape[1])
+    lib().oracle_push(_p(src), C.c_int64(lds), _p(idx), C.c_int64(idx.size), C.c_int32(hist.shape[1]),
+                      C.c_int32(hist.itemsize), _p(hist), C.c_int64(ldh))
+
+
+def gcn_norm(ptr, ind, n_id, deg) -> np.ndarray:
+    ptr, ind, n_id, deg = _i32(ptr), _i32(ind), _i32(n_id), _i32(deg)
+    val = np.empty(ind.size, dtype=np.float32)
+    lib().oracle_gcn_norm(_p(ptr), _p(ind), C.c_int64(ptr.size - 1), _p(n_id), _p(deg), _p(val))
+    return val
+
+
+def spmm(rowptr, col, val, x, diag=0.0, s_agg=1.0, r=None, s_res=0.0, out_dt=None) -> np.ndarray:
+    rowptr, col = _i32(rowptr), _i32(col)
+    x, ldx = _rows(x)
+    n_rows, f = rowptr.size - 1, x.shape[1]
+    if val is not None:
+        val = np.ascontiguousarray(val)
+        assert val.dtype == np.float32 and val.size == col.size
+    ldr = 0
+    if r is not None:
+        r, ldr = _rows(r)
+        assert r.dtype == x.dtype and r.shape[1] == f and r.shape[0] >= n_rows
+    out_dt = _dt(x) if out_dt is None else out_dt
+    z = np.empty((n_rows, f), dtype=_np_dtype(out_dt))
+    lib().oracle_spmm(_p(rowptr), _p(col), _p(val), C.c_double(diag), _p(x), C.c_int64(ldx), C.c_int(_dt(x)),
+                      C.c_int32(f), C.c_double(s_agg), _p(r), C.c_int64(ldr), C.c_double(s_res),
+                      _p(z), C.c_int64(f), C.c_int(out_dt), C.c_int64(n_rows))
+    return z
+
+
+def spmm_t(rowptr, col, val, g, n_out, diag=0.0, out_dt=None) -> np.ndarray:
+    rowptr, col = _i32(rowptr), _i32(col)
+    g, ldg = _rows(g)
+    n_rows, f = rowptr.size - 1, g.shape[1]
+    assert g.shape[0] == n_rows
+    if val is not None:
+        val = np.ascontiguousarray(val)
+        assert val.dtype == np.float32
+    out_dt = _dt(g) if out_dt is None else out_dt
+    gx = np.empty((n_out, f), dtype=_np_dtype(out_dt))
+    lib().oracle_spmm_t(_p(rowptr), _p(col), _p(val), C.c_double(diag), _p(g), C.c_int64(ldg), C.c_int(_dt(g)),
+                        C.c_int32(f), C.c_int64(n_rows), C.c_int64(n_out), _p(gx), C.c_int64(f), C.c_int(out_dt))
+    return gx
+
+
+def linear(z, w, bias=None, c_identity=0.0, c_weight=1.0, relu=False, out_dt=None) -> np.ndarray:
+    z, ldz = _rows(z)
+    w = np.ascontiguousarray(w)
+    assert w.dtype == z.dtype and w.shape[0] == z.shape[1]
+    if c_identity != 0.0:
+        assert w.shape[0] == w.shape[1]
+    out_dt = _dt(z) if out_dt is None else out_dt
+    y = np.empty((z.shape[0], w.shape[1]), dtype=_np_dtype(out_dt))
+    lib().oracle_linear(_p(z), C.c_int64(ldz), C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _p(w),
+                        C.c_int32(w.shape[1]), _p(bias), C.c_int(_dt(z)), C.c_double(c_identity),
+                        C.c_double(c_weight), C.c_int(int(relu)), _p(y), C.c_int64(w.shape[1]), C.c_int(out_dt))
+    return y
+
+
+def mlp2(z, w1, w2, b1=None, b2=None, relu_out=False, out_dt=None) -> np.ndarray:
+    z, ldz = _rows(z)
+    w1, w2 = np.ascontiguousarray(w1), np.ascontiguousarray(w2)
+    assert w1.dtype == z.dtype == w2.dtype and w1.shape[0] == z.shape[1] and w2.shape[0] == w1.shape[1]
+    out_dt = _dt(z) if out_dt is None else out_dt
+    y = np.empty((z.shape[0], w2.shape[1]), dtype=_np_dtype(out_dt))
+    lib().oracle_mlp2(_p(z), C.c_int64(ldz), C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _p(w1),
+                      C.c_int32(w1.shape[1]), _p(b1), _p(w2), C.c_int32(w2.shape[1]), _p(b2), C.c_int(_dt(z)),
+                      C.c_int(int(relu_out)), _p(y), C.c_int64(w2.shape[1]), C.c_int(out_dt))
+    return y

@@ -1,0 +1,187 @@
+/*
+ * gas.h - C ABI of the MI355X (gfx950) library for the GNNAutoScale (GAS)
+ * mini-batch message-passing step with historical embeddings.
+ *
+ * One layer of the step, for a mini-batch B with halo V_b \ B (paper,
+ * Algorithm 1 and Eq. 2):
+ *     gas_pull    halo rows of the mini-batch tensor  <- history table rows
+ *     gas_spmm    Z = aggregation over the rows of the batch subgraph G_b
+ *     gas_linear  Y = dense transform of Z          (gas_mlp2 for GIN's MLP)
+ *     gas_push    history table rows                <- fresh in-batch rows
+ * and gas_spmm_t, the adjoint of the aggregation, for the backward pass.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     neither frees nor keeps them.  The only library-owned memory is inside a
+ *     gas_plan.
+ *   - Matrices are row-major; "ld" is the row stride in ELEMENTS (ld >= F).
+ *   - Indices are int32; byte offsets are computed in 64 bits, so tables
+ *     larger than 4 GiB are fine.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls are asynchronous on it and never synchronise, with one exception:
+ *     gas_plan_create and gas_validate_indices copy a little data to the host
+ *     and wait for it.
+ *   - Every call returns a gas_status; gas_last_error() gives a message for
+ *     the last failure on the calling thread.  Arguments are checked on the
+ *     host before anything is launched; a failed call launches nothing.
+ *   - Index VALUES are not range-checked on the hot path (an out-of-range
+ *     index is undefined behaviour); gas_validate_indices checks them.
+ *   - Rows whose base address and byte stride are multiples of 16 take the
+ *     128-bit path; anything else falls back to an element-wise path with
+ *     identical results.
+ *   - Reductions use no atomics and a fixed order: results are bit-identical
+ *     from run to run for the same inputs and the same plan.
+ */
+#ifndef GAS_H
+#define GAS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbol (the library is built with hidden default visibility). */
+#define GAS_API __attribute__((visibility("default")))
+
+typedef enum { GAS_F32 = 0, GAS_BF16 = 1 } gas_dtype;
+
+typedef enum {
+    GAS_OK = 0,
+    GAS_ERR_ARG = -1,    /* null pointer, negative size, ld < F, ... */
+    GAS_ERR_DTYPE = -2,  /* unknown or unsupported dtype combination */
+    GAS_ERR_RANGE = -4,  /* gas_validate_indices found an index out of range */
+    GAS_ERR_HIP = -5,    /* a HIP runtime call failed */
+    GAS_ERR_NOMEM = -6   /* device allocation for a plan failed */
+} gas_status;
+
+/* Message of the last failure on this thread (static storage, never NULL). */
+GAS_API const char* gas_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+GAS_API int gas_version(void);
+
+/*
+ * Pull (Algorithm 1: h_w <- Pull(w) for all w in V_b \ B_b).
+ *     dst[i, 0:F] = hist[r(i), 0:F],  i in [0, n),
+ *     r(i) = idx[i] if idx != NULL else base + i.
+ * hist:  [n_hist_rows, F] table, row stride ld_hist.  dst: [n, F], stride ld_dst.
+ * idx:   int32[n] global node ids (duplicates allowed), or NULL for the
+ *        contiguous range starting at `base` (`base` is ignored otherwise).
+ * The first layer's input is the same call on the feature table.
+ * Pure data movement: the result is bit-exact.  n == 0 is a no-op.
+ */
+GAS_API gas_status gas_pull(const void* hist, int64_t n_hist_rows, int64_t ld_hist,
+                    const int32_t* idx, int64_t base, int64_t n, int32_t F, gas_dtype dt,
+                    void* dst, int64_t ld_dst, void* stream);
+
+/*
+ * Push (Algorithm 1: Push(h_v) for all v in B_b).
+ *     hist[r(i), 0:F] = src[i, 0:F],  i in [0, n),  r(i) as in gas_pull.
+ * idx must hold DISTINCT ids (a mini-batch is a set of nodes); duplicates
+ * are undefined behaviour.  Rows of hist not named by idx are not touched.
+ */
+GAS_API gas_status gas_push(const void* src, int64_t ld_src,
+                    const int32_t* idx, int64_t base, int64_t n, int32_t F, gas_dtype dt,
+                    void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+
+/*
+ * Edge coefficients of the GCN operator (operator appendix, GCN):
+ *     val[k] = 1 / ( sqrt(deg[n_id[ind[k]]] + 1) * sqrt(deg[n_id[r]] + 1) )
+ * for every stored entry k of row r of a compressed sparse pattern (ptr, ind)
+ * with n_rows rows.  deg holds the degrees of the FULL graph, indexed by
+ * global id; n_id maps local ids to global ids.  Evaluated in fp64 and rounded
+ * once to fp32.  The formula is symmetric, so the same call serves the CSR and
+ * the CSC copy of a batch subgraph.
+ */
+GAS_API gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t n_rows,
+                        const int32_t* n_id, const int32_t* deg, float* val, void* stream);
+
+/*
+ * Schedule for one compressed sparse pattern (degree bins, chunk lists of the
+ * heavy rows, partial-sum workspace).  Built once per batch subgraph and
+ * reused by every layer and every epoch; one plan for the CSR, one for the CSC
+ * copy.  ptr is a device pointer (int32[n_rows+1]); it is copied to the host
+ * inside this call, which therefore waits for `stream`.  max_F is the widest
+ * feature dimension the plan will be used with (sizes the workspace).
+ * A plan must not be used by two streams at the same time.
+ */
+typedef struct gas_plan gas_plan;
+GAS_API gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int32_t max_F,
+                           void* stream, gas_plan** out);
+GAS_API void gas_plan_destroy(gas_plan* plan);
+
+/*
+ * Aggregation over the batch subgraph (Eq. 1 / Eq. 2 with the operators of the
+ * operator appendix), rows = in-batch nodes, columns = in-batch nodes followed
+ * by halo nodes:
+ *     Z[v, :] = s_agg * sum_{k in row v} val[k] * X[col[k], :]
+ *               + diag * X[v, :] + s_res * R[v, :],          v in [0, n_rows)
+ * where n_rows is the row count the plan was created with.
+ * GCN:   val = 1/c (self-loop stored as an entry), diag = 0, s_agg = 1, R = NULL.
+ * GIN:   val = NULL (all ones), diag = 1 + eps.
+ * GCNII: s_agg = 1 - alpha, R = initial embedding of the in-batch nodes, s_res = alpha.
+ * rowptr int32[n_rows+1], col int32[nnz] (local ids), val fp32[nnz] or NULL.
+ * X: [>= max(col)+1, F] of type dt_x; R (optional): [n_rows, F] of type dt_x;
+ * Z: [n_rows, F] of type dt_z.  Accumulation is fp32 in a fixed order; bf16
+ * outputs are rounded to nearest even.  `plan` must have been created from
+ * this rowptr.  Z must not alias X or R.
+ */
+GAS_API gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const int32_t* col,
+                    const float* val, float diag,
+                    const void* X, int64_t ldx, gas_dtype dt_x, int32_t F,
+                    float s_agg, const void* R, int64_t ldr, float s_res,
+                    void* Z, int64_t ldz, gas_dtype dt_z, void* stream);
+
+/*
+ * Backward aggregation: the adjoint of gas_spmm's sum, computed as a
+ * row-parallel product over the CSC copy of the same pattern (no atomics):
+ *     GX[u, :] = sum_{k in column u} val[k] * G[row[k], :] + [u < n_diag] diag * G[u, :]
+ * for u in [0, n_out), n_out being the row count of the plan.  colptr
+ * int32[n_out+1], row int32[nnz], val in CSC order.  n_out = number of
+ * in-batch nodes when gradients into halo rows are not needed (histories are
+ * constants), or all of V_b.  n_diag = number of
+ * rows of G (the diagonal term exists for in-batch nodes only).
+ * `plan` must have been created from colptr[0 .. n_out].
+ */
+GAS_API gas_status gas_spmm_t(const gas_plan* plan, const int32_t* colptr, const int32_t* row,
+                      const float* val, float diag, int64_t n_diag,
+                      const void* G, int64_t ldg, gas_dtype dt_g, int32_t F,
+                      void* GX, int64_t ldgx, gas_dtype dt_gx, void* stream);
+
+/*
+ * Dense transform of the GCN / GCNII operators:
+ *     Y = act( c_identity * Z + c_weight * (Z W) + bias )
+ * Z [n_rows, F_in], W [F_in, F_out] row-major contiguous, bias [F_out] or NULL,
+ * all of type dt; Y [n_rows, F_out] of type dt.  GCN: c_identity = 0,
+ * c_weight = 1.  GCNII's identity map W <- (1-beta) I + beta W: c_identity =
+ * 1 - beta, c_weight = beta (then F_in must equal F_out).  relu != 0 applies
+ * max(0, .).  Runs on the matrix cores: fp32 MFMA for GAS_F32; bf16 MFMA with
+ * fp32 accumulation for GAS_BF16.  Y must not alias Z.
+ */
+GAS_API gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                      const void* W, int32_t F_out, const void* bias, gas_dtype dt,
+                      float c_identity, float c_weight, int relu,
+                      void* Y, int64_t ldy, void* stream);
+
+/*
+ * GIN update (operator appendix, GIN): Y = act( relu(Z W1 + b1) W2 + b2 ),
+ * both products in one kernel; the hidden activation never leaves the chip
+ * (kept in fp32 for GAS_F32, rounded to bf16 for GAS_BF16).
+ * W1 [F_in, F_hid], W2 [F_hid, F_out]; F_hid <= 256.
+ */
+GAS_API gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                    const void* W1, int32_t F_hid, const void* b1,
+                    const void* W2, int32_t F_out, const void* b2, gas_dtype dt,
+                    int relu_out, void* Y, int64_t ldy, void* stream);
+
+/*
+ * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
+ * flag back and waits for `stream`.
+ */
+GAS_API gas_status gas_validate_indices(const int32_t* idx, int64_t n, int64_t limit, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GAS_H */

@@ -1,0 +1,49 @@
+"""Compile the HIP sources into paper_2106_05609_amd/libgas.so for gfx950."""
+import glob
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+LIB = os.path.join(HERE, "libgas.so")
+SOURCES = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
+HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + [os.path.join(ROOT, "include", "gas.h")]
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-command-line-argument", "-I" + os.path.join(ROOT, "include")]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    if force or stale():
+        objs = []
+        build_dir = os.path.join(HERE, "_build")
+        os.makedirs(build_dir, exist_ok=True)
+        procs = []
+        for src in SOURCES:
+            obj = os.path.join(build_dir, os.path.basename(src) + ".o")
+            objs.append(obj)
+            if (not force and os.path.exists(obj)
+                    and os.path.getmtime(obj) > max(os.path.getmtime(f) for f in [src] + HEADERS)):
+                continue
+            cmd = ["hipcc"] + [f for f in FLAGS if f != "-shared"] + ["-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd))
+            procs.append((src, subprocess.Popen(cmd)))
+        for src, p in procs:
+            if p.wait() != 0:
+                raise RuntimeError(f"hipcc failed on {src}")
+        subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    return LIB
+
+
+if __name__ == "__main__":
+    import sys
+    print(build(force="--incremental" not in sys.argv, verbose=True))

@@ -1,0 +1,188 @@
+"""Thin ctypes binding of libgas.so: same names as the C ABI (include/gas.h),
+argument marshalling only.  Tensors are torch tensors on the GPU; every step
+runs in the library's kernels on torch's current stream."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgas.so")
+
+F32, BF16 = 0, 1
+OK = 0
+
+EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
+           "gas_plan_destroy", "gas_spmm", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices"]
+
+_lib = None
+
+
+class GasError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"gas status {status}: {message}")
+        self.status = status
+
+
+def lib():
+    """Load libgas.so.  There is no fallback: without the HIP library nothing runs."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2106_05609_amd._build` "
+                              "(or __graft_entry__.build())")
+        L = C.CDLL(LIB_PATH)
+        L.gas_last_error.restype = C.c_char_p
+        L.gas_version.restype = C.c_int
+        L.gas_plan_destroy.restype = None
+        for name in EXPORTS:
+            if name not in ("gas_last_error", "gas_version", "gas_plan_destroy"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(st):
+    if st != OK:
+        raise GasError(st, lib().gas_last_error().decode())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"feature tensors are float32 or bfloat16, got {t.dtype}")
+
+
+def _mat(t: torch.Tensor):
+    """(pointer, leading dimension in elements) of a 2-D row-major tensor or view."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("need a 2-D tensor with contiguous rows")
+    return C.c_void_p(t.data_ptr()), C.c_int64(t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return C.c_void_p(0)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("need a contiguous tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def gas_version() -> int:
+    return int(lib().gas_version())
+
+
+def gas_pull(hist, idx, dst, base=0, n=None):
+    """dst[i] = hist[idx[i]] (idx int32 tensor) or hist[base+i] (idx None)."""
+    n = (idx.numel() if idx is not None else dst.shape[0]) if n is None else n
+    hp, ldh = _mat(hist)
+    dp, ldd = _mat(dst)
+    if dst.dtype != hist.dtype or dst.shape[1] != hist.shape[1] or dst.shape[0] < n:
+        raise ValueError("gas_pull: dst does not match")
+    _check(lib().gas_pull(hp, C.c_int64(hist.shape[0]), ldh, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n),
+                          C.c_int32(hist.shape[1]), C.c_int(_dt(hist)), dp, ldd, _stream()))
+
+
+def gas_push(src, idx, hist, base=0, n=None):
+    """hist[idx[i]] = src[i] (idx int32 tensor, distinct) or hist[base+i] = src[i] (idx None)."""
+    n = (idx.numel() if idx is not None else src.shape[0]) if n is None else n
+    hp, ldh = _mat(hist)
+    sp, lds = _mat(src)
+    if src.dtype != hist.dtype or src.shape[1] != hist.shape[1] or src.shape[0] < n:
+        raise ValueError("gas_push: src does not match")
+    _check(lib().gas_push(sp, lds, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n), C.c_int32(hist.shape[1]),
+                          C.c_int(_dt(hist)), hp, C.c_int64(hist.shape[0]), ldh, _stream()))
+
+
+def gas_gcn_norm(ptr, ind, n_id, deg, val):
+    _check(lib().gas_gcn_norm(_ptr(ptr, torch.int32), _ptr(ind, torch.int32), C.c_int64(ptr.numel() - 1),
+                              _ptr(n_id, torch.int32), _ptr(deg, torch.int32), _ptr(val, torch.float32), _stream()))
+
+
+class Plan:
+    """Owner of a gas_plan handle."""
+
+    def __init__(self, ptr: torch.Tensor, nnz: int, max_F: int, n_rows=None):
+        self.n_rows = ptr.numel() - 1 if n_rows is None else n_rows
+        self.handle = C.c_void_p(0)
+        _check(lib().gas_plan_create(_ptr(ptr, torch.int32), C.c_int64(self.n_rows), C.c_int64(nnz), C.c_int32(max_F),
+                                     _stream(), C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            lib().gas_plan_destroy(self.handle)
+            self.handle = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gas_plan_create(ptr, nnz, max_F, n_rows=None) -> Plan:
+    return Plan(ptr, nnz, max_F, n_rows)
+
+
+def gas_plan_destroy(plan: Plan):
+    plan.close()
+
+
+def gas_spmm(plan, rowptr, col, val, x, z, diag=0.0, s_agg=1.0, r=None, s_res=0.0):
+    xp, ldx = _mat(x)
+    zp, ldz = _mat(z)
+    rp, ldr = (C.c_void_p(0), C.c_int64(0)) if r is None else _mat(r)
+    if r is not None and r.dtype != x.dtype:
+        raise TypeError("gas_spmm: R must have X's dtype")
+    if z.shape[1] != x.shape[1] or z.shape[0] < plan.n_rows:
+        raise ValueError("gas_spmm: Z does not match")
+    _check(lib().gas_spmm(plan.handle, _ptr(rowptr, torch.int32), _ptr(col, torch.int32), _ptr(val, torch.float32),
+                          C.c_float(diag), xp, ldx, C.c_int(_dt(x)), C.c_int32(x.shape[1]), C.c_float(s_agg), rp, ldr,
+                          C.c_float(s_res), zp, ldz, C.c_int(_dt(z)), _stream()))
+
+
+def gas_spmm_t(plan, colptr, row, val, g, gx, diag=0.0):
+    gp, ldg = _mat(g)
+    op, ldo = _mat(gx)
+    if gx.shape[1] != g.shape[1] or gx.shape[0] < plan.n_rows:
+        raise ValueError("gas_spmm_t: GX does not match")
+    _check(lib().gas_spmm_t(plan.handle, _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(val, torch.float32),
+                            C.c_float(diag), C.c_int64(g.shape[0]), gp, ldg, C.c_int(_dt(g)), C.c_int32(g.shape[1]),
+                            op, ldo, C.c_int(_dt(gx)), _stream()))
+
+
+def gas_linear(z, w, y, bias=None, c_identity=0.0, c_weight=1.0, relu=False):
+    zp, ldz = _mat(z)
+    yp, ldy = _mat(y)
+    if w.dtype != z.dtype or y.dtype != z.dtype or w.shape[0] != z.shape[1] or y.shape != (z.shape[0], w.shape[1]):
+        raise ValueError("gas_linear: shapes or dtypes do not match")
+    _check(lib().gas_linear(zp, ldz, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _ptr(w), C.c_int32(w.shape[1]),
+                            _ptr(bias), C.c_int(_dt(z)), C.c_float(c_identity), C.c_float(c_weight),
+                            C.c_int(int(relu)), yp, ldy, _stream()))
+
+
+def gas_mlp2(z, w1, w2, y, b1=None, b2=None, relu_out=False):
+    zp, ldz = _mat(z)
+    yp, ldy = _mat(y)
+    if not (w1.dtype == w2.dtype == z.dtype == y.dtype) or w1.shape[0] != z.shape[1] or w2.shape[0] != w1.shape[1] \
+            or y.shape != (z.shape[0], w2.shape[1]):
+        raise ValueError("gas_mlp2: shapes or dtypes do not match")
+    _check(lib().gas_mlp2(zp, ldz, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _ptr(w1), C.c_int32(w1.shape[1]),
+                          _ptr(b1), _ptr(w2), C.c_int32(w2.shape[1]), _ptr(b2), C.c_int(_dt(z)),
+                          C.c_int(int(relu_out)), yp, ldy, _stream()))
+
+
+def gas_validate_indices(idx, limit) -> bool:
+    st = lib().gas_validate_indices(_ptr(idx, torch.int32), C.c_int64(idx.numel()), C.c_int64(limit), _stream())
+    if st == -4:
+        return False
+    _check(st)
+    return True

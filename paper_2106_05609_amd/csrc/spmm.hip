@@ -1,0 +1,436 @@
+// Neighbourhood aggregation over the batch subgraph (gas_spmm) and its adjoint
+// (gas_spmm_t): row-parallel compressed-sparse-row products without atomics.
+//
+// What is computed is the sum of the paper's Eq. (1)/(2) for the in-batch
+// rows, with the edge weights of the GCN / GCNII / GIN operators folded into
+// `val`, `diag`, `s_agg` and the residual term.
+//
+// Mapping to the machine.  A feature row is cut into 16-byte units; a "team" of
+// G = 2^k lanes (G >= units per row, at most 64) owns one row, so one wavefront
+// works on 64/G neighbours at a time and a wavefront-wide load instruction
+// always fetches whole contiguous rows.  The wavefront stages 64 column
+// indices and weights at a time in registers (one coalesced load) and
+// broadcasts them with lane permutes; U independent row loads are in flight
+// per lane.  Rows with at most `threshold` entries take one wavefront each.
+// Heavier rows (power-law hubs) are cut into chunks of `chunk` entries, one
+// wavefront per chunk, whose fp32 partial sums go to a workspace and are added
+// in chunk order by a second kernel: the summation order is a function of the
+// row pointer array alone, so results are bit-identical from run to run.
+#include "common.h"
+
+#include <cstdlib>
+#include <vector>
+
+struct gas_plan {
+    int64_t n_rows = 0, nnz = 0;
+    int32_t max_F = 0;
+    int32_t threshold = 0, chunk = 0;
+    int64_t n_heavy = 0, n_chunks = 0;
+    int32_t* d_chunk = nullptr;        // [3 * n_chunks]: row, begin, end
+    int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
+    float* d_partial = nullptr;        // [n_chunks, max_F]
+    int device = 0;
+};
+
+namespace gas {
+namespace {
+
+struct SpmmArgs {
+    const int32_t* ptr;
+    const int32_t* ind;
+    const float* val;
+    const char* X;
+    int64_t x_stride;     // bytes
+    const char* R;
+    int64_t r_stride;
+    char* Z;
+    int64_t z_stride;
+    float diag, s_agg, s_res;
+    int64_t n_rows, n_diag;
+    int units;            // 16-byte units per row of X
+    int F;
+    int threshold;
+    const int32_t* chunk;       // plan lists
+    int64_t n_chunks;
+    const int32_t* heavy;
+    int64_t n_heavy;
+    float* partial;
+};
+
+template <bool XBF>
+struct Unit {
+    static constexpr int E = XBF ? 8 : 4;   // elements per 16-byte unit
+    static __device__ __forceinline__ void fma(float (&acc)[E], float w, const u32x4& v) {
+        if constexpr (XBF) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[2 * i] = fmaf(w, bf16_lo(v[i]), acc[2 * i]);
+                acc[2 * i + 1] = fmaf(w, bf16_hi(v[i]), acc[2 * i + 1]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = fmaf(w, __uint_as_float(v[i]), acc[i]);
+        }
+    }
+};
+
+template <int G>
+__device__ __forceinline__ int bcast_i(int v, int k) {
+    if constexpr (G == 64) return __builtin_amdgcn_readlane(v, k);
+    else return __shfl(v, k, 64);
+}
+template <int G>
+__device__ __forceinline__ float bcast_f(float v, int k) {
+    if constexpr (G == 64) return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k));
+    else return __shfl(v, k, 64);
+}
+
+// Sum of val[k] * X[ind[k], :] over k in [begin, end) for this lane's units.
+// Afterwards every team of the wavefront holds the full sum.
+template <int G, int UPT, int U, bool XBF>
+__device__ __forceinline__ void accumulate(const SpmmArgs& a, int begin, int end,
+                                           float (&acc)[UPT][Unit<XBF>::E]) {
+    constexpr int S = kWave / G;
+    constexpr int E = Unit<XBF>::E;
+    const int lane = threadIdx.x & 63;
+    const int team = lane / G, tl = lane % G;
+#pragma unroll
+    for (int p = 0; p < UPT; ++p)
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
+    const char* xb = a.X + (int64_t)tl * 16;
+    for (int t = begin; t < end; t += kWave) {
+        const int cnt = min(kWave, end - t);
+        int my_c = 0;
+        float my_w = 0.f;
+        if (lane < cnt) {
+            my_c = a.ind[t + lane];
+            my_w = a.val ? a.val[t + lane] : 1.f;
+        }
+        for (int j = 0; j < cnt; j += S * U) {
+            u32x4 v[U][UPT];
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = j + u * S + team;
+                const bool ok = k < cnt;
+                const int c = bcast_i<G>(my_c, k & 63);
+                const float ww = bcast_f<G>(my_w, k & 63);
+                w[u] = ok ? ww : 0.f;
+#pragma unroll
+                for (int p = 0; p < UPT; ++p) {
+                    v[u][p] = u32x4{0u, 0u, 0u, 0u};
+                    if (ok && tl + p * G < a.units)
+                        v[u][p] = *reinterpret_cast<const u32x4*>(xb + (int64_t)c * a.x_stride + (int64_t)p * G * 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int p = 0; p < UPT; ++p) Unit<XBF>::fma(acc[p], w[u], v[u][p]);
+        }
+    }
+    if constexpr (S > 1) {
+#pragma unroll
+        for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+            for (int p = 0; p < UPT; ++p)
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[p][e] += __shfl_xor(acc[p][e], off, 64);
+    }
+}
+
+// Z[row, unit] = s_agg * acc + diag * X[row, unit] + s_res * R[row, unit]
+template <bool XBF, bool ZBF>
+__device__ __forceinline__ void epilogue(const SpmmArgs& a, int64_t row, int unit, float (&acc)[Unit<XBF>::E]) {
+    constexpr int E = Unit<XBF>::E;
+    float z[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) z[e] = a.s_agg * acc[e];
+    if (a.diag != 0.f && row < a.n_diag) {
+        float t[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) t[e] = 0.f;
+        Unit<XBF>::fma(t, a.diag, *reinterpret_cast<const u32x4*>(a.X + row * a.x_stride + (int64_t)unit * 16));
+#pragma unroll
+        for (int e = 0; e < E; ++e) z[e] += t[e];
+    }
+    if (a.R) {
+        float t[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) t[e] = 0.f;
+        Unit<XBF>::fma(t, a.s_res, *reinterpret_cast<const u32x4*>(a.R + row * a.r_stride + (int64_t)unit * 16));
+#pragma unroll
+        for (int e = 0; e < E; ++e) z[e] += t[e];
+    }
+    char* zp = a.Z + row * a.z_stride;
+    if constexpr (ZBF) {
+        static_assert(!ZBF || XBF, "bf16 output needs bf16 input");
+        u32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = pack_bf16(z[2 * i], z[2 * i + 1]);
+        *reinterpret_cast<u32x4*>(zp + (int64_t)unit * 16) = o;
+    } else {
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            f32x4 o = {z[4 * q], z[4 * q + 1], z[4 * q + 2], z[4 * q + 3]};
+            *reinterpret_cast<f32x4*>(zp + ((int64_t)unit * E + 4 * q) * 4) = o;
+        }
+    }
+}
+
+template <int G, int UPT, int U, bool XBF, bool ZBF>
+__global__ __launch_bounds__(256) void spmm_light_kernel(SpmmArgs a) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.n_rows) return;
+    const int begin = a.ptr[row], end = a.ptr[row + 1];
+    if (end - begin > a.threshold) return;       // heavy rows go through the chunk kernels
+    float acc[UPT][Unit<XBF>::E];
+    accumulate<G, UPT, U, XBF>(a, begin, end, acc);
+    const int lane = threadIdx.x & 63;
+    if (lane < G) {
+#pragma unroll
+        for (int p = 0; p < UPT; ++p)
+            if (lane + p * G < a.units) epilogue<XBF, ZBF>(a, row, lane + p * G, acc[p]);
+    }
+}
+
+template <int G, int UPT, int U, bool XBF>
+__global__ __launch_bounds__(256) void spmm_chunk_kernel(SpmmArgs a) {
+    const int64_t c = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= a.n_chunks) return;
+    const int begin = a.chunk[3 * c + 1], end = a.chunk[3 * c + 2];
+    constexpr int E = Unit<XBF>::E;
+    float acc[UPT][E];
+    accumulate<G, UPT, U, XBF>(a, begin, end, acc);
+    const int lane = threadIdx.x & 63;
+    if (lane < G) {
+#pragma unroll
+        for (int p = 0; p < UPT; ++p) {
+            const int unit = lane + p * G;
+            if (unit < a.units) {
+                float* dst = a.partial + c * (int64_t)a.F + (int64_t)unit * E;
+#pragma unroll
+                for (int q = 0; q < E / 4; ++q)
+                    *reinterpret_cast<f32x4*>(dst + 4 * q) =
+                        f32x4{acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2], acc[p][4 * q + 3]};
+            }
+        }
+    }
+}
+
+// One wavefront per heavy row: add the chunk partials in chunk order.
+template <bool XBF, bool ZBF>
+__global__ __launch_bounds__(256) void spmm_heavy_reduce_kernel(SpmmArgs a) {
+    const int64_t h = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (h >= a.n_heavy) return;
+    constexpr int E = Unit<XBF>::E;
+    const int64_t row = a.heavy[h];
+    const int first = a.heavy[a.n_heavy + h], last = a.heavy[a.n_heavy + h + 1];
+    for (int unit = threadIdx.x & 63; unit < a.units; unit += kWave) {
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = 0.f;
+        for (int c = first; c < last; ++c) {
+            const float* src = a.partial + (int64_t)c * a.F + (int64_t)unit * E;
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(src + 4 * q);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[4 * q + i] += v[i];
+            }
+        }
+        epilogue<XBF, ZBF>(a, row, unit, acc);
+    }
+}
+
+// Element-wise path for rows that are not 16-byte aligned or not a whole
+// number of 16-byte units: one wavefront per row, one lane per feature.
+template <bool XBF, bool ZBF>
+__global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.n_rows) return;
+    const int begin = a.ptr[row], end = a.ptr[row + 1];
+    auto ld = [](const char* base, int64_t stride, int64_t r, int f) -> float {
+        if constexpr (XBF) return __uint_as_float((uint32_t) * reinterpret_cast<const uint16_t*>(base + r * stride + 2 * f) << 16);
+        else return *reinterpret_cast<const float*>(base + r * stride + 4 * (int64_t)f);
+    };
+    for (int f = threadIdx.x & 63; f < a.F; f += kWave) {
+        float acc = 0.f;
+        for (int k = begin; k < end; ++k) acc = fmaf(a.val ? a.val[k] : 1.f, ld(a.X, a.x_stride, a.ind[k], f), acc);
+        float z = a.s_agg * acc;
+        if (a.diag != 0.f && row < a.n_diag) z += a.diag * ld(a.X, a.x_stride, row, f);
+        if (a.R) z += a.s_res * ld(a.R, a.r_stride, row, f);
+        if constexpr (ZBF) *reinterpret_cast<uint16_t*>(a.Z + row * a.z_stride + 2 * f) = (uint16_t)f32_to_bf16(z);
+        else *reinterpret_cast<float*>(a.Z + row * a.z_stride + 4 * (int64_t)f) = z;
+    }
+}
+
+template <int G, int UPT, int U, bool XBF, bool ZBF>
+gas_status launch_vector(const SpmmArgs& a, hipStream_t s) {
+    const unsigned blocks = (unsigned)((a.n_rows + 3) / 4);
+    hipLaunchKernelGGL((spmm_light_kernel<G, UPT, U, XBF, ZBF>), dim3(blocks), dim3(256), 0, s, a);
+    if (a.n_chunks > 0) {
+        hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF>), dim3((unsigned)((a.n_chunks + 3) / 4)), dim3(256), 0,
+                           s, a);
+        hipLaunchKernelGGL((spmm_heavy_reduce_kernel<XBF, ZBF>), dim3((unsigned)((a.n_heavy + 3) / 4)), dim3(256),
+                           0, s, a);
+    }
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+template <bool XBF, bool ZBF>
+gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
+    const int u = a.units;
+    if (u <= 8) return launch_vector<8, 1, 2, XBF, ZBF>(a, s);
+    if (u <= 16) return launch_vector<16, 1, 4, XBF, ZBF>(a, s);
+    if (u <= 32) return launch_vector<32, 1, 4, XBF, ZBF>(a, s);
+    if (u <= 64) return launch_vector<64, 1, 8, XBF, ZBF>(a, s);
+    if (u <= 128) return launch_vector<64, 2, 4, XBF, ZBF>(a, s);
+    if (u <= 256) return launch_vector<64, 4, 2, XBF, ZBF>(a, s);
+    return fail(GAS_ERR_ARG, "feature rows longer than 4096 bytes are not supported (F*size = %d)", u * 16);
+}
+
+gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, const int32_t* ind, const float* val,
+                    float diag, int64_t n_diag, const void* X, int64_t ldx, gas_dtype dt_x, int32_t F, float s_agg,
+                    const void* R, int64_t ldr, float s_res, void* Z, int64_t ldz, gas_dtype dt_z, hipStream_t s) {
+    if (!valid_dtype(dt_x) || !valid_dtype(dt_z)) return fail(GAS_ERR_DTYPE, "%s: unknown dtype", who);
+    if (dt_x == GAS_F32 && dt_z == GAS_BF16)
+        return fail(GAS_ERR_DTYPE, "%s: fp32 input with bf16 output is not supported", who);
+    GAS_REQUIRE(plan, "%s: null plan", who);
+    if (plan->n_rows == 0) return GAS_OK;
+    GAS_REQUIRE(ptr && X && Z, "%s: null pointer", who);
+    GAS_REQUIRE(plan->nnz == 0 || ind, "%s: null index array", who);
+    GAS_REQUIRE(F > 0 && F <= plan->max_F, "%s: F=%d outside (0, plan max_F=%d]", who, F, plan->max_F);
+    GAS_REQUIRE(ldx >= F && ldz >= F && (!R || ldr >= F), "%s: row stride smaller than F", who);
+    GAS_REQUIRE(Z != X && Z != R, "%s: output aliases an input", who);
+    const int xb = elem_bytes(dt_x), zb = elem_bytes(dt_z);
+    SpmmArgs a;
+    a.ptr = ptr; a.ind = ind; a.val = val;
+    a.X = static_cast<const char*>(X); a.x_stride = ldx * xb;
+    a.R = static_cast<const char*>(R); a.r_stride = ldr * xb;
+    a.Z = static_cast<char*>(Z); a.z_stride = ldz * zb;
+    a.diag = diag; a.s_agg = s_agg; a.s_res = s_res;
+    a.n_rows = plan->n_rows; a.n_diag = n_diag;
+    a.units = (F * xb) / 16; a.F = F;
+    a.threshold = plan->threshold;
+    a.chunk = plan->d_chunk; a.n_chunks = plan->n_chunks;
+    a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
+    a.partial = plan->d_partial;
+    const bool vec = (F * xb) % 16 == 0 && aligned16(X) && a.x_stride % 16 == 0 && aligned16(Z) &&
+                     a.z_stride % 16 == 0 && (!R || (aligned16(R) && a.r_stride % 16 == 0));
+    const bool xbf = dt_x == GAS_BF16, zbf = dt_z == GAS_BF16;
+    if (vec) {
+        if (!xbf) return dispatch_units<false, false>(a, s);
+        return zbf ? dispatch_units<true, true>(a, s) : dispatch_units<true, false>(a, s);
+    }
+    const unsigned blocks = (unsigned)((a.n_rows + 3) / 4);
+    if (!xbf) hipLaunchKernelGGL((spmm_generic_kernel<false, false>), dim3(blocks), dim3(256), 0, s, a);
+    else if (zbf) hipLaunchKernelGGL((spmm_generic_kernel<true, true>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((spmm_generic_kernel<true, false>), dim3(blocks), dim3(256), 0, s, a);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+int env_int(const char* name, int dflt, int lo, int hi) {
+    const char* e = getenv(name);
+    if (!e || !*e) return dflt;
+    const long v = strtol(e, nullptr, 10);
+    return (v < lo || v > hi) ? dflt : (int)v;
+}
+
+}  // namespace
+}  // namespace gas
+
+using namespace gas;
+
+extern "C" {
+
+gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int32_t max_F, void* stream,
+                           gas_plan** out) {
+    GAS_REQUIRE(out, "gas_plan_create: null output");
+    *out = nullptr;
+    GAS_REQUIRE(n_rows >= 0 && n_rows < 0x7FFFFFF0LL && nnz >= 0 && nnz < 0x7FFFFFF0LL && max_F > 0,
+                "gas_plan_create: n_rows=%lld nnz=%lld max_F=%d", (long long)n_rows, (long long)nnz, max_F);
+    GAS_REQUIRE(ptr || n_rows == 0, "gas_plan_create: null row pointer array");
+    hipStream_t s = (hipStream_t)stream;
+    gas_plan* p = new gas_plan();
+    p->n_rows = n_rows; p->nnz = nnz; p->max_F = max_F;
+    p->threshold = env_int("GAS_SPMM_HEAVY", 256, 1, 1 << 24);
+    p->chunk = env_int("GAS_SPMM_CHUNK", 256, 32, 1 << 24);
+    (void)hipGetDevice(&p->device);
+    std::vector<int32_t> h_ptr((size_t)n_rows + 1, 0);
+    if (n_rows > 0) {
+        hipError_t e = hipMemcpyAsync(h_ptr.data(), ptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ptr failed: %s", hipGetErrorString(e)); }
+        if (h_ptr[0] != 0 || h_ptr[n_rows] != nnz) {
+            delete p;
+            return fail(GAS_ERR_ARG, "gas_plan_create: ptr[0]=%d ptr[n_rows]=%d do not match nnz=%lld", h_ptr[0],
+                        h_ptr[n_rows], (long long)nnz);
+        }
+    }
+    std::vector<int32_t> chunk, heavy_row, heavy_first;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int32_t b = h_ptr[r], e = h_ptr[r + 1];
+        if (e < b) { delete p; return fail(GAS_ERR_ARG, "gas_plan_create: ptr decreases at row %lld", (long long)r); }
+        if (e - b > p->threshold) {
+            heavy_row.push_back((int32_t)r);
+            heavy_first.push_back((int32_t)(chunk.size() / 3));
+            for (int32_t c = b; c < e; c += p->chunk) {
+                chunk.push_back((int32_t)r);
+                chunk.push_back(c);
+                chunk.push_back(c + p->chunk < e ? c + p->chunk : e);
+            }
+        }
+    }
+    p->n_heavy = (int64_t)heavy_row.size();
+    p->n_chunks = (int64_t)chunk.size() / 3;
+    if (p->n_heavy > 0) {
+        heavy_first.push_back((int32_t)p->n_chunks);
+        heavy_row.insert(heavy_row.end(), heavy_first.begin(), heavy_first.end());
+        hipError_t e = hipMalloc(&p->d_chunk, chunk.size() * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(&p->d_heavy, heavy_row.size() * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(&p->d_partial, (size_t)p->n_chunks * max_F * sizeof(float));
+        if (e != hipSuccess) {
+            gas_plan_destroy(p);
+            return fail(GAS_ERR_NOMEM, "gas_plan_create: device allocation failed: %s", hipGetErrorString(e));
+        }
+        e = hipMemcpyAsync(p->d_chunk, chunk.data(), chunk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(p->d_heavy, heavy_row.data(), heavy_row.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) {
+            gas_plan_destroy(p);
+            return fail(GAS_ERR_HIP, "gas_plan_create: upload failed: %s", hipGetErrorString(e));
+        }
+    }
+    *out = p;
+    return GAS_OK;
+}
+
+void gas_plan_destroy(gas_plan* p) {
+    if (!p) return;
+    if (p->d_chunk) (void)hipFree(p->d_chunk);
+    if (p->d_heavy) (void)hipFree(p->d_heavy);
+    if (p->d_partial) (void)hipFree(p->d_partial);
+    delete p;
+}
+
+gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const int32_t* col, const float* val, float diag,
+                    const void* X, int64_t ldx, gas_dtype dt_x, int32_t F, float s_agg, const void* R, int64_t ldr,
+                    float s_res, void* Z, int64_t ldz, gas_dtype dt_z, void* stream) {
+    return run_spmm("gas_spmm", plan, rowptr, col, val, diag, plan ? plan->n_rows : 0, X, ldx, dt_x, F, s_agg, R, ldr,
+                    s_res, Z, ldz, dt_z, (hipStream_t)stream);
+}
+
+gas_status gas_spmm_t(const gas_plan* plan, const int32_t* colptr, const int32_t* row, const float* val, float diag,
+                      int64_t n_diag, const void* G, int64_t ldg, gas_dtype dt_g, int32_t F, void* GX, int64_t ldgx,
+                      gas_dtype dt_gx, void* stream) {
+    GAS_REQUIRE(n_diag >= 0, "gas_spmm_t: n_diag=%lld", (long long)n_diag);
+    return run_spmm("gas_spmm_t", plan, colptr, row, val, diag, n_diag, G, ldg, dt_g, F, 1.f, nullptr, 0, 0.f, GX,
+                    ldgx, dt_gx, (hipStream_t)stream);
+}
+
+}  // extern "C"

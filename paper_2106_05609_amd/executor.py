@@ -1,0 +1,105 @@
+"""Sequencing of the C-ABI calls for one mini-batch (paper, Algorithm 1).
+
+Nothing is computed here: buffers are torch allocations and every step is a
+gas_* call.  For layer l of a batch B with halo V_b \\ B:
+
+    gas_spmm   Z      = aggregation of the mini-batch tensor X over the rows of G_b
+    gas_linear Y      = transform(Z)            (gas_mlp2 for GIN), written into rows 0..nb-1 of the next X
+    gas_push   H[l]   <- Y   for the in-batch nodes        (not for the last layer)
+    gas_pull   X[nb:] <- H[l] for the halo nodes
+
+The first layer's X is a gas_pull of all of V_b from the feature table (exact
+inputs); GCNII first applies its graph-agnostic input projection to all rows.
+"""
+import math
+
+import torch
+
+from . import binding as B
+
+
+class BatchGraph:
+    """Device-side index structure of one batch subgraph plus its plans."""
+
+    def __init__(self, nb, n_id, rowptr, col, deg=None, colptr=None, row=None, max_F=256, normalise=True):
+        self.nb, self.nv = int(nb), int(n_id.numel())
+        self.n_id, self.rowptr, self.col = n_id, rowptr, col
+        self.nnz = int(col.numel())
+        self.plan = B.gas_plan_create(rowptr, self.nnz, max_F)
+        self.val = None
+        if normalise:
+            self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
+            B.gas_gcn_norm(rowptr, col, n_id, deg, self.val)
+        self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
+        if colptr is not None:
+            # backward over the in-batch columns only: histories are constants
+            self.plan_t = B.gas_plan_create(colptr[: self.nb + 1], int(colptr[self.nb].item()), max_F, n_rows=self.nb)
+            if normalise:
+                self.val_t = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
+                B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t)
+
+
+class Model:
+    def __init__(self, op, weights, w_in=None, alpha=0.0, gin_eps=0.0):
+        self.op, self.weights, self.w_in, self.alpha, self.gin_eps = op, weights, w_in, alpha, gin_eps
+
+    @property
+    def n_layers(self):
+        return len(self.weights)
+
+    def out_width(self, l):
+        w = self.weights[l]
+        return (w[1] if self.op == "gin" else w).shape[1]
+
+
+def gcnii_beta(layer: int) -> float:
+    return math.log(0.5 / layer + 1.0)
+
+
+def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True, keep_layers=False):
+    """Run all layers for one batch.  Returns the last layer's [nb, F] output
+    (and the list of mini-batch tensors if keep_layers)."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    h0 = None
+    if model.op == "gcnii":
+        h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x, model.w_in, h0, relu=True)
+        x = h0
+    layers = []
+    L = model.n_layers
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        f_in, f_out = x.shape[1], model.out_width(l - 1)
+        z = torch.empty((nb, f_in), dtype=dt, device=dev)
+        if last:
+            y = torch.empty((nb, f_out), dtype=dt, device=dev)
+        else:
+            x_next = torch.empty((nv, f_out), dtype=dt, device=dev)
+            y = x_next[:nb]
+        if model.op == "gcn":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+        elif model.op == "gin":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
+            w1, w2 = model.weights[l - 1]
+            B.gas_mlp2(z, w1, w2, y, relu_out=not last)
+        elif model.op == "gcnii":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            beta = gcnii_beta(l)
+            B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
+        else:
+            raise ValueError(model.op)
+        if last:
+            break
+        if do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        if nv > nb:
+            B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
+        x = x_next
+        if keep_layers:
+            layers.append(x)
+    return (y, layers) if keep_layers else y

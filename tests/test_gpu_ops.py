@@ -1,0 +1,210 @@
+"""GPU parity of every C-ABI call against the CPU oracle, element by element,
+on the same seeded inputs.  Pull, push, the GCN coefficients and index work
+are bit-exact; aggregation and transform are within 1e-5 (fp32) or 2e-2 (bf16
+storage) of the oracle, measured as max|a-b| / max|b| per output tensor."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from gas_inputs import configs, batches, rng
+from oracle import ops as oops
+from tests.util import to_np, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def gas():
+    import paper_2106_05609_amd as g
+    g.lib()
+    return g
+
+
+def dev(t):
+    return t.to("cuda")
+
+
+# ------------------------------------------------------------------ pull / push
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld", [(256, 256), (64, 64), (100, 100), (128, 160), (7, 7), (1, 1), (520, 520), (2048, 2048)])
+def test_pull_push_bit_exact(gas, dtype, F, ld):
+    n_hist, n = 5003, 1237                                  # ragged against every tile size
+    table = rng.normal_matrix(1, 300, n_hist, ld, dtype=dtype)
+    hist = dev(table)[:, :F]
+    idx = rng.randint(1, 301, torch.arange(n), n_hist).to(torch.int32)
+    dst_full = torch.full((n, ld), -7.0, dtype=dtype, device="cuda")
+    dst = dst_full[:, :F]
+    gas.gas_pull(hist, dev(idx), dst)
+    want = oops.pull(to_np(table)[:, :F], to_np(idx))
+    assert np.array_equal(to_np(dst), want)
+    if ld > F:
+        assert (dst_full[:, F:] == -7.0).all()              # padding untouched
+    # push distinct rows back into a fresh table
+    uniq = rng.permutation(1, 302, n_hist)[:n].to(torch.int32)
+    src = rng.normal_matrix(1, 303, n, F, dtype=dtype)
+    hist2 = dev(table.clone())
+    gas.gas_push(dev(src), dev(uniq), hist2[:, :F])
+    ref = to_np(table).copy()
+    oops.push(to_np(src), to_np(uniq), ref[:, :F])
+    assert np.array_equal(to_np(hist2), ref)
+    # contiguous-range forms
+    dst2 = torch.empty((100, F), dtype=dtype, device="cuda")
+    gas.gas_pull(hist, None, dst2, base=4900, n=100)
+    assert np.array_equal(to_np(dst2), to_np(table)[4900:5000, :F])
+    gas.gas_push(dst2, None, hist2[:, :F], base=3, n=100)
+    assert np.array_equal(to_np(hist2)[3:103, :F], to_np(table)[4900:5000, :F])
+
+
+def test_pull_push_empty_and_errors(gas):
+    hist = torch.zeros((10, 8), device="cuda")
+    dst = torch.zeros((0, 8), device="cuda")
+    gas.gas_pull(hist, torch.zeros(0, dtype=torch.int32, device="cuda"), dst)
+    gas.gas_push(dst, torch.zeros(0, dtype=torch.int32, device="cuda"), hist)
+    with pytest.raises(gas.GasError):
+        gas.gas_pull(hist, None, torch.zeros((4, 8), device="cuda"), base=8, n=4)     # range leaves the table
+    assert gas.gas_validate_indices(torch.tensor([0, 9, 3], dtype=torch.int32, device="cuda"), 10)
+    assert not gas.gas_validate_indices(torch.tensor([0, 10, 3], dtype=torch.int32, device="cuda"), 10)
+    assert not gas.gas_validate_indices(torch.tensor([-1], dtype=torch.int32, device="cuda"), 10)
+
+
+# ------------------------------------------------------------------ batch subgraphs
+def _batch(cfg_id, scale, batch=0, self_loops=None):
+    cfg = configs.config(cfg_id, scale)
+    g = configs.build_graph(cfg)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    sg = batches.batch_subgraph(g, bl[batch], cfg.self_loops if self_loops is None else self_loops)
+    return cfg, g, sg
+
+
+@pytest.fixture(scope="module")
+def graphs_small():
+    return {"sbm": _batch(0, 1.0, 1), "powerlaw": _batch(2, 0.01), "gin": _batch(4, 0.0005)}
+
+
+def test_gcn_norm_bit_exact(gas, graphs_small):
+    for name in ("sbm", "powerlaw"):
+        cfg, g, sg = graphs_small[name]
+        val = torch.empty(sg.nnz, dtype=torch.float32, device="cuda")
+        gas.gas_gcn_norm(dev(sg.rowptr), dev(sg.col), dev(sg.n_id), dev(g.deg), val)
+        want = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg))
+        assert np.array_equal(to_np(val), want)
+        val_t = torch.empty(sg.nnz, dtype=torch.float32, device="cuda")
+        gas.gas_gcn_norm(dev(sg.colptr), dev(sg.row), dev(sg.n_id), dev(g.deg), val_t)
+        assert np.array_equal(to_np(val_t), want[to_np(sg.csc_perm)])
+
+
+def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld_pad=0, out_dtype=None):
+    x = rng.normal_matrix(2, 310, sg.nv, F + ld_pad, dtype=dtype)
+    r = rng.normal_matrix(2, 311, sg.nb, F + ld_pad, dtype=dtype) if res else None
+    val = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg)) if use_val else None
+    out_dtype = out_dtype or dtype
+    z = torch.full((sg.nb, F + ld_pad), float("nan"), dtype=out_dtype, device="cuda")
+    plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F)
+    dval = None if val is None else dev(torch.from_numpy(val))
+    xd, rd = dev(x), None if r is None else dev(r)
+    args = (plan, dev(sg.rowptr), dev(sg.col), dval, xd[:, :F], z[:, :F])
+    kw = dict(diag=diag, s_agg=s_agg, r=None if rd is None else rd[:, :F], s_res=0.3 if res else 0.0)
+    gas.gas_spmm(*args, **kw)
+    want = oops.spmm(to_np(sg.rowptr), to_np(sg.col), val, to_np(x)[:, :F], diag=diag, s_agg=s_agg,
+                     r=None if r is None else to_np(r)[:, :F], s_res=0.3 if res else 0.0,
+                     out_dt=oops.F32 if out_dtype == torch.float32 else oops.BF16)
+    got = to_np(z[:, :F])
+    err = max_rel_err(got, want)
+    # run-to-run determinism: no atomics, fixed order
+    z2 = torch.full_like(z, float("nan"))
+    gas.gas_spmm(plan, *args[1:4], xd[:, :F], z2[:, :F], **kw)
+    assert np.array_equal(to_np(z2[:, :F]).view(np.uint8), got.view(np.uint8))
+    return err
+
+
+@pytest.mark.parametrize("F", [64, 100, 128, 256, 512, 12, 1024, 7])
+def test_spmm_fp32_gcn(gas, graphs_small, F):
+    for name in ("sbm", "powerlaw"):
+        cfg, g, sg = graphs_small[name]
+        assert _spmm_case(gas, g, sg, F, torch.float32, True) <= TOL[torch.float32], (name, F)
+
+
+@pytest.mark.parametrize("F", [128, 256, 64, 8, 520, 9])
+def test_spmm_bf16_gin(gas, graphs_small, F):
+    cfg, g, sg = graphs_small["gin"]
+    assert _spmm_case(gas, g, sg, F, torch.bfloat16, False, diag=1.0) <= TOL[torch.bfloat16]
+    assert _spmm_case(gas, g, sg, F, torch.bfloat16, False, diag=1.1, out_dtype=torch.float32) <= 1e-5
+
+
+def test_spmm_epilogues_padding_and_heavy_rows(gas, graphs_small, monkeypatch):
+    cfg, g, sg = graphs_small["powerlaw"]
+    deg = np.diff(to_np(sg.rowptr))
+    assert deg.max() > 256 and deg.min() < 32          # both the chunked and the one-wavefront path run
+    assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True, ld_pad=8) <= 1e-5
+    assert _spmm_case(gas, g, sg, 64, torch.float32, False, diag=1.25) <= 1e-5
+    # tiny thresholds: almost every row is cut into many chunks
+    monkeypatch.setenv("GAS_SPMM_HEAVY", "8")
+    monkeypatch.setenv("GAS_SPMM_CHUNK", "32")
+    assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True) <= 1e-5
+    assert _spmm_case(gas, g, sg, 128, torch.bfloat16, True, diag=0.5) <= 2e-2
+    assert _spmm_case(gas, g, sg, 20, torch.float32, True) <= 1e-5
+
+
+def test_spmm_empty_rows_and_empty_matrix(gas):
+    ptr = torch.tensor([0, 0, 2, 2, 5], dtype=torch.int32, device="cuda")
+    col = torch.tensor([0, 2, 1, 3, 4], dtype=torch.int32, device="cuda")
+    x = torch.arange(20, dtype=torch.float32, device="cuda").view(5, 4)
+    z = torch.full((4, 4), float("nan"), device="cuda")
+    plan = gas.gas_plan_create(ptr, 5, 4)
+    gas.gas_spmm(plan, ptr, col, None, x, z)
+    want = oops.spmm(to_np(ptr), to_np(col), None, to_np(x))
+    assert np.array_equal(to_np(z), want) and (want[0] == 0).all()
+    gas.gas_spmm(plan, ptr, col, None, x, z, diag=2.0)
+    assert np.array_equal(to_np(z), oops.spmm(to_np(ptr), to_np(col), None, to_np(x), diag=2.0))
+    empty = gas.gas_plan_create(torch.zeros(1, dtype=torch.int32, device="cuda"), 0, 4)
+    gas.gas_spmm(empty, ptr, col, None, x, z[:0])
+    with pytest.raises(gas.GasError):
+        gas.gas_plan_create(ptr, 4, 4)                   # nnz does not match ptr
+
+
+@pytest.mark.parametrize("dtype,F", [(torch.float32, 256), (torch.float32, 100), (torch.bfloat16, 256), (torch.float32, 6)])
+def test_spmm_t_parity(gas, graphs_small, dtype, F):
+    for name in ("sbm", "powerlaw"):
+        cfg, g, sg = graphs_small[name]
+        val = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg))
+        val_t = torch.from_numpy(val[to_np(sg.csc_perm)])
+        gz = rng.normal_matrix(3, 320, sg.nb, F, dtype=dtype)
+        for n_out in (sg.nb, sg.nv):
+            nnz_out = int(sg.colptr[n_out])
+            plan = gas.gas_plan_create(dev(sg.colptr[: n_out + 1]), nnz_out, F, n_rows=n_out)
+            gx = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
+            gas.gas_spmm_t(plan, dev(sg.colptr), dev(sg.row), dev(val_t), dev(gz), gx, diag=0.75)
+            want = oops.spmm_t(to_np(sg.rowptr), to_np(sg.col), val, to_np(gz), n_out, diag=0.75)
+            assert max_rel_err(to_np(gx), want) <= TOL[dtype], (name, n_out)
+
+
+# ------------------------------------------------------------------ dense transform
+@pytest.mark.parametrize("M,K,N", [(1000, 256, 256), (37, 64, 64), (4097, 100, 256), (513, 128, 64),
+                                    (300, 15, 20), (129, 256, 130), (64, 8, 8)])
+def test_linear_fp32_parity(gas, M, K, N):
+    z = rng.normal_matrix(4, 330, M, K)
+    w = rng.glorot_uniform(4, 331, K, N)
+    b = rng.normal(4, 332, 0, N)
+    for kw in (dict(), dict(relu=True), dict(bias=b, relu=True)):
+        y = torch.full((M, N), float("nan"), device="cuda")
+        gas.gas_linear(dev(z), dev(w), y, bias=None if "bias" not in kw else dev(b), relu=kw.get("relu", False))
+        want = oops.linear(to_np(z), to_np(w), bias=None if "bias" not in kw else to_np(b), relu=kw.get("relu", False))
+        assert max_rel_err(to_np(y), want) <= 1e-5, (M, K, N, kw)
+    if K == N:
+        y = torch.full((M, N), float("nan"), device="cuda")
+        gas.gas_linear(dev(z), dev(w), y, c_identity=0.6, c_weight=0.4, relu=True)
+        want = oops.linear(to_np(z), to_np(w), c_identity=0.6, c_weight=0.4, relu=True)
+        assert max_rel_err(to_np(y), want) <= 1e-5
+
+
+def test_linear_strided_rows(gas):
+    zbuf = rng.normal_matrix(4, 333, 700, 300)
+    w = rng.glorot_uniform(4, 334, 256, 64)
+    ybuf = torch.full((900, 64), float("nan"), device="cuda")
+    gas.gas_linear(dev(zbuf)[:, :256], dev(w), ybuf[:700])
+    want = oops.linear(to_np(zbuf)[:, :256], to_np(w))
+    assert max_rel_err(to_np(ybuf[:700]), want) <= 1e-5 and torch.isnan(ybuf[700:]).all()

@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the GAS layer step on one MI355X.
+
+A step is one pass of the whole hot path over one mini-batch of the synthetic
+workload, for a middle layer (hidden width in and out):
+
+    gas_pull    halo rows of the mini-batch tensor <- history table l
+    gas_spmm    aggregation over the batch subgraph
+    gas_linear  dense transform (+ReLU)             (gas_mlp2 for GIN)
+    gas_push    in-batch rows -> history table l+1
+    gas_spmm_t  backward aggregation over the CSC copy
+
+All inputs are resident in HBM before the timed region.  Prints one JSON line
+with the whole-step throughput in aggregated edges per second, the roofline of
+the dominant kernel (the aggregation) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4")
+    p.add_argument("--scale", type=float, default=1.0, help="shrink the node count (debugging only)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--skip-spmm-t", action="store_true",
+                   help="profiling aid: leave the backward aggregation out, so that the per-kernel averages of a "
+                        "trace are those of the forward aggregation alone (the reported value is then not the metric)")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also launch three plain 1 GiB contiguous copies (gas_pull without an index) before the "
+                        "timed region: a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by")
+    p.add_argument("--cpu-sample-rows", type=int, default=0, help="rows of the batch the oracle is timed on")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    import paper_2106_05609_amd as gas
+    from paper_2106_05609_amd import executor
+    from gas_inputs import configs, batches, rng
+
+    gas.lib()   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    cfg = configs.config(args.config, args.scale)
+    t0 = time.time()
+    g = configs.build_graph(cfg, device=dev)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    sg = batches.batch_subgraph(g, bl[0], cfg.self_loops)
+    torch.cuda.synchronize()
+    nb, nh, nv, nnz = sg.nb, sg.nh, sg.nv, sg.nnz
+    nnz_t = int(sg.colptr[nb].item())            # entries in in-batch columns (backward over the batch only)
+    log(f"[bench] {cfg.name}: N={g.n} nnz={g.nnz} | batch nb={nb} nh={nh} nnz_b={nnz} nnz_bt={nnz_t} "
+        f"max_row={int((sg.rowptr[1:] - sg.rowptr[:-1]).max())} | generated in {time.time() - t0:.1f}s")
+
+    F = cfg.widths[-2]                            # hidden width: the middle layer is F -> F
+    dt = cfg.dtype
+    s = 4 if dt == torch.float32 else 2
+    gin = cfg.op == "gin"
+    bg = executor.BatchGraph(nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row, max_F=F, normalise=not gin)
+    hist_in = rng.normal_matrix(cfg.seed, 200, cfg.n, F, dev, dt)
+    hist_out = torch.zeros((cfg.n, F), dtype=dt, device=dev)
+    x = rng.normal_matrix(cfg.seed, 210, nv, F, dev, dt)          # rows 0..nb-1: fresh in-batch embeddings
+    z = torch.empty((nb, F), dtype=dt, device=dev)
+    x_next = torch.empty((nv, F), dtype=dt, device=dev)
+    gz = rng.normal_matrix(cfg.seed, 211, nb, F, dev, dt)          # upstream gradient for the backward aggregation
+    gx = torch.empty((nb, F), dtype=dt, device=dev)
+    if gin:
+        w1 = rng.glorot_uniform(cfg.seed, 102, F, cfg.gin_hidden, dev, dt)
+        w2 = rng.glorot_uniform(cfg.seed, 103, cfg.gin_hidden, F, dev, dt)
+    else:
+        w = rng.glorot_uniform(cfg.seed, 101, F, F, dev, dt)
+    halo, batch_ids = bg.n_id[nb:], bg.n_id[:nb]
+    alpha = cfg.alpha
+    h0 = rng.normal_matrix(cfg.seed, 212, nb, F, dev, dt) if cfg.op == "gcnii" else None
+
+    names = ["pull", "spmm", "linear", "push", "spmm_t"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        gas.gas_pull(hist_in, halo, x[nb:])
+        mark(1)
+        if gin:
+            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + cfg.gin_eps)
+        elif cfg.op == "gcnii":
+            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - alpha, r=h0, s_res=alpha)
+        else:
+            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+        mark(2)
+        if gin:
+            gas.gas_mlp2(z, w1, w2, x_next[:nb], relu_out=True)
+        elif cfg.op == "gcnii":
+            b = executor.gcnii_beta(2)
+            gas.gas_linear(z, w, x_next[:nb], c_identity=1.0 - b, c_weight=b, relu=True)
+        else:
+            gas.gas_linear(z, w, x_next[:nb], relu=True)
+        mark(3)
+        gas.gas_push(x_next[:nb], batch_ids, hist_out)
+        mark(4)
+        if not args.skip_spmm_t:
+            gas.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, gz, gx, diag=(1.0 + cfg.gin_eps) if gin else 0.0)
+        mark(5)
+
+    if args.calibrate_copy:
+        src = torch.ones((1 << 20, 256), dtype=torch.float32, device=dev)      # exactly 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            gas.gas_pull(src, None, dst, base=0, n=1 << 20)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall / args.steps * 1e3
+    per = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
+
+    # algorithmic bytes (what the method must move at least once), per launch
+    val_bytes = 0 if gin else 4
+    by = {
+        "pull": nh * (2 * F * s + 4),
+        "spmm": nnz * (4 + val_bytes) + (nb + 1) * 4 + nv * F * s + nb * F * s,
+        "linear": nb * 2 * F * s + F * F * s * (2 if gin else 1),
+        "push": nb * (2 * F * s + 4),
+        "spmm_t": nnz_t * (4 + val_bytes) + (nb + 1) * 4 + nb * F * s + nb * F * s,
+    }
+    spmm_hi = nnz * (4 + val_bytes) + (nb + 1) * 4 + nnz * F * s + nb * F * s     # no reuse of gathered rows
+    edges = nnz + (0 if args.skip_spmm_t else nnz_t)
+    value = edges / (ms_step * 1e-3)
+    kern = {}
+    for n in names:
+        gbs = by[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
+        kern[n] = {"ms": round(per[n], 4), "alg_GB": round(by[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
+                   "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2)}
+        log(f"[bench] {n:7s} {per[n]:8.3f} ms  alg {by[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "
+            f"{100 * gbs / HBM_PEAK_GBS:5.1f}% of peak")
+    flops = 2.0 * nb * F * F * (2 if gin else 1)
+    kern["linear"]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
+    kern["spmm"]["edges_per_s"] = round(nnz / (per["spmm"] * 1e-3), 1)
+    kern["spmm"]["gathered_GBps"] = round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)
+    hbm3 = (by["pull"] + by["spmm"] + by["push"]) / ((per["pull"] + per["spmm"] + per["push"]) * 1e-3) / 1e9
+    log(f"[bench] step {ms_step:.3f} ms (sum of kernels {sum(per.values()):.3f}) | pull+spmm+push {hbm3:.1f} GB/s "
+        f"= {100 * hbm3 / HBM_PEAK_GBS:.1f}% of HBM peak | spmm gathers {kern['spmm']['gathered_GBps']} GB/s from cache+HBM "
+        f"| linear {kern['linear']['TFLOPs']} TFLOP/s")
+
+    spmm_gbs = by["spmm"] / (per["spmm"] * 1e-3) / 1e9
+    out = {
+        "metric": "GAS layer step: edges aggregated/sec + achieved HBM GB/s (% of peak), 1 GPU",
+        "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if dt == torch.float32 else "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch",
+                   "N": g.n, "nnz": g.nnz, "nb": nb, "nh": nh, "nnz_b": nnz, "nnz_bt": nnz_t, "F": F,
+                   "scale": args.scale},
+        "hbm_pull_spmm_push": {"GBps": round(hbm3, 1), "pct_of_peak": round(100 * hbm3 / HBM_PEAK_GBS, 2)},
+        "kernels": kern,
+        "roofline": {"kernel": "spmm_kernel (gas_spmm)", "bound": "hbm", "achieved": round(spmm_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(spmm_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": load_traffic(args.config, args.scale)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, g, sg, hist_in, x, w1 if gin else w, w2 if gin else None, gz, F,
+                                           args.cpu_sample_rows)
+    print(json.dumps(out), flush=True)
+
+
+def load_traffic(config, scale):
+    """HBM bytes per aggregation launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if scale != 1.0 or not os.path.exists(path):
+        return None
+    try:
+        with open(path) as f:
+            return json.load(f).get(f"config{config}", {}).get("spmm_kernel_bytes")
+    except Exception:
+        return None
+
+
+def cpu_baseline(cfg, g, sg, hist_in, x, w, w2, gz, F, sample_rows):
+    """The oracle's own pull + spmm + linear + push + spmm_t on the first rows of
+    the same batch, sized for roughly 10-30 s of CPU work."""
+    import numpy as np
+    from oracle import ops as oops
+    from tests.util import to_np
+    nb = sg.nb
+    rowptr = sg.rowptr.cpu().numpy()
+    colall = sg.col.cpu().numpy()
+    if sample_rows <= 0:
+        # every k-th row of the batch, so that the sample has the batch's degree mix
+        sample_rows = int(min(nb, max(1, round(nb * 3_000_000 / max(1, rowptr[-1])))))
+    m = min(sample_rows, nb)
+    rows = np.unique(np.linspace(0, nb - 1, m).astype(np.int64))
+    m = rows.size
+    lens = rowptr[rows + 1] - rowptr[rows]
+    rp = np.zeros(m + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(lens)
+    e = int(rp[-1])
+    col = np.concatenate([colall[rowptr[r]:rowptr[r + 1]] for r in rows]).astype(np.int32)
+    # renumber the sampled rows 0..m-1 in front (they stay "in-batch"), everything else behind them
+    remap = np.full(sg.nv, -1, dtype=np.int64)
+    remap[rows] = np.arange(m)
+    others = np.setdiff1d(np.unique(col), rows)
+    remap[others] = m + np.arange(others.size)
+    col = remap[col].astype(np.int32)
+    order = np.concatenate([rows, others])            # old local id of every new local id
+    gin = cfg.op == "gin"
+    n_id = sg.n_id.cpu().numpy()
+    val = None if gin else oops.gcn_norm(rp, col, np.ascontiguousarray(n_id[order]), g.deg.cpu().numpy())
+    dev_order = torch.from_numpy(order).to(x.device)
+    xs = to_np(x[dev_order])                            # compact mini-batch tensor: sampled rows, then their neighbours
+    n_halo = others.size
+    hist_rows = to_np(hist_in[sg.n_id[dev_order[m:]].long()])   # compact stand-in for the history table
+    idx_local = np.arange(n_halo, dtype=np.int32)
+    wn = to_np(w)
+    w2n = None if w2 is None else to_np(w2)
+    gzn = to_np(gz[dev_order[:m]])
+    hist_out = np.zeros((m, F), dtype=xs.dtype)
+    t0 = time.perf_counter()
+    xs[m:] = oops.pull(hist_rows, idx_local)
+    t1 = time.perf_counter()
+    z = oops.spmm(rp, col, val, xs, diag=(1.0 + cfg.gin_eps) if gin else 0.0)
+    t2 = time.perf_counter()
+    y = oops.mlp2(z, wn, w2n, relu_out=True) if gin else oops.linear(z, wn, relu=True)
+    t3 = time.perf_counter()
+    oops.push(y, np.arange(m, dtype=np.int32), hist_out)
+    t4 = time.perf_counter()
+    oops.spmm_t(rp, col, val, gzn, m, diag=(1.0 + cfg.gin_eps) if gin else 0.0)
+    t5 = time.perf_counter()
+    nnz_t = int((col < m).sum())
+    total = t5 - t0
+    log(f"[bench] oracle on {m} rows / {e} entries: pull {t1 - t0:.2f}s spmm {t2 - t1:.2f}s linear {t3 - t2:.2f}s "
+        f"push {t4 - t3:.3f}s spmm_t {t5 - t4:.2f}s ({oops.num_threads()} threads)")
+    return {"value": (e + nnz_t) / total, "unit": "edges/s", "cores": oops.num_threads(), "kind": "oracle",
+            "sample": f"{m} evenly spaced in-batch rows of the same batch ({e} entries, {n_halo} neighbour rows pulled), "
+                      f"same five calls, {total:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,24 +1,32 @@
 // Dense transform of the GNN operators on the matrix cores (gas_linear,
-// gas_mlp2):  Y = act(c_identity * Z + c_weight * (Z W) + bias).
+// gas_mlp2):  Y = act(c_identity * Z + c_weight * (Z W) + bias), and the fused
+// two-layer MLP of the GIN operator.
 //
 // This is the only dense contraction of the step (the W of the paper's GCN,
 // GCNII and GIN operator equations), so it is the only place MFMA is used.
 // fp32 data uses v_mfma_f32_32x32x2_f32, bf16 data v_mfma_f32_32x32x16_bf16
 // with fp32 accumulation.
 //
-// Tiling (fp32): a workgroup of 4 wavefronts owns a BM x BN tile of Y, each
-// wavefront a (BM/2) x (BN/2) sub-tile made of 32x32 MFMA blocks.  K is walked
-// in steps of 32: the next A (rows of Z) and B (rows of W) tiles are fetched
-// from global memory into registers while the current ones are consumed from
-// LDS.  A is stored [m][k] so that one 128-bit LDS read gives a lane the four
-// k values of four consecutive MFMAs; lanes 0-31 and 32-63 of an MFMA take
-// different k, and A and B agree on which.
+// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of Y, each
+// wavefront a sub-tile made of 32x32 MFMA blocks.  K is walked in tiles: the
+// next A (rows of Z) and B (rows of W) tiles are fetched from global memory
+// into registers while the current ones are consumed from LDS.
+//   fp32: A is stored [m][k] so that one 128-bit LDS read gives a lane the four
+//         k values of four consecutive MFMAs; lanes 0-31 and 32-63 of an MFMA
+//         take different k, and A and B agree on which.
+//   bf16: both operands need eight consecutive k per lane.  Z is [m][k]
+//         already; W is [k][n], so its tiles are transposed on the way into
+//         LDS: a thread loads an 8(k) x 8(n) block as eight 16-byte row pieces,
+//         regroups it in registers and writes eight 16-byte [n][k] pieces.
+// The accumulator of a 32x32 block keeps, in register r of lane (li, lh),
+// row 8*(r/4) + 4*lh + r%4 and column li.
 #include "common.h"
 
 namespace gas {
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct LinArgs {
     const char* Z;   int64_t ldz;      // elements
@@ -31,114 +39,153 @@ struct LinArgs {
     int relu;
 };
 
-constexpr int kBK = 32;
-constexpr int kPadA = 4, kPadB = 4;
+struct MlpArgs {
+    const char* Z;   int64_t ldz;
+    const char* W1;  const char* b1;
+    const char* W2;  const char* b2;
+    char* Y;         int64_t ldy;
+    int64_t M;
+    int K, H, N;     // F_in, F_hid (<= kHidMax), F_out
+    int relu_out;
+};
 
-// ------------------------------------------------------------------ fp32
-template <int BM, int BN, bool VEC>
-__global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
-    constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 blocks per wavefront
-    constexpr int A_V4 = BM * kBK / 4 / 256;           // float4 per thread per tile
-    constexpr int B_V4 = kBK * BN / 4 / 256;
-    __shared__ __attribute__((aligned(16))) float As[BM][kBK + kPadA];
-    __shared__ __attribute__((aligned(16))) float Bs[kBK][BN + kPadB];
+constexpr int kHidMax = 256;
+constexpr int kMlpRowsF32 = 32, kMlpRowsBF16 = 64;     // rows per workgroup of the fused MLP kernels
 
-    const float* Z = reinterpret_cast<const float*>(a.Z);
-    const float* W = reinterpret_cast<const float*>(a.W);
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int li = lane & 31, lh = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int n0 = blockIdx.y * BN;
-    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
-
-    f32x16 acc[TM][TN];
+template <int TM, int TN>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[TM][TN]) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+}
 
-    f32x4 ra[A_V4], rb[B_V4];
-    auto fetch = [&](int k0) {
+__device__ __forceinline__ float bf16_val(const uint16_t* p, int64_t i) { return __uint_as_float((uint32_t)p[i] << 16); }
+
+// ====================================================================== fp32
+constexpr int kBK = 32;                    // k per tile
+constexpr int kLdA = kBK + 4;              // padded LDS row of the A tile (floats)
+
+// Fetch / stage one BM x kBK tile of a row-major fp32 matrix with row stride ld.
+template <int BM, bool VEC>
+struct ATileF32 {
+    static constexpr int NV = BM * kBK / 4 / 256;
+    f32x4 r[NV];
+    __device__ __forceinline__ void fetch(const float* Z, int64_t ld, int64_t M, int K, int64_t m0, int k0, int tid) {
 #pragma unroll
-        for (int i = 0; i < A_V4; ++i) {
+        for (int i = 0; i < NV; ++i) {
             const int idx = tid + 256 * i;
-            const int row = idx / (kBK / 4), c4 = idx % (kBK / 4);
-            const int64_t m = m0 + row;
-            const int k = k0 + 4 * c4;
+            const int64_t m = m0 + idx / (kBK / 4);
+            const int k = k0 + 4 * (idx % (kBK / 4));
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (m < a.M) {
+            if (m < M) {
                 if constexpr (VEC) {
-                    if (k < a.K) v = *reinterpret_cast<const f32x4*>(Z + m * a.ldz + k);
+                    if (k < K) v = *reinterpret_cast<const f32x4*>(Z + m * ld + k);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (k + e < a.K) v[e] = Z[m * a.ldz + k + e];
+                        if (k + e < K) v[e] = Z[m * ld + k + e];
                 }
             }
-            ra[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < B_V4; ++i) {
-            const int idx = tid + 256 * i;
-            const int kr = idx / (BN / 4), c4 = idx % (BN / 4);
-            const int k = k0 + kr, n = n0 + 4 * c4;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (k < a.K) {
-                if constexpr (VEC) {
-                    if (n < a.N) v = *reinterpret_cast<const f32x4*>(W + (int64_t)k * a.N + n);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < a.N) v[e] = W[(int64_t)k * a.N + n + e];
-                }
-            }
-            rb[i] = v;
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_V4; ++i) {
-            const int idx = tid + 256 * i;
-            *reinterpret_cast<f32x4*>(&As[idx / (kBK / 4)][4 * (idx % (kBK / 4))]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_V4; ++i) {
-            const int idx = tid + 256 * i;
-            *reinterpret_cast<f32x4*>(&Bs[idx / (BN / 4)][4 * (idx % (BN / 4))]) = rb[i];
-        }
-    };
-
-    fetch(0);
-    for (int k0 = 0; k0 < a.K; k0 += kBK) {
-        __syncthreads();                 // everyone is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (k0 + kBK < a.K) fetch(k0 + kBK);
-#pragma unroll
-        for (int kq = 0; kq < kBK / 8; ++kq) {
-            f32x4 fa[TM];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const f32x4*>(&As[wm0 + 32 * i + li][kq * 8 + lh * 4]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float fb[TN];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[j] = Bs[kq * 8 + lh * 4 + q][wn0 + 32 * j + li];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q], fb[j], acc[i][j], 0, 0, 0);
-            }
+            r[i] = v;
         }
     }
+    __device__ __forceinline__ void stage(float (*As)[kLdA], int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<f32x4*>(&As[idx / (kBK / 4)][4 * (idx % (kBK / 4))]) = r[i];
+        }
+    }
+};
 
-    // accumulator layout of a 32x32 block: register r of lane (li, lh) holds
-    // row 8*(r/4) + 4*lh + r%4, column li
+// Fetch / stage one kBK x BN tile of a row-major fp32 [K][N] matrix.
+template <int BN, bool VEC>
+struct BTileF32 {
+    static constexpr int NV = kBK * BN / 4 / 256;
+    f32x4 r[NV];
+    __device__ __forceinline__ void fetch(const float* W, int K, int N, int k0, int n0, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + 256 * i;
+            const int k = k0 + idx / (BN / 4), n = n0 + 4 * (idx % (BN / 4));
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (k < K) {
+                if constexpr (VEC) {
+                    if (n < N) v = *reinterpret_cast<const f32x4*>(W + (int64_t)k * N + n);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) v[e] = W[(int64_t)k * N + n + e];
+                }
+            }
+            r[i] = v;
+        }
+    }
+    __device__ __forceinline__ void stage(float (*Bs)[BN + 4], int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<f32x4*>(&Bs[idx / (BN / 4)][4 * (idx % (BN / 4))]) = r[i];
+        }
+    }
+};
+
+// acc += A[arow0.., acol0 .. acol0+kBK) * Bs, A an LDS array with row stride lda floats
+template <int TM, int TN, int BN>
+__device__ __forceinline__ void mfma_tile_f32(const float* A, int lda, int arow0, int acol0,
+                                              const float (*Bs)[BN + 4], int bcol0, int li, int lh,
+                                              f32x16 (&acc)[TM][TN]) {
+#pragma unroll
+    for (int kq = 0; kq < kBK / 8; ++kq) {
+        f32x4 fa[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *reinterpret_cast<const f32x4*>(A + (arow0 + 32 * i + li) * lda + acol0 + kq * 8 + lh * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float fb[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = Bs[kq * 8 + lh * 4 + q][bcol0 + 32 * j + li];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][q], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+}
+
+template <int BM, int BN, bool VEC>
+__global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
+    constexpr int TM = BM / 64, TN = BN / 64;
+    __shared__ __attribute__((aligned(16))) float As[BM][kLdA];
+    __shared__ __attribute__((aligned(16))) float Bs[kBK][BN + 4];
+    const float* Z = reinterpret_cast<const float*>(a.Z);
+    const float* W = reinterpret_cast<const float*>(a.W);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    f32x16 acc[TM][TN];
+    zero_acc(acc);
+    ATileF32<BM, VEC> ta;
+    BTileF32<BN, VEC> tb;
+    ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
+    tb.fetch(W, a.K, a.N, 0, n0, tid);
+    for (int k0 = 0; k0 < a.K; k0 += kBK) {
+        __syncthreads();                 // everyone is done reading the previous tile
+        ta.stage(As, tid);
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBK < a.K) {
+            ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBK, tid);
+            tb.fetch(W, a.K, a.N, k0 + kBK, n0, tid);
+        }
+        mfma_tile_f32<TM, TN, BN>(&As[0][0], kLdA, wm0, 0, Bs, wn0, li, lh, acc);
+    }
     float* Y = reinterpret_cast<float*>(a.Y);
     const float* bias = reinterpret_cast<const float*>(a.bias);
 #pragma unroll
@@ -160,6 +207,332 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
         }
 }
 
+// fp32 fused MLP: 32 rows per workgroup; wavefront w owns hidden / output
+// columns [64w, 64w+64).  Phase 1 leaves relu(Z W1 + b1) in LDS (fp32), phase 2
+// multiplies it by W2 with the hidden tile as the A operand.
+template <bool VEC>
+__global__ __launch_bounds__(256) void mlp2_f32_kernel(MlpArgs a) {
+    constexpr int BM = kMlpRowsF32, BN = 256, TN = 2;
+    constexpr int kLdH = kHidMax + 4;
+    extern __shared__ __attribute__((aligned(16))) char smem[];   // above the 64 KB static limit
+    float (*Hs)[kLdH] = reinterpret_cast<float (*)[kLdH]>(smem);
+    float (*As)[kLdA] = reinterpret_cast<float (*)[kLdA]>(smem + sizeof(float) * BM * kLdH);
+    float (*Bs)[BN + 4] = reinterpret_cast<float (*)[BN + 4]>(smem + sizeof(float) * BM * (kLdH + kLdA));
+    const float* Z = reinterpret_cast<const float*>(a.Z);
+    const float* W1 = reinterpret_cast<const float*>(a.W1);
+    const float* W2 = reinterpret_cast<const float*>(a.W2);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int wn0 = wave * 64;
+    f32x16 acc[1][TN];
+    zero_acc(acc);
+    ATileF32<BM, VEC> ta;
+    BTileF32<BN, VEC> tb;
+    ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
+    tb.fetch(W1, a.K, a.H, 0, 0, tid);
+    for (int k0 = 0; k0 < a.K; k0 += kBK) {
+        __syncthreads();
+        ta.stage(As, tid);
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBK < a.K) {
+            ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBK, tid);
+            tb.fetch(W1, a.K, a.H, k0 + kBK, 0, tid);
+        }
+        mfma_tile_f32<1, TN, BN>(&As[0][0], kLdA, 0, 0, Bs, wn0, li, lh, acc);
+    }
+    const float* b1 = reinterpret_cast<const float*>(a.b1);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int h = wn0 + 32 * j + li;
+        const float bv = (b1 && h < a.H) ? b1[h] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            Hs[8 * (r / 4) + 4 * lh + (r % 4)][h] = h < a.H ? fmaxf(acc[0][j][r] + bv, 0.f) : 0.f;
+    }
+    zero_acc(acc);
+    tb.fetch(W2, a.H, a.N, 0, n0, tid);
+    for (int k0 = 0; k0 < a.H; k0 += kBK) {
+        __syncthreads();                 // Hs written / previous Bs consumed
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBK < a.H) tb.fetch(W2, a.H, a.N, k0 + kBK, n0, tid);
+        mfma_tile_f32<1, TN, BN>(&Hs[0][0], kLdH, 0, k0, Bs, wn0, li, lh, acc);
+    }
+    float* Y = reinterpret_cast<float*>(a.Y);
+    const float* b2 = reinterpret_cast<const float*>(a.b2);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn0 + 32 * j + li;
+        if (n >= a.N) continue;
+        const float bv = b2 ? b2[n] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t m = m0 + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (m >= a.M) continue;
+            float y = acc[0][j][r] + bv;
+            if (a.relu_out) y = fmaxf(y, 0.f);
+            Y[m * a.ldy + n] = y;
+        }
+    }
+}
+
+// ====================================================================== bf16
+constexpr int kBKh = 64;            // k per tile
+constexpr int kLdh = kBKh + 8;      // padded LDS row, in bf16 elements
+
+__device__ __forceinline__ void transpose8x8_bf16(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+    // in[r] holds n = 0..7 of k-row r (two per dword); out[c] holds k = 0..7 of column c
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t lo = in[2 * q][c >> 1], hi = in[2 * q + 1][c >> 1];
+            out[c][q] = (c & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+        }
+}
+
+template <int BM>
+struct ATileBF16 {
+    static constexpr int NV = BM * kBKh / 8 / 256;
+    u32x4 r[NV];
+    __device__ __forceinline__ void fetch(const uint16_t* Z, int64_t ld, int64_t M, int K, int64_t m0, int k0, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + 256 * i;
+            const int64_t m = m0 + (idx >> 3);
+            const int k = k0 + 8 * (idx & 7);
+            r[i] = u32x4{0u, 0u, 0u, 0u};
+            if (m < M && k < K) r[i] = *reinterpret_cast<const u32x4*>(Z + m * ld + k);
+        }
+    }
+    __device__ __forceinline__ void stage(uint16_t (*As)[kLdh], int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<u32x4*>(&As[idx >> 3][8 * (idx & 7)]) = r[i];
+        }
+    }
+};
+
+// One kBKh x BN tile of a row-major bf16 [K][N] matrix, transposed into Bs[n][k].
+template <int BN>
+struct BTileBF16 {
+    u32x4 r[8];
+    __device__ __forceinline__ void fetch(const uint16_t* W, int K, int N, int k0, int n0, int tid) {
+        if (tid >= BN) return;              // kBKh/8 * BN/8 = BN blocks of 8 x 8
+        const int kb = tid / (BN / 8), n = n0 + 8 * (tid % (BN / 8));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int k = k0 + 8 * kb + i;
+            r[i] = u32x4{0u, 0u, 0u, 0u};
+            if (k < K && n < N) r[i] = *reinterpret_cast<const u32x4*>(W + (int64_t)k * N + n);
+        }
+    }
+    __device__ __forceinline__ void stage(uint16_t (*Bs)[kLdh], int tid) {
+        if (tid >= BN) return;
+        const int kb = tid / (BN / 8), nb = tid % (BN / 8);
+        u32x4 t[8];
+        transpose8x8_bf16(r, t);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(&Bs[8 * nb + c][8 * kb]) = t[c];
+    }
+};
+
+template <int TM, int TN>
+__device__ __forceinline__ void mfma_tile_bf16(const uint16_t* A, int lda, int arow0, int acol0,
+                                               const uint16_t (*Bs)[kLdh], int brow0, int li, int lh,
+                                               f32x16 (&acc)[TM][TN]) {
+#pragma unroll
+    for (int kk = 0; kk < kBKh / 16; ++kk) {
+        bf16x8 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4*>(A + (arow0 + 32 * i + li) * lda + acol0 + kk * 16 + 8 * lh));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[j] = __builtin_bit_cast(bf16x8,
+                                       *reinterpret_cast<const u32x4*>(&Bs[brow0 + 32 * j + li][kk * 16 + 8 * lh]));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+template <int BN>
+__global__ __launch_bounds__(256) void linear_bf16_kernel(LinArgs a) {
+    constexpr int BM = 128, TM = 2, TN = BN / 64;
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM][kLdh];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN][kLdh];
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * (BN / 2);
+    f32x16 acc[TM][TN];
+    zero_acc(acc);
+    ATileBF16<BM> ta;
+    BTileBF16<BN> tb;
+    ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
+    tb.fetch(W, a.K, a.N, 0, n0, tid);
+    for (int k0 = 0; k0 < a.K; k0 += kBKh) {
+        __syncthreads();
+        ta.stage(As, tid);
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBKh < a.K) {
+            ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBKh, tid);
+            tb.fetch(W, a.K, a.N, k0 + kBKh, n0, tid);
+        }
+        mfma_tile_bf16<TM, TN>(&As[0][0], kLdh, wm0, 0, Bs, wn0, li, lh, acc);
+    }
+    uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
+    const uint16_t* bias = reinterpret_cast<const uint16_t*>(a.bias);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn0 + 32 * j + li;
+            if (n >= a.N) continue;
+            const float bv = bias ? bf16_val(bias, n) : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * lh + (r % 4);
+                if (m >= a.M) continue;
+                float y = a.c_w * acc[i][j][r] + bv;
+                if (a.c_id != 0.f) y += a.c_id * bf16_val(Z, m * a.ldz + n);
+                if (a.relu) y = fmaxf(y, 0.f);
+                Y[m * a.ldy + n] = (uint16_t)f32_to_bf16(y);
+            }
+        }
+}
+
+// bf16 fused MLP: 64 rows per workgroup, wavefronts 2 x 2 over (rows, columns).
+// Phase 1: hidden = relu(Z W1 + b1) for all F_hid columns, rounded to bf16 into
+// LDS.  Phase 2: Y = act(hidden W2 + b2), the hidden tile being the A operand.
+__global__ __launch_bounds__(256) void mlp2_bf16_kernel(MlpArgs a) {
+    constexpr int BM = kMlpRowsBF16, BN = 256, TN = 4;
+    constexpr int kLdHid = kHidMax + 8;
+    extern __shared__ __attribute__((aligned(16))) char smem[];   // above the 64 KB static limit
+    uint16_t (*Hs)[kLdHid] = reinterpret_cast<uint16_t (*)[kLdHid]>(smem);
+    uint16_t (*As)[kLdh] = reinterpret_cast<uint16_t (*)[kLdh]>(smem + 2 * BM * kLdHid);
+    uint16_t (*Bs)[kLdh] = reinterpret_cast<uint16_t (*)[kLdh]>(smem + 2 * BM * (kLdHid + kLdh));
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* W1 = reinterpret_cast<const uint16_t*>(a.W1);
+    const uint16_t* W2 = reinterpret_cast<const uint16_t*>(a.W2);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * (BN / 2);
+    f32x16 acc[1][TN];
+    zero_acc(acc);
+    ATileBF16<BM> ta;
+    BTileBF16<BN> tb;
+    ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
+    tb.fetch(W1, a.K, a.H, 0, 0, tid);
+    for (int k0 = 0; k0 < a.K; k0 += kBKh) {
+        __syncthreads();
+        ta.stage(As, tid);
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBKh < a.K) {
+            ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBKh, tid);
+            tb.fetch(W1, a.K, a.H, k0 + kBKh, 0, tid);
+        }
+        mfma_tile_bf16<1, TN>(&As[0][0], kLdh, wm0, 0, Bs, wn0, li, lh, acc);
+    }
+    const uint16_t* b1 = reinterpret_cast<const uint16_t*>(a.b1);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int h = wn0 + 32 * j + li;
+        const float bv = (b1 && h < a.H) ? bf16_val(b1, h) : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float v = h < a.H ? fmaxf(acc[0][j][r] + bv, 0.f) : 0.f;
+            Hs[wm0 + 8 * (r / 4) + 4 * lh + (r % 4)][h] = (uint16_t)f32_to_bf16(v);
+        }
+    }
+    zero_acc(acc);
+    tb.fetch(W2, a.H, a.N, 0, n0, tid);
+    for (int k0 = 0; k0 < a.H; k0 += kBKh) {
+        __syncthreads();                 // Hs written / previous Bs consumed
+        tb.stage(Bs, tid);
+        __syncthreads();
+        if (k0 + kBKh < a.H) tb.fetch(W2, a.H, a.N, k0 + kBKh, n0, tid);
+        mfma_tile_bf16<1, TN>(&Hs[0][0], kLdHid, wm0, k0, Bs, wn0, li, lh, acc);
+    }
+    uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
+    const uint16_t* b2 = reinterpret_cast<const uint16_t*>(a.b2);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn0 + 32 * j + li;
+        if (n >= a.N) continue;
+        const float bv = b2 ? bf16_val(b2, n) : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t m = m0 + wm0 + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (m >= a.M) continue;
+            float y = acc[0][j][r] + bv;
+            if (a.relu_out) y = fmaxf(y, 0.f);
+            Y[m * a.ldy + n] = (uint16_t)f32_to_bf16(y);
+        }
+    }
+}
+
+// ====================================================================== element-wise paths
+// For bf16 operands that are not 16-byte aligned (odd widths, odd strides):
+// one thread per output element, fp32 accumulation.
+__global__ __launch_bounds__(256) void linear_bf16_generic_kernel(LinArgs a) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.M * a.N) return;
+    const int64_t m = idx / a.N;
+    const int n = (int)(idx % a.N);
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W);
+    float s = 0.f;
+    for (int k = 0; k < a.K; ++k) s = fmaf(bf16_val(Z, m * a.ldz + k), bf16_val(W, (int64_t)k * a.N + n), s);
+    float y = a.c_w * s;
+    if (a.bias) y += bf16_val(reinterpret_cast<const uint16_t*>(a.bias), n);
+    if (a.c_id != 0.f) y += a.c_id * bf16_val(Z, m * a.ldz + n);
+    if (a.relu) y = fmaxf(y, 0.f);
+    reinterpret_cast<uint16_t*>(a.Y)[m * a.ldy + n] = (uint16_t)f32_to_bf16(y);
+}
+
+// One workgroup per row; the hidden row goes through LDS (bf16-rounded for
+// bf16 data, as in the MFMA kernel).
+template <bool BF>
+__global__ __launch_bounds__(256) void mlp2_generic_kernel(MlpArgs a) {
+    __shared__ float h[kHidMax];
+    const int64_t m = blockIdx.x;
+    auto ld = [](const char* p, int64_t i) -> float {
+        if constexpr (BF) return bf16_val(reinterpret_cast<const uint16_t*>(p), i);
+        else return reinterpret_cast<const float*>(p)[i];
+    };
+    for (int j = threadIdx.x; j < a.H; j += 256) {
+        float s = 0.f;
+        for (int k = 0; k < a.K; ++k) s = fmaf(ld(a.Z, m * a.ldz + k), ld(a.W1, (int64_t)k * a.H + j), s);
+        if (a.b1) s += ld(a.b1, j);
+        s = fmaxf(s, 0.f);
+        if constexpr (BF) s = __uint_as_float(f32_to_bf16(s) << 16);
+        h[j] = s;
+    }
+    __syncthreads();
+    for (int n = threadIdx.x; n < a.N; n += 256) {
+        float s = 0.f;
+        for (int k = 0; k < a.H; ++k) s = fmaf(h[k], ld(a.W2, (int64_t)k * a.N + n), s);
+        if (a.b2) s += ld(a.b2, n);
+        if (a.relu_out) s = fmaxf(s, 0.f);
+        if constexpr (BF) reinterpret_cast<uint16_t*>(a.Y)[m * a.ldy + n] = (uint16_t)f32_to_bf16(s);
+        else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = s;
+    }
+}
+
+// ====================================================================== launchers
 template <int BM, int BN>
 gas_status launch_f32(const LinArgs& a, bool vec, hipStream_t s) {
     const int64_t gm = (a.M + BM - 1) / BM;
@@ -168,6 +541,16 @@ gas_status launch_f32(const LinArgs& a, bool vec, hipStream_t s) {
     dim3 grid((unsigned)gm, (unsigned)gn), block(256);
     if (vec) hipLaunchKernelGGL((linear_f32_kernel<BM, BN, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((linear_f32_kernel<BM, BN, false>), grid, block, 0, s, a);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+template <int BN>
+gas_status launch_bf16(const LinArgs& a, hipStream_t s) {
+    const int64_t gm = (a.M + 127) / 128;
+    const int gn = (a.N + BN - 1) / BN;
+    if (gm > 0x7FFFFFFF || gn > 65535) return fail(GAS_ERR_ARG, "gas_linear: problem too large for one launch");
+    hipLaunchKernelGGL((linear_bf16_kernel<BN>), dim3((unsigned)gm, (unsigned)gn), dim3(256), 0, s, a);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
@@ -203,15 +586,67 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
         if (F_out <= 64) return launch_f32<128, 64>(a, vec, s);
         return launch_f32<128, 128>(a, vec, s);
     }
-    return fail(GAS_ERR_DTYPE, "gas_linear: bf16 is not implemented yet");
+    const bool vec = aligned16(Z) && aligned16(W) && ldz % 8 == 0 && F_in % 8 == 0 && F_out % 8 == 0;
+    if (!vec) {
+        const int64_t total = n_rows * (int64_t)F_out;
+        const int64_t blocks = (total + 255) / 256;
+        if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_linear: problem too large for the element-wise path");
+        hipLaunchKernelGGL(linear_bf16_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+        GAS_CHECK_HIP(hipGetLastError());
+        return GAS_OK;
+    }
+    if (F_out <= 64) return launch_bf16<64>(a, s);
+    if (F_out <= 128) return launch_bf16<128>(a, s);
+    return launch_bf16<256>(a, s);
 }
 
 gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
                     const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
                     void* Y, int64_t ldy, void* stream) {
-    (void)Z; (void)ldz; (void)n_rows; (void)F_in; (void)W1; (void)F_hid; (void)b1; (void)W2; (void)F_out; (void)b2;
-    (void)dt; (void)relu_out; (void)Y; (void)ldy; (void)stream;
-    return fail(GAS_ERR_DTYPE, "gas_mlp2: not implemented yet");
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_mlp2: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_hid > 0 && F_out > 0, "gas_mlp2: n_rows=%lld F_in=%d F_hid=%d F_out=%d",
+                (long long)n_rows, F_in, F_hid, F_out);
+    GAS_REQUIRE(F_hid <= kHidMax, "gas_mlp2: F_hid=%d exceeds %d", F_hid, kHidMax);
+    if (n_rows == 0) return GAS_OK;
+    GAS_REQUIRE(Z && W1 && W2 && Y, "gas_mlp2: null pointer");
+    GAS_REQUIRE(ldz >= F_in && ldy >= F_out, "gas_mlp2: row stride smaller than the row");
+    GAS_REQUIRE(Y != Z, "gas_mlp2: Y must not alias Z");
+    MlpArgs a;
+    a.Z = static_cast<const char*>(Z); a.ldz = ldz;
+    a.W1 = static_cast<const char*>(W1); a.b1 = static_cast<const char*>(b1);
+    a.W2 = static_cast<const char*>(W2); a.b2 = static_cast<const char*>(b2);
+    a.Y = static_cast<char*>(Y); a.ldy = ldy;
+    a.M = n_rows; a.K = F_in; a.H = F_hid; a.N = F_out;
+    a.relu_out = relu_out;
+    hipStream_t s = (hipStream_t)stream;
+    const int q = dt == GAS_F32 ? 4 : 8;    // elements per 16 bytes
+    const bool vec = aligned16(Z) && aligned16(W1) && aligned16(W2) && ldz % q == 0 && F_in % q == 0 &&
+                     F_hid % q == 0 && F_out % q == 0;
+    const int gn = (F_out + 255) / 256;
+    if (n_rows > 0x7FFFFFFFLL || gn > 65535) return fail(GAS_ERR_ARG, "gas_mlp2: problem too large for one launch");
+    if (dt == GAS_F32) {
+        constexpr int smem = 4 * (kMlpRowsF32 * (kHidMax + 4 + kBK + 4) + kBK * (256 + 4));
+        static const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp2_f32_kernel<true>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        static const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp2_f32_kernel<false>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        GAS_CHECK_HIP(e1);
+        GAS_CHECK_HIP(e2);
+        dim3 grid((unsigned)((n_rows + kMlpRowsF32 - 1) / kMlpRowsF32), (unsigned)gn);
+        if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
+        else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
+    } else if (vec) {
+        constexpr int smem = 2 * (kMlpRowsBF16 * (kHidMax + 8 + kBKh + 8) + 256 * (kBKh + 8));
+        static const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp2_bf16_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        GAS_CHECK_HIP(e1);
+        hipLaunchKernelGGL(mlp2_bf16_kernel, dim3((unsigned)((n_rows + kMlpRowsBF16 - 1) / kMlpRowsBF16), (unsigned)gn),
+                           dim3(256), smem, s, a);
+    } else {
+        hipLaunchKernelGGL(mlp2_generic_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, s, a);
+    }
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
 }
 
 }  // extern "C"

@@ -13,8 +13,8 @@
 // broadcasts them with lane permutes; U independent row loads are in flight
 // per lane.  Rows with at most `threshold` entries take one wavefront each.
 // Heavier rows (power-law hubs) are cut into chunks of `chunk` entries, one
-// wavefront per chunk, whose fp32 partial sums go to a workspace and are added
-// in chunk order by a second kernel: the summation order is a function of the
+// wavefront per chunk in the same launch, whose fp32 partial sums go to a
+// workspace and are added in chunk order by a second, small kernel: the summation order is a function of the
 // row pointer array alone, so results are bit-identical from run to run.
 #include "common.h"
 
@@ -24,7 +24,7 @@
 struct gas_plan {
     int64_t n_rows = 0, nnz = 0;
     int32_t max_F = 0;
-    int32_t threshold = 0, chunk = 0;
+    int32_t threshold = 0, chunk = 0, slices = 1;
     int64_t n_heavy = 0, n_chunks = 0;
     int32_t* d_chunk = nullptr;        // [3 * n_chunks]: row, begin, end
     int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
@@ -48,6 +48,8 @@ struct SpmmArgs {
     float diag, s_agg, s_res;
     int64_t n_rows, n_diag;
     int units;            // 16-byte units per row of X
+    int n_slices;         // the row is cut into n_slices equal feature slices, one per workgroup
+    int slice_units;      // units per slice
     int F;
     int threshold;
     const int32_t* chunk;       // plan lists
@@ -88,7 +90,7 @@ __device__ __forceinline__ float bcast_f(float v, int k) {
 // Sum of val[k] * X[ind[k], :] over k in [begin, end) for this lane's units.
 // Afterwards every team of the wavefront holds the full sum.
 template <int G, int UPT, int U, bool XBF>
-__device__ __forceinline__ void accumulate(const SpmmArgs& a, int begin, int end,
+__device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int begin, int end,
                                            float (&acc)[UPT][Unit<XBF>::E]) {
     constexpr int S = kWave / G;
     constexpr int E = Unit<XBF>::E;
@@ -98,14 +100,14 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int begin, int end
     for (int p = 0; p < UPT; ++p)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
-    const char* xb = a.X + (int64_t)tl * 16;
+    const char* xb = a.X + (int64_t)(unit0 + tl) * 16;
     for (int t = begin; t < end; t += kWave) {
         const int cnt = min(kWave, end - t);
         int my_c = 0;
         float my_w = 0.f;
         if (lane < cnt) {
-            my_c = a.ind[t + lane];
-            my_w = a.val ? a.val[t + lane] : 1.f;
+            my_c = __builtin_nontemporal_load(a.ind + t + lane);     // streamed once: keep it out of the way of X in L2
+            my_w = a.val ? __builtin_nontemporal_load(a.val + t + lane) : 1.f;
         }
         for (int j = 0; j < cnt; j += S * U) {
             u32x4 v[U][UPT];
@@ -120,7 +122,7 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int begin, int end
 #pragma unroll
                 for (int p = 0; p < UPT; ++p) {
                     v[u][p] = u32x4{0u, 0u, 0u, 0u};
-                    if (ok && tl + p * G < a.units)
+                    if (ok && tl + p * G < a.slice_units)
                         v[u][p] = *reinterpret_cast<const u32x4*>(xb + (int64_t)c * a.x_stride + (int64_t)p * G * 16);
                 }
             }
@@ -169,53 +171,59 @@ __device__ __forceinline__ void epilogue(const SpmmArgs& a, int64_t row, int uni
         u32x4 o;
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = pack_bf16(z[2 * i], z[2 * i + 1]);
-        *reinterpret_cast<u32x4*>(zp + (int64_t)unit * 16) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(zp + (int64_t)unit * 16));
     } else {
 #pragma unroll
         for (int q = 0; q < E / 4; ++q) {
             f32x4 o = {z[4 * q], z[4 * q + 1], z[4 * q + 2], z[4 * q + 3]};
-            *reinterpret_cast<f32x4*>(zp + ((int64_t)unit * E + 4 * q) * 4) = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(zp + ((int64_t)unit * E + 4 * q) * 4));
         }
     }
 }
 
+// One launch covers both kinds of work: the first ceil(n_chunks/4) workgroups
+// take one chunk of a heavy row per wavefront (partial sums to the workspace,
+// scheduled first because they are the longest items), the remaining ones take
+// one light row per wavefront and finish it (epilogue and store).
 template <int G, int UPT, int U, bool XBF, bool ZBF>
-__global__ __launch_bounds__(256) void spmm_light_kernel(SpmmArgs a) {
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+__global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
+    constexpr int E = Unit<XBF>::E;
+    const int lane = threadIdx.x & 63;
+    // consecutive workgroup ids go to different XCDs (round robin), so with 8
+    // slices every XCD keeps to one feature slice and its L2 holds 8x more rows
+    const int slice = blockIdx.x % a.n_slices;
+    const int64_t blk = blockIdx.x / a.n_slices;
+    const int unit0 = slice * a.slice_units;
+    const int64_t chunk_blocks = (a.n_chunks + 3) >> 2;
+    float acc[UPT][E];
+    if (blk < chunk_blocks) {
+        const int64_t c = blk * 4 + (threadIdx.x >> 6);
+        if (c >= a.n_chunks) return;
+        accumulate<G, UPT, U, XBF>(a, unit0, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
+        if (lane < G) {
+#pragma unroll
+            for (int p = 0; p < UPT; ++p) {
+                const int unit = lane + p * G;
+                if (unit < a.slice_units) {
+                    float* dst = a.partial + c * (int64_t)a.F + (int64_t)(unit0 + unit) * E;
+#pragma unroll
+                    for (int q = 0; q < E / 4; ++q)
+                        *reinterpret_cast<f32x4*>(dst + 4 * q) =
+                            f32x4{acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2], acc[p][4 * q + 3]};
+                }
+            }
+        }
+        return;
+    }
+    const int64_t row = (blk - chunk_blocks) * 4 + (threadIdx.x >> 6);
     if (row >= a.n_rows) return;
     const int begin = a.ptr[row], end = a.ptr[row + 1];
-    if (end - begin > a.threshold) return;       // heavy rows go through the chunk kernels
-    float acc[UPT][Unit<XBF>::E];
-    accumulate<G, UPT, U, XBF>(a, begin, end, acc);
-    const int lane = threadIdx.x & 63;
+    if (end - begin > a.threshold) return;       // heavy row: done by the chunk workgroups
+    accumulate<G, UPT, U, XBF>(a, unit0, begin, end, acc);
     if (lane < G) {
 #pragma unroll
         for (int p = 0; p < UPT; ++p)
-            if (lane + p * G < a.units) epilogue<XBF, ZBF>(a, row, lane + p * G, acc[p]);
-    }
-}
-
-template <int G, int UPT, int U, bool XBF>
-__global__ __launch_bounds__(256) void spmm_chunk_kernel(SpmmArgs a) {
-    const int64_t c = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (c >= a.n_chunks) return;
-    const int begin = a.chunk[3 * c + 1], end = a.chunk[3 * c + 2];
-    constexpr int E = Unit<XBF>::E;
-    float acc[UPT][E];
-    accumulate<G, UPT, U, XBF>(a, begin, end, acc);
-    const int lane = threadIdx.x & 63;
-    if (lane < G) {
-#pragma unroll
-        for (int p = 0; p < UPT; ++p) {
-            const int unit = lane + p * G;
-            if (unit < a.units) {
-                float* dst = a.partial + c * (int64_t)a.F + (int64_t)unit * E;
-#pragma unroll
-                for (int q = 0; q < E / 4; ++q)
-                    *reinterpret_cast<f32x4*>(dst + 4 * q) =
-                        f32x4{acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2], acc[p][4 * q + 3]};
-            }
-        }
+            if (lane + p * G < a.slice_units) epilogue<XBF, ZBF>(a, row, unit0 + lane + p * G, acc[p]);
     }
 }
 
@@ -268,21 +276,19 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
 
 template <int G, int UPT, int U, bool XBF, bool ZBF>
 gas_status launch_vector(const SpmmArgs& a, hipStream_t s) {
-    const unsigned blocks = (unsigned)((a.n_rows + 3) / 4);
-    hipLaunchKernelGGL((spmm_light_kernel<G, UPT, U, XBF, ZBF>), dim3(blocks), dim3(256), 0, s, a);
-    if (a.n_chunks > 0) {
-        hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF>), dim3((unsigned)((a.n_chunks + 3) / 4)), dim3(256), 0,
-                           s, a);
+    const int64_t blocks = ((a.n_rows + 3) / 4 + (a.n_chunks + 3) / 4) * a.n_slices;
+    if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
+    hipLaunchKernelGGL((spmm_kernel<G, UPT, U, XBF, ZBF>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (a.n_heavy > 0)
         hipLaunchKernelGGL((spmm_heavy_reduce_kernel<XBF, ZBF>), dim3((unsigned)((a.n_heavy + 3) / 4)), dim3(256),
                            0, s, a);
-    }
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
 
 template <bool XBF, bool ZBF>
 gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
-    const int u = a.units;
+    const int u = a.slice_units;
     if (u <= 8) return launch_vector<8, 1, 2, XBF, ZBF>(a, s);
     if (u <= 16) return launch_vector<16, 1, 4, XBF, ZBF>(a, s);
     if (u <= 32) return launch_vector<32, 1, 4, XBF, ZBF>(a, s);
@@ -314,6 +320,9 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     a.diag = diag; a.s_agg = s_agg; a.s_res = s_res;
     a.n_rows = plan->n_rows; a.n_diag = n_diag;
     a.units = (F * xb) / 16; a.F = F;
+    a.n_slices = plan->slices;
+    while (a.n_slices > 1 && (a.units % a.n_slices != 0)) a.n_slices >>= 1;
+    a.slice_units = a.units / (a.n_slices > 0 ? a.n_slices : 1);
     a.threshold = plan->threshold;
     a.chunk = plan->d_chunk; a.n_chunks = plan->n_chunks;
     a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
@@ -359,6 +368,8 @@ gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int3
     p->n_rows = n_rows; p->nnz = nnz; p->max_F = max_F;
     p->threshold = env_int("GAS_SPMM_HEAVY", 256, 1, 1 << 24);
     p->chunk = env_int("GAS_SPMM_CHUNK", 256, 32, 1 << 24);
+    p->slices = env_int("GAS_SPMM_SLICES", 1, 1, 8);
+    if (p->slices & (p->slices - 1)) p->slices = 1;
     (void)hipGetDevice(&p->device);
     std::vector<int32_t> h_ptr((size_t)n_rows + 1, 0);
     if (n_rows > 0) {

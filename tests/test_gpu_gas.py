@@ -86,3 +86,16 @@ def test_config3_deep_gcnii_scaled_and_full():
     _run_both(wl, [0, 3], "normal")
     wl = configs.build_workload(configs.config(3))
     _run_both(wl, [0], "normal", check_layers=False)
+
+
+def test_config4_huge_gin_bf16_scaled():
+    wl = configs.build_workload(configs.config(4, 0.001))
+    assert wl.cfg.dtype == torch.bfloat16 and wl.cfg.op == "gin"
+    _run_both(wl, [0, 5], "normal")
+
+
+def test_gin_fp32_small():
+    cfg = configs.config(4, 0.0004)
+    cfg.dtype = torch.float32
+    wl = configs.build_workload(cfg)
+    _run_both(wl, [1], "normal")

@@ -208,3 +208,42 @@ def test_linear_strided_rows(gas):
     gas.gas_linear(dev(zbuf)[:, :256], dev(w), ybuf[:700])
     want = oops.linear(to_np(zbuf)[:, :256], to_np(w))
     assert max_rel_err(to_np(ybuf[:700]), want) <= 1e-5 and torch.isnan(ybuf[700:]).all()
+
+
+@pytest.mark.parametrize("M,K,N", [(1000, 256, 256), (4097, 128, 256), (300, 64, 64), (129, 256, 128), (257, 72, 200),
+                                    (100, 15, 20), (64, 8, 8)])
+def test_linear_bf16_parity(gas, M, K, N):
+    z = rng.normal_matrix(5, 340, M, K, dtype=torch.bfloat16)
+    w = rng.glorot_uniform(5, 341, K, N, dtype=torch.bfloat16)
+    b = rng.normal(5, 342, 0, N, dtype=torch.bfloat16)
+    for kw in (dict(), dict(bias=b, relu=True)):
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        gas.gas_linear(dev(z), dev(w), y, bias=None if "bias" not in kw else dev(b), relu=kw.get("relu", False))
+        want = oops.linear(to_np(z), to_np(w), bias=None if "bias" not in kw else to_np(b), relu=kw.get("relu", False))
+        assert max_rel_err(to_np(y), want) <= 2e-2, (M, K, N, kw)
+    if K == N:
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        gas.gas_linear(dev(z), dev(w), y, c_identity=0.6, c_weight=0.4, relu=True)
+        want = oops.linear(to_np(z), to_np(w), c_identity=0.6, c_weight=0.4, relu=True)
+        assert max_rel_err(to_np(y), want) <= 2e-2
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,K,H,N", [(1000, 256, 256, 256), (4099, 128, 256, 256), (77, 64, 96, 40), (130, 24, 256, 264),
+                                      (50, 10, 17, 6)])
+def test_mlp2_parity(gas, dtype, M, K, H, N):
+    z = rng.normal_matrix(6, 350, M, K, dtype=dtype)
+    w1 = rng.glorot_uniform(6, 351, K, H, dtype=dtype)
+    w2 = rng.glorot_uniform(6, 352, H, N, dtype=dtype)
+    b1 = rng.normal(6, 353, 0, H, dtype=dtype)
+    b2 = rng.normal(6, 354, 0, N, dtype=dtype)
+    for bias, relu_out in ((False, False), (True, True)):
+        y = torch.full((M, N), float("nan"), dtype=dtype, device="cuda")
+        gas.gas_mlp2(dev(z), dev(w1), dev(w2), y, b1=dev(b1) if bias else None, b2=dev(b2) if bias else None,
+                     relu_out=relu_out)
+        want = oops.mlp2(to_np(z), to_np(w1), to_np(w2), b1=to_np(b1) if bias else None,
+                         b2=to_np(b2) if bias else None, relu_out=relu_out)
+        assert max_rel_err(to_np(y), want) <= TOL[dtype], (dtype, M, K, H, N, bias)
+    with pytest.raises(gas.GasError):
+        gas.gas_mlp2(dev(z), dev(rng.glorot_uniform(6, 355, K, 300, dtype=dtype)),
+                     dev(rng.glorot_uniform(6, 356, 300, N, dtype=dtype)), y)      # hidden width above the limit

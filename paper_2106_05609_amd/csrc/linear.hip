@@ -484,6 +484,221 @@ __global__ __launch_bounds__(256) void mlp2_bf16_kernel(MlpArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------- weights-stationary bf16 kernels
+// For feature widths up to 256 the whole weight matrix fits in the registers
+// of one workgroup: wavefront w of 8 keeps the MFMA B-fragments of columns
+// [32w, 32w+32) for every k (K/16 fragments of 8 bf16 per lane), loaded once.
+// The workgroup is persistent (one per compute unit) and streams 32-row tiles
+// of Z through LDS, so after start-up the only global traffic is Z in and Y
+// out: the transform runs at the HBM rate, not at the rate weights can be
+// re-staged.  With KT2 > 0 the same workgroup also keeps W2 and chains the
+// second product of the GIN MLP through an LDS-resident hidden tile.
+struct WsArgs {
+    const uint16_t* Z;  int64_t ldz;
+    const uint16_t* W1; const uint16_t* b1;
+    const uint16_t* W2; const uint16_t* b2;
+    uint16_t* Y;        int64_t ldy;
+    int64_t M, n_tiles;
+    int K, H, N;        // single product: H == N is the output width and W2 is unused
+    float c_id, c_w;
+    int relu1, relu_out;
+};
+
+constexpr int kWsRows = 64;
+
+template <int KT>
+__device__ __forceinline__ void load_w_frags(const uint16_t* W, int K, int ncols, int col, int lh, bf16x8 (&f)[KT]) {
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = 16 * kk + 8 * lh + e;
+            uint32_t x = 0;
+            if (k < K && col < ncols) x = W[(int64_t)k * ncols + col];
+            v[e >> 1] |= x << (16 * (e & 1));
+        }
+        f[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+// The products are evaluated transposed, D' = W^T Z^T: the weight fragment is
+// the MFMA A operand and the Z fragment the B operand (both hold 8 consecutive
+// k of one row/column, so the register contents are what they would be the
+// other way round).  Then a lane holds, for ONE row m of the tile, 4 groups of
+// 4 consecutive output columns, which go to the [m][n] LDS tiles as 8-byte
+// stores after a packed hardware fp32->bf16 conversion.
+template <int KT1, int KT2>
+__global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
+    constexpr bool TWO = KT2 > 0;
+    constexpr int LDA = 16 * KT1 + 8;                 // bf16 elements per LDS row of the Z tile
+    constexpr int LDH = 16 * (TWO ? KT2 : 1) + 8;     // ... of the hidden tile
+    constexpr int LDY = 256 + 8;                      // ... of the output staging tile
+    constexpr int VPR = 2 * KT1;                      // 16-byte vectors per Z-tile row
+    constexpr int NVA = (kWsRows * VPR + 511) / 512;  // vectors per thread per tile
+    constexpr int MT = kWsRows / 32;                  // 32-row blocks per tile
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);                       // [2][64][LDA]
+    uint16_t* Hs = As + 2 * kWsRows * LDA;                                  // [64][LDH]
+    uint16_t* Ys = Hs + (TWO ? kWsRows * LDH : 0);                          // [64][LDY]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+
+    bf16x8 w1f[KT1];
+    bf16x8 w2f[TWO ? KT2 : 1];
+    load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f);
+    if constexpr (TWO) load_w_frags<KT2>(a.W2, a.H, a.N, 32 * wave + li, lh, w2f);
+    // output columns of this lane: n(q, e) = 32*wave + 8*q + 4*lh + e, q, e in 0..3
+    const int nbase = 32 * wave + 4 * lh;
+    float bias1[16], bias2[TWO ? 16 : 1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int n = nbase + 8 * (r / 4) + (r % 4);
+        bias1[r] = (a.b1 && n < a.H) ? bf16_val(a.b1, n) : 0.f;
+        if constexpr (TWO) bias2[r] = (a.b2 && n < a.N) ? bf16_val(a.b2, n) : 0.f;
+    }
+
+    u32x4 ra[NVA];
+    auto fetch = [&](int64_t tile) {
+#pragma unroll
+        for (int i = 0; i < NVA; ++i) {
+            const int idx = tid + 512 * i;
+            const int row = idx / VPR, k = 8 * (idx % VPR);
+            const int64_t m = tile * kWsRows + row;
+            ra[i] = u32x4{0u, 0u, 0u, 0u};
+            if (idx < kWsRows * VPR && m < a.M && k < a.K)
+                ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.Z + m * a.ldz + k));
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NVA; ++i) {
+            const int idx = tid + 512 * i;
+            if (idx < kWsRows * VPR)
+                *reinterpret_cast<u32x4*>(As + (buf * kWsRows + idx / VPR) * LDA + 8 * (idx % VPR)) = ra[i];
+        }
+    };
+
+    int64_t tile = blockIdx.x;
+    if (tile < a.n_tiles) {
+        fetch(tile);
+        stage(0);
+    }
+    int buf = 0;
+    for (; tile < a.n_tiles; tile += gridDim.x, buf ^= 1) {
+        const int64_t next = tile + gridDim.x;
+        if (next < a.n_tiles) fetch(next);            // in flight during this tile's MFMAs
+        __syncthreads();                               // (1) Z tile `buf` staged; previous tile fully consumed
+        const uint16_t* At = As + buf * kWsRows * LDA;
+        f32x16 acc[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        if (32 * wave < a.H) {
+#pragma unroll
+            for (int kk = 0; kk < KT1; ++kk)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    const bf16x8 fz = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const u32x4*>(At + (32 * t + li) * LDA + 16 * kk + 8 * lh));
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1f[kk], fz, acc[t], 0, 0, 0);
+                }
+        }
+        if constexpr (TWO) {
+            // hidden tile: relu(Z W1 + b1) in bf16; columns at and beyond H are zero
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = (nbase + 8 * q + e < a.H) ? fmaxf(acc[t][4 * q + e] + bias1[4 * q + e], 0.f) : 0.f;
+                    if (nbase + 8 * q < 16 * KT2)
+                        *reinterpret_cast<u32x2*>(Hs + (32 * t + li) * LDH + nbase + 8 * q) =
+                            u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                }
+            __syncthreads();                           // (2) hidden tile complete
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+            if (32 * wave < a.N) {
+#pragma unroll
+                for (int kk = 0; kk < KT2; ++kk)
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const bf16x8 fh = __builtin_bit_cast(
+                            bf16x8, *reinterpret_cast<const u32x4*>(Hs + (32 * t + li) * LDH + 16 * kk + 8 * lh));
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2f[kk], fh, acc[t], 0, 0, 0);
+                    }
+            }
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[t][4 * q + e] + bias2[4 * q + e];
+                        if (a.relu_out) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
+                        u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                }
+        } else {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = a.c_w * acc[t][4 * q + e] + bias1[4 * q + e];
+                    if (a.c_id != 0.f && nbase + 8 * q < a.N) {      // identity term straight from the staged Z tile (K == N)
+                        const u32x2 z = *reinterpret_cast<const u32x2*>(At + (32 * t + li) * LDA + nbase + 8 * q);
+                        v[0] += a.c_id * bf16_lo(z[0]); v[1] += a.c_id * bf16_hi(z[0]);
+                        v[2] += a.c_id * bf16_lo(z[1]); v[3] += a.c_id * bf16_hi(z[1]);
+                    }
+                    if (a.relu1) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
+                        u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                }
+        }
+        if (next < a.n_tiles) stage(buf ^ 1);          // the other buffer: nobody reads it before the next (1)
+        __syncthreads();                               // (3) output tile staged
+        {
+            const int vpr = a.N >> 3;                  // 16-byte vectors per output row
+            for (int idx = tid; idx < kWsRows * vpr; idx += 512) {
+                const int row = idx / vpr, v = idx % vpr;
+                const int64_t m = tile * kWsRows + row;
+                if (m < a.M)
+                    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v),
+                                                reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
+            }
+        }
+    }
+}
+
+template <int KT1, int KT2>
+gas_status launch_ws(const WsArgs& a, hipStream_t s) {
+    constexpr int smem = 2 * (2 * kWsRows * (16 * KT1 + 8) + (KT2 > 0 ? kWsRows * (16 * KT2 + 8) : 0) + kWsRows * (256 + 8));
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_bf16_kernel<KT1, KT2>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    GAS_CHECK_HIP(attr);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    }
+    const int64_t blocks = a.n_tiles < cus ? a.n_tiles : cus;
+    hipLaunchKernelGGL((ws_bf16_kernel<KT1, KT2>), dim3((unsigned)blocks), dim3(512), smem, s, a);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
 // ====================================================================== element-wise paths
 // For bf16 operands that are not 16-byte aligned (odd widths, odd strides):
 // one thread per output element, fp32 accumulation.
@@ -595,6 +810,18 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
         GAS_CHECK_HIP(hipGetLastError());
         return GAS_OK;
     }
+    if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+        WsArgs w{};
+        w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
+        w.W1 = static_cast<const uint16_t*>(W); w.b1 = static_cast<const uint16_t*>(bias);
+        w.Y = static_cast<uint16_t*>(Y); w.ldy = ldy;
+        w.M = n_rows; w.n_tiles = (n_rows + kWsRows - 1) / kWsRows;
+        w.K = F_in; w.H = F_out; w.N = F_out;
+        w.c_id = c_identity; w.c_w = c_weight; w.relu1 = relu; w.relu_out = 0;
+        if (F_in <= 64) return launch_ws<4, 0>(w, s);
+        if (F_in <= 128) return launch_ws<8, 0>(w, s);
+        return launch_ws<16, 0>(w, s);
+    }
     if (F_out <= 64) return launch_bf16<64>(a, s);
     if (F_out <= 128) return launch_bf16<128>(a, s);
     return launch_bf16<256>(a, s);
@@ -635,6 +862,17 @@ gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, co
         dim3 grid((unsigned)((n_rows + kMlpRowsF32 - 1) / kMlpRowsF32), (unsigned)gn);
         if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
         else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
+    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+        WsArgs w{};
+        w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
+        w.W1 = static_cast<const uint16_t*>(W1); w.b1 = static_cast<const uint16_t*>(b1);
+        w.W2 = static_cast<const uint16_t*>(W2); w.b2 = static_cast<const uint16_t*>(b2);
+        w.Y = static_cast<uint16_t*>(Y); w.ldy = ldy;
+        w.M = n_rows; w.n_tiles = (n_rows + kWsRows - 1) / kWsRows;
+        w.K = F_in; w.H = F_hid; w.N = F_out;
+        w.c_id = 0.f; w.c_w = 1.f; w.relu1 = 1; w.relu_out = relu_out;
+        if (F_in <= 128) return launch_ws<8, 16>(w, s);
+        return launch_ws<16, 16>(w, s);
     } else if (vec) {
         constexpr int smem = 2 * (kMlpRowsBF16 * (kHidMax + 8 + kBKh + 8) + 256 * (kBKh + 8));
         static const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp2_bf16_kernel),

@@ -211,7 +211,8 @@ def test_linear_strided_rows(gas):
 
 
 @pytest.mark.parametrize("M,K,N", [(1000, 256, 256), (4097, 128, 256), (300, 64, 64), (129, 256, 128), (257, 72, 200),
-                                    (100, 15, 20), (64, 8, 8)])
+                                    (100, 15, 20), (64, 8, 8), (5001, 256, 256), (4500, 64, 200), (4100, 128, 128),
+                                    (9000, 40, 24)])
 def test_linear_bf16_parity(gas, M, K, N):
     z = rng.normal_matrix(5, 340, M, K, dtype=torch.bfloat16)
     w = rng.glorot_uniform(5, 341, K, N, dtype=torch.bfloat16)
@@ -230,7 +231,7 @@ def test_linear_bf16_parity(gas, M, K, N):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("M,K,H,N", [(1000, 256, 256, 256), (4099, 128, 256, 256), (77, 64, 96, 40), (130, 24, 256, 264),
-                                      (50, 10, 17, 6)])
+                                      (50, 10, 17, 6), (6001, 256, 256, 256), (5000, 200, 136, 72)])
 def test_mlp2_parity(gas, dtype, M, K, H, N):
     z = rng.normal_matrix(6, 350, M, K, dtype=dtype)
     w1 = rng.glorot_uniform(6, 351, K, H, dtype=dtype)

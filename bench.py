@@ -74,56 +74,12 @@ def main():
     log(f"[bench] {cfg.name}: N={g.n} nnz={g.nnz} | batch nb={nb} nh={nh} nnz_b={nnz} nnz_bt={nnz_t} "
         f"max_row={int((sg.rowptr[1:] - sg.rowptr[:-1]).max())} | generated in {time.time() - t0:.1f}s")
 
-    F = cfg.widths[-2]                            # hidden width: the middle layer is F -> F
-    dt = cfg.dtype
-    s = 4 if dt == torch.float32 else 2
-    gin = cfg.op == "gin"
-    bg = executor.BatchGraph(nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row, max_F=F, normalise=not gin)
-    hist_in = rng.normal_matrix(cfg.seed, 200, cfg.n, F, dev, dt)
-    hist_out = torch.zeros((cfg.n, F), dtype=dt, device=dev)
-    x = rng.normal_matrix(cfg.seed, 210, nv, F, dev, dt)          # rows 0..nb-1: fresh in-batch embeddings
-    z = torch.empty((nb, F), dtype=dt, device=dev)
-    x_next = torch.empty((nv, F), dtype=dt, device=dev)
-    gz = rng.normal_matrix(cfg.seed, 211, nb, F, dev, dt)          # upstream gradient for the backward aggregation
-    gx = torch.empty((nb, F), dtype=dt, device=dev)
-    if gin:
-        w1 = rng.glorot_uniform(cfg.seed, 102, F, cfg.gin_hidden, dev, dt)
-        w2 = rng.glorot_uniform(cfg.seed, 103, cfg.gin_hidden, F, dev, dt)
-    else:
-        w = rng.glorot_uniform(cfg.seed, 101, F, F, dev, dt)
-    halo, batch_ids = bg.n_id[nb:], bg.n_id[:nb]
-    alpha = cfg.alpha
-    h0 = rng.normal_matrix(cfg.seed, 212, nb, F, dev, dt) if cfg.op == "gcnii" else None
-
-    names = ["pull", "spmm", "linear", "push", "spmm_t"]
+    from paper_2106_05609_amd.layer_step import LayerStep, NAMES as names
+    ls = LayerStep(cfg, g, sg, rng, dev)
+    F, dt, gin = ls.F, ls.dt, ls.gin
 
     def step(ev=None):
-        def mark(i):
-            if ev is not None:
-                ev[i].record()
-        mark(0)
-        gas.gas_pull(hist_in, halo, x[nb:])
-        mark(1)
-        if gin:
-            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + cfg.gin_eps)
-        elif cfg.op == "gcnii":
-            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - alpha, r=h0, s_res=alpha)
-        else:
-            gas.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
-        mark(2)
-        if gin:
-            gas.gas_mlp2(z, w1, w2, x_next[:nb], relu_out=True)
-        elif cfg.op == "gcnii":
-            b = executor.gcnii_beta(2)
-            gas.gas_linear(z, w, x_next[:nb], c_identity=1.0 - b, c_weight=b, relu=True)
-        else:
-            gas.gas_linear(z, w, x_next[:nb], relu=True)
-        mark(3)
-        gas.gas_push(x_next[:nb], batch_ids, hist_out)
-        mark(4)
-        if not args.skip_spmm_t:
-            gas.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, gz, gx, diag=(1.0 + cfg.gin_eps) if gin else 0.0)
-        mark(5)
+        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t)
 
     if args.calibrate_copy:
         src = torch.ones((1 << 20, 256), dtype=torch.float32, device=dev)      # exactly 1 GiB
@@ -146,15 +102,8 @@ def main():
     per = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
 
     # algorithmic bytes (what the method must move at least once), per launch
-    val_bytes = 0 if gin else 4
-    by = {
-        "pull": nh * (2 * F * s + 4),
-        "spmm": nnz * (4 + val_bytes) + (nb + 1) * 4 + nv * F * s + nb * F * s,
-        "linear": nb * 2 * F * s + F * F * s * (2 if gin else 1),
-        "push": nb * (2 * F * s + 4),
-        "spmm_t": nnz_t * (4 + val_bytes) + (nb + 1) * 4 + nb * F * s + nb * F * s,
-    }
-    spmm_hi = nnz * (4 + val_bytes) + (nb + 1) * 4 + nnz * F * s + nb * F * s     # no reuse of gathered rows
+    by = ls.algorithmic_bytes()
+    spmm_hi = by.pop("spmm_no_reuse")             # no reuse of gathered rows at all
     edges = nnz + (0 if args.skip_spmm_t else nnz_t)
     value = edges / (ms_step * 1e-3)
     kern = {}
@@ -189,8 +138,8 @@ def main():
                      "traffic": load_traffic(args.config, args.scale)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, g, sg, hist_in, x, w1 if gin else w, w2 if gin else None, gz, F,
-                                           args.cpu_sample_rows)
+        out["cpu_baseline"] = cpu_baseline(cfg, g, sg, ls.hist_in, ls.x, ls.w1 if gin else ls.w,
+                                           ls.w2 if gin else None, ls.gz, F, args.cpu_sample_rows)
     print(json.dumps(out), flush=True)
 
 

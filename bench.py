@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--skip-spmm-t", action="store_true",
                    help="profiling aid: leave the backward aggregation out, so that the per-kernel averages of a "
                         "trace are those of the forward aggregation alone (the reported value is then not the metric)")
+    p.add_argument("--fused", action="store_true",
+                   help="aggregate with gas_spmm_hist (halo rows read from the history table in place, no pull launch)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also launch three plain 1 GiB contiguous copies (gas_pull without an index) before the "
                         "timed region: a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by")
@@ -79,7 +81,7 @@ def main():
     F, dt, gin = ls.F, ls.dt, ls.gin
 
     def step(ev=None):
-        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t)
+        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t, fused=args.fused)
 
     if args.calibrate_copy:
         src = torch.ones((1 << 20, 256), dtype=torch.float32, device=dev)      # exactly 1 GiB
@@ -128,7 +130,8 @@ def main():
         "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if dt == torch.float32 else "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch"
+                               + (", halo rows read in place by the aggregation (no pull launch)" if args.fused else ""),
                    "N": g.n, "nnz": g.nnz, "nb": nb, "nh": nh, "nnz_b": nnz, "nnz_bt": nnz_t, "F": F,
                    "scale": args.scale},
         "hbm_pull_spmm_push": {"GBps": round(hbm3, 1), "pct_of_peak": round(100 * hbm3 / HBM_PEAK_GBS, 2)},

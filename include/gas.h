@@ -134,6 +134,33 @@ GAS_API gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const i
                     void* Z, int64_t ldz, gas_dtype dt_z, void* stream);
 
 /*
+ * Aggregation with the historical embeddings read in place (Eq. 2, line 3:
+ * in-batch neighbours contribute their fresh embeddings, out-of-batch
+ * neighbours their stored ones).  Same sum, same order and bit-identical
+ * result as gas_pull of the halo rows followed by gas_spmm, without writing
+ * and re-reading the halo rows of the mini-batch tensor.
+ * src int32[nnz] replaces col: src[k] >= 0 is a row of X (an in-batch node,
+ * X is [n_rows, F]); src[k] < 0 names row -1-src[k] of the history table
+ * hist [n_hist_rows, F] (same dtype as X).  gas_fuse_sources builds src.
+ * diag, s_agg, R, s_res, Z, plan as in gas_spmm.
+ */
+GAS_API gas_status gas_spmm_hist(const gas_plan* plan, const int32_t* rowptr, const int32_t* src,
+                         const float* val, float diag,
+                         const void* X, int64_t ldx,
+                         const void* hist, int64_t n_hist_rows, int64_t ld_hist, gas_dtype dt_x, int32_t F,
+                         float s_agg, const void* R, int64_t ldr, float s_res,
+                         void* Z, int64_t ldz, gas_dtype dt_z, void* stream);
+
+/*
+ * Source indices for gas_spmm_hist from the local column ids of a batch
+ * subgraph: src[k] = col[k] if col[k] < nb (in-batch), else -1 - n_id[col[k]]
+ * (global id of the halo node, i.e. its row in every history table).  Done
+ * once per batch; the result serves every layer.  src is caller-owned, int32[nnz].
+ */
+GAS_API gas_status gas_fuse_sources(const int32_t* col, int64_t nnz, int64_t nb, const int32_t* n_id,
+                            int32_t* src, void* stream);
+
+/*
  * Backward aggregation: the adjoint of gas_spmm's sum, computed as a
  * row-parallel product over the CSC copy of the same pattern (no atomics):
  *     GX[u, :] = sum_{k in column u} val[k] * G[row[k], :] + [u < n_diag] diag * G[u, :]

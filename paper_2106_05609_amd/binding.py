@@ -13,7 +13,7 @@ F32, BF16 = 0, 1
 OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
-           "gas_plan_destroy", "gas_spmm", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices"]
+           "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices"]
 
 _lib = None
 
@@ -147,6 +147,27 @@ def gas_spmm(plan, rowptr, col, val, x, z, diag=0.0, s_agg=1.0, r=None, s_res=0.
     _check(lib().gas_spmm(plan.handle, _ptr(rowptr, torch.int32), _ptr(col, torch.int32), _ptr(val, torch.float32),
                           C.c_float(diag), xp, ldx, C.c_int(_dt(x)), C.c_int32(x.shape[1]), C.c_float(s_agg), rp, ldr,
                           C.c_float(s_res), zp, ldz, C.c_int(_dt(z)), _stream()))
+
+
+def gas_fuse_sources(col, nb, n_id, src):
+    _check(lib().gas_fuse_sources(_ptr(col, torch.int32), C.c_int64(col.numel()), C.c_int64(nb), _ptr(n_id, torch.int32),
+                                  _ptr(src, torch.int32), _stream()))
+
+
+def gas_spmm_hist(plan, rowptr, src, val, x, hist, z, diag=0.0, s_agg=1.0, r=None, s_res=0.0):
+    """x: the in-batch rows [n_rows, F]; hist: the history table the halo rows are read from."""
+    xp, ldx = _mat(x)
+    hp, ldh = _mat(hist)
+    zp, ldz = _mat(z)
+    rp, ldr = (C.c_void_p(0), C.c_int64(0)) if r is None else _mat(r)
+    if hist.dtype != x.dtype or hist.shape[1] != x.shape[1] or (r is not None and r.dtype != x.dtype):
+        raise TypeError("gas_spmm_hist: hist and R must match X")
+    if z.shape[1] != x.shape[1] or z.shape[0] < plan.n_rows or x.shape[0] < plan.n_rows:
+        raise ValueError("gas_spmm_hist: shapes do not match")
+    _check(lib().gas_spmm_hist(plan.handle, _ptr(rowptr, torch.int32), _ptr(src, torch.int32), _ptr(val, torch.float32),
+                               C.c_float(diag), xp, ldx, hp, C.c_int64(hist.shape[0]), ldh, C.c_int(_dt(x)),
+                               C.c_int32(x.shape[1]), C.c_float(s_agg), rp, ldr, C.c_float(s_res), zp, ldz,
+                               C.c_int(_dt(z)), _stream()))
 
 
 def gas_spmm_t(plan, colptr, row, val, g, gx, diag=0.0):

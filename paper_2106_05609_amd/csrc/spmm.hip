@@ -41,6 +41,8 @@ struct SpmmArgs {
     const float* val;
     const char* X;
     int64_t x_stride;     // bytes
+    const char* H;        // history table for entries with a negative index (row -1-index), or null
+    int64_t h_stride;
     const char* R;
     int64_t r_stride;
     char* Z;
@@ -101,6 +103,7 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int beg
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
     const char* xb = a.X + (int64_t)(unit0 + tl) * 16;
+    const char* hb = a.H + (int64_t)(unit0 + tl) * 16;
     for (int t = begin; t < end; t += kWave) {
         const int cnt = min(kWave, end - t);
         int my_c = 0;
@@ -122,8 +125,10 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int beg
 #pragma unroll
                 for (int p = 0; p < UPT; ++p) {
                     v[u][p] = u32x4{0u, 0u, 0u, 0u};
+                    // index >= 0: row of the mini-batch tensor; index < 0: row -1-index of the history table
+                    const char* src = c >= 0 ? xb + (int64_t)c * a.x_stride : hb + (int64_t)(-1 - c) * a.h_stride;
                     if (ok && tl + p * G < a.slice_units)
-                        v[u][p] = *reinterpret_cast<const u32x4*>(xb + (int64_t)c * a.x_stride + (int64_t)p * G * 16);
+                        v[u][p] = *reinterpret_cast<const u32x4*>(src + (int64_t)p * G * 16);
                 }
             }
 #pragma unroll
@@ -265,7 +270,11 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
     };
     for (int f = threadIdx.x & 63; f < a.F; f += kWave) {
         float acc = 0.f;
-        for (int k = begin; k < end; ++k) acc = fmaf(a.val ? a.val[k] : 1.f, ld(a.X, a.x_stride, a.ind[k], f), acc);
+        for (int k = begin; k < end; ++k) {
+            const int c = a.ind[k];
+            const float x = c >= 0 ? ld(a.X, a.x_stride, c, f) : ld(a.H, a.h_stride, -1 - c, f);
+            acc = fmaf(a.val ? a.val[k] : 1.f, x, acc);
+        }
         float z = a.s_agg * acc;
         if (a.diag != 0.f && row < a.n_diag) z += a.diag * ld(a.X, a.x_stride, row, f);
         if (a.R) z += a.s_res * ld(a.R, a.r_stride, row, f);
@@ -299,7 +308,8 @@ gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
 }
 
 gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, const int32_t* ind, const float* val,
-                    float diag, int64_t n_diag, const void* X, int64_t ldx, gas_dtype dt_x, int32_t F, float s_agg,
+                    float diag, int64_t n_diag, const void* X, int64_t ldx, const void* H, int64_t ldh,
+                    gas_dtype dt_x, int32_t F, float s_agg,
                     const void* R, int64_t ldr, float s_res, void* Z, int64_t ldz, gas_dtype dt_z, hipStream_t s) {
     if (!valid_dtype(dt_x) || !valid_dtype(dt_z)) return fail(GAS_ERR_DTYPE, "%s: unknown dtype", who);
     if (dt_x == GAS_F32 && dt_z == GAS_BF16)
@@ -309,12 +319,13 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     GAS_REQUIRE(ptr && X && Z, "%s: null pointer", who);
     GAS_REQUIRE(plan->nnz == 0 || ind, "%s: null index array", who);
     GAS_REQUIRE(F > 0 && F <= plan->max_F, "%s: F=%d outside (0, plan max_F=%d]", who, F, plan->max_F);
-    GAS_REQUIRE(ldx >= F && ldz >= F && (!R || ldr >= F), "%s: row stride smaller than F", who);
+    GAS_REQUIRE(ldx >= F && ldz >= F && (!R || ldr >= F) && (!H || ldh >= F), "%s: row stride smaller than F", who);
     GAS_REQUIRE(Z != X && Z != R, "%s: output aliases an input", who);
     const int xb = elem_bytes(dt_x), zb = elem_bytes(dt_z);
     SpmmArgs a;
     a.ptr = ptr; a.ind = ind; a.val = val;
     a.X = static_cast<const char*>(X); a.x_stride = ldx * xb;
+    a.H = static_cast<const char*>(H); a.h_stride = ldh * xb;
     a.R = static_cast<const char*>(R); a.r_stride = ldr * xb;
     a.Z = static_cast<char*>(Z); a.z_stride = ldz * zb;
     a.diag = diag; a.s_agg = s_agg; a.s_res = s_res;
@@ -328,7 +339,8 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
     a.partial = plan->d_partial;
     const bool vec = (F * xb) % 16 == 0 && aligned16(X) && a.x_stride % 16 == 0 && aligned16(Z) &&
-                     a.z_stride % 16 == 0 && (!R || (aligned16(R) && a.r_stride % 16 == 0));
+                     a.z_stride % 16 == 0 && (!R || (aligned16(R) && a.r_stride % 16 == 0)) &&
+                     (!H || (aligned16(H) && a.h_stride % 16 == 0));
     const bool xbf = dt_x == GAS_BF16, zbf = dt_z == GAS_BF16;
     if (vec) {
         if (!xbf) return dispatch_units<false, false>(a, s);
@@ -340,6 +352,15 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     else hipLaunchKernelGGL((spmm_generic_kernel<true, false>), dim3(blocks), dim3(256), 0, s, a);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
+}
+
+__global__ __launch_bounds__(256) void fuse_sources_kernel(const int32_t* __restrict__ col, int64_t nnz, int64_t nb,
+                                                           const int32_t* __restrict__ n_id,
+                                                           int32_t* __restrict__ src) {
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= nnz) return;
+    const int32_t c = col[k];
+    src[k] = c < nb ? c : -1 - n_id[c];
 }
 
 int env_int(const char* name, int dflt, int lo, int hi) {
@@ -432,16 +453,39 @@ void gas_plan_destroy(gas_plan* p) {
 gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const int32_t* col, const float* val, float diag,
                     const void* X, int64_t ldx, gas_dtype dt_x, int32_t F, float s_agg, const void* R, int64_t ldr,
                     float s_res, void* Z, int64_t ldz, gas_dtype dt_z, void* stream) {
-    return run_spmm("gas_spmm", plan, rowptr, col, val, diag, plan ? plan->n_rows : 0, X, ldx, dt_x, F, s_agg, R, ldr,
-                    s_res, Z, ldz, dt_z, (hipStream_t)stream);
+    return run_spmm("gas_spmm", plan, rowptr, col, val, diag, plan ? plan->n_rows : 0, X, ldx, nullptr, 0, dt_x, F,
+                    s_agg, R, ldr, s_res, Z, ldz, dt_z, (hipStream_t)stream);
 }
 
 gas_status gas_spmm_t(const gas_plan* plan, const int32_t* colptr, const int32_t* row, const float* val, float diag,
                       int64_t n_diag, const void* G, int64_t ldg, gas_dtype dt_g, int32_t F, void* GX, int64_t ldgx,
                       gas_dtype dt_gx, void* stream) {
     GAS_REQUIRE(n_diag >= 0, "gas_spmm_t: n_diag=%lld", (long long)n_diag);
-    return run_spmm("gas_spmm_t", plan, colptr, row, val, diag, n_diag, G, ldg, dt_g, F, 1.f, nullptr, 0, 0.f, GX,
-                    ldgx, dt_gx, (hipStream_t)stream);
+    return run_spmm("gas_spmm_t", plan, colptr, row, val, diag, n_diag, G, ldg, nullptr, 0, dt_g, F, 1.f, nullptr, 0,
+                    0.f, GX, ldgx, dt_gx, (hipStream_t)stream);
+}
+
+gas_status gas_spmm_hist(const gas_plan* plan, const int32_t* rowptr, const int32_t* src, const float* val,
+                         float diag, const void* X, int64_t ldx, const void* hist, int64_t n_hist_rows,
+                         int64_t ld_hist, gas_dtype dt_x, int32_t F, float s_agg, const void* R, int64_t ldr,
+                         float s_res, void* Z, int64_t ldz, gas_dtype dt_z, void* stream) {
+    GAS_REQUIRE(hist && n_hist_rows > 0, "gas_spmm_hist: null or empty history table");
+    GAS_REQUIRE(Z != hist, "gas_spmm_hist: output aliases the history table");
+    return run_spmm("gas_spmm_hist", plan, rowptr, src, val, diag, plan ? plan->n_rows : 0, X, ldx, hist, ld_hist,
+                    dt_x, F, s_agg, R, ldr, s_res, Z, ldz, dt_z, (hipStream_t)stream);
+}
+
+gas_status gas_fuse_sources(const int32_t* col, int64_t nnz, int64_t nb, const int32_t* n_id, int32_t* src,
+                            void* stream) {
+    GAS_REQUIRE(nnz >= 0 && nb >= 0, "gas_fuse_sources: nnz=%lld nb=%lld", (long long)nnz, (long long)nb);
+    if (nnz == 0) return GAS_OK;
+    GAS_REQUIRE(col && n_id && src, "gas_fuse_sources: null pointer");
+    const int64_t blocks = (nnz + 255) / 256;
+    GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_fuse_sources: too many entries");
+    hipLaunchKernelGGL(fuse_sources_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, col, nnz, nb,
+                       n_id, src);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
 }
 
 }  // extern "C"

@@ -30,6 +30,7 @@ class BatchGraph:
         if normalise:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
             B.gas_gcn_norm(rowptr, col, n_id, deg, self.val)
+        self._src = None
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
         if colptr is not None:
             # backward over the in-batch columns only: histories are constants
@@ -37,6 +38,15 @@ class BatchGraph:
             if normalise:
                 self.val_t = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
                 B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t)
+
+
+    @property
+    def src(self):
+        """Source indices for gas_spmm_hist (built on first use, once per batch)."""
+        if self._src is None:
+            self._src = torch.empty_like(self.col)
+            B.gas_fuse_sources(self.col, self.nb, self.n_id, self._src)
+        return self._src
 
 
 class Model:
@@ -54,6 +64,37 @@ class Model:
 
 def gcnii_beta(layer: int) -> float:
     return math.log(0.5 / layer + 1.0)
+
+
+def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push=True):
+    """Same result as forward_batch, with the halo rows read in place by the
+    aggregation (gas_spmm_hist) instead of being pulled into the mini-batch
+    tensor: per layer  aggregate(X_batch, H[l-1]) -> transform -> push(H[l]).
+    Layer 1 reads its halo rows from the feature table the same way."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb = bg.nb
+    if model.op == "gcnii":
+        raise ValueError("GCNII's first layer aggregates the projected features, which no table holds: use forward_batch")
+    x = torch.empty((nb, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id[:nb], x)
+    L = model.n_layers
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        table = x_feat if l == 1 else histories[l - 2]
+        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+        if model.op == "gcn":
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z)
+            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+        else:
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, x, table, z, diag=1.0 + model.gin_eps)
+            w1, w2 = model.weights[l - 1]
+            B.gas_mlp2(z, w1, w2, y, relu_out=not last)
+        if not last and do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        x = y
+    return y
 
 
 def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True, keep_layers=False):

@@ -46,13 +46,25 @@ class LayerStep:
         self.beta = executor.gcnii_beta(2)
         self.diag = (1.0 + cfg.gin_eps) if self.gin else 0.0
 
-    def run(self, mark=None, skip_spmm_t=False):
+    def run(self, mark=None, skip_spmm_t=False, fused=False):
+        """fused: the aggregation reads the halo rows from the history table itself
+        (gas_spmm_hist); the pull launch disappears."""
         cfg, bg, nb = self.cfg, self.bg, self.nb
         mark = mark or (lambda i: None)
         mark(0)
-        B.gas_pull(self.hist_in, bg.n_id[nb:], self.x[nb:])
+        if not fused:
+            B.gas_pull(self.hist_in, bg.n_id[nb:], self.x[nb:])
         mark(1)
-        if self.gin:
+        if fused:
+            xb = self.x[:nb]
+            if self.gin:
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, xb, self.hist_in, self.z, diag=self.diag)
+            elif cfg.op == "gcnii":
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z, s_agg=1.0 - cfg.alpha,
+                                r=self.h0, s_res=cfg.alpha)
+            else:
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z)
+        elif self.gin:
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, self.x, self.z, diag=self.diag)
         elif cfg.op == "gcnii":
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, self.x, self.z, s_agg=1.0 - cfg.alpha, r=self.h0,
@@ -88,3 +100,8 @@ class LayerStep:
             "spmm_t": nnz_t * (4 + vb) + (nb + 1) * 4 + nb * F * s + nb * F * s,
             "spmm_no_reuse": nnz * (4 + vb) + (nb + 1) * 4 + nnz * F * s + nb * F * s,
         }
+
+    def fused_algorithmic_bytes(self):
+        """The fused aggregation reads the same rows once (in-batch from X, halo
+        from the history table) and writes Z; no halo copy is written or re-read."""
+        return self.algorithmic_bytes()["spmm"]

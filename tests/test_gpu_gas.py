@@ -99,3 +99,24 @@ def test_gin_fp32_small():
     cfg.dtype = torch.float32
     wl = configs.build_workload(cfg)
     _run_both(wl, [1], "normal")
+
+
+@pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (2, 0.02), (4, 0.001)])
+def test_fused_execution_matches_oracle(cfg_id, scale):
+    """Algorithm 1 with the halo rows read in place by the aggregation: same outputs and histories."""
+    from paper_2106_05609_amd import executor
+    wl = configs.build_workload(configs.config(cfg_id, scale))
+    cfg, g = wl.cfg, wl.graph
+    hs_cpu = [to_np(h).copy() for h in configs.make_histories(cfg, init="normal")]
+    hs_gpu = [h.to("cuda") for h in configs.make_histories(cfg, init="normal")]
+    om, gm = oracle_model(wl), _gpu_model(wl)
+    x_dev, deg_dev = wl.x.to("cuda"), g.deg.to("cuda")
+    for b in (0, 1):
+        sg = batches.batch_subgraph(g, wl.batches[b], cfg.self_loops)
+        bg = _gpu_batch(wl, sg, deg_dev)
+        y_gpu = executor.forward_batch_fused(gm, bg, x_dev, hs_gpu)
+        y_cpu = omodel.gas_batch_forward(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
+                                         to_np(wl.x), hs_cpu)
+        assert max_rel_err(to_np(y_gpu), y_cpu) <= TOL[cfg.dtype]
+    for a, c in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), c) <= TOL[cfg.dtype]

@@ -248,3 +248,36 @@ def test_mlp2_parity(gas, dtype, M, K, H, N):
     with pytest.raises(gas.GasError):
         gas.gas_mlp2(dev(z), dev(rng.glorot_uniform(6, 355, K, 300, dtype=dtype)),
                      dev(rng.glorot_uniform(6, 356, 300, N, dtype=dtype)), y)      # hidden width above the limit
+
+
+@pytest.mark.parametrize("name,dtype,F", [("powerlaw", torch.float32, 256), ("sbm", torch.float32, 100),
+                                           ("gin", torch.bfloat16, 256), ("powerlaw", torch.float32, 12)])
+def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
+    cfg, g, sg = graphs_small[name]
+    use_val = name != "gin"
+    nb, nv = sg.nb, sg.nv
+    hist = rng.normal_matrix(7, 360, g.n, F, dtype=dtype)
+    xb = rng.normal_matrix(7, 361, nb, F, dtype=dtype)
+    val = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg)) if use_val else None
+    dval = None if val is None else dev(torch.from_numpy(val))
+    diag = 0.0 if use_val else 1.1
+    d_hist, d_xb, d_nid, d_ptr, d_col = dev(hist), dev(xb), dev(sg.n_id), dev(sg.rowptr), dev(sg.col)
+    plan = gas.gas_plan_create(d_ptr, sg.nnz, F)
+    # unfused: pull the halo rows, then aggregate
+    x = torch.empty((nv, F), dtype=dtype, device="cuda")
+    x[:nb] = d_xb
+    gas.gas_pull(d_hist, d_nid[nb:], x[nb:])
+    z_ref = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_spmm(plan, d_ptr, d_col, dval, x, z_ref, diag=diag)
+    # fused
+    src = torch.empty_like(d_col)
+    gas.gas_fuse_sources(d_col, nb, d_nid, src)
+    col_np, nid_np = to_np(sg.col), to_np(sg.n_id)
+    assert np.array_equal(to_np(src), np.where(col_np < nb, col_np, -1 - nid_np[col_np]))
+    z = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_spmm_hist(plan, d_ptr, src, dval, d_xb, d_hist, z, diag=diag)
+    assert np.array_equal(to_np(z).view(np.uint8), to_np(z_ref).view(np.uint8))     # same sum, same order
+    # and against the oracle's pull + aggregation
+    xo = np.concatenate([to_np(xb), oops.pull(to_np(hist), nid_np[nb:])])
+    want = oops.spmm(to_np(sg.rowptr), col_np, val, xo, diag=diag)
+    assert max_rel_err(to_np(z), want) <= TOL[dtype]

@@ -38,14 +38,16 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4")
+    p.add_argument("--config", type=int, default=4, help="benchmark configuration 0..4")
     p.add_argument("--scale", type=float, default=1.0, help="shrink the node count (debugging only)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--skip-spmm-t", action="store_true",
                    help="profiling aid: leave the backward aggregation out, so that the per-kernel averages of a "
                         "trace are those of the forward aggregation alone (the reported value is then not the metric)")
-    p.add_argument("--fused", action="store_true",
-                   help="aggregate with gas_spmm_hist (halo rows read from the history table in place, no pull launch)")
+    p.add_argument("--path", choices=["both", "separate", "in-place"], default="both",
+                   help="separate: pull, aggregate, transform, push, backward aggregate as five launches; in-place: the "
+                        "aggregation reads the halo rows from the history table itself (gas_spmm_hist, same result bit "
+                        "for bit, no pull launch); both (default): time K steps of each, headline = in-place")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also launch three plain 1 GiB contiguous copies (gas_pull without an index) before the "
                         "timed region: a kernel of known traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by")
@@ -80,9 +82,6 @@ def main():
     ls = LayerStep(cfg, g, sg, rng, dev)
     F, dt, gin = ls.F, ls.dt, ls.gin
 
-    def step(ev=None):
-        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t, fused=args.fused)
-
     if args.calibrate_copy:
         src = torch.ones((1 << 20, 256), dtype=torch.float32, device=dev)      # exactly 1 GiB
         dst = torch.empty_like(src)
@@ -90,56 +89,85 @@ def main():
             gas.gas_pull(src, None, dst, base=0, n=1 << 20)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(evs[k])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall / args.steps * 1e3
-    per = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
 
-    # algorithmic bytes (what the method must move at least once), per launch
-    by = ls.algorithmic_bytes()
+    by = ls.algorithmic_bytes()                   # what the method must move at least once, per launch
     spmm_hi = by.pop("spmm_no_reuse")             # no reuse of gathered rows at all
-    edges = nnz + (0 if args.skip_spmm_t else nnz_t)
-    value = edges / (ms_step * 1e-3)
-    kern = {}
-    for n in names:
-        gbs = by[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
-        kern[n] = {"ms": round(per[n], 4), "alg_GB": round(by[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
-                   "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2)}
-        log(f"[bench] {n:7s} {per[n]:8.3f} ms  alg {by[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "
-            f"{100 * gbs / HBM_PEAK_GBS:5.1f}% of peak")
     flops = 2.0 * nb * F * F * (2 if gin else 1)
-    kern["linear"]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
-    kern["spmm"]["edges_per_s"] = round(nnz / (per["spmm"] * 1e-3), 1)
-    kern["spmm"]["gathered_GBps"] = round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)
-    hbm3 = (by["pull"] + by["spmm"] + by["push"]) / ((per["pull"] + per["spmm"] + per["push"]) * 1e-3) / 1e9
-    log(f"[bench] step {ms_step:.3f} ms (sum of kernels {sum(per.values()):.3f}) | pull+spmm+push {hbm3:.1f} GB/s "
-        f"= {100 * hbm3 / HBM_PEAK_GBS:.1f}% of HBM peak | spmm gathers {kern['spmm']['gathered_GBps']} GB/s from cache+HBM "
-        f"| linear {kern['linear']['TFLOPs']} TFLOP/s")
+    edges = nnz + (0 if args.skip_spmm_t else nnz_t)
 
+    def measure(fused):
+        """W warm-up steps, then exactly K timed steps bracketed by synchronisation; per-call times from
+        events recorded on the stream the kernels run on."""
+        def step(ev=None):
+            ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t, fused=fused)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(evs[k])
+        torch.cuda.synchronize()
+        ms_step = (time.perf_counter() - t0) / args.steps * 1e3
+        per = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
+        tag = "in-place" if fused else "separate"
+        kern = {}
+        for n in names:
+            if fused and n == "pull":
+                continue                         # no such launch: the aggregation reads the history itself
+            gbs = by[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
+            key = "spmm_hist" if (fused and n == "spmm") else n
+            kern[key] = {"ms": round(per[n], 4), "alg_GB": round(by[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
+                         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2)}
+            log(f"[bench] {tag:8s} {key:9s} {per[n]:8.3f} ms  alg {by[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "
+                f"{100 * gbs / HBM_PEAK_GBS:5.1f}% of peak")
+        sk = "spmm_hist" if fused else "spmm"
+        kern["linear"]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
+        kern[sk]["edges_per_s"] = round(nnz / (per["spmm"] * 1e-3), 1)
+        kern[sk]["gathered_GBps"] = round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)
+        t3 = (per["spmm"] + per["push"] + (0.0 if fused else per["pull"])) * 1e-3
+        # bytes of the three operations as separate launches (pull + aggregation + push); the in-place variant
+        # does the same work without writing and re-reading the halo copy, so its own byte count is smaller
+        hbm3 = (by["pull"] + by["spmm"] + by["push"]) / t3 / 1e9
+        hbm3_own = ((by["spmm"] + by["push"]) / t3 / 1e9) if fused else hbm3
+        log(f"[bench] {tag:8s} step {ms_step:.3f} ms (sum of kernels {sum(per.values()):.3f}) | pull+aggregate+push "
+            f"{hbm3:.1f} GB/s = {100 * hbm3 / HBM_PEAK_GBS:.1f}% of HBM peak on the separate-launch byte count"
+            + (f" ({hbm3_own:.1f} GB/s on its own byte count)" if fused else "")
+            + f" | aggregation gathers {kern[sk]['gathered_GBps']} GB/s | transform {kern['linear']['TFLOPs']} TFLOP/s")
+        return {"ms_per_step": ms_step, "value": edges / (ms_step * 1e-3), "kernels": kern, "per": per,
+                "hbm_pull_spmm_push": {"GBps": round(hbm3, 1), "pct_of_peak": round(100 * hbm3 / HBM_PEAK_GBS, 2),
+                                       "GBps_own_bytes": round(hbm3_own, 1)}}
+
+    res = {}
+    if args.path in ("separate", "both"):
+        res["separate"] = measure(False)
+    if args.path in ("in-place", "both"):
+        res["in-place"] = measure(True)
+    head = res.get("in-place") or res["separate"]
+    fused_head = "in-place" in res
+    per = head.pop("per")
     spmm_gbs = by["spmm"] / (per["spmm"] * 1e-3) / 1e9
     out = {
         "metric": "GAS layer step: edges aggregated/sec + achieved HBM GB/s (% of peak), 1 GPU",
-        "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if dt == torch.float32 else "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch"
-                               + (", halo rows read in place by the aggregation (no pull launch)" if args.fused else ""),
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch; "
+                               + ("aggregate (halo rows read from the history table in place) + transform + push + "
+                                  "backward aggregate" if fused_head else
+                                  "pull + aggregate + transform + push + backward aggregate"),
                    "N": g.n, "nnz": g.nnz, "nb": nb, "nh": nh, "nnz_b": nnz, "nnz_bt": nnz_t, "F": F,
                    "scale": args.scale},
-        "hbm_pull_spmm_push": {"GBps": round(hbm3, 1), "pct_of_peak": round(100 * hbm3 / HBM_PEAK_GBS, 2)},
-        "kernels": kern,
-        "roofline": {"kernel": "spmm_kernel (gas_spmm)", "bound": "hbm", "achieved": round(spmm_gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(spmm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": load_traffic(args.config, args.scale)},
+        "hbm_pull_spmm_push": head["hbm_pull_spmm_push"],
+        "kernels": head["kernels"],
+        "roofline": {"kernel": "spmm_kernel (" + ("gas_spmm_hist" if fused_head else "gas_spmm") + ")", "bound": "hbm",
+                     "achieved": round(spmm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(spmm_gbs / HBM_PEAK_GBS, 4), "traffic": load_traffic(args.config, args.scale)},
     }
+    if fused_head and "separate" in res:
+        res["separate"].pop("per")
+        out["separate_launches"] = res["separate"]   # the same step as five launches, pull included
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, g, sg, ls.hist_in, ls.x, ls.w1 if gin else ls.w,
                                            ls.w2 if gin else None, ls.gz, F, args.cpu_sample_rows)

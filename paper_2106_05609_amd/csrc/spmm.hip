@@ -29,6 +29,8 @@ struct gas_plan {
     int32_t* d_chunk = nullptr;        // [3 * n_chunks]: row, begin, end
     int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
     float* d_partial = nullptr;        // [n_chunks, max_F]
+    int32_t* d_group = nullptr;        // [2 * n_groups] first and end row of every group of light rows
+    int64_t n_groups = 0;
     int device = 0;
 };
 
@@ -59,6 +61,8 @@ struct SpmmArgs {
     const int32_t* heavy;
     int64_t n_heavy;
     float* partial;
+    const int32_t* group;       // row groups of the light rows (wave-per-row path)
+    int64_t n_groups;
 };
 
 template <bool XBF>
@@ -126,7 +130,9 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int beg
                 for (int p = 0; p < UPT; ++p) {
                     v[u][p] = u32x4{0u, 0u, 0u, 0u};
                     // index >= 0: row of the mini-batch tensor; index < 0: row -1-index of the history table
-                    const char* src = c >= 0 ? xb + (int64_t)c * a.x_stride : hb + (int64_t)(-1 - c) * a.h_stride;
+                    const bool in_batch = c >= 0;
+                    const char* src = (in_batch ? xb : hb) +
+                                      (int64_t)(in_batch ? c : -1 - c) * (in_batch ? a.x_stride : a.h_stride);
                     if (ok && tl + p * G < a.slice_units)
                         v[u][p] = *reinterpret_cast<const u32x4*>(src + (int64_t)p * G * 16);
                 }
@@ -186,11 +192,147 @@ __device__ __forceinline__ void epilogue(const SpmmArgs& a, int64_t row, int uni
     }
 }
 
+// ---- wave-per-row path for rows of exactly 64 vectors of VB bytes (1 KiB or 512 B)
+// Short rows are the common case on power-law graphs, and one wavefront per row
+// pays three dependent memory latencies (row pointers, indices, feature rows)
+// for a handful of gathers.  Here consecutive light rows are bundled at plan
+// time into groups of at most 64 entries and 63 rows: the wavefront loads the
+// group's row pointers with one load and all its indices and weights with
+// another, then streams the gathers of the whole group, 8 in flight per lane,
+// flushing a row (epilogue + store) whenever the entry cursor crosses a row
+// boundary.  Every lane works on every row (lane l owns bytes [l*VB, (l+1)*VB) of
+// the row), all control flow is wavefront-uniform, and the order of summation
+// within a row is the stored order.
+template <int VB> struct VecOf;
+template <> struct VecOf<16> { typedef u32x4 type; };
+template <> struct VecOf<8> { typedef u32x2 type; };
+
+template <int VB, bool XBF>
+struct LaneAcc {
+    static constexpr int NW = VB / 4;                 // dwords per lane and row
+    static constexpr int E = XBF ? 2 * NW : NW;       // elements per lane and row
+    typedef typename VecOf<VB>::type V;
+    float v[E];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = 0.f;
+    }
+    __device__ __forceinline__ void fma(float w, const V& x) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            if constexpr (XBF) {
+                v[2 * i] = fmaf(w, bf16_lo(x[i]), v[2 * i]);
+                v[2 * i + 1] = fmaf(w, bf16_hi(x[i]), v[2 * i + 1]);
+            } else {
+                v[i] = fmaf(w, __uint_as_float(x[i]), v[i]);
+            }
+        }
+    }
+};
+
+template <int VB, bool XBF, bool ZBF>
+__device__ __forceinline__ void flush_row(const SpmmArgs& a, int64_t row, int lane, LaneAcc<VB, XBF>& acc) {
+    typedef typename VecOf<VB>::type V;
+    constexpr int E = LaneAcc<VB, XBF>::E, NW = VB / 4;
+    float z[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) z[e] = a.s_agg * acc.v[e];
+    if (a.diag != 0.f && row < a.n_diag) {
+        LaneAcc<VB, XBF> t;
+        t.clear();
+        t.fma(a.diag, *reinterpret_cast<const V*>(a.X + row * a.x_stride + (int64_t)lane * VB));
+#pragma unroll
+        for (int e = 0; e < E; ++e) z[e] += t.v[e];
+    }
+    if (a.R) {
+        LaneAcc<VB, XBF> t;
+        t.clear();
+        t.fma(a.s_res, *reinterpret_cast<const V*>(a.R + row * a.r_stride + (int64_t)lane * VB));
+#pragma unroll
+        for (int e = 0; e < E; ++e) z[e] += t.v[e];
+    }
+    char* zp = a.Z + row * a.z_stride;
+    if constexpr (ZBF) {
+        V o;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) o[i] = pack_bf16(z[2 * i], z[2 * i + 1]);
+        __builtin_nontemporal_store(o, reinterpret_cast<V*>(zp + (int64_t)lane * VB));
+    } else if constexpr (XBF) {      // bf16 in, fp32 out: twice the bytes
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            V o;
+#pragma unroll
+            for (int i = 0; i < NW; ++i) o[i] = __float_as_uint(z[q * NW + i]);
+            __builtin_nontemporal_store(o, reinterpret_cast<V*>(zp + (int64_t)lane * 2 * VB + q * VB));
+        }
+    } else {
+        V o;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) o[i] = __float_as_uint(z[i]);
+        __builtin_nontemporal_store(o, reinterpret_cast<V*>(zp + (int64_t)lane * VB));
+    }
+    acc.clear();
+}
+
+template <int VB, bool XBF, bool ZBF>
+__device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
+    typedef typename VecOf<VB>::type V;
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63;
+    const int r0 = a.group[2 * g], nrows = a.group[2 * g + 1] - r0;   // 1 <= nrows <= 63
+    const int my_ptr = lane <= nrows ? a.ptr[r0 + lane] : 0;
+    const int e0 = __builtin_amdgcn_readlane(my_ptr, 0);
+    const int e1 = __builtin_amdgcn_readlane(my_ptr, nrows);
+    const char* xb = a.X + (int64_t)lane * VB;
+    const char* hb = a.H + (int64_t)lane * VB;
+    LaneAcc<VB, XBF> acc;
+    acc.clear();
+    int r = 0;                                                     // row being accumulated (relative to r0)
+    int row_end = __builtin_amdgcn_readlane(my_ptr, 1);            // first entry after row r
+    // a single row longer than 64 entries makes its own group: walk it 64 entries at a time
+    for (int t = e0; t < e1; t += kWave) {
+        const int cnt = min(kWave, e1 - t);
+        int my_c = 0;
+        float my_w = 0.f;
+        if (lane < cnt) {
+            my_c = __builtin_nontemporal_load(a.ind + t + lane);
+            my_w = a.val ? __builtin_nontemporal_load(a.val + t + lane) : 1.f;
+        }
+        for (int j = 0; j < cnt; j += U) {
+            V v[U];
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = j + u;
+                const int c = __builtin_amdgcn_readlane(my_c, k & 63);
+                w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k & 63));
+                const bool in_batch = c >= 0;
+                const char* src = (in_batch ? xb : hb) +
+                                  (int64_t)(in_batch ? c : -1 - c) * (in_batch ? a.x_stride : a.h_stride);
+                if (k < cnt) v[u] = *reinterpret_cast<const V*>(src);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = j + u;
+                if (k < cnt) {
+                    while (t + k >= row_end) {                     // crossed into the next row (or over empty rows)
+                        flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);
+                        ++r;
+                        row_end = __builtin_amdgcn_readlane(my_ptr, (r + 1) & 63);
+                    }
+                    acc.fma(w[u], v[u]);
+                }
+            }
+        }
+    }
+    for (; r < nrows; ++r) flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);   // last row and trailing empty rows
+}
+
 // One launch covers both kinds of work: the first ceil(n_chunks/4) workgroups
 // take one chunk of a heavy row per wavefront (partial sums to the workspace,
 // scheduled first because they are the longest items), the remaining ones take
 // one light row per wavefront and finish it (epilogue and store).
-template <int G, int UPT, int U, bool XBF, bool ZBF>
+template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
 __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
     constexpr int E = Unit<XBF>::E;
     const int lane = threadIdx.x & 63;
@@ -218,6 +360,11 @@ __global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
                 }
             }
         }
+        return;
+    }
+    if constexpr (VB > 0) {                       // light rows in groups, one wavefront per row (n_slices == 1)
+        const int64_t g = (blk - chunk_blocks) * 4 + (threadIdx.x >> 6);
+        if (g < a.n_groups) light_group<VB, XBF, ZBF>(a, g);
         return;
     }
     const int64_t row = (blk - chunk_blocks) * 4 + (threadIdx.x >> 6);
@@ -283,11 +430,12 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
     }
 }
 
-template <int G, int UPT, int U, bool XBF, bool ZBF>
+template <int G, int UPT, int U, bool XBF, bool ZBF, int VB = 0>
 gas_status launch_vector(const SpmmArgs& a, hipStream_t s) {
-    const int64_t blocks = ((a.n_rows + 3) / 4 + (a.n_chunks + 3) / 4) * a.n_slices;
+    const int64_t light_items = VB > 0 ? a.n_groups : a.n_rows;
+    const int64_t blocks = ((light_items + 3) / 4 + (a.n_chunks + 3) / 4) * a.n_slices;
     if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
-    hipLaunchKernelGGL((spmm_kernel<G, UPT, U, XBF, ZBF>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (blocks > 0) hipLaunchKernelGGL((spmm_kernel<G, UPT, U, XBF, ZBF, VB>), dim3((unsigned)blocks), dim3(256), 0, s, a);
     if (a.n_heavy > 0)
         hipLaunchKernelGGL((spmm_heavy_reduce_kernel<XBF, ZBF>), dim3((unsigned)((a.n_heavy + 3) / 4)), dim3(256),
                            0, s, a);
@@ -298,6 +446,9 @@ gas_status launch_vector(const SpmmArgs& a, hipStream_t s) {
 template <bool XBF, bool ZBF>
 gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
     const int u = a.slice_units;
+    // rows of exactly 1 KiB or 512 B: grouped wave-per-row path for the light rows
+    if (a.group && a.n_slices == 1 && u == 64) return launch_vector<64, 1, 8, XBF, ZBF, 16>(a, s);
+    if (a.group && a.n_slices == 1 && u == 32) return launch_vector<32, 1, 4, XBF, ZBF, 8>(a, s);
     if (u <= 8) return launch_vector<8, 1, 2, XBF, ZBF>(a, s);
     if (u <= 16) return launch_vector<16, 1, 4, XBF, ZBF>(a, s);
     if (u <= 32) return launch_vector<32, 1, 4, XBF, ZBF>(a, s);
@@ -338,6 +489,7 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     a.chunk = plan->d_chunk; a.n_chunks = plan->n_chunks;
     a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
     a.partial = plan->d_partial;
+    a.group = plan->d_group; a.n_groups = plan->n_groups;
     const bool vec = (F * xb) % 16 == 0 && aligned16(X) && a.x_stride % 16 == 0 && aligned16(Z) &&
                      a.z_stride % 16 == 0 && (!R || (aligned16(R) && a.r_stride % 16 == 0)) &&
                      (!H || (aligned16(H) && a.h_stride % 16 == 0));
@@ -403,10 +555,28 @@ gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int3
                         h_ptr[n_rows], (long long)nnz);
         }
     }
-    std::vector<int32_t> chunk, heavy_row, heavy_first;
+    std::vector<int32_t> chunk, heavy_row, heavy_first, group;
+    const bool grouping = env_int("GAS_SPMM_GROUPS", 1, 0, 1) != 0;
+    int64_t g_start = -1;          // first row of the open group, -1 if none
+    int32_t g_entries = 0;
+    auto close_group = [&](int64_t end_row) {
+        if (g_start >= 0) { group.push_back((int32_t)g_start); group.push_back((int32_t)end_row); }
+        g_start = -1; g_entries = 0;
+    };
     for (int64_t r = 0; r < n_rows; ++r) {
         const int32_t b = h_ptr[r], e = h_ptr[r + 1];
         if (e < b) { delete p; return fail(GAS_ERR_ARG, "gas_plan_create: ptr decreases at row %lld", (long long)r); }
+        if (grouping) {
+            // groups are runs of consecutive light rows: <= 64 entries and <= 63 rows, or one row alone
+            const int32_t len = e - b;
+            if (len > p->threshold) {
+                close_group(r);
+            } else {
+                if (g_start >= 0 && (g_entries + len > 64 || r - g_start >= 63)) close_group(r);
+                if (g_start < 0) g_start = r;
+                g_entries += len;
+            }
+        }
         if (e - b > p->threshold) {
             heavy_row.push_back((int32_t)r);
             heavy_first.push_back((int32_t)(chunk.size() / 3));
@@ -417,8 +587,21 @@ gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int3
             }
         }
     }
+    close_group(n_rows);
     p->n_heavy = (int64_t)heavy_row.size();
     p->n_chunks = (int64_t)chunk.size() / 3;
+    if (!group.empty()) {
+        const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
+        p->n_groups = (int64_t)group.size() / 2;
+        hipError_t e = hipMalloc(&p->d_group, bounds.size() * sizeof(int32_t));
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(p->d_group, bounds.data(), bounds.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) {
+            gas_plan_destroy(p);
+            return fail(GAS_ERR_NOMEM, "gas_plan_create: group list: %s", hipGetErrorString(e));
+        }
+    }
     if (p->n_heavy > 0) {
         heavy_first.push_back((int32_t)p->n_chunks);
         heavy_row.insert(heavy_row.end(), heavy_first.begin(), heavy_first.end());
@@ -447,6 +630,7 @@ void gas_plan_destroy(gas_plan* p) {
     if (p->d_chunk) (void)hipFree(p->d_chunk);
     if (p->d_heavy) (void)hipFree(p->d_heavy);
     if (p->d_partial) (void)hipFree(p->d_partial);
+    if (p->d_group) (void)hipFree(p->d_group);
     delete p;
 }
 

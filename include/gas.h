@@ -102,13 +102,17 @@ GAS_API gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t 
  * heavy rows, partial-sum workspace).  Built once per batch subgraph and
  * reused by every layer and every epoch; one plan for the CSR, one for the CSC
  * copy.  ptr is a device pointer (int32[n_rows+1]); it is copied to the host
- * inside this call, which therefore waits for `stream`.  max_F is the widest
- * feature dimension the plan will be used with (sizes the workspace).
- * A plan must not be used by two streams at the same time.
+ * inside this call, which therefore waits for `stream`.  ind (device,
+ * int32[nnz], each row ascending) may be NULL; when given it is used to cut
+ * and order the chunks of heavy rows by column range (better cache reuse of
+ * the gathered rows) and is copied to the host as well.  Either the local
+ * column ids or the source indices of gas_fuse_sources may be passed.  max_F
+ * is the widest feature dimension the plan will be used with (sizes the
+ * workspace).  A plan must not be used by two streams at the same time.
  */
 typedef struct gas_plan gas_plan;
-GAS_API gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int32_t max_F,
-                           void* stream, gas_plan** out);
+GAS_API gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz,
+                           int32_t max_F, void* stream, gas_plan** out);
 GAS_API void gas_plan_destroy(gas_plan* plan);
 
 /*

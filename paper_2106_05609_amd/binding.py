@@ -110,11 +110,13 @@ def gas_gcn_norm(ptr, ind, n_id, deg, val):
 class Plan:
     """Owner of a gas_plan handle."""
 
-    def __init__(self, ptr: torch.Tensor, nnz: int, max_F: int, n_rows=None):
+    def __init__(self, ptr: torch.Tensor, nnz: int, max_F: int, n_rows=None, ind=None):
         self.n_rows = ptr.numel() - 1 if n_rows is None else n_rows
         self.handle = C.c_void_p(0)
-        _check(lib().gas_plan_create(_ptr(ptr, torch.int32), C.c_int64(self.n_rows), C.c_int64(nnz), C.c_int32(max_F),
-                                     _stream(), C.byref(self.handle)))
+        if ind is not None and ind.numel() < nnz:
+            raise ValueError("gas_plan_create: ind is shorter than nnz")
+        _check(lib().gas_plan_create(_ptr(ptr, torch.int32), _ptr(ind, torch.int32), C.c_int64(self.n_rows),
+                                     C.c_int64(nnz), C.c_int32(max_F), _stream(), C.byref(self.handle)))
 
     def close(self):
         if self.handle:
@@ -128,8 +130,8 @@ class Plan:
             pass
 
 
-def gas_plan_create(ptr, nnz, max_F, n_rows=None) -> Plan:
-    return Plan(ptr, nnz, max_F, n_rows)
+def gas_plan_create(ptr, nnz, max_F, n_rows=None, ind=None) -> Plan:
+    return Plan(ptr, nnz, max_F, n_rows, ind)
 
 
 def gas_plan_destroy(plan: Plan):

@@ -12,12 +12,14 @@
 // indices and weights at a time in registers (one coalesced load) and
 // broadcasts them with lane permutes; U independent row loads are in flight
 // per lane.  Rows with at most `threshold` entries take one wavefront each.
-// Heavier rows (power-law hubs) are cut into chunks of `chunk` entries, one
-// wavefront per chunk in the same launch, whose fp32 partial sums go to a
-// workspace and are added in chunk order by a second, small kernel: the summation order is a function of the
-// row pointer array alone, so results are bit-identical from run to run.
+// Heavier rows (power-law hubs) are cut into chunks of at most `chunk` entries,
+// one wavefront per chunk (spmm_chunk_kernel), whose fp32 partial sums go to a
+// workspace and are added in a fixed order by spmm_heavy_reduce_kernel; the
+// light rows follow in spmm_rows_kernel.  The summation order is a function of
+// the plan alone, so results are bit-identical from run to run.
 #include "common.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <vector>
 
@@ -26,7 +28,7 @@ struct gas_plan {
     int32_t max_F = 0;
     int32_t threshold = 0, chunk = 0, slices = 1;
     int64_t n_heavy = 0, n_chunks = 0;
-    int32_t* d_chunk = nullptr;        // [3 * n_chunks]: row, begin, end
+    int32_t* d_chunk = nullptr;        // [3 * n_chunks]: slot of the partial sum, begin, end (in processing order)
     int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
     float* d_partial = nullptr;        // [n_chunks, max_F]
     int32_t* d_group = nullptr;        // [2 * n_groups] first and end row of every group of light rows
@@ -96,7 +98,7 @@ __device__ __forceinline__ float bcast_f(float v, int k) {
 // Sum of val[k] * X[ind[k], :] over k in [begin, end) for this lane's units.
 // Afterwards every team of the wavefront holds the full sum.
 template <int G, int UPT, int U, bool XBF>
-__device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int begin, int end,
+__device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int nunits, int begin, int end,
                                            float (&acc)[UPT][Unit<XBF>::E]) {
     constexpr int S = kWave / G;
     constexpr int E = Unit<XBF>::E;
@@ -133,7 +135,7 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int beg
                     const bool in_batch = c >= 0;
                     const char* src = (in_batch ? xb : hb) +
                                       (int64_t)(in_batch ? c : -1 - c) * (in_batch ? a.x_stride : a.h_stride);
-                    if (ok && tl + p * G < a.slice_units)
+                    if (ok && tl + p * G < nunits)
                         v[u][p] = *reinterpret_cast<const u32x4*>(src + (int64_t)p * G * 16);
                 }
             }
@@ -328,54 +330,58 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
     for (; r < nrows; ++r) flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);   // last row and trailing empty rows
 }
 
-// One launch covers both kinds of work: the first ceil(n_chunks/4) workgroups
-// take one chunk of a heavy row per wavefront (partial sums to the workspace,
-// scheduled first because they are the longest items), the remaining ones take
-// one light row per wavefront and finish it (epilogue and store).
-template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
-__global__ __launch_bounds__(256) void spmm_kernel(SpmmArgs a) {
+// Chunks of heavy rows: one wavefront per chunk, partial sums to the workspace.
+// With n_slices > 1 a feature row is cut into equal slices and workgroup b
+// works on slice b % n_slices: consecutive workgroup ids go to different XCDs
+// (round robin), so with 8 slices every XCD keeps to one slice and the same L2
+// capacity holds 8x more rows of it.
+template <int G, int UPT, int U, bool XBF>
+__global__ __launch_bounds__(256) void spmm_chunk_kernel(SpmmArgs a) {
     constexpr int E = Unit<XBF>::E;
     const int lane = threadIdx.x & 63;
-    // consecutive workgroup ids go to different XCDs (round robin), so with 8
-    // slices every XCD keeps to one feature slice and its L2 holds 8x more rows
     const int slice = blockIdx.x % a.n_slices;
-    const int64_t blk = blockIdx.x / a.n_slices;
+    const int64_t c = (int64_t)(blockIdx.x / a.n_slices) * 4 + (threadIdx.x >> 6);
+    if (c >= a.n_chunks) return;
     const int unit0 = slice * a.slice_units;
-    const int64_t chunk_blocks = (a.n_chunks + 3) >> 2;
     float acc[UPT][E];
-    if (blk < chunk_blocks) {
-        const int64_t c = blk * 4 + (threadIdx.x >> 6);
-        if (c >= a.n_chunks) return;
-        accumulate<G, UPT, U, XBF>(a, unit0, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
-        if (lane < G) {
-#pragma unroll
-            for (int p = 0; p < UPT; ++p) {
-                const int unit = lane + p * G;
-                if (unit < a.slice_units) {
-                    float* dst = a.partial + c * (int64_t)a.F + (int64_t)(unit0 + unit) * E;
-#pragma unroll
-                    for (int q = 0; q < E / 4; ++q)
-                        *reinterpret_cast<f32x4*>(dst + 4 * q) =
-                            f32x4{acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2], acc[p][4 * q + 3]};
-                }
-            }
-        }
-        return;
-    }
-    if constexpr (VB > 0) {                       // light rows in groups, one wavefront per row (n_slices == 1)
-        const int64_t g = (blk - chunk_blocks) * 4 + (threadIdx.x >> 6);
-        if (g < a.n_groups) light_group<VB, XBF, ZBF>(a, g);
-        return;
-    }
-    const int64_t row = (blk - chunk_blocks) * 4 + (threadIdx.x >> 6);
-    if (row >= a.n_rows) return;
-    const int begin = a.ptr[row], end = a.ptr[row + 1];
-    if (end - begin > a.threshold) return;       // heavy row: done by the chunk workgroups
-    accumulate<G, UPT, U, XBF>(a, unit0, begin, end, acc);
+    accumulate<G, UPT, U, XBF>(a, unit0, a.slice_units, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
     if (lane < G) {
 #pragma unroll
-        for (int p = 0; p < UPT; ++p)
-            if (lane + p * G < a.slice_units) epilogue<XBF, ZBF>(a, row, unit0 + lane + p * G, acc[p]);
+        for (int p = 0; p < UPT; ++p) {
+            const int unit = lane + p * G;
+            if (unit < a.slice_units) {
+                float* dst = a.partial + (int64_t)a.chunk[3 * c] * a.F + (int64_t)(unit0 + unit) * E;
+#pragma unroll
+                for (int q = 0; q < E / 4; ++q)
+                    *reinterpret_cast<f32x4*>(dst + 4 * q) =
+                        f32x4{acc[p][4 * q], acc[p][4 * q + 1], acc[p][4 * q + 2], acc[p][4 * q + 3]};
+            }
+        }
+    }
+}
+
+// Light rows, finished in one go (epilogue and store).  VB > 0: bundled into
+// groups, one wavefront per row (rows of exactly 64 vectors of VB bytes);
+// VB == 0: one wavefront per row, teams of G lanes per neighbour.
+template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
+__global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
+    if constexpr (VB > 0) {
+        const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        if (g < a.n_groups) light_group<VB, XBF, ZBF>(a, g);
+    } else {
+        constexpr int E = Unit<XBF>::E;
+        const int lane = threadIdx.x & 63;
+        const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        if (row >= a.n_rows) return;
+        const int begin = a.ptr[row], end = a.ptr[row + 1];
+        if (end - begin > a.threshold) return;       // heavy row: done by the chunk kernel
+        float acc[UPT][E];
+        accumulate<G, UPT, U, XBF>(a, 0, a.units, begin, end, acc);
+        if (lane < G) {
+#pragma unroll
+            for (int p = 0; p < UPT; ++p)
+                if (lane + p * G < a.units) epilogue<XBF, ZBF>(a, row, lane + p * G, acc[p]);
+        }
     }
 }
 
@@ -430,32 +436,59 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
     }
 }
 
-template <int G, int UPT, int U, bool XBF, bool ZBF, int VB = 0>
-gas_status launch_vector(const SpmmArgs& a, hipStream_t s) {
-    const int64_t light_items = VB > 0 ? a.n_groups : a.n_rows;
-    const int64_t blocks = ((light_items + 3) / 4 + (a.n_chunks + 3) / 4) * a.n_slices;
+template <int G, int UPT, int U, bool XBF>
+gas_status launch_chunks(const SpmmArgs& a, hipStream_t s) {
+    const int64_t blocks = ((a.n_chunks + 3) / 4) * a.n_slices;
     if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
-    if (blocks > 0) hipLaunchKernelGGL((spmm_kernel<G, UPT, U, XBF, ZBF, VB>), dim3((unsigned)blocks), dim3(256), 0, s, a);
-    if (a.n_heavy > 0)
-        hipLaunchKernelGGL((spmm_heavy_reduce_kernel<XBF, ZBF>), dim3((unsigned)((a.n_heavy + 3) / 4)), dim3(256),
-                           0, s, a);
-    GAS_CHECK_HIP(hipGetLastError());
+    hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return GAS_OK;
+}
+
+template <bool XBF>
+gas_status dispatch_chunks(const SpmmArgs& a, hipStream_t s) {
+    const int u = a.slice_units;
+    if (u <= 8) return launch_chunks<8, 1, 8, XBF>(a, s);
+    if (u <= 16) return launch_chunks<16, 1, 8, XBF>(a, s);
+    if (u <= 32) return launch_chunks<32, 1, 8, XBF>(a, s);
+    if (u <= 64) return launch_chunks<64, 1, 8, XBF>(a, s);
+    if (u <= 128) return launch_chunks<64, 2, 4, XBF>(a, s);
+    return launch_chunks<64, 4, 2, XBF>(a, s);
+}
+
+template <int G, int UPT, int U, bool XBF, bool ZBF, int VB = 0>
+gas_status launch_rows(const SpmmArgs& a, hipStream_t s) {
+    const int64_t items = VB > 0 ? a.n_groups : a.n_rows;
+    const int64_t blocks = (items + 3) / 4;
+    if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
+    if (blocks > 0)
+        hipLaunchKernelGGL((spmm_rows_kernel<G, UPT, U, XBF, ZBF, VB>), dim3((unsigned)blocks), dim3(256), 0, s, a);
     return GAS_OK;
 }
 
 template <bool XBF, bool ZBF>
 gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
-    const int u = a.slice_units;
-    // rows of exactly 1 KiB or 512 B: grouped wave-per-row path for the light rows
-    if (a.group && a.n_slices == 1 && u == 64) return launch_vector<64, 1, 8, XBF, ZBF, 16>(a, s);
-    if (a.group && a.n_slices == 1 && u == 32) return launch_vector<32, 1, 4, XBF, ZBF, 8>(a, s);
-    if (u <= 8) return launch_vector<8, 1, 2, XBF, ZBF>(a, s);
-    if (u <= 16) return launch_vector<16, 1, 4, XBF, ZBF>(a, s);
-    if (u <= 32) return launch_vector<32, 1, 4, XBF, ZBF>(a, s);
-    if (u <= 64) return launch_vector<64, 1, 8, XBF, ZBF>(a, s);
-    if (u <= 128) return launch_vector<64, 2, 4, XBF, ZBF>(a, s);
-    if (u <= 256) return launch_vector<64, 4, 2, XBF, ZBF>(a, s);
-    return fail(GAS_ERR_ARG, "feature rows longer than 4096 bytes are not supported (F*size = %d)", u * 16);
+    const int u = a.units;
+    if (u > 256) return fail(GAS_ERR_ARG, "feature rows longer than 4096 bytes are not supported (F*size = %d)", u * 16);
+    // heavy rows first: chunk partials, then their reduction; the light rows follow on the same stream
+    if (a.n_chunks > 0) {
+        const gas_status st = dispatch_chunks<XBF>(a, s);
+        if (st != GAS_OK) return st;
+        hipLaunchKernelGGL((spmm_heavy_reduce_kernel<XBF, ZBF>), dim3((unsigned)((a.n_heavy + 3) / 4)), dim3(256),
+                           0, s, a);
+    }
+    gas_status st;
+    // rows of exactly 1 KiB or 512 B: grouped wave-per-row path
+    if (a.group && u == 64) st = launch_rows<64, 1, 8, XBF, ZBF, 16>(a, s);
+    else if (a.group && u == 32) st = launch_rows<32, 1, 4, XBF, ZBF, 8>(a, s);
+    else if (u <= 8) st = launch_rows<8, 1, 2, XBF, ZBF>(a, s);
+    else if (u <= 16) st = launch_rows<16, 1, 4, XBF, ZBF>(a, s);
+    else if (u <= 32) st = launch_rows<32, 1, 4, XBF, ZBF>(a, s);
+    else if (u <= 64) st = launch_rows<64, 1, 8, XBF, ZBF>(a, s);
+    else if (u <= 128) st = launch_rows<64, 2, 4, XBF, ZBF>(a, s);
+    else st = launch_rows<64, 4, 2, XBF, ZBF>(a, s);
+    if (st != GAS_OK) return st;
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
 }
 
 gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, const int32_t* ind, const float* val,
@@ -529,8 +562,8 @@ using namespace gas;
 
 extern "C" {
 
-gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int32_t max_F, void* stream,
-                           gas_plan** out) {
+gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
+                           void* stream, gas_plan** out) {
     GAS_REQUIRE(out, "gas_plan_create: null output");
     *out = nullptr;
     GAS_REQUIRE(n_rows >= 0 && n_rows < 0x7FFFFFF0LL && nnz >= 0 && nnz < 0x7FFFFFF0LL && max_F > 0,
@@ -555,7 +588,22 @@ gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int3
                         h_ptr[n_rows], (long long)nnz);
         }
     }
-    std::vector<int32_t> chunk, heavy_row, heavy_first, group;
+    // Heavy rows are cut into chunks.  With the column indices at hand a chunk also ends where the (sorted)
+    // columns of the row cross a multiple of `window`, and the chunks are then processed window by window:
+    // wavefronts that run at the same time gather from the same range of feature rows, which therefore stay
+    // in the caches between their uses.  The partial sums keep their row-major slots, so the order in which
+    // a row's partials are added does not depend on the processing order.
+    const int window = env_int("GAS_SPMM_WINDOW", 32768, 0, 1 << 30);
+    std::vector<int32_t> h_ind;
+    bool any_heavy = false;
+    for (int64_t r = 0; r < n_rows && !any_heavy; ++r) any_heavy = h_ptr[r + 1] - h_ptr[r] > p->threshold;
+    if (ind && window > 0 && any_heavy) {
+        h_ind.resize((size_t)nnz);
+        hipError_t e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
+    }
+    std::vector<int32_t> chunk, heavy_row, heavy_first, group, chunk_window;
     const bool grouping = env_int("GAS_SPMM_GROUPS", 1, 0, 1) != 0;
     int64_t g_start = -1;          // first row of the open group, -1 if none
     int32_t g_entries = 0;
@@ -580,16 +628,42 @@ gas_status gas_plan_create(const int32_t* ptr, int64_t n_rows, int64_t nnz, int3
         if (e - b > p->threshold) {
             heavy_row.push_back((int32_t)r);
             heavy_first.push_back((int32_t)(chunk.size() / 3));
-            for (int32_t c = b; c < e; c += p->chunk) {
-                chunk.push_back((int32_t)r);
-                chunk.push_back(c);
-                chunk.push_back(c + p->chunk < e ? c + p->chunk : e);
+            if (h_ind.empty()) {
+                for (int32_t c = b; c < e; c += p->chunk) {
+                    chunk.push_back((int32_t)(chunk.size() / 3));      // slot of the partial sum
+                    chunk.push_back(c);
+                    chunk.push_back(c + p->chunk < e ? c + p->chunk : e);
+                }
+            } else {
+                int32_t c = b;
+                while (c < e) {
+                    // negative indices (history rows of the in-place variant) order like their magnitudes
+                    auto key = [&](int32_t k) { const int32_t v = h_ind[k]; return (v >= 0 ? v : -1 - v) / window; };
+                    const int32_t w = key(c);
+                    int32_t stop = c + 1;
+                    while (stop < e && stop - c < p->chunk && key(stop) == w) ++stop;
+                    chunk.push_back((int32_t)(chunk.size() / 3));
+                    chunk.push_back(c);
+                    chunk.push_back(stop);
+                    chunk_window.push_back(w);
+                    c = stop;
+                }
             }
         }
     }
     close_group(n_rows);
     p->n_heavy = (int64_t)heavy_row.size();
     p->n_chunks = (int64_t)chunk.size() / 3;
+    if (!chunk_window.empty()) {
+        std::vector<int32_t> order((size_t)p->n_chunks);
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t x, int32_t y) { return chunk_window[x] < chunk_window[y]; });
+        std::vector<int32_t> sorted(chunk.size());
+        for (size_t i = 0; i < order.size(); ++i)
+            for (int q = 0; q < 3; ++q) sorted[3 * i + q] = chunk[3 * (size_t)order[i] + q];
+        chunk.swap(sorted);
+    }
     if (!group.empty()) {
         const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
         p->n_groups = (int64_t)group.size() / 2;

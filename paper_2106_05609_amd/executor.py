@@ -25,7 +25,7 @@ class BatchGraph:
         self.nb, self.nv = int(nb), int(n_id.numel())
         self.n_id, self.rowptr, self.col = n_id, rowptr, col
         self.nnz = int(col.numel())
-        self.plan = B.gas_plan_create(rowptr, self.nnz, max_F)
+        self.plan = B.gas_plan_create(rowptr, self.nnz, max_F, ind=col)
         self.val = None
         if normalise:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
@@ -34,7 +34,8 @@ class BatchGraph:
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
         if colptr is not None:
             # backward over the in-batch columns only: histories are constants
-            self.plan_t = B.gas_plan_create(colptr[: self.nb + 1], int(colptr[self.nb].item()), max_F, n_rows=self.nb)
+            self.plan_t = B.gas_plan_create(colptr[: self.nb + 1], int(colptr[self.nb].item()), max_F, n_rows=self.nb,
+                                              ind=row)
             if normalise:
                 self.val_t = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
                 B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t)

@@ -103,7 +103,7 @@ def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld
     val = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg)) if use_val else None
     out_dtype = out_dtype or dtype
     z = torch.full((sg.nb, F + ld_pad), float("nan"), dtype=out_dtype, device="cuda")
-    plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F)
+    plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col))
     dval = None if val is None else dev(torch.from_numpy(val))
     xd, rd = dev(x), None if r is None else dev(r)
     args = (plan, dev(sg.rowptr), dev(sg.col), dval, xd[:, :F], z[:, :F])
@@ -147,6 +147,13 @@ def test_spmm_epilogues_padding_and_heavy_rows(gas, graphs_small, monkeypatch):
     assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True) <= 1e-5
     assert _spmm_case(gas, g, sg, 128, torch.bfloat16, True, diag=0.5) <= 2e-2
     assert _spmm_case(gas, g, sg, 20, torch.float32, True) <= 1e-5
+    # heavy rows cut at column-window boundaries and processed window by window
+    monkeypatch.setenv("GAS_SPMM_HEAVY", "64")
+    monkeypatch.setenv("GAS_SPMM_CHUNK", "64")
+    for window in ("1000", "37", "1000000"):
+        monkeypatch.setenv("GAS_SPMM_WINDOW", window)
+        assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True) <= 1e-5
+        assert _spmm_case(gas, g, sg, 256, torch.bfloat16, False, diag=1.0) <= 2e-2
 
 
 def test_spmm_empty_rows_and_empty_matrix(gas):

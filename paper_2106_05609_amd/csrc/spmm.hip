@@ -593,15 +593,31 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
     // wavefronts that run at the same time gather from the same range of feature rows, which therefore stay
     // in the caches between their uses.  The partial sums keep their row-major slots, so the order in which
     // a row's partials are added does not depend on the processing order.
-    const int window = env_int("GAS_SPMM_WINDOW", 32768, 0, 1 << 30);
+    // The window is at least GAS_SPMM_WINDOW rows (default 32768, 32 MB of 1 KiB rows; 0 turns windows off) and
+    // wide enough that an average heavy row keeps about 32 entries per window: narrower windows would shred
+    // the rows into tiny chunks whose partial sums cost more traffic than the reuse saves.
+    int64_t window = env_int("GAS_SPMM_WINDOW", 32768, 0, 1 << 30);
     std::vector<int32_t> h_ind;
-    bool any_heavy = false;
-    for (int64_t r = 0; r < n_rows && !any_heavy; ++r) any_heavy = h_ptr[r + 1] - h_ptr[r] > p->threshold;
-    if (ind && window > 0 && any_heavy) {
+    int64_t n_heavy_rows = 0, heavy_entries = 0;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int64_t len = h_ptr[r + 1] - h_ptr[r];
+        if (len > p->threshold) { ++n_heavy_rows; heavy_entries += len; }
+    }
+    if (ind && window > 0 && n_heavy_rows > 0) {
         h_ind.resize((size_t)nnz);
         hipError_t e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
+        int64_t max_col = 0;
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (h_ptr[r + 1] - h_ptr[r] > p->threshold) {      // rows are ascending: look at both ends
+                for (int32_t k : {h_ptr[r], h_ptr[r + 1] - 1}) {
+                    const int64_t v = h_ind[k] >= 0 ? h_ind[k] : -1 - (int64_t)h_ind[k];
+                    if (v > max_col) max_col = v;
+                }
+            }
+        const int64_t keep32 = (max_col + 1) * 32 / (heavy_entries / n_heavy_rows);
+        if (keep32 > window) window = keep32;
     }
     std::vector<int32_t> chunk, heavy_row, heavy_first, group, chunk_window;
     const bool grouping = env_int("GAS_SPMM_GROUPS", 1, 0, 1) != 0;
@@ -638,7 +654,7 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
                 int32_t c = b;
                 while (c < e) {
                     // negative indices (history rows of the in-place variant) order like their magnitudes
-                    auto key = [&](int32_t k) { const int32_t v = h_ind[k]; return (v >= 0 ? v : -1 - v) / window; };
+                    auto key = [&](int32_t k) { const int64_t v = h_ind[k]; return (int32_t)((v >= 0 ? v : -1 - v) / window); };
                     const int32_t w = key(c);
                     int32_t stop = c + 1;
                     while (stop < e && stop - c < p->chunk && key(stop) == w) ++stop;

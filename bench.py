@@ -10,9 +10,14 @@ workload, for a middle layer (hidden width in and out):
     gas_push    in-batch rows -> history table l+1
     gas_spmm_t  backward aggregation over the CSC copy
 
+It is timed in two forms that give the same result bit for bit: as these five
+launches ("separate"), and with the aggregation reading the halo rows from the
+history table itself (gas_spmm_hist, "in-place": no pull launch, no halo copy).
+The headline value is the in-place form; the other one is reported beside it.
+
 All inputs are resident in HBM before the timed region.  Prints one JSON line
 with the whole-step throughput in aggregated edges per second, the roofline of
-the dominant kernel (the aggregation) and the CPU oracle timed on a bounded
+the dominant call (the aggregation) and the CPU oracle timed on a bounded
 sample of the same workload.
 """
 import argparse
@@ -161,7 +166,8 @@ def main():
                    "scale": args.scale},
         "hbm_pull_spmm_push": head["hbm_pull_spmm_push"],
         "kernels": head["kernels"],
-        "roofline": {"kernel": "spmm_kernel (" + ("gas_spmm_hist" if fused_head else "gas_spmm") + ")", "bound": "hbm",
+        "roofline": {"kernel": ("gas_spmm_hist" if fused_head else "gas_spmm")
+                               + " = spmm_chunk_kernel + spmm_heavy_reduce_kernel + spmm_rows_kernel", "bound": "hbm",
                      "achieved": round(spmm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(spmm_gbs / HBM_PEAK_GBS, 4), "traffic": load_traffic(args.config, args.scale)},
     }
@@ -181,7 +187,7 @@ def load_traffic(config, scale):
         return None
     try:
         with open(path) as f:
-            return json.load(f).get(f"config{config}", {}).get("spmm_kernel_bytes")
+            return json.load(f).get(f"config{config}", {}).get("spmm_bytes")
     except Exception:
         return None
 

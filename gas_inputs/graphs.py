@@ -234,3 +234,28 @@ def chung_lu_bfs_blocks(n: int, exponent: float, mean_degree: float, max_degree:
     g = chung_lu(n, exponent, mean_degree, max_degree, seed, device)
     order = bfs_order(g, seed)
     return relabel(g, order, equal_block_ptr(n, n_blocks))
+
+
+def batch_with_outside_links(n_batch: int, n_outside: int, links: int, seed: int, device="cpu") -> Graph:
+    """The paper's synthetic overhead workload (Section 5, runtime analysis): a mini-batch of `n_batch` nodes,
+    each randomly linked to `links` other nodes of the batch, plus `n_outside` out-of-batch nodes each randomly
+    linked to `links` nodes inside the batch.  Nodes 0..n_batch-1 are the batch (block 0), the rest block 1.
+    "Linked to 60 other nodes" is read as an average degree of 60 inside the batch: every node draws links/2
+    partners and the union is symmetrised; an outside node draws `links` distinct-or-not partners, deduplicated."""
+    node = torch.arange(n_batch, dtype=torch.int64, device=device)
+    half = max(1, links // 2)
+    src = node.repeat_interleave(half)
+    slot = torch.arange(src.numel(), dtype=torch.int64, device=device)
+    dst = rng.randint(seed, 20, slot, n_batch - 1)
+    dst = torch.where(dst >= src, dst + 1, dst)                     # anyone but oneself
+    n = n_batch + n_outside
+    pairs_a, pairs_b = [src], [dst]
+    if n_outside > 0:
+        out = n_batch + torch.arange(n_outside, dtype=torch.int64, device=device)
+        osrc = out.repeat_interleave(links)
+        oslot = torch.arange(osrc.numel(), dtype=torch.int64, device=device)
+        pairs_a.append(osrc)
+        pairs_b.append(rng.randint(seed, 21, oslot, n_batch))
+    a, b = torch.cat(pairs_a), torch.cat(pairs_b)
+    block_ptr = torch.tensor([0, n_batch, n], dtype=torch.int64)
+    return _csr_from_unordered_pairs(n, _dedup_pairs(n, a, b), block_ptr)

@@ -572,7 +572,7 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
     hipStream_t s = (hipStream_t)stream;
     gas_plan* p = new gas_plan();
     p->n_rows = n_rows; p->nnz = nnz; p->max_F = max_F;
-    p->threshold = env_int("GAS_SPMM_HEAVY", 256, 1, 1 << 24);
+    p->threshold = env_int("GAS_SPMM_HEAVY", 512, 1, 1 << 24);
     p->chunk = env_int("GAS_SPMM_CHUNK", 256, 32, 1 << 24);
     p->slices = env_int("GAS_SPMM_SLICES", 1, 1, 8);
     if (p->slices & (p->slices - 1)) p->slices = 1;

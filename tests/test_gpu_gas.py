@@ -120,3 +120,26 @@ def test_fused_execution_matches_oracle(cfg_id, scale):
         assert max_rel_err(to_np(y_gpu), y_cpu) <= TOL[cfg.dtype]
     for a, c in zip(hs_gpu, hs_cpu):
         assert max_rel_err(to_np(a), c) <= TOL[cfg.dtype]
+
+
+def test_paper_overhead_workload_matches_oracle():
+    """The paper's synthetic runtime workload (Section 5): 4-layer GIN, batch of 4,000 nodes x 60 links,
+    out-of-batch nodes x 60 links, at ratio 1; both history-access variants against the oracle."""
+    from gas_inputs import graphs, rng
+    from paper_2106_05609_amd import executor
+    nb, F, L = 4000, 64, 4
+    g = graphs.batch_with_outside_links(nb, 4000, 60, seed=0)
+    sg = batches.batch_subgraph(g, torch.arange(nb), False)
+    assert sg.nb == nb and sg.nh == 4000 and abs((sg.col >= nb).sum().item() / (sg.col < nb).sum().item() - 1.0) < 0.02
+    ws = [(rng.glorot_uniform(0, 400 + 2 * l, F, F), rng.glorot_uniform(0, 401 + 2 * l, F, F)) for l in range(L)]
+    x = rng.normal_matrix(0, 410, g.n, F)
+    hist = [rng.normal_matrix(0, 411 + l, g.n, F) for l in range(L - 1)]
+    om = omodel.Model("gin", [(to_np(a), to_np(b)) for a, b in ws])
+    want = omodel.gas_batch_forward(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), nb, to_np(g.deg), to_np(x),
+                                    [to_np(h).copy() for h in hist])
+    d = lambda t: t.to("cuda")
+    gm = executor.Model("gin", [(d(a), d(b)) for a, b in ws])
+    bg = executor.BatchGraph(nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=F, normalise=False)
+    for fn in (executor.forward_batch, executor.forward_batch_fused):
+        y = fn(gm, bg, d(x), [d(h).clone() for h in hist])
+        assert max_rel_err(to_np(y), want) <= 1e-5, fn.__name__

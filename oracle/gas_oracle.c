@@ -128,9 +128,9 @@ void oracle_spmm(const int32_t* rowptr, const int32_t* col, const float* val, do
 }
 
 /* Adjoint of the aggregation, written from the SAME row-major entries as the
- * forward: GX[col[k],:] += val[k] * G[v,:] for every stored (v, col[k]), plus
- * diag * G[u,:] for u < n_rows.  Rows u >= n_out of GX are not produced. */
-void oracle_spmm_t(const int32_t* rowptr, const int32_t* col, const float* val, double diag,
+ * forward: GX[col[k],:] += s_agg * val[k] * G[v,:] for every stored (v, col[k]),
+ * plus diag * G[u,:] for u < n_rows.  Rows u >= n_out of GX are not produced. */
+void oracle_spmm_t(const int32_t* rowptr, const int32_t* col, const float* val, double diag, double s_agg,
                    const void* G, int64_t ldg, int dtg, int32_t F, int64_t n_rows,
                    int64_t n_out, void* GX, int64_t ldgx, int dtgx) {
     double* acc = (double*)calloc((size_t)n_out * F, sizeof(double));
@@ -143,7 +143,7 @@ void oracle_spmm_t(const int32_t* rowptr, const int32_t* col, const float* val, 
         }
     for (int64_t u = 0; u < n_out; ++u)
         for (int32_t j = 0; j < F; ++j) {
-            double g = acc[u * F + j];
+            double g = s_agg * acc[u * F + j];
             if (diag != 0.0 && u < n_rows) g += diag * load_elem(G, u * ldg + j, dtg);
             store_elem(GX, u * ldgx + j, dtgx, g);
         }
@@ -208,4 +208,52 @@ int oracle_num_threads(void) {
     }
 #endif
     return n;
+}
+
+/* ------------------------------------------------------------------------
+ * Backward pass of the transform (chain rule on the operator equations of the
+ * paper's operator appendix; the paper itself only states that gradients are
+ * taken through the layers, Section 2 advantage (1)).
+ * ------------------------------------------------------------------------ */
+
+/* ReLU backward: GP = GY where Y > 0, else 0. */
+void oracle_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy, int64_t n_rows, int32_t F,
+                     int dt, void* GP, int64_t ldgp) {
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t j = 0; j < F; ++j) {
+            double y = load_elem(Y, i * ldy + j, dt);
+            store_elem(GP, i * ldgp + j, dt, y > 0.0 ? load_elem(GY, i * ldgy + j, dt) : 0.0);
+        }
+}
+
+/* Input gradient of Y = c_identity * Z + c_weight * (Z W):
+ *   GZ = c_identity * GP + c_weight * (GP W^T),  then GZ *= [mask > 0] if a mask is given
+ * (the mask is the hidden activation of a GIN MLP).  W is [F_in, F_out]. */
+void oracle_linear_bwd_input(const void* GP, int64_t ldgp, int64_t n_rows, int32_t F_out,
+                             const void* W, int32_t F_in, int dt, double c_identity, double c_weight,
+                             const void* mask, int64_t ldmask, void* GZ, int64_t ldgz) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t k = 0; k < F_in; ++k) {
+            double s = 0.0;
+            for (int32_t j = 0; j < F_out; ++j)
+                s += load_elem(GP, i * ldgp + j, dt) * load_elem(W, (int64_t)k * F_out + j, dt);
+            double g = c_weight * s;
+            if (c_identity != 0.0) g += c_identity * load_elem(GP, i * ldgp + k, dt);
+            if (mask && !(load_elem(mask, i * ldmask + k, dt) > 0.0)) g = 0.0;
+            store_elem(GZ, i * ldgz + k, dt, g);
+        }
+}
+
+/* Weight gradient of the same transform: dW[k, j] = c_weight * sum_i Z[i, k] * GP[i, j], kept in fp32. */
+void oracle_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
+                              int32_t F_in, int32_t F_out, int dt, double c_weight, float* dW) {
+#pragma omp parallel for schedule(static)
+    for (int32_t k = 0; k < F_in; ++k)
+        for (int32_t j = 0; j < F_out; ++j) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n_rows; ++i)
+                s += load_elem(Z, i * ldz + k, dt) * load_elem(GP, i * ldgp + j, dt);
+            dW[(int64_t)k * F_out + j] = (float)(c_weight * s);
+        }
 }

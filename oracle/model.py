@@ -171,3 +171,93 @@ def dense_adjacency(n_id, rowptr, col, val, nb):
         for k in range(rowptr[v], rowptr[v + 1]):
             a[v, col[k]] += 1.0 if val is None else float(val[k])
     return a
+
+
+# ----------------------------------------------------------------------------
+# one mini-batch forward + backward (training step without the optimiser)
+# ----------------------------------------------------------------------------
+def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, grad_out, do_push=True):
+    """Forward as gas_batch_forward (GIN's MLP as two stored linears), then the chain rule backwards.
+
+    Historical embeddings are constants: gradients flow through in-batch rows only, layer by layer
+    (the pulled halo rows of layers >= 2 receive none).  GCNII's input projection is computed in-graph for
+    halo rows too, so its weight gradient includes them.  `grad_out` is dLoss/dY_L [nb, F_L] in the storage
+    dtype.  Returns (Y_L, grads) with grads[l] = dW_l (or (dW1, dW2) for GIN) as float32, and grads["w_in"]
+    for GCNII."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    val = ops.gcn_norm(rowptr, col, n_id, deg) if model.op in ("gcn", "gcnii") else None
+    x0 = ops.pull(x_feat, n_id)
+    x = x0
+    h0 = None
+    if model.op == "gcnii":
+        h0 = ops.linear(x0, model.w_in, relu=True)
+        x = h0
+    L = model.n_layers
+    saved = []
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        if model.op == "gcn":
+            z = ops.spmm(rowptr, col, val, x)
+            y = ops.linear(z, model.weights[l - 1], relu=not last)
+            saved.append((z, None, y))
+        elif model.op == "gin":
+            z = ops.spmm(rowptr, col, None, x, diag=1.0 + model.gin_eps)
+            w1, w2 = model.weights[l - 1]
+            h = ops.linear(z, w1, relu=True)
+            y = ops.linear(h, w2, relu=not last)
+            saved.append((z, h, y))
+        else:
+            z = ops.spmm(rowptr, col, val, x, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            b = model.betas[l - 1]
+            y = ops.linear(z, model.weights[l - 1], c_identity=1.0 - b, c_weight=b, relu=not last)
+            saved.append((z, None, y))
+        if last:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        xn = np.empty((nv, y.shape[1]), dtype=y.dtype)
+        xn[:nb] = y
+        xn[nb:] = ops.pull(histories[l - 1], n_id[nb:])
+        x = xn
+    # ---- backward
+    grads = {}
+    g = np.ascontiguousarray(grad_out)
+    g_h0 = None           # GCNII: gradient w.r.t. the initial embedding, all nv rows, accumulated in float64
+    for l in range(L, 0, -1):
+        z, h, yl = saved[l - 1]
+        if l != L:
+            g = ops.relu_bwd(g, yl)
+        if model.op == "gcn":
+            grads[l - 1] = ops.linear_bwd_weight(z, g)
+            gz = ops.linear_bwd_input(g, model.weights[l - 1])
+        elif model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            dw2 = ops.linear_bwd_weight(h, g)
+            gh = ops.linear_bwd_input(g, w2, mask=h)
+            grads[l - 1] = (ops.linear_bwd_weight(z, gh), dw2)
+            gz = ops.linear_bwd_input(gh, w1)
+        else:
+            b = model.betas[l - 1]
+            grads[l - 1] = ops.linear_bwd_weight(z, g, c_weight=b)
+            gz = ops.linear_bwd_input(g, model.weights[l - 1], c_identity=1.0 - b, c_weight=b)
+            if g_h0 is None:
+                g_h0 = np.zeros((nv, gz.shape[1]), dtype=np.float64)
+            g_h0[:nb] += model.alpha * ops.to_f64(gz)
+        if l == 1:
+            if model.op == "gcnii":
+                # layer 1 aggregates h0 itself, for every column of the batch subgraph (halo rows included)
+                gx = ops.spmm_t(rowptr, col, val, gz, nv, s_agg=1.0 - model.alpha)
+                g_h0 += ops.to_f64(gx)
+            break
+        if model.op == "gin":
+            g = ops.spmm_t(rowptr, col, None, gz, nb, diag=1.0 + model.gin_eps)
+        elif model.op == "gcn":
+            g = ops.spmm_t(rowptr, col, val, gz, nb)
+        else:
+            g = ops.spmm_t(rowptr, col, val, gz, nb, s_agg=1.0 - model.alpha)
+    if model.op == "gcnii":
+        gh0 = np.where(ops.to_f64(h0) > 0.0, g_h0, 0.0)
+        grads["w_in"] = (ops.to_f64(x0).T @ gh0).astype(np.float32)
+    return y, grads

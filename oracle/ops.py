@@ -114,7 +114,7 @@ def spmm(rowptr, col, val, x, diag=0.0, s_agg=1.0, r=None, s_res=0.0, out_dt=Non
     return z
 
 
-def spmm_t(rowptr, col, val, g, n_out, diag=0.0, out_dt=None) -> np.ndarray:
+def spmm_t(rowptr, col, val, g, n_out, diag=0.0, out_dt=None, s_agg=1.0) -> np.ndarray:
     rowptr, col = _i32(rowptr), _i32(col)
     g, ldg = _rows(g)
     n_rows, f = rowptr.size - 1, g.shape[1]
@@ -124,7 +124,7 @@ def spmm_t(rowptr, col, val, g, n_out, diag=0.0, out_dt=None) -> np.ndarray:
         assert val.dtype == np.float32
     out_dt = _dt(g) if out_dt is None else out_dt
     gx = np.empty((n_out, f), dtype=_np_dtype(out_dt))
-    lib().oracle_spmm_t(_p(rowptr), _p(col), _p(val), C.c_double(diag), _p(g), C.c_int64(ldg), C.c_int(_dt(g)),
+    lib().oracle_spmm_t(_p(rowptr), _p(col), _p(val), C.c_double(diag), C.c_double(s_agg), _p(g), C.c_int64(ldg), C.c_int(_dt(g)),
                         C.c_int32(f), C.c_int64(n_rows), C.c_int64(n_out), _p(gx), C.c_int64(f), C.c_int(out_dt))
     return gx
 
@@ -153,3 +153,41 @@ def mlp2(z, w1, w2, b1=None, b2=None, relu_out=False, out_dt=None) -> np.ndarray
                       C.c_int32(w1.shape[1]), _p(b1), _p(w2), C.c_int32(w2.shape[1]), _p(b2), C.c_int(_dt(z)),
                       C.c_int(int(relu_out)), _p(y), C.c_int64(w2.shape[1]), C.c_int(out_dt))
     return y
+
+
+def relu_bwd(gy, y) -> np.ndarray:
+    gy, ldgy = _rows(gy)
+    y, ldy = _rows(y)
+    assert gy.shape == y.shape and gy.dtype == y.dtype
+    gp = np.empty(gy.shape, dtype=gy.dtype)
+    lib().oracle_relu_bwd(_p(gy), C.c_int64(ldgy), _p(y), C.c_int64(ldy), C.c_int64(gy.shape[0]), C.c_int32(gy.shape[1]),
+                          C.c_int(_dt(gy)), _p(gp), C.c_int64(gy.shape[1]))
+    return gp
+
+
+def linear_bwd_input(gp, w, c_identity=0.0, c_weight=1.0, mask=None) -> np.ndarray:
+    """gp [n, F_out], w [F_in, F_out] -> gz [n, F_in]."""
+    gp, ldgp = _rows(gp)
+    w = np.ascontiguousarray(w)
+    assert w.dtype == gp.dtype and w.shape[1] == gp.shape[1]
+    ldm = 0
+    if mask is not None:
+        mask, ldm = _rows(mask)
+        assert mask.dtype == gp.dtype and mask.shape == (gp.shape[0], w.shape[0])
+    gz = np.empty((gp.shape[0], w.shape[0]), dtype=gp.dtype)
+    lib().oracle_linear_bwd_input(_p(gp), C.c_int64(ldgp), C.c_int64(gp.shape[0]), C.c_int32(gp.shape[1]), _p(w),
+                                  C.c_int32(w.shape[0]), C.c_int(_dt(gp)), C.c_double(c_identity), C.c_double(c_weight),
+                                  _p(mask), C.c_int64(ldm), _p(gz), C.c_int64(w.shape[0]))
+    return gz
+
+
+def linear_bwd_weight(z, gp, c_weight=1.0) -> np.ndarray:
+    """z [n, F_in], gp [n, F_out] -> dW [F_in, F_out] float32."""
+    z, ldz = _rows(z)
+    gp, ldgp = _rows(gp)
+    assert z.dtype == gp.dtype and z.shape[0] == gp.shape[0]
+    dw = np.empty((z.shape[1], gp.shape[1]), dtype=np.float32)
+    lib().oracle_linear_bwd_weight(_p(z), C.c_int64(ldz), _p(gp), C.c_int64(ldgp), C.c_int64(z.shape[0]),
+                                   C.c_int32(z.shape[1]), C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_double(c_weight),
+                                   _p(dw))
+    return dw

@@ -167,7 +167,7 @@ GAS_API gas_status gas_fuse_sources(const int32_t* col, int64_t nnz, int64_t nb,
 /*
  * Backward aggregation: the adjoint of gas_spmm's sum, computed as a
  * row-parallel product over the CSC copy of the same pattern (no atomics):
- *     GX[u, :] = sum_{k in column u} val[k] * G[row[k], :] + [u < n_diag] diag * G[u, :]
+ *     GX[u, :] = s_agg * sum_{k in column u} val[k] * G[row[k], :] + [u < n_diag] diag * G[u, :]
  * for u in [0, n_out), n_out being the row count of the plan.  colptr
  * int32[n_out+1], row int32[nnz], val in CSC order.  n_out = number of
  * in-batch nodes when gradients into halo rows are not needed (histories are
@@ -176,7 +176,7 @@ GAS_API gas_status gas_fuse_sources(const int32_t* col, int64_t nnz, int64_t nb,
  * `plan` must have been created from colptr[0 .. n_out].
  */
 GAS_API gas_status gas_spmm_t(const gas_plan* plan, const int32_t* colptr, const int32_t* row,
-                      const float* val, float diag, int64_t n_diag,
+                      const float* val, float diag, float s_agg, int64_t n_diag,
                       const void* G, int64_t ldg, gas_dtype dt_g, int32_t F,
                       void* GX, int64_t ldgx, gas_dtype dt_gx, void* stream);
 
@@ -205,6 +205,34 @@ GAS_API gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t 
                     const void* W1, int32_t F_hid, const void* b1,
                     const void* W2, int32_t F_out, const void* b2, gas_dtype dt,
                     int relu_out, void* Y, int64_t ldy, void* stream);
+
+/*
+ * Backward pass of the transform (chain rule on the operator equations; the
+ * paper takes gradients through its layers, Section 2 advantage (1), without
+ * spelling them out).  With P = c_identity * Z + c_weight * (Z W) and Y = relu(P):
+ *
+ * gas_relu_bwd:            GP = GY where Y > 0, else 0 (element-wise; GP may alias GY).
+ * gas_linear_bwd_input:    GZ = c_identity * GP + c_weight * (GP W^T), then, if mask != NULL,
+ *                          GZ = 0 where mask <= 0 (mask [n_rows, F_in] is the hidden
+ *                          activation of a GIN MLP: the ReLU between its two linears).
+ *                          GP [n_rows, F_out], W [F_in, F_out] as in gas_linear, GZ [n_rows, F_in].
+ * gas_linear_bwd_weight:   dW [F_in, F_out] fp32 = c_weight * Z^T GP.  The sum over the rows
+ *                          is formed in slabs of rows whose partial results go to
+ *                          `workspace` (device memory, at least
+ *                          gas_linear_bwd_weight_workspace(n_rows, F_in, F_out) bytes, caller-
+ *                          owned, contents undefined afterwards) and are added in slab order:
+ *                          no atomics, bit-identical from run to run.
+ * All matrices have type dt except dW (fp32).  Products run on the matrix cores.
+ */
+GAS_API gas_status gas_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy, int64_t n_rows,
+                        int32_t F, gas_dtype dt, void* GP, int64_t ldgp, void* stream);
+GAS_API gas_status gas_linear_bwd_input(const void* GP, int64_t ldgp, int64_t n_rows, int32_t F_out,
+                                const void* W, int32_t F_in, gas_dtype dt, float c_identity, float c_weight,
+                                const void* mask, int64_t ldmask, void* GZ, int64_t ldgz, void* stream);
+GAS_API int64_t gas_linear_bwd_weight_workspace(int64_t n_rows, int32_t F_in, int32_t F_out);
+GAS_API gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp,
+                                 int64_t n_rows, int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight,
+                                 float* dW, void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a

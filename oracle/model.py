@@ -221,7 +221,15 @@ def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories,
         xn[:nb] = y
         xn[nb:] = ops.pull(histories[l - 1], n_id[nb:])
         x = xn
-    # ---- backward
+    return y, gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, grad_out)
+
+
+def gas_batch_backward(model: Model, n_id, rowptr, col, nb, val, x0, h0, saved, grad_out):
+    """The chain rule backwards through the layers, from the activations a forward pass has kept:
+    saved[l] = (Z, hidden or None, Y) of layer l+1, x0 = the pulled features, h0 = GCNII's initial embedding.
+    The ReLU masks are read off these stored activations."""
+    nv = len(n_id)
+    L = model.n_layers
     grads = {}
     g = np.ascontiguousarray(grad_out)
     g_h0 = None           # GCNII: gradient w.r.t. the initial embedding, all nv rows, accumulated in float64
@@ -260,4 +268,4 @@ def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories,
     if model.op == "gcnii":
         gh0 = np.where(ops.to_f64(h0) > 0.0, g_h0, 0.0)
         grads["w_in"] = (ops.to_f64(x0).T @ gh0).astype(np.float32)
-    return y, grads
+    return grads

@@ -13,7 +13,8 @@ F32, BF16 = 0, 1
 OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
-           "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices"]
+           "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace"]
 
 _lib = None
 
@@ -35,8 +36,9 @@ def lib():
         L.gas_last_error.restype = C.c_char_p
         L.gas_version.restype = C.c_int
         L.gas_plan_destroy.restype = None
+        L.gas_linear_bwd_weight_workspace.restype = C.c_int64
         for name in EXPORTS:
-            if name not in ("gas_last_error", "gas_version", "gas_plan_destroy"):
+            if name not in ("gas_last_error", "gas_version", "gas_plan_destroy", "gas_linear_bwd_weight_workspace"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -172,13 +174,13 @@ def gas_spmm_hist(plan, rowptr, src, val, x, hist, z, diag=0.0, s_agg=1.0, r=Non
                                C.c_int(_dt(z)), _stream()))
 
 
-def gas_spmm_t(plan, colptr, row, val, g, gx, diag=0.0):
+def gas_spmm_t(plan, colptr, row, val, g, gx, diag=0.0, s_agg=1.0):
     gp, ldg = _mat(g)
     op, ldo = _mat(gx)
     if gx.shape[1] != g.shape[1] or gx.shape[0] < plan.n_rows:
         raise ValueError("gas_spmm_t: GX does not match")
     _check(lib().gas_spmm_t(plan.handle, _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(val, torch.float32),
-                            C.c_float(diag), C.c_int64(g.shape[0]), gp, ldg, C.c_int(_dt(g)), C.c_int32(g.shape[1]),
+                            C.c_float(diag), C.c_float(s_agg), C.c_int64(g.shape[0]), gp, ldg, C.c_int(_dt(g)), C.c_int32(g.shape[1]),
                             op, ldo, C.c_int(_dt(gx)), _stream()))
 
 
@@ -209,3 +211,45 @@ def gas_validate_indices(idx, limit) -> bool:
         return False
     _check(st)
     return True
+
+
+def gas_relu_bwd(gy, y, gp):
+    """gp = gy where y > 0 else 0 (gp may be gy itself)."""
+    a, lda = _mat(gy)
+    b, ldb = _mat(y)
+    c, ldc = _mat(gp)
+    if not (gy.shape == y.shape == gp.shape and gy.dtype == y.dtype == gp.dtype):
+        raise ValueError("gas_relu_bwd: shapes or dtypes do not match")
+    _check(lib().gas_relu_bwd(a, lda, b, ldb, C.c_int64(gy.shape[0]), C.c_int32(gy.shape[1]), C.c_int(_dt(gy)), c, ldc,
+                              _stream()))
+
+
+def gas_linear_bwd_input(gp, w, gz, c_identity=0.0, c_weight=1.0, mask=None):
+    """gz [n, F_in] = c_identity * gp + c_weight * gp @ w.T, zeroed where mask <= 0; w is [F_in, F_out]."""
+    a, lda = _mat(gp)
+    c, ldc = _mat(gz)
+    mp, ldm = (C.c_void_p(0), C.c_int64(0)) if mask is None else _mat(mask)
+    if w.dtype != gp.dtype or gz.dtype != gp.dtype or w.shape[1] != gp.shape[1] or gz.shape != (gp.shape[0], w.shape[0]) \
+            or (mask is not None and (mask.shape != gz.shape or mask.dtype != gp.dtype)):
+        raise ValueError("gas_linear_bwd_input: shapes or dtypes do not match")
+    _check(lib().gas_linear_bwd_input(a, lda, C.c_int64(gp.shape[0]), C.c_int32(gp.shape[1]), _ptr(w),
+                                      C.c_int32(w.shape[0]), C.c_int(_dt(gp)), C.c_float(c_identity),
+                                      C.c_float(c_weight), mp, ldm, c, ldc, _stream()))
+
+
+def gas_linear_bwd_weight_workspace(n_rows, f_in, f_out) -> int:
+    return int(lib().gas_linear_bwd_weight_workspace(C.c_int64(n_rows), C.c_int32(f_in), C.c_int32(f_out)))
+
+
+def gas_linear_bwd_weight(z, gp, dw, workspace, c_weight=1.0):
+    """dw [F_in, F_out] float32 = c_weight * z.T @ gp; workspace: a uint8 tensor of at least
+    gas_linear_bwd_weight_workspace(...) bytes."""
+    a, lda = _mat(z)
+    b, ldb = _mat(gp)
+    if z.dtype != gp.dtype or z.shape[0] != gp.shape[0] or dw.dtype != torch.float32 or \
+            dw.shape != (z.shape[1], gp.shape[1]) or not dw.is_contiguous():
+        raise ValueError("gas_linear_bwd_weight: shapes or dtypes do not match")
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().gas_linear_bwd_weight(a, lda, b, ldb, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]),
+                                       C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_float(c_weight), _ptr(dw),
+                                       _ptr(workspace), C.c_int64(nbytes), _stream()))

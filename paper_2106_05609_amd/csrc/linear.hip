@@ -37,6 +37,8 @@ struct LinArgs {
     int K, N;
     float c_id, c_w;
     int relu;
+    int trans_w;                       // W is given as [N][K] (the product is Z W^T of a [N, K] matrix)
+    const char* mask; int64_t ldmask;  // optional [M, N]: outputs where mask <= 0 are set to zero
 };
 
 struct MlpArgs {
@@ -106,29 +108,49 @@ template <int BN, bool VEC>
 struct BTileF32 {
     static constexpr int NV = kBK * BN / 4 / 256;
     f32x4 r[NV];
-    __device__ __forceinline__ void fetch(const float* W, int K, int N, int k0, int n0, int tid) {
+    // trans: W is [N][K] row-major; a vector then holds 4 consecutive k of one n
+    __device__ __forceinline__ void fetch(const float* W, int K, int N, int k0, int n0, int tid, bool trans = false) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int idx = tid + 256 * i;
-            const int k = k0 + idx / (BN / 4), n = n0 + 4 * (idx % (BN / 4));
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (k < K) {
-                if constexpr (VEC) {
-                    if (n < N) v = *reinterpret_cast<const f32x4*>(W + (int64_t)k * N + n);
-                } else {
+            if (!trans) {
+                const int k = k0 + idx / (BN / 4), n = n0 + 4 * (idx % (BN / 4));
+                if (k < K) {
+                    if constexpr (VEC) {
+                        if (n < N) v = *reinterpret_cast<const f32x4*>(W + (int64_t)k * N + n);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < N) v[e] = W[(int64_t)k * N + n + e];
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) v[e] = W[(int64_t)k * N + n + e];
+                    }
+                }
+            } else {
+                const int n = n0 + idx / (kBK / 4), k = k0 + 4 * (idx % (kBK / 4));
+                if (n < N) {
+                    if constexpr (VEC) {
+                        if (k < K) v = *reinterpret_cast<const f32x4*>(W + (int64_t)n * K + k);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (k + e < K) v[e] = W[(int64_t)n * K + k + e];
+                    }
                 }
             }
             r[i] = v;
         }
     }
-    __device__ __forceinline__ void stage(float (*Bs)[BN + 4], int tid) {
+    __device__ __forceinline__ void stage(float (*Bs)[BN + 4], int tid, bool trans = false) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<f32x4*>(&Bs[idx / (BN / 4)][4 * (idx % (BN / 4))]) = r[i];
+            if (!trans) {
+                *reinterpret_cast<f32x4*>(&Bs[idx / (BN / 4)][4 * (idx % (BN / 4))]) = r[i];
+            } else {
+                const int n = idx / (kBK / 4), k = 4 * (idx % (kBK / 4));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Bs[k + e][n] = r[i][e];
+            }
         }
     }
 };
@@ -173,21 +195,23 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
     zero_acc(acc);
     ATileF32<BM, VEC> ta;
     BTileF32<BN, VEC> tb;
+    const bool tr = a.trans_w != 0;
     ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
-    tb.fetch(W, a.K, a.N, 0, n0, tid);
+    tb.fetch(W, a.K, a.N, 0, n0, tid, tr);
     for (int k0 = 0; k0 < a.K; k0 += kBK) {
         __syncthreads();                 // everyone is done reading the previous tile
         ta.stage(As, tid);
-        tb.stage(Bs, tid);
+        tb.stage(Bs, tid, tr);
         __syncthreads();
         if (k0 + kBK < a.K) {
             ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBK, tid);
-            tb.fetch(W, a.K, a.N, k0 + kBK, n0, tid);
+            tb.fetch(W, a.K, a.N, k0 + kBK, n0, tid, tr);
         }
         mfma_tile_f32<TM, TN, BN>(&As[0][0], kLdA, wm0, 0, Bs, wn0, li, lh, acc);
     }
     float* Y = reinterpret_cast<float*>(a.Y);
     const float* bias = reinterpret_cast<const float*>(a.bias);
+    const float* mask = reinterpret_cast<const float*>(a.mask);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -202,6 +226,7 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
                 float y = a.c_w * acc[i][j][r] + bv;
                 if (a.c_id != 0.f) y += a.c_id * Z[m * a.ldz + n];
                 if (a.relu) y = fmaxf(y, 0.f);
+                if (mask && !(mask[m * a.ldmask + n] > 0.f)) y = 0.f;
                 Y[m * a.ldy + n] = y;
             }
         }
@@ -316,27 +341,46 @@ struct ATileBF16 {
     }
 };
 
-// One kBKh x BN tile of a row-major bf16 [K][N] matrix, transposed into Bs[n][k].
+// One kBKh x BN tile of a bf16 weight matrix into Bs[n][k].  Row-major [K][N]: transposed on the way (8 x 8
+// blocks).  trans (the matrix is [N][K] row-major): already in the layout the MFMA wants, plain 16-byte copies.
 template <int BN>
 struct BTileBF16 {
     u32x4 r[8];
-    __device__ __forceinline__ void fetch(const uint16_t* W, int K, int N, int k0, int n0, int tid) {
-        if (tid >= BN) return;              // kBKh/8 * BN/8 = BN blocks of 8 x 8
-        const int kb = tid / (BN / 8), n = n0 + 8 * (tid % (BN / 8));
+    __device__ __forceinline__ void fetch(const uint16_t* W, int K, int N, int k0, int n0, int tid, bool trans = false) {
+        if (!trans) {
+            if (tid >= BN) return;              // kBKh/8 * BN/8 = BN blocks of 8 x 8
+            const int kb = tid / (BN / 8), n = n0 + 8 * (tid % (BN / 8));
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int k = k0 + 8 * kb + i;
-            r[i] = u32x4{0u, 0u, 0u, 0u};
-            if (k < K && n < N) r[i] = *reinterpret_cast<const u32x4*>(W + (int64_t)k * N + n);
+            for (int i = 0; i < 8; ++i) {
+                const int k = k0 + 8 * kb + i;
+                r[i] = u32x4{0u, 0u, 0u, 0u};
+                if (k < K && n < N) r[i] = *reinterpret_cast<const u32x4*>(W + (int64_t)k * N + n);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < BN / 32; ++i) {  // BN * 8 pieces of 16 bytes over 256 threads
+                const int idx = tid + 256 * i;
+                const int n = n0 + (idx >> 3), k = k0 + 8 * (idx & 7);
+                r[i] = u32x4{0u, 0u, 0u, 0u};
+                if (n < N && k < K) r[i] = *reinterpret_cast<const u32x4*>(W + (int64_t)n * K + k);
+            }
         }
     }
-    __device__ __forceinline__ void stage(uint16_t (*Bs)[kLdh], int tid) {
-        if (tid >= BN) return;
-        const int kb = tid / (BN / 8), nb = tid % (BN / 8);
-        u32x4 t[8];
-        transpose8x8_bf16(r, t);
+    __device__ __forceinline__ void stage(uint16_t (*Bs)[kLdh], int tid, bool trans = false) {
+        if (!trans) {
+            if (tid >= BN) return;
+            const int kb = tid / (BN / 8), nb = tid % (BN / 8);
+            u32x4 t[8];
+            transpose8x8_bf16(r, t);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(&Bs[8 * nb + c][8 * kb]) = t[c];
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(&Bs[8 * nb + c][8 * kb]) = t[c];
+        } else {
+#pragma unroll
+            for (int i = 0; i < BN / 32; ++i) {
+                const int idx = tid + 256 * i;
+                *reinterpret_cast<u32x4*>(&Bs[idx >> 3][8 * (idx & 7)]) = r[i];
+            }
+        }
     }
 };
 
@@ -378,21 +422,23 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(LinArgs a) {
     zero_acc(acc);
     ATileBF16<BM> ta;
     BTileBF16<BN> tb;
+    const bool tr = a.trans_w != 0;
     ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
-    tb.fetch(W, a.K, a.N, 0, n0, tid);
+    tb.fetch(W, a.K, a.N, 0, n0, tid, tr);
     for (int k0 = 0; k0 < a.K; k0 += kBKh) {
         __syncthreads();
         ta.stage(As, tid);
-        tb.stage(Bs, tid);
+        tb.stage(Bs, tid, tr);
         __syncthreads();
         if (k0 + kBKh < a.K) {
             ta.fetch(Z, a.ldz, a.M, a.K, m0, k0 + kBKh, tid);
-            tb.fetch(W, a.K, a.N, k0 + kBKh, n0, tid);
+            tb.fetch(W, a.K, a.N, k0 + kBKh, n0, tid, tr);
         }
         mfma_tile_bf16<TM, TN>(&As[0][0], kLdh, wm0, 0, Bs, wn0, li, lh, acc);
     }
     uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
     const uint16_t* bias = reinterpret_cast<const uint16_t*>(a.bias);
+    const uint16_t* mask = reinterpret_cast<const uint16_t*>(a.mask);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -407,6 +453,7 @@ __global__ __launch_bounds__(256) void linear_bf16_kernel(LinArgs a) {
                 float y = a.c_w * acc[i][j][r] + bv;
                 if (a.c_id != 0.f) y += a.c_id * bf16_val(Z, m * a.ldz + n);
                 if (a.relu) y = fmaxf(y, 0.f);
+                if (mask && !(bf16_val(mask, m * a.ldmask + n) > 0.f)) y = 0.f;
                 Y[m * a.ldy + n] = (uint16_t)f32_to_bf16(y);
             }
         }
@@ -502,21 +549,29 @@ struct WsArgs {
     int K, H, N;        // single product: H == N is the output width and W2 is unused
     float c_id, c_w;
     int relu1, relu_out;
+    int trans_w1;                          // W1 is given as [H][K] (single product only)
+    const uint16_t* mask; int64_t ldmask;  // optional [M, N]: outputs where mask <= 0 are set to zero
 };
 
 constexpr int kWsRows = 64;
 
 template <int KT>
-__device__ __forceinline__ void load_w_frags(const uint16_t* W, int K, int ncols, int col, int lh, bf16x8 (&f)[KT]) {
+__device__ __forceinline__ void load_w_frags(const uint16_t* W, int K, int ncols, int col, int lh, bf16x8 (&f)[KT],
+                                             bool trans = false) {
 #pragma unroll
     for (int kk = 0; kk < KT; ++kk) {
         u32x4 v = {0u, 0u, 0u, 0u};
+        if (trans) {                     // [ncols][K] row-major, K a multiple of 8: the fragment is contiguous
+            const int k = 16 * kk + 8 * lh;
+            if (k < K && col < ncols) v = *reinterpret_cast<const u32x4*>(W + (int64_t)col * K + k);
+        } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int k = 16 * kk + 8 * lh + e;
-            uint32_t x = 0;
-            if (k < K && col < ncols) x = W[(int64_t)k * ncols + col];
-            v[e >> 1] |= x << (16 * (e & 1));
+            for (int e = 0; e < 8; ++e) {
+                const int k = 16 * kk + 8 * lh + e;
+                uint32_t x = 0;
+                if (k < K && col < ncols) x = W[(int64_t)k * ncols + col];
+                v[e >> 1] |= x << (16 * (e & 1));
+            }
         }
         f[kk] = __builtin_bit_cast(bf16x8, v);
     }
@@ -545,7 +600,7 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
 
     bf16x8 w1f[KT1];
     bf16x8 w2f[TWO ? KT2 : 1];
-    load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f);
+    load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f, !TWO && a.trans_w1 != 0);
     if constexpr (TWO) load_w_frags<KT2>(a.W2, a.H, a.N, 32 * wave + li, lh, w2f);
     // output columns of this lane: n(q, e) = 32*wave + 8*q + 4*lh + e, q, e in 0..3
     const int nbase = 32 * wave + 4 * lh;
@@ -674,9 +729,18 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
             for (int idx = tid; idx < kWsRows * vpr; idx += 512) {
                 const int row = idx / vpr, v = idx % vpr;
                 const int64_t m = tile * kWsRows + row;
-                if (m < a.M)
-                    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v),
-                                                reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
+                if (m < a.M) {
+                    u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
+                    if (a.mask) {
+                        const u32x4 k = *reinterpret_cast<const u32x4*>(a.mask + m * a.ldmask + 8 * v);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            if (!(bf16_lo(k[q]) > 0.f)) o[q] &= 0xFFFF0000u;
+                            if (!(bf16_hi(k[q]) > 0.f)) o[q] &= 0x0000FFFFu;
+                        }
+                    }
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
+                }
             }
         }
     }
@@ -710,11 +774,13 @@ __global__ __launch_bounds__(256) void linear_bf16_generic_kernel(LinArgs a) {
     const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
     const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W);
     float s = 0.f;
-    for (int k = 0; k < a.K; ++k) s = fmaf(bf16_val(Z, m * a.ldz + k), bf16_val(W, (int64_t)k * a.N + n), s);
+    for (int k = 0; k < a.K; ++k)
+        s = fmaf(bf16_val(Z, m * a.ldz + k), bf16_val(W, a.trans_w ? (int64_t)n * a.K + k : (int64_t)k * a.N + n), s);
     float y = a.c_w * s;
     if (a.bias) y += bf16_val(reinterpret_cast<const uint16_t*>(a.bias), n);
     if (a.c_id != 0.f) y += a.c_id * bf16_val(Z, m * a.ldz + n);
     if (a.relu) y = fmaxf(y, 0.f);
+    if (a.mask && !(bf16_val(reinterpret_cast<const uint16_t*>(a.mask), m * a.ldmask + n) > 0.f)) y = 0.f;
     reinterpret_cast<uint16_t*>(a.Y)[m * a.ldy + n] = (uint16_t)f32_to_bf16(y);
 }
 
@@ -744,6 +810,225 @@ __global__ __launch_bounds__(256) void mlp2_generic_kernel(MlpArgs a) {
         if (a.relu_out) s = fmaxf(s, 0.f);
         if constexpr (BF) reinterpret_cast<uint16_t*>(a.Y)[m * a.ldy + n] = (uint16_t)f32_to_bf16(s);
         else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = s;
+    }
+}
+
+// ====================================================================== backward kernels
+// Weight gradient dW[k, j] = c_w * sum_m Z[m, k] * G[m, j]: the reduction runs over the rows.  The rows are cut
+// into slabs; a workgroup forms the 128 x 128 tile (tk, tj) of the partial product of one slab in fp32 and
+// writes it to the workspace; dw_reduce_kernel adds the slabs in slab order (fixed order, no atomics).
+constexpr int kDwSlab = 4096;      // rows per slab
+constexpr int kDwTile = 128;
+
+struct DwArgs {
+    const char* Z;  int64_t ldz;
+    const char* G;  int64_t ldg;
+    int64_t M;
+    int K, N;                       // F_in, F_out
+    float c_w;
+    float* partial;                 // [n_slabs][K][N]
+    float* dW;                      // [K][N]
+    int n_slabs;
+};
+
+// fp32: both operands are read as single dwords from row-major LDS tiles (lanes run along the feature index).
+template <bool VEC>
+__global__ __launch_bounds__(256) void dw_f32_kernel(DwArgs a) {
+    constexpr int BM = 32;                                  // rows per step
+    __shared__ __attribute__((aligned(16))) float Zs[BM][kDwTile + 4];
+    __shared__ __attribute__((aligned(16))) float Gs[BM][kDwTile + 4];
+    const float* Z = reinterpret_cast<const float*>(a.Z);
+    const float* G = reinterpret_cast<const float*>(a.G);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int slab = blockIdx.x, k0 = blockIdx.y * kDwTile, n0 = blockIdx.z * kDwTile;
+    const int64_t m_begin = (int64_t)slab * kDwSlab;
+    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+    f32x16 acc[2][2];
+    zero_acc(acc);
+    f32x4 rz[4], rg[4];
+    auto fetch = [&](int64_t m0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                       // 32 x 128 floats = 1024 float4 per operand
+            const int idx = tid + 256 * i;
+            const int64_t m = m0 + idx / 32;
+            const int c = 4 * (idx % 32);
+            f32x4 vz = {0.f, 0.f, 0.f, 0.f}, vg = {0.f, 0.f, 0.f, 0.f};
+            if (m < m_end) {
+                if constexpr (VEC) {
+                    if (k0 + c < a.K) vz = *reinterpret_cast<const f32x4*>(Z + m * a.ldz + k0 + c);
+                    if (n0 + c < a.N) vg = *reinterpret_cast<const f32x4*>(G + m * a.ldg + n0 + c);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (k0 + c + e < a.K) vz[e] = Z[m * a.ldz + k0 + c + e];
+                        if (n0 + c + e < a.N) vg[e] = G[m * a.ldg + n0 + c + e];
+                    }
+                }
+            }
+            rz[i] = vz;
+            rg[i] = vg;
+        }
+    };
+    fetch(m_begin);
+    for (int64_t m0 = m_begin; m0 < m_end; m0 += BM) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<f32x4*>(&Zs[idx / 32][4 * (idx % 32)]) = rz[i];
+            *reinterpret_cast<f32x4*>(&Gs[idx / 32][4 * (idx % 32)]) = rg[i];
+        }
+        __syncthreads();
+        if (m0 + BM < m_end) fetch(m0 + BM);
+#pragma unroll
+        for (int mm = 0; mm < BM; mm += 2) {                // one MFMA step covers rows mm (lanes 0-31) and mm+1
+            float fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = Zs[mm + lh][wk0 + 32 * i + li];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[j] = Gs[mm + lh][wn0 + 32 * j + li];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    float* out = a.partial + (int64_t)slab * a.K * a.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn0 + 32 * j + li;
+            if (n >= a.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = k0 + wk0 + 32 * i + 8 * (r / 4) + 4 * lh + (r % 4);
+                if (k < a.K) out[(int64_t)k * a.N + n] = acc[i][j][r];
+            }
+        }
+}
+
+// bf16: both operands need 8 consecutive rows per lane, so both tiles are transposed on the way into LDS
+// (the same 8 x 8 register transposition as for the weights of the forward kernel).
+__global__ __launch_bounds__(256) void dw_bf16_kernel(DwArgs a) {
+    __shared__ __attribute__((aligned(16))) uint16_t Zt[kDwTile][kLdh];     // [feature][row]
+    __shared__ __attribute__((aligned(16))) uint16_t Gt[kDwTile][kLdh];
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* G = reinterpret_cast<const uint16_t*>(a.G);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int slab = blockIdx.x, k0 = blockIdx.y * kDwTile, n0 = blockIdx.z * kDwTile;
+    const int64_t m_begin = (int64_t)slab * kDwSlab;
+    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+    f32x16 acc[2][2];
+    zero_acc(acc);
+    // a 64(row) x 128(feature) tile is 8 x 16 blocks of 8 x 8: threads 0-127 take Z's, threads 128-255 G's
+    const bool mine_z = tid < 128;
+    const int t = tid & 127, rb = t / 16, fb = t % 16;
+    u32x4 r[8];
+    auto fetch = [&](int64_t m0) {
+        const uint16_t* src = mine_z ? Z : G;
+        const int64_t ld = mine_z ? a.ldz : a.ldg;
+        const int f = (mine_z ? k0 : n0) + 8 * fb, flim = mine_z ? a.K : a.N;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int64_t m = m0 + 8 * rb + i;
+            r[i] = u32x4{0u, 0u, 0u, 0u};
+            if (m < m_end && f < flim) r[i] = *reinterpret_cast<const u32x4*>(src + m * ld + f);
+        }
+    };
+    fetch(m_begin);
+    for (int64_t m0 = m_begin; m0 < m_end; m0 += kBKh) {
+        __syncthreads();
+        {
+            u32x4 tt[8];
+            transpose8x8_bf16(r, tt);
+            uint16_t (*dst)[kLdh] = mine_z ? Zt : Gt;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(&dst[8 * fb + c][8 * rb]) = tt[c];
+        }
+        __syncthreads();
+        if (m0 + kBKh < m_end) fetch(m0 + kBKh);
+        mfma_tile_bf16<2, 2>(&Zt[0][0], kLdh, wk0, 0, Gt, wn0, li, lh, acc);
+    }
+    float* out = a.partial + (int64_t)slab * a.K * a.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn0 + 32 * j + li;
+            if (n >= a.N) continue;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                const int k = k0 + wk0 + 32 * i + 8 * (rr / 4) + 4 * lh + (rr % 4);
+                if (k < a.K) out[(int64_t)k * a.N + n] = acc[i][j][rr];
+            }
+        }
+}
+
+// element-wise path for bf16 operands that are not 16-byte aligned: one thread per (slab, k, j)
+__global__ __launch_bounds__(256) void dw_bf16_generic_kernel(DwArgs a) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t per = (int64_t)a.K * a.N;
+    if (idx >= per * a.n_slabs) return;
+    const int slab = (int)(idx / per);
+    const int k = (int)((idx % per) / a.N), n = (int)(idx % a.N);
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* G = reinterpret_cast<const uint16_t*>(a.G);
+    const int64_t m_begin = (int64_t)slab * kDwSlab;
+    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    float s = 0.f;
+    for (int64_t m = m_begin; m < m_end; ++m) s = fmaf(bf16_val(Z, m * a.ldz + k), bf16_val(G, m * a.ldg + n), s);
+    a.partial[idx] = s;
+}
+
+__global__ __launch_bounds__(256) void dw_reduce_kernel(DwArgs a) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t per = (int64_t)a.K * a.N;
+    if (idx >= per) return;
+    float s = 0.f;
+    for (int sl = 0; sl < a.n_slabs; ++sl) s += a.partial[(int64_t)sl * per + idx];
+    a.dW[idx] = a.c_w * s;
+}
+
+// ReLU backward, element-wise: GP = GY where Y > 0, else 0
+template <bool BF>
+__global__ __launch_bounds__(256) void relu_bwd_kernel(const char* GY, int64_t ldgy, const char* Y, int64_t ldy,
+                                                       char* GP, int64_t ldgp, int64_t M, int F, int vec) {
+    // vec: 16-byte pieces per row (0 = element-wise)
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    constexpr int EB = BF ? 2 : 4;
+    if (vec > 0) {
+        if (idx >= M * vec) return;
+        const int64_t m = idx / vec;
+        const int v = (int)(idx % vec);
+        const u32x4 g = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(GY + (m * ldgy) * EB) + v);
+        const u32x4 y = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Y + (m * ldy) * EB) + v);
+        u32x4 o = g;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if constexpr (BF) {
+                if (!(bf16_lo(y[q]) > 0.f)) o[q] &= 0xFFFF0000u;
+                if (!(bf16_hi(y[q]) > 0.f)) o[q] &= 0x0000FFFFu;
+            } else {
+                if (!(__uint_as_float(y[q]) > 0.f)) o[q] = 0u;
+            }
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(GP + (m * ldgp) * EB) + v);
+    } else {
+        if (idx >= M * F) return;
+        const int64_t m = idx / F;
+        const int f = (int)(idx % F);
+        if constexpr (BF) {
+            const uint16_t* y = reinterpret_cast<const uint16_t*>(Y);
+            const uint16_t g = reinterpret_cast<const uint16_t*>(GY)[m * ldgy + f];
+            reinterpret_cast<uint16_t*>(GP)[m * ldgp + f] = bf16_val(y, m * ldy + f) > 0.f ? g : (uint16_t)0;
+        } else {
+            const float g = reinterpret_cast<const float*>(GY)[m * ldgy + f];
+            reinterpret_cast<float*>(GP)[m * ldgp + f] = reinterpret_cast<const float*>(Y)[m * ldy + f] > 0.f ? g : 0.f;
+        }
     }
 }
 
@@ -777,17 +1062,19 @@ using namespace gas;
 
 extern "C" {
 
-gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W, int32_t F_out,
-                      const void* bias, gas_dtype dt, float c_identity, float c_weight, int relu, void* Y,
-                      int64_t ldy, void* stream) {
-    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_linear: unknown dtype %d", (int)dt);
-    GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_out > 0, "gas_linear: n_rows=%lld F_in=%d F_out=%d", (long long)n_rows,
-                F_in, F_out);
+// Y = act(c_identity * Z + c_weight * (Z op(W)) + bias) with optional output mask; op(W) = W ([F_in, F_out]) or,
+// with trans_w, the transpose of a [F_out, F_in] matrix.
+static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W,
+                             int trans_w, int32_t F_out, const void* bias, gas_dtype dt, float c_identity,
+                             float c_weight, int relu, const void* mask, int64_t ldmask, void* Y, int64_t ldy,
+                             hipStream_t s) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_out > 0, "%s: n_rows=%lld widths %d, %d", who, (long long)n_rows, F_in, F_out);
     if (n_rows == 0) return GAS_OK;
-    GAS_REQUIRE(Z && W && Y, "gas_linear: null pointer");
-    GAS_REQUIRE(ldz >= F_in && ldy >= F_out, "gas_linear: row stride smaller than the row");
-    GAS_REQUIRE(c_identity == 0.f || F_in == F_out, "gas_linear: the identity term needs F_in == F_out");
-    GAS_REQUIRE(Y != Z, "gas_linear: Y must not alias Z");
+    GAS_REQUIRE(Z && W && Y, "%s: null pointer", who);
+    GAS_REQUIRE(ldz >= F_in && ldy >= F_out && (!mask || ldmask >= F_out), "%s: row stride smaller than the row", who);
+    GAS_REQUIRE(c_identity == 0.f || F_in == F_out, "%s: the identity term needs equal widths", who);
+    GAS_REQUIRE(Y != Z, "%s: the output must not alias the input", who);
     LinArgs a;
     a.Z = static_cast<const char*>(Z); a.ldz = ldz;
     a.W = static_cast<const char*>(W);
@@ -795,7 +1082,7 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
     a.Y = static_cast<char*>(Y); a.ldy = ldy;
     a.M = n_rows; a.K = F_in; a.N = F_out;
     a.c_id = c_identity; a.c_w = c_weight; a.relu = relu;
-    hipStream_t s = (hipStream_t)stream;
+    a.trans_w = trans_w; a.mask = static_cast<const char*>(mask); a.ldmask = ldmask;
     if (dt == GAS_F32) {
         const bool vec = aligned16(Z) && aligned16(W) && ldz % 4 == 0 && F_in % 4 == 0 && F_out % 4 == 0;
         if (F_out <= 64) return launch_f32<128, 64>(a, vec, s);
@@ -805,12 +1092,13 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
     if (!vec) {
         const int64_t total = n_rows * (int64_t)F_out;
         const int64_t blocks = (total + 255) / 256;
-        if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_linear: problem too large for the element-wise path");
+        if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "%s: problem too large for the element-wise path", who);
         hipLaunchKernelGGL(linear_bf16_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
         GAS_CHECK_HIP(hipGetLastError());
         return GAS_OK;
     }
-    if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+    if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
+        (!mask || (aligned16(mask) && ldmask % 8 == 0))) {
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
         w.W1 = static_cast<const uint16_t*>(W); w.b1 = static_cast<const uint16_t*>(bias);
@@ -818,6 +1106,7 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
         w.M = n_rows; w.n_tiles = (n_rows + kWsRows - 1) / kWsRows;
         w.K = F_in; w.H = F_out; w.N = F_out;
         w.c_id = c_identity; w.c_w = c_weight; w.relu1 = relu; w.relu_out = 0;
+        w.trans_w1 = trans_w; w.mask = static_cast<const uint16_t*>(mask); w.ldmask = ldmask;
         if (F_in <= 64) return launch_ws<4, 0>(w, s);
         if (F_in <= 128) return launch_ws<8, 0>(w, s);
         return launch_ws<16, 0>(w, s);
@@ -825,6 +1114,103 @@ gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, 
     if (F_out <= 64) return launch_bf16<64>(a, s);
     if (F_out <= 128) return launch_bf16<128>(a, s);
     return launch_bf16<256>(a, s);
+}
+
+gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W, int32_t F_out,
+                      const void* bias, gas_dtype dt, float c_identity, float c_weight, int relu, void* Y,
+                      int64_t ldy, void* stream) {
+    return run_linear("gas_linear", Z, ldz, n_rows, F_in, W, 0, F_out, bias, dt, c_identity, c_weight, relu, nullptr,
+                      0, Y, ldy, (hipStream_t)stream);
+}
+
+gas_status gas_linear_bwd_input(const void* GP, int64_t ldgp, int64_t n_rows, int32_t F_out, const void* W,
+                                int32_t F_in, gas_dtype dt, float c_identity, float c_weight, const void* mask,
+                                int64_t ldmask, void* GZ, int64_t ldgz, void* stream) {
+    // GZ = c_identity * GP + c_weight * (GP W^T): a product with the [F_in, F_out] matrix taken transposed
+    return run_linear("gas_linear_bwd_input", GP, ldgp, n_rows, F_out, W, 1, F_in, nullptr, dt, c_identity, c_weight,
+                      0, mask, ldmask, GZ, ldgz, (hipStream_t)stream);
+}
+
+int64_t gas_linear_bwd_weight_workspace(int64_t n_rows, int32_t F_in, int32_t F_out) {
+    if (n_rows <= 0 || F_in <= 0 || F_out <= 0) return 0;
+    return ((n_rows + kDwSlab - 1) / kDwSlab) * (int64_t)F_in * F_out * (int64_t)sizeof(float);
+}
+
+gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
+                                 int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight, float* dW,
+                                 void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_linear_bwd_weight: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_out > 0, "gas_linear_bwd_weight: n_rows=%lld widths %d, %d",
+                (long long)n_rows, F_in, F_out);
+    GAS_REQUIRE(dW, "gas_linear_bwd_weight: null output");
+    hipStream_t s = (hipStream_t)stream;
+    DwArgs a;
+    a.Z = static_cast<const char*>(Z); a.ldz = ldz;
+    a.G = static_cast<const char*>(GP); a.ldg = ldgp;
+    a.M = n_rows; a.K = F_in; a.N = F_out; a.c_w = c_weight;
+    a.partial = static_cast<float*>(workspace); a.dW = dW;
+    const int64_t n_slabs = (n_rows + kDwSlab - 1) / kDwSlab;
+    GAS_REQUIRE(n_slabs <= 0x7FFFFFFFLL, "gas_linear_bwd_weight: too many rows");
+    a.n_slabs = (int)n_slabs;
+    const int64_t per = (int64_t)F_in * F_out;
+    const unsigned rblocks = (unsigned)((per + 255) / 256);
+    if (n_rows == 0) {                                   // empty sum: dW = 0
+        hipLaunchKernelGGL(dw_reduce_kernel, dim3(rblocks), dim3(256), 0, s, a);
+        GAS_CHECK_HIP(hipGetLastError());
+        return GAS_OK;
+    }
+    GAS_REQUIRE(Z && GP, "gas_linear_bwd_weight: null pointer");
+    GAS_REQUIRE(ldz >= F_in && ldgp >= F_out, "gas_linear_bwd_weight: row stride smaller than the row");
+    GAS_REQUIRE(workspace && workspace_bytes >= gas_linear_bwd_weight_workspace(n_rows, F_in, F_out),
+                "gas_linear_bwd_weight: workspace of %lld bytes needed, %lld given",
+                (long long)gas_linear_bwd_weight_workspace(n_rows, F_in, F_out), (long long)workspace_bytes);
+    const unsigned tk = (unsigned)((F_in + kDwTile - 1) / kDwTile), tn = (unsigned)((F_out + kDwTile - 1) / kDwTile);
+    GAS_REQUIRE(tk <= 65535 && tn <= 65535, "gas_linear_bwd_weight: widths too large");
+    dim3 grid((unsigned)n_slabs, tk, tn);
+    if (dt == GAS_F32) {
+        const bool vec = aligned16(Z) && aligned16(GP) && ldz % 4 == 0 && ldgp % 4 == 0;
+        if (vec) hipLaunchKernelGGL(dw_f32_kernel<true>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(dw_f32_kernel<false>, grid, dim3(256), 0, s, a);
+    } else {
+        const bool vec = aligned16(Z) && aligned16(GP) && ldz % 8 == 0 && ldgp % 8 == 0 && F_in % 8 == 0 && F_out % 8 == 0;
+        if (vec) {
+            hipLaunchKernelGGL(dw_bf16_kernel, grid, dim3(256), 0, s, a);
+        } else {
+            const int64_t blocks = (per * n_slabs + 255) / 256;
+            GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_linear_bwd_weight: problem too large for the element-wise path");
+            hipLaunchKernelGGL(dw_bf16_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+        }
+    }
+    hipLaunchKernelGGL(dw_reduce_kernel, dim3(rblocks), dim3(256), 0, s, a);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+gas_status gas_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy, int64_t n_rows, int32_t F,
+                        gas_dtype dt, void* GP, int64_t ldgp, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_relu_bwd: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_relu_bwd: n_rows=%lld F=%d", (long long)n_rows, F);
+    if (n_rows == 0) return GAS_OK;
+    GAS_REQUIRE(GY && Y && GP, "gas_relu_bwd: null pointer");
+    GAS_REQUIRE(ldgy >= F && ldy >= F && ldgp >= F, "gas_relu_bwd: row stride smaller than F");
+    const int eb = elem_bytes(dt);
+    const bool vec = aligned16(GY) && aligned16(Y) && aligned16(GP) && (F * eb) % 16 == 0 && (ldgy * eb) % 16 == 0 &&
+                     (ldy * eb) % 16 == 0 && (ldgp * eb) % 16 == 0;
+    const int v = vec ? F * eb / 16 : 0;
+    const int64_t items = vec ? n_rows * v : n_rows * (int64_t)F;
+    const int64_t blocks = (items + 255) / 256;
+    GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_relu_bwd: too many elements for one launch");
+    const char* gy = static_cast<const char*>(GY);
+    const char* y = static_cast<const char*>(Y);
+    char* gp = static_cast<char*>(GP);
+    if (dt == GAS_BF16)
+        hipLaunchKernelGGL(relu_bwd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, gy, ldgy, y,
+                           ldy, gp, ldgp, n_rows, F, v);
+    else
+        hipLaunchKernelGGL(relu_bwd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, gy, ldgy,
+                           y, ldy, gp, ldgp, n_rows, F, v);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
 }
 
 gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,

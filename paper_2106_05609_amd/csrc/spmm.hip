@@ -732,11 +732,11 @@ gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const int32_t* 
 }
 
 gas_status gas_spmm_t(const gas_plan* plan, const int32_t* colptr, const int32_t* row, const float* val, float diag,
-                      int64_t n_diag, const void* G, int64_t ldg, gas_dtype dt_g, int32_t F, void* GX, int64_t ldgx,
-                      gas_dtype dt_gx, void* stream) {
+                      float s_agg, int64_t n_diag, const void* G, int64_t ldg, gas_dtype dt_g, int32_t F, void* GX,
+                      int64_t ldgx, gas_dtype dt_gx, void* stream) {
     GAS_REQUIRE(n_diag >= 0, "gas_spmm_t: n_diag=%lld", (long long)n_diag);
-    return run_spmm("gas_spmm_t", plan, colptr, row, val, diag, n_diag, G, ldg, nullptr, 0, dt_g, F, 1.f, nullptr, 0,
-                    0.f, GX, ldgx, dt_gx, (hipStream_t)stream);
+    return run_spmm("gas_spmm_t", plan, colptr, row, val, diag, n_diag, G, ldg, nullptr, 0, dt_g, F, s_agg, nullptr,
+                    0, 0.f, GX, ldgx, dt_gx, (hipStream_t)stream);
 }
 
 gas_status gas_spmm_hist(const gas_plan* plan, const int32_t* rowptr, const int32_t* src, const float* val,

@@ -145,3 +145,108 @@ def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True,
         if keep_layers:
             layers.append(x)
     return (y, layers) if keep_layers else y
+
+
+def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_push=True):
+    """Forward with the activations kept, then the backward pass through all layers (no optimiser step).
+    Historical embeddings are constants, so gradients travel along in-batch rows only; GCNII's input projection
+    is computed in-graph for the halo rows too and its gradient includes them.  GIN's MLP runs as two stored
+    linears here (the hidden activation is needed again by the backward pass).  Returns (Y_L, grads, kept) with
+    grads[l] = dW_l (float32; a pair for GIN), grads["w_in"] for GCNII, and kept = the stored activations the
+    backward pass read (x0, h0, per layer (Z, hidden, Y)).  Every step is a gas_* call."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x0 = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x0)
+    x, h0 = x0, None
+    if model.op == "gcnii":
+        h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x0, model.w_in, h0, relu=True)
+        x = h0
+    L = model.n_layers
+    saved = []
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        f_in, f_out = x.shape[1], model.out_width(l - 1)
+        z = torch.empty((nb, f_in), dtype=dt, device=dev)
+        x_next = torch.empty((nb if last else nv, f_out), dtype=dt, device=dev)
+        y = x_next[:nb]
+        h = None
+        if model.op == "gcn":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+        elif model.op == "gin":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
+            w1, w2 = model.weights[l - 1]
+            h = torch.empty((nb, w1.shape[1]), dtype=dt, device=dev)
+            B.gas_linear(z, w1, h, relu=True)
+            B.gas_linear(h, w2, y, relu=not last)
+        else:
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            beta = gcnii_beta(l)
+            B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
+        saved.append((z, h, y))
+        if last:
+            break
+        if do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        if nv > nb:
+            B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
+        x = x_next
+    # ---- backward
+    def weight_grad(zz, gg, c=1.0):
+        dw = torch.empty((zz.shape[1], gg.shape[1]), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(1, B.gas_linear_bwd_weight_workspace(zz.shape[0], zz.shape[1], gg.shape[1])),
+                         dtype=torch.uint8, device=dev)
+        B.gas_linear_bwd_weight(zz, gg, dw, ws, c_weight=c)
+        return dw
+
+    grads = {}
+    g = grad_out
+    g_h0 = None
+    for l in range(L, 0, -1):
+        z, h, yl = saved[l - 1]
+        if l != L:
+            gp = torch.empty_like(g)
+            B.gas_relu_bwd(g, yl, gp)
+            g = gp
+        gz = torch.empty_like(z)
+        if model.op == "gcn":
+            grads[l - 1] = weight_grad(z, g)
+            B.gas_linear_bwd_input(g, model.weights[l - 1], gz)
+        elif model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            dw2 = weight_grad(h, g)
+            gh = torch.empty_like(h)
+            B.gas_linear_bwd_input(g, w2, gh, mask=h)
+            grads[l - 1] = (weight_grad(z, gh), dw2)
+            B.gas_linear_bwd_input(gh, w1, gz)
+        else:
+            beta = gcnii_beta(l)
+            grads[l - 1] = weight_grad(z, g, beta)
+            B.gas_linear_bwd_input(g, model.weights[l - 1], gz, c_identity=1.0 - beta, c_weight=beta)
+            if g_h0 is None:
+                g_h0 = torch.zeros((nv, gz.shape[1]), dtype=torch.float32, device=dev)
+            g_h0[:nb] += model.alpha * gz.float()        # small accumulation on the side (fp32), not a hot-path step
+        if l == 1:
+            if model.op == "gcnii":
+                plan_all = B.gas_plan_create(bg.colptr, bg.nnz, gz.shape[1], ind=bg.row)
+                gx = torch.empty((nv, gz.shape[1]), dtype=dt, device=dev)
+                B.gas_spmm_t(plan_all, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
+                g_h0 += gx.float()
+            break
+        gx = torch.empty((nb, gz.shape[1]), dtype=dt, device=dev)
+        if model.op == "gin":
+            B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, None, gz, gx, diag=1.0 + model.gin_eps)
+        elif model.op == "gcn":
+            B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, gz, gx)
+        else:
+            B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
+        g = gx
+    if model.op == "gcnii":
+        gh0 = g_h0.to(dt)
+        gp = torch.empty_like(gh0)
+        B.gas_relu_bwd(gh0, h0, gp)
+        grads["w_in"] = weight_grad(x0, gp)
+    return y, grads, {"x0": x0, "h0": h0, "layers": saved}

@@ -203,7 +203,7 @@ def cpu_baseline(cfg, g, sg, hist_in, x, w, w2, gz, F, sample_rows):
     colall = sg.col.cpu().numpy()
     if sample_rows <= 0:
         # every k-th row of the batch, so that the sample has the batch's degree mix
-        sample_rows = int(min(nb, max(1, round(nb * 3_000_000 / max(1, rowptr[-1])))))
+        sample_rows = int(min(nb, max(1, round(nb * 24_000_000 / max(1, rowptr[-1])))))
     m = min(sample_rows, nb)
     rows = np.unique(np.linspace(0, nb - 1, m).astype(np.int64))
     m = rows.size

@@ -180,7 +180,7 @@ __device__ __forceinline__ void mfma_tile_f32(const float* A, int lda, int arow0
     }
 }
 
-template <int BM, int BN, bool VEC>
+template <int BM, int BN, bool VEC, bool TRANS>
 __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
     constexpr int TM = BM / 64, TN = BN / 64;
     __shared__ __attribute__((aligned(16))) float As[BM][kLdA];
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
     zero_acc(acc);
     ATileF32<BM, VEC> ta;
     BTileF32<BN, VEC> tb;
-    const bool tr = a.trans_w != 0;
+    constexpr bool tr = TRANS;           // compile-time: the plain path keeps its straight-line staging
     ta.fetch(Z, a.ldz, a.M, a.K, m0, 0, tid);
     tb.fetch(W, a.K, a.N, 0, n0, tid, tr);
     for (int k0 = 0; k0 < a.K; k0 += kBK) {
@@ -1039,8 +1039,13 @@ gas_status launch_f32(const LinArgs& a, bool vec, hipStream_t s) {
     const int gn = (a.N + BN - 1) / BN;
     if (gm > 0x7FFFFFFF || gn > 65535) return fail(GAS_ERR_ARG, "gas_linear: problem too large for one launch");
     dim3 grid((unsigned)gm, (unsigned)gn), block(256);
-    if (vec) hipLaunchKernelGGL((linear_f32_kernel<BM, BN, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((linear_f32_kernel<BM, BN, false>), grid, block, 0, s, a);
+    if (a.trans_w) {
+        if (vec) hipLaunchKernelGGL((linear_f32_kernel<BM, BN, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((linear_f32_kernel<BM, BN, false, true>), grid, block, 0, s, a);
+    } else {
+        if (vec) hipLaunchKernelGGL((linear_f32_kernel<BM, BN, true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((linear_f32_kernel<BM, BN, false, false>), grid, block, 0, s, a);
+    }
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }

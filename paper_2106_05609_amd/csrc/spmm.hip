@@ -19,6 +19,12 @@
 // the plan alone, so results are bit-identical from run to run.
 #include "common.h"
 
+#ifndef GAS_WAVES
+#define GAS_WAVES_ATTR
+#else
+#define GAS_WAVES_ATTR __attribute__((amdgpu_waves_per_eu(GAS_WAVES, GAS_WAVES)))
+#endif
+
 #include <algorithm>
 #include <cstdlib>
 #include <vector>
@@ -330,18 +336,72 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
     for (; r < nrows; ++r) flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);   // last row and trailing empty rows
 }
 
+// One chunk of a heavy row on the wave-per-row layout (rows of 64 vectors of VB bytes): every lane owns VB bytes
+// of the row, 8 gathers in flight per lane, the fp32 partial sum goes to the chunk's slot of the workspace.
+template <int VB, bool XBF>
+__device__ __forceinline__ void chunk_wave_per_row(const SpmmArgs& a, int64_t c) {
+    typedef typename VecOf<VB>::type V;
+    constexpr int U = 8;
+    constexpr int E = LaneAcc<VB, XBF>::E;
+    const int lane = threadIdx.x & 63;
+    const int begin = a.chunk[3 * c + 1], end = a.chunk[3 * c + 2];
+    const char* xb = a.X + (int64_t)lane * VB;
+    const char* hb = a.H + (int64_t)lane * VB;
+    LaneAcc<VB, XBF> acc;
+    acc.clear();
+    for (int t = begin; t < end; t += kWave) {
+        const int cnt = min(kWave, end - t);
+        int my_c = 0;
+        float my_w = 0.f;
+        if (lane < cnt) {
+            my_c = __builtin_nontemporal_load(a.ind + t + lane);
+            my_w = a.val ? __builtin_nontemporal_load(a.val + t + lane) : 1.f;
+        }
+        for (int j = 0; j < cnt; j += U) {
+            V v[U];
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = j + u;
+                const int ci = __builtin_amdgcn_readlane(my_c, k & 63);
+                w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k & 63));
+                const bool in_batch = ci >= 0;
+                const char* src = (in_batch ? xb : hb) +
+                                  (int64_t)(in_batch ? ci : -1 - ci) * (in_batch ? a.x_stride : a.h_stride);
+                if (k < cnt) v[u] = *reinterpret_cast<const V*>(src);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (j + u < cnt) acc.fma(w[u], v[u]);
+        }
+    }
+    float* dst = a.partial + (int64_t)a.chunk[3 * c] * a.F + (int64_t)lane * E;
+    if constexpr (E == 8) {
+        *reinterpret_cast<f32x4*>(dst) = f32x4{acc.v[0], acc.v[1], acc.v[2], acc.v[3]};
+        *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc.v[4], acc.v[5], acc.v[6], acc.v[7]};
+    } else if constexpr (E == 4) {
+        *reinterpret_cast<f32x4*>(dst) = f32x4{acc.v[0], acc.v[1], acc.v[2], acc.v[3]};
+    } else {
+        *reinterpret_cast<u32x2*>(dst) = u32x2{__float_as_uint(acc.v[0]), __float_as_uint(acc.v[1])};
+    }
+}
+
 // Chunks of heavy rows: one wavefront per chunk, partial sums to the workspace.
 // With n_slices > 1 a feature row is cut into equal slices and workgroup b
 // works on slice b % n_slices: consecutive workgroup ids go to different XCDs
 // (round robin), so with 8 slices every XCD keeps to one slice and the same L2
 // capacity holds 8x more rows of it.
-template <int G, int UPT, int U, bool XBF>
-__global__ __launch_bounds__(256) void spmm_chunk_kernel(SpmmArgs a) {
+template <int G, int UPT, int U, bool XBF, int VB>
+__global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_chunk_kernel(SpmmArgs a) {
     constexpr int E = Unit<XBF>::E;
     const int lane = threadIdx.x & 63;
     const int slice = blockIdx.x % a.n_slices;
     const int64_t c = (int64_t)(blockIdx.x / a.n_slices) * 4 + (threadIdx.x >> 6);
     if (c >= a.n_chunks) return;
+    if constexpr (VB > 0) {                 // rows of 64 vectors, not sliced
+        chunk_wave_per_row<VB, XBF>(a, c);
+        return;
+    }
     const int unit0 = slice * a.slice_units;
     float acc[UPT][E];
     accumulate<G, UPT, U, XBF>(a, unit0, a.slice_units, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
@@ -364,7 +424,7 @@ __global__ __launch_bounds__(256) void spmm_chunk_kernel(SpmmArgs a) {
 // groups, one wavefront per row (rows of exactly 64 vectors of VB bytes);
 // VB == 0: one wavefront per row, teams of G lanes per neighbour.
 template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
-__global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_rows_kernel(SpmmArgs a) {
     if constexpr (VB > 0) {
         const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
         if (g < a.n_groups) light_group<VB, XBF, ZBF>(a, g);
@@ -436,17 +496,26 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
     }
 }
 
-template <int G, int UPT, int U, bool XBF>
+int env_int(const char* name, int dflt, int lo, int hi);
+
+template <int G, int UPT, int U, bool XBF, int VB = 0>
 gas_status launch_chunks(const SpmmArgs& a, hipStream_t s) {
-    const int64_t blocks = ((a.n_chunks + 3) / 4) * a.n_slices;
+    const int64_t blocks = ((a.n_chunks + 3) / 4) * (VB > 0 ? 1 : a.n_slices);
     if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
-    hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    // Unused dynamic LDS caps the workgroups per compute unit (bytes per workgroup; 33,000 -> 4 workgroups =
+    // 4 wavefronts per SIMD): fewer chunks in flight keep the gathers of the running chunks inside a narrower
+    // range of feature rows.  Measured on the power-law configuration: 4 per SIMD is 2-4 % faster than 5 or 8,
+    // 3 and fewer are slower.
+    static const int lds = env_int("GAS_SPMM_CHUNK_LDS", 33000, 0, 160 * 1024);
+    hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF, VB>), dim3((unsigned)blocks), dim3(256), lds, s, a);
     return GAS_OK;
 }
 
 template <bool XBF>
 gas_status dispatch_chunks(const SpmmArgs& a, hipStream_t s) {
     const int u = a.slice_units;
+    if (a.n_slices == 1 && a.units == 64) return launch_chunks<64, 1, 8, XBF, 16>(a, s);
+    if (a.n_slices == 1 && a.units == 32) return launch_chunks<32, 1, 8, XBF, 8>(a, s);
     if (u <= 8) return launch_chunks<8, 1, 8, XBF>(a, s);
     if (u <= 16) return launch_chunks<16, 1, 8, XBF>(a, s);
     if (u <= 32) return launch_chunks<32, 1, 8, XBF>(a, s);

@@ -12,7 +12,9 @@ workload, for a middle layer (hidden width in and out):
 
 It is timed in two forms that give the same result bit for bit: as these five
 launches ("separate"), and with the aggregation reading the halo rows from the
-history table itself (gas_spmm_hist, "in-place": no pull launch, no halo copy).
+history table itself and the transform storing its rows to the next table as
+well (gas_spmm_hist, gas_linear_push / gas_mlp2_push: "in-place", no pull or
+push launch, no halo copy, the transform's output is not re-read).
 The headline value is the in-place form; the other one is reported beside it.
 
 All inputs are resident in HBM before the timed region.  Prints one JSON line
@@ -117,29 +119,51 @@ def main():
         ms_step = (time.perf_counter() - t0) / args.steps * 1e3
         per = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
         tag = "in-place" if fused else "separate"
+        if fused:
+            # the push is part of the transform call: its share = that call minus the plain transform, timed after
+            # the K steps on the same buffers
+            pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+            for a, b in pe:
+                a.record()
+                ls.transform(push=False)
+                b.record()
+            torch.cuda.synchronize()
+            plain = sum(a.elapsed_time(b) for a, b in pe) / args.steps
+            per["linear_push"] = per["linear"] + per["push"]
+            per["linear"] = min(plain, per["linear_push"])
+            per["push"] = per["linear_push"] - per["linear"]
+        bytes_of = dict(by)
+        if fused:
+            bytes_of["push"] = by["push_in_epilogue"]
         kern = {}
         for n in names:
             if fused and n == "pull":
                 continue                         # no such launch: the aggregation reads the history itself
-            gbs = by[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
-            key = "spmm_hist" if (fused and n == "spmm") else n
-            kern[key] = {"ms": round(per[n], 4), "alg_GB": round(by[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
+            gbs = bytes_of[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
+            key = {"spmm": "spmm_hist", "linear": "linear_alone", "push": "push_in_epilogue"}.get(n, n) if fused else n
+            kern[key] = {"ms": round(per[n], 4), "alg_GB": round(bytes_of[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
                          "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2)}
-            log(f"[bench] {tag:8s} {key:9s} {per[n]:8.3f} ms  alg {by[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "
+            log(f"[bench] {tag:8s} {key:16s} {per[n]:8.3f} ms  alg {bytes_of[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "
                 f"{100 * gbs / HBM_PEAK_GBS:5.1f}% of peak")
         sk = "spmm_hist" if fused else "spmm"
-        kern["linear"]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
+        lk = "linear_alone" if fused else "linear"
+        kern[lk]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
+        if fused:
+            kern["linear_push"] = {"ms": round(per["linear_push"], 4),
+                                   "TFLOPs": round(flops / (per["linear_push"] * 1e-3) / 1e12, 2)}
         kern[sk]["edges_per_s"] = round(nnz / (per["spmm"] * 1e-3), 1)
         kern[sk]["gathered_GBps"] = round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)
         t3 = (per["spmm"] + per["push"] + (0.0 if fused else per["pull"])) * 1e-3
         # bytes of the three operations as separate launches (pull + aggregation + push); the in-place variant
-        # does the same work without writing and re-reading the halo copy, so its own byte count is smaller
+        # does the same work without writing and re-reading the halo copy and without re-reading the transform's
+        # output, so its own byte count is smaller
         hbm3 = (by["pull"] + by["spmm"] + by["push"]) / t3 / 1e9
-        hbm3_own = ((by["spmm"] + by["push"]) / t3 / 1e9) if fused else hbm3
-        log(f"[bench] {tag:8s} step {ms_step:.3f} ms (sum of kernels {sum(per.values()):.3f}) | pull+aggregate+push "
+        hbm3_own = ((by["spmm"] + by["push_in_epilogue"]) / t3 / 1e9) if fused else hbm3
+        step_sum = sum(per[n] for n in names)
+        log(f"[bench] {tag:8s} step {ms_step:.3f} ms (sum of kernels {step_sum:.3f}) | pull+aggregate+push "
             f"{hbm3:.1f} GB/s = {100 * hbm3 / HBM_PEAK_GBS:.1f}% of HBM peak on the separate-launch byte count"
             + (f" ({hbm3_own:.1f} GB/s on its own byte count)" if fused else "")
-            + f" | aggregation gathers {kern[sk]['gathered_GBps']} GB/s | transform {kern['linear']['TFLOPs']} TFLOP/s")
+            + f" | aggregation gathers {kern[sk]['gathered_GBps']} GB/s | transform {kern[lk]['TFLOPs']} TFLOP/s")
         return {"ms_per_step": ms_step, "value": edges / (ms_step * 1e-3), "kernels": kern, "per": per,
                 "hbm_pull_spmm_push": {"GBps": round(hbm3, 1), "pct_of_peak": round(100 * hbm3 / HBM_PEAK_GBS, 2),
                                        "GBps_own_bytes": round(hbm3_own, 1)}}
@@ -159,8 +183,8 @@ def main():
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if dt == torch.float32 else "bf16", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: middle layer {F}->{F}, first batch; "
-                               + ("aggregate (halo rows read from the history table in place) + transform + push + "
-                                  "backward aggregate" if fused_head else
+                               + ("aggregate (halo rows read from the history table in place) + transform with the "
+                                  "push in its epilogue + backward aggregate" if fused_head else
                                   "pull + aggregate + transform + push + backward aggregate"),
                    "N": g.n, "nnz": g.nnz, "nb": nb, "nh": nh, "nnz_b": nnz, "nnz_bt": nnz_t, "F": F,
                    "scale": args.scale},

@@ -207,6 +207,24 @@ GAS_API gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t 
                     int relu_out, void* Y, int64_t ldy, void* stream);
 
 /*
+ * Transform with the Push fused into its epilogue (Algorithm 1: compute the
+ * layer for the in-batch nodes, Push the result): same as gas_linear /
+ * gas_mlp2, and every output row i is also stored to hist[idx[i], 0:F_out]
+ * (idx int32[n_rows], distinct; hist [n_hist_rows, F_out] of type dt, row stride
+ * ld_hist).  Y is written as well (it is the next layer's input).  Same bits as
+ * the unfused call followed by gas_push; the output is not re-read.
+ */
+GAS_API gas_status gas_linear_push(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                           const void* W, int32_t F_out, const void* bias, gas_dtype dt,
+                           float c_identity, float c_weight, int relu, void* Y, int64_t ldy,
+                           const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+GAS_API gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                         const void* W1, int32_t F_hid, const void* b1,
+                         const void* W2, int32_t F_out, const void* b2, gas_dtype dt,
+                         int relu_out, void* Y, int64_t ldy,
+                         const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+
+/*
  * Backward pass of the transform (chain rule on the operator equations; the
  * paper takes gradients through its layers, Section 2 advantage (1), without
  * spelling them out).  With P = c_identity * Z + c_weight * (Z W) and Y = relu(P):

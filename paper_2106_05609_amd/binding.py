@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push"]
 
 _lib = None
 
@@ -253,3 +253,32 @@ def gas_linear_bwd_weight(z, gp, dw, workspace, c_weight=1.0):
     _check(lib().gas_linear_bwd_weight(a, lda, b, ldb, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]),
                                        C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_float(c_weight), _ptr(dw),
                                        _ptr(workspace), C.c_int64(nbytes), _stream()))
+
+
+def gas_linear_push(z, w, y, idx, hist, bias=None, c_identity=0.0, c_weight=1.0, relu=False):
+    """gas_linear, and y[i] is also stored to hist[idx[i]] (Push fused into the epilogue)."""
+    zp, ldz = _mat(z)
+    yp, ldy = _mat(y)
+    hp, ldh = _mat(hist)
+    if w.dtype != z.dtype or y.dtype != z.dtype or hist.dtype != z.dtype or w.shape[0] != z.shape[1] or \
+            y.shape != (z.shape[0], w.shape[1]) or hist.shape[1] != w.shape[1] or idx.numel() != z.shape[0]:
+        raise ValueError("gas_linear_push: shapes or dtypes do not match")
+    _check(lib().gas_linear_push(zp, ldz, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _ptr(w), C.c_int32(w.shape[1]),
+                                 _ptr(bias), C.c_int(_dt(z)), C.c_float(c_identity), C.c_float(c_weight),
+                                 C.c_int(int(relu)), yp, ldy, _ptr(idx, torch.int32), hp, C.c_int64(hist.shape[0]), ldh,
+                                 _stream()))
+
+
+def gas_mlp2_push(z, w1, w2, y, idx, hist, b1=None, b2=None, relu_out=False):
+    """gas_mlp2, and y[i] is also stored to hist[idx[i]]."""
+    zp, ldz = _mat(z)
+    yp, ldy = _mat(y)
+    hp, ldh = _mat(hist)
+    if not (w1.dtype == w2.dtype == z.dtype == y.dtype == hist.dtype) or w1.shape[0] != z.shape[1] or \
+            w2.shape[0] != w1.shape[1] or y.shape != (z.shape[0], w2.shape[1]) or hist.shape[1] != w2.shape[1] or \
+            idx.numel() != z.shape[0]:
+        raise ValueError("gas_mlp2_push: shapes or dtypes do not match")
+    _check(lib().gas_mlp2_push(zp, ldz, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _ptr(w1), C.c_int32(w1.shape[1]),
+                               _ptr(b1), _ptr(w2), C.c_int32(w2.shape[1]), _ptr(b2), C.c_int(_dt(z)),
+                               C.c_int(int(relu_out)), yp, ldy, _ptr(idx, torch.int32), hp, C.c_int64(hist.shape[0]),
+                               ldh, _stream()))

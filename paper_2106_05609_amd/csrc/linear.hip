@@ -39,6 +39,8 @@ struct LinArgs {
     int relu;
     int trans_w;                       // W is given as [N][K] (the product is Z W^T of a [N, K] matrix)
     const char* mask; int64_t ldmask;  // optional [M, N]: outputs where mask <= 0 are set to zero
+    const int32_t* push_idx = nullptr; // optional (fp32 tile kernel): row m also goes to push_hist[push_idx[m], :]
+    char* push_hist = nullptr; int64_t ld_push = 0;
 };
 
 struct MlpArgs {
@@ -212,6 +214,7 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
     float* Y = reinterpret_cast<float*>(a.Y);
     const float* bias = reinterpret_cast<const float*>(a.bias);
     const float* mask = reinterpret_cast<const float*>(a.mask);
+    float* PH = reinterpret_cast<float*>(a.push_hist);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -228,6 +231,7 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
                 if (a.relu) y = fmaxf(y, 0.f);
                 if (mask && !(mask[m * a.ldmask + n] > 0.f)) y = 0.f;
                 Y[m * a.ldy + n] = y;
+                if (a.push_idx) PH[(int64_t)a.push_idx[m] * a.ld_push + n] = y;   // Push in the epilogue
             }
         }
 }
@@ -551,6 +555,8 @@ struct WsArgs {
     int relu1, relu_out;
     int trans_w1;                          // W1 is given as [H][K] (single product only)
     const uint16_t* mask; int64_t ldmask;  // optional [M, N]: outputs where mask <= 0 are set to zero
+    const int32_t* push_idx;               // optional: output row m is also stored to push_hist[push_idx[m], :]
+    uint16_t* push_hist; int64_t ld_push;
 };
 
 constexpr int kWsRows = 64;
@@ -740,6 +746,9 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
                         }
                     }
                     __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
+                    if (a.push_idx)          // Push fused into the epilogue: the row goes to its history slot as well
+                        __builtin_nontemporal_store(
+                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)a.push_idx[m] * a.ld_push + 8 * v));
                 }
             }
         }
@@ -1069,10 +1078,27 @@ extern "C" {
 
 // Y = act(c_identity * Z + c_weight * (Z op(W)) + bias) with optional output mask; op(W) = W ([F_in, F_out]) or,
 // with trans_w, the transpose of a [F_out, F_in] matrix.
+struct PushTarget {                 // optional fused Push: output row i also goes to hist[idx[i], :]
+    const int32_t* idx = nullptr;
+    void* hist = nullptr;
+    int64_t n_hist_rows = 0, ld_hist = 0;
+};
+
+// rows the kernel did not scatter itself are pushed by the row-copy kernel
+static gas_status push_after(const PushTarget& p, const void* Y, int64_t ldy, int64_t n_rows, int32_t F, gas_dtype dt,
+                             hipStream_t s) {
+    if (!p.idx) return GAS_OK;
+    return gas_push(Y, ldy, p.idx, 0, n_rows, F, dt, p.hist, p.n_hist_rows, p.ld_hist, s);
+}
+
 static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W,
                              int trans_w, int32_t F_out, const void* bias, gas_dtype dt, float c_identity,
                              float c_weight, int relu, const void* mask, int64_t ldmask, void* Y, int64_t ldy,
-                             hipStream_t s) {
+                             hipStream_t s, const PushTarget& push = PushTarget()) {
+    if (push.idx) {
+        GAS_REQUIRE(push.hist && push.ld_hist >= F_out && push.n_hist_rows > 0, "%s: bad history table for the fused push", who);
+        GAS_REQUIRE(push.hist != Y, "%s: the history table aliases the output", who);
+    }
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "%s: unknown dtype %d", who, (int)dt);
     GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_out > 0, "%s: n_rows=%lld widths %d, %d", who, (long long)n_rows, F_in, F_out);
     if (n_rows == 0) return GAS_OK;
@@ -1090,8 +1116,8 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
     a.trans_w = trans_w; a.mask = static_cast<const char*>(mask); a.ldmask = ldmask;
     if (dt == GAS_F32) {
         const bool vec = aligned16(Z) && aligned16(W) && ldz % 4 == 0 && F_in % 4 == 0 && F_out % 4 == 0;
-        if (F_out <= 64) return launch_f32<128, 64>(a, vec, s);
-        return launch_f32<128, 128>(a, vec, s);
+        a.push_idx = push.idx; a.push_hist = static_cast<char*>(push.hist); a.ld_push = push.ld_hist;
+        return F_out <= 64 ? launch_f32<128, 64>(a, vec, s) : launch_f32<128, 128>(a, vec, s);
     }
     const bool vec = aligned16(Z) && aligned16(W) && ldz % 8 == 0 && F_in % 8 == 0 && F_out % 8 == 0;
     if (!vec) {
@@ -1100,10 +1126,11 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "%s: problem too large for the element-wise path", who);
         hipLaunchKernelGGL(linear_bf16_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
         GAS_CHECK_HIP(hipGetLastError());
-        return GAS_OK;
+        return push_after(push, Y, ldy, n_rows, F_out, dt, s);
     }
     if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
-        (!mask || (aligned16(mask) && ldmask % 8 == 0))) {
+        (!mask || (aligned16(mask) && ldmask % 8 == 0)) &&
+        (!push.idx || (aligned16(push.hist) && push.ld_hist % 8 == 0))) {
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
         w.W1 = static_cast<const uint16_t*>(W); w.b1 = static_cast<const uint16_t*>(bias);
@@ -1112,13 +1139,24 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         w.K = F_in; w.H = F_out; w.N = F_out;
         w.c_id = c_identity; w.c_w = c_weight; w.relu1 = relu; w.relu_out = 0;
         w.trans_w1 = trans_w; w.mask = static_cast<const uint16_t*>(mask); w.ldmask = ldmask;
+        w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist;
         if (F_in <= 64) return launch_ws<4, 0>(w, s);
         if (F_in <= 128) return launch_ws<8, 0>(w, s);
         return launch_ws<16, 0>(w, s);
     }
-    if (F_out <= 64) return launch_bf16<64>(a, s);
-    if (F_out <= 128) return launch_bf16<128>(a, s);
-    return launch_bf16<256>(a, s);
+    const gas_status st = F_out <= 64 ? launch_bf16<64>(a, s) : (F_out <= 128 ? launch_bf16<128>(a, s) : launch_bf16<256>(a, s));
+    return st != GAS_OK ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
+}
+
+gas_status gas_linear_push(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W, int32_t F_out,
+                           const void* bias, gas_dtype dt, float c_identity, float c_weight, int relu, void* Y,
+                           int64_t ldy, const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist,
+                           void* stream) {
+    GAS_REQUIRE(idx || n_rows == 0, "gas_linear_push: null index array");
+    PushTarget p;
+    p.idx = idx; p.hist = hist; p.n_hist_rows = n_hist_rows; p.ld_hist = ld_hist;
+    return run_linear("gas_linear_push", Z, ldz, n_rows, F_in, W, 0, F_out, bias, dt, c_identity, c_weight, relu,
+                      nullptr, 0, Y, ldy, (hipStream_t)stream, p);
 }
 
 gas_status gas_linear(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W, int32_t F_out,
@@ -1218,10 +1256,14 @@ gas_status gas_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy
     return GAS_OK;
 }
 
-gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
-                    const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
-                    void* Y, int64_t ldy, void* stream) {
+static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
+                           const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
+                           void* Y, int64_t ldy, void* stream, const PushTarget& push) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_mlp2: unknown dtype %d", (int)dt);
+    if (push.idx) {
+        GAS_REQUIRE(push.hist && push.ld_hist >= F_out && push.n_hist_rows > 0, "gas_mlp2_push: bad history table");
+        GAS_REQUIRE(push.hist != Y, "gas_mlp2_push: the history table aliases the output");
+    }
     GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_hid > 0 && F_out > 0, "gas_mlp2: n_rows=%lld F_in=%d F_hid=%d F_out=%d",
                 (long long)n_rows, F_in, F_hid, F_out);
     GAS_REQUIRE(F_hid <= kHidMax, "gas_mlp2: F_hid=%d exceeds %d", F_hid, kHidMax);
@@ -1253,7 +1295,8 @@ gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, co
         dim3 grid((unsigned)((n_rows + kMlpRowsF32 - 1) / kMlpRowsF32), (unsigned)gn);
         if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
         else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
-    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
+               (!push.idx || (aligned16(push.hist) && push.ld_hist % 8 == 0))) {
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
         w.W1 = static_cast<const uint16_t*>(W1); w.b1 = static_cast<const uint16_t*>(b1);
@@ -1262,6 +1305,7 @@ gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, co
         w.M = n_rows; w.n_tiles = (n_rows + kWsRows - 1) / kWsRows;
         w.K = F_in; w.H = F_hid; w.N = F_out;
         w.c_id = 0.f; w.c_w = 1.f; w.relu1 = 1; w.relu_out = relu_out;
+        w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist;
         if (F_in <= 128) return launch_ws<8, 16>(w, s);
         return launch_ws<16, 16>(w, s);
     } else if (vec) {
@@ -1275,7 +1319,23 @@ gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, co
         hipLaunchKernelGGL(mlp2_generic_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, s, a);
     }
     GAS_CHECK_HIP(hipGetLastError());
-    return GAS_OK;
+    return push_after(push, Y, ldy, n_rows, F_out, dt, s);
+}
+
+gas_status gas_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
+                    const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
+                    void* Y, int64_t ldy, void* stream) {
+    return run_mlp2(Z, ldz, n_rows, F_in, W1, F_hid, b1, W2, F_out, b2, dt, relu_out, Y, ldy, stream, PushTarget());
+}
+
+gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
+                         const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
+                         void* Y, int64_t ldy, const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist,
+                         void* stream) {
+    GAS_REQUIRE(idx || n_rows == 0, "gas_mlp2_push: null index array");
+    PushTarget p;
+    p.idx = idx; p.hist = hist; p.n_hist_rows = n_hist_rows; p.ld_hist = ld_hist;
+    return run_mlp2(Z, ldz, n_rows, F_in, W1, F_hid, b1, W2, F_out, b2, dt, relu_out, Y, ldy, stream, p);
 }
 
 }  // extern "C"

@@ -239,7 +239,9 @@ struct LaneAcc {
 };
 
 template <int VB, bool XBF, bool ZBF>
-__device__ __forceinline__ void flush_row(const SpmmArgs& a, int64_t row, int lane, LaneAcc<VB, XBF>& acc) {
+__device__ __forceinline__ void flush_row(const SpmmArgs& a, int64_t row, int lane, LaneAcc<VB, XBF>& acc,
+                                          const typename VecOf<VB>::type& own) {
+    // `own` = this lane's piece of X[row, :], loaded ahead of time by the caller (only read when diag != 0)
     typedef typename VecOf<VB>::type V;
     constexpr int E = LaneAcc<VB, XBF>::E, NW = VB / 4;
     float z[E];
@@ -248,7 +250,7 @@ __device__ __forceinline__ void flush_row(const SpmmArgs& a, int64_t row, int la
     if (a.diag != 0.f && row < a.n_diag) {
         LaneAcc<VB, XBF> t;
         t.clear();
-        t.fma(a.diag, *reinterpret_cast<const V*>(a.X + row * a.x_stride + (int64_t)lane * VB));
+        t.fma(a.diag, own);
 #pragma unroll
         for (int e = 0; e < E; ++e) z[e] += t.v[e];
     }
@@ -297,6 +299,27 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
     acc.clear();
     int r = 0;                                                     // row being accumulated (relative to r0)
     int row_end = __builtin_amdgcn_readlane(my_ptr, 1);            // first entry after row r
+    // The diagonal term needs X[row, :] at every flush.  Its address depends on the row number alone, so the
+    // pieces of the next four rows are kept in flight in a small ring instead of being loaded (and waited for)
+    // at the flush itself: rows of 0-1 entries would otherwise pay a full memory latency each.
+    constexpr int D = 4;
+    V own[D];
+    const bool use_diag = a.diag != 0.f;
+    auto load_own = [&](int rr) -> V {
+        V v{};
+        const int64_t row = (int64_t)r0 + rr;
+        if (use_diag && rr < nrows && row < a.n_diag) v = *reinterpret_cast<const V*>(xb + row * a.x_stride);
+        return v;
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) own[d] = load_own(d);
+    auto flush = [&]() {
+        flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc, own[0]);
+#pragma unroll
+        for (int d = 0; d + 1 < D; ++d) own[d] = own[d + 1];
+        own[D - 1] = load_own(r + D);
+        ++r;
+    };
     // a single row longer than 64 entries makes its own group: walk it 64 entries at a time
     for (int t = e0; t < e1; t += kWave) {
         const int cnt = min(kWave, e1 - t);
@@ -324,8 +347,7 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
                 const int k = j + u;
                 if (k < cnt) {
                     while (t + k >= row_end) {                     // crossed into the next row (or over empty rows)
-                        flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);
-                        ++r;
+                        flush();
                         row_end = __builtin_amdgcn_readlane(my_ptr, (r + 1) & 63);
                     }
                     acc.fma(w[u], v[u]);
@@ -333,7 +355,7 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
             }
         }
     }
-    for (; r < nrows; ++r) flush_row<VB, XBF, ZBF>(a, r0 + r, lane, acc);   // last row and trailing empty rows
+    while (r < nrows) flush();                                     // last row and trailing empty rows
 }
 
 // One chunk of a heavy row on the wave-per-row layout (rows of 64 vectors of VB bytes): every lane owns VB bytes

@@ -70,7 +70,8 @@ def gcnii_beta(layer: int) -> float:
 def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push=True):
     """Same result as forward_batch, with the halo rows read in place by the
     aggregation (gas_spmm_hist) instead of being pulled into the mini-batch
-    tensor: per layer  aggregate(X_batch, H[l-1]) -> transform -> push(H[l]).
+    tensor, and the Push taken in the transform's epilogue: per layer
+    aggregate(X_batch, H[l-1]) -> transform, rows stored to H[l] as well.
     Layer 1 reads its halo rows from the feature table the same way."""
     dev, dt = x_feat.device, x_feat.dtype
     nb = bg.nb
@@ -85,15 +86,20 @@ def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push
         table = x_feat if l == 1 else histories[l - 2]
         z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
         y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+        push = not last and do_push          # the transform stores its rows to the next history table as well
         if model.op == "gcn":
             B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z)
-            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+            if push:
+                B.gas_linear_push(z, model.weights[l - 1], y, bg.n_id[:nb], histories[l - 1], relu=True)
+            else:
+                B.gas_linear(z, model.weights[l - 1], y, relu=not last)
         else:
             B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, x, table, z, diag=1.0 + model.gin_eps)
             w1, w2 = model.weights[l - 1]
-            B.gas_mlp2(z, w1, w2, y, relu_out=not last)
-        if not last and do_push:
-            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+            if push:
+                B.gas_mlp2_push(z, w1, w2, y, bg.n_id[:nb], histories[l - 1], relu_out=True)
+            else:
+                B.gas_mlp2(z, w1, w2, y, relu_out=not last)
         x = y
     return y
 

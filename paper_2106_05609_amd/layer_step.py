@@ -7,6 +7,11 @@ operation is a C-ABI call.
     gas_linear  dense transform + ReLU              (gas_mlp2 for GIN)
     gas_push    in-batch rows -> history table l+1
     gas_spmm_t  backward aggregation over the CSC copy (in-batch columns)
+
+The in-place form of the same step is three calls: gas_spmm_hist (halo rows
+read from the history table by the aggregation itself), gas_linear_push /
+gas_mlp2_push (the transform stores each output row to its history slot as
+well), gas_spmm_t.
 """
 import torch
 
@@ -48,7 +53,8 @@ class LayerStep:
 
     def run(self, mark=None, skip_spmm_t=False, fused=False):
         """fused: the aggregation reads the halo rows from the history table itself
-        (gas_spmm_hist); the pull launch disappears."""
+        (gas_spmm_hist) and the transform pushes its output rows (gas_linear_push /
+        gas_mlp2_push); the pull and push launches disappear."""
         cfg, bg, nb = self.cfg, self.bg, self.nb
         mark = mark or (lambda i: None)
         mark(0)
@@ -72,19 +78,31 @@ class LayerStep:
         else:
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, self.x, self.z)
         mark(2)
-        y = self.x_next[:nb]
-        if self.gin:
-            B.gas_mlp2(self.z, self.w1, self.w2, y, relu_out=True)
-        elif cfg.op == "gcnii":
-            B.gas_linear(self.z, self.w, y, c_identity=1.0 - self.beta, c_weight=self.beta, relu=True)
-        else:
-            B.gas_linear(self.z, self.w, y, relu=True)
+        self.transform(push=fused)
         mark(3)
-        B.gas_push(y, bg.n_id[:nb], self.hist_out)
+        if not fused:
+            B.gas_push(self.x_next[:nb], bg.n_id[:nb], self.hist_out)
         mark(4)
         if not skip_spmm_t:
             B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, self.gz, self.gx, diag=self.diag)
         mark(5)
+
+    def transform(self, push):
+        """Dense transform of the aggregated rows into the next mini-batch tensor; with push, each row
+        also goes to its slot of the next history table in the same call."""
+        cfg, nb = self.cfg, self.nb
+        y, idx = self.x_next[:nb], self.bg.n_id[:nb]
+        if self.gin:
+            if push:
+                B.gas_mlp2_push(self.z, self.w1, self.w2, y, idx, self.hist_out, relu_out=True)
+            else:
+                B.gas_mlp2(self.z, self.w1, self.w2, y, relu_out=True)
+            return
+        c_id, c_w = (1.0 - self.beta, self.beta) if cfg.op == "gcnii" else (0.0, 1.0)
+        if push:
+            B.gas_linear_push(self.z, self.w, y, idx, self.hist_out, c_identity=c_id, c_weight=c_w, relu=True)
+        else:
+            B.gas_linear(self.z, self.w, y, c_identity=c_id, c_weight=c_w, relu=True)
 
     def algorithmic_bytes(self):
         """Bytes each call must move at least once (indices and values once, every
@@ -97,6 +115,7 @@ class LayerStep:
             "spmm": nnz * (4 + vb) + (nb + 1) * 4 + nv * F * s + nb * F * s,
             "linear": nb * 2 * F * s + F * F * s * (2 if self.gin else 1),
             "push": nb * (2 * F * s + 4),
+            "push_in_epilogue": nb * (F * s + 4),       # the transform already holds the row: only the store is left
             "spmm_t": nnz_t * (4 + vb) + (nb + 1) * 4 + nb * F * s + nb * F * s,
             "spmm_no_reuse": nnz * (4 + vb) + (nb + 1) * 4 + nnz * F * s + nb * F * s,
         }

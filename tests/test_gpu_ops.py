@@ -288,3 +288,40 @@ def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     xo = np.concatenate([to_np(xb), oops.pull(to_np(hist), nid_np[nb:])])
     want = oops.spmm(to_np(sg.rowptr), col_np, val, xo, diag=diag)
     assert max_rel_err(to_np(z), want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,K,H,N,ld_hist", [(5000, 256, 256, 256, 256), (4100, 128, 256, 64, 72), (300, 64, 96, 40, 40),
+                                             (4097, 256, 256, 256, 260), (0, 32, 32, 32, 32)])
+def test_transform_with_fused_push(gas, dtype, M, K, H, N, ld_hist):
+    """Algorithm 1's Push taken in the transform's epilogue: same bits as the transform followed by Push, the
+    oracle's Push of those rows gives the same table, rows that are not pushed keep their contents."""
+    n_hist = 2 * M + 11
+    z = dev(rng.normal_matrix(8, 370, M, K, dtype=dtype))
+    w1 = dev(rng.glorot_uniform(8, 371, K, H, dtype=dtype))
+    w2 = dev(rng.glorot_uniform(8, 372, H, N, dtype=dtype))
+    w = dev(rng.glorot_uniform(8, 373, K, N, dtype=dtype))
+    b1 = dev(rng.normal(8, 374, 0, H, dtype=dtype))
+    b2 = dev(rng.normal(8, 375, 0, N, dtype=dtype))
+    idx = dev(rng.permutation(8, 376, n_hist)[:M].to(torch.int32))
+    hist0 = rng.normal_matrix(8, 377, n_hist, ld_hist, dtype=dtype)
+    for kind in ("linear", "mlp2"):
+        y_ref = torch.full((M, N), float("nan"), dtype=dtype, device="cuda")
+        y = torch.full((M, N), float("nan"), dtype=dtype, device="cuda")
+        hist_ref, hist = dev(hist0.clone()), dev(hist0.clone())
+        if kind == "linear":
+            gas.gas_linear(z, w, y_ref, bias=b2, relu=True)
+            gas.gas_linear_push(z, w, y, idx, hist[:, :N], bias=b2, relu=True)
+        else:
+            gas.gas_mlp2(z, w1, w2, y_ref, b1=b1, b2=b2, relu_out=True)
+            gas.gas_mlp2_push(z, w1, w2, y, idx, hist[:, :N], b1=b1, b2=b2, relu_out=True)
+        gas.gas_push(y_ref, idx, hist_ref[:, :N])
+        assert np.array_equal(to_np(y).view(np.uint8), to_np(y_ref).view(np.uint8)), kind
+        assert np.array_equal(to_np(hist).view(np.uint8), to_np(hist_ref).view(np.uint8)), kind
+        want = to_np(hist0.clone())
+        if M:
+            oops.push(to_np(y), to_np(idx), want[:, :N])
+        assert np.array_equal(to_np(hist).view(np.uint8), want.view(np.uint8)), kind
+    if M:
+        with pytest.raises(gas.GasError):
+            gas.gas_linear_push(z, w, y, idx, y, bias=b2)            # the table must not be the output

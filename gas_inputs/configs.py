@@ -139,3 +139,27 @@ def make_histories(cfg: Config, device="cpu", init=None):
         else:
             out.append(rng.normal_matrix(cfg.seed, 200 + l, cfg.n, f, device, cfg.dtype))
     return out
+
+
+def block_labels(g: graphs.Graph, n_classes: int, seed: int, unlabelled: float = 0.0, device="cpu") -> torch.Tensor:
+    """Synthetic node-classification target: the class of a node is its locality block modulo n_classes
+    (communities are what a message-passing model can read off the structure); a seeded fraction of the
+    nodes is left unlabelled (-1), as in the semi-supervised splits of the paper's datasets.  int32 [n]."""
+    bp = g.block_ptr.to(torch.int64)
+    node = torch.arange(g.n, dtype=torch.int64)
+    block = torch.searchsorted(bp, node, right=True) - 1
+    lab = (block % n_classes).to(torch.int32)
+    if unlabelled > 0.0:
+        u = rng.uniform01(seed, 900, node)
+        lab = torch.where(u < unlabelled, torch.full_like(lab, -1), lab)
+    return lab.to(device)
+
+
+def class_features(g: graphs.Graph, n_classes: int, width: int, seed: int, signal: float = 1.0, device="cpu",
+                   dtype=torch.float32) -> torch.Tensor:
+    """Input features that carry the class weakly: seeded N(0,1) noise plus `signal` times a seeded N(0,1)
+    prototype row of the node's class (the class of block_labels with no node left out).  [n, width]."""
+    lab = block_labels(g, n_classes, seed).to(torch.int64)
+    proto = rng.normal_matrix(seed, 901, n_classes, width, "cpu", torch.float32)
+    x = rng.normal_matrix(seed, 902, g.n, width, "cpu", torch.float32) + signal * proto[lab]
+    return x.to(dtype).to(device)

@@ -257,3 +257,53 @@ void oracle_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_
             dW[(int64_t)k * F_out + j] = (float)(c_weight * s);
         }
 }
+
+/*
+ * Loss on the mini-batch and the optimisation step that closes Algorithm 1's
+ * loop body.  The paper computes the loss on the in-batch nodes only (Section 1,
+ * mini-batch training) and evaluates on node classification; it names neither
+ * the loss nor the optimiser.  Taken here: softmax cross-entropy over the
+ * labelled in-batch rows and plain gradient descent with L2 weight decay
+ * (Section 3, "L2 regularization is usually sufficient" for GCN).
+ *
+ *   p_ic       = exp(a_ic) / sum_c' exp(a_ic')
+ *   loss_i     = -log p_{i, label_i}                (0 where label_i < 0)
+ *   grad_ic    = scale * (p_ic - [c == label_i])    (0 where label_i < 0)
+ * loss_sum = sum_i loss_i in double.
+ */
+void oracle_softmax_xent(const void* A, int64_t lda, int64_t n_rows, int32_t n_classes, int dt,
+                         const int32_t* labels, double scale, float* loss_rows, double* loss_sum,
+                         void* G, int64_t ldg) {
+    double total = 0.0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int32_t y = labels[i];
+        if (y < 0) {
+            loss_rows[i] = 0.f;
+            for (int32_t c = 0; c < n_classes; ++c) store_elem(G, i * ldg + c, dt, 0.0);
+            continue;
+        }
+        double amax = -INFINITY;
+        for (int32_t c = 0; c < n_classes; ++c) {
+            double a = load_elem(A, i * lda + c, dt);
+            if (a > amax) amax = a;
+        }
+        double denom = 0.0;
+        for (int32_t c = 0; c < n_classes; ++c) denom += exp(load_elem(A, i * lda + c, dt) - amax);
+        double li = -(load_elem(A, i * lda + y, dt) - amax - log(denom));
+        loss_rows[i] = (float)li;
+        total += li;
+        for (int32_t c = 0; c < n_classes; ++c) {
+            double p = exp(load_elem(A, i * lda + c, dt) - amax) / denom;
+            store_elem(G, i * ldg + c, dt, scale * (p - (c == y ? 1.0 : 0.0)));
+        }
+    }
+    if (loss_sum) *loss_sum = total;
+}
+
+/* W <- W - lr * (dW + weight_decay * W), element-wise; dW is fp32, W is stored in dt. */
+void oracle_sgd_step(void* W, int64_t n, int dt, const float* dW, double lr, double weight_decay) {
+    for (int64_t i = 0; i < n; ++i) {
+        double w = load_elem(W, i, dt);
+        store_elem(W, i, dt, w - lr * ((double)dW[i] + weight_decay * w));
+    }
+}

@@ -176,14 +176,9 @@ def dense_adjacency(n_id, rowptr, col, val, nb):
 # ----------------------------------------------------------------------------
 # one mini-batch forward + backward (training step without the optimiser)
 # ----------------------------------------------------------------------------
-def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, grad_out, do_push=True):
-    """Forward as gas_batch_forward (GIN's MLP as two stored linears), then the chain rule backwards.
-
-    Historical embeddings are constants: gradients flow through in-batch rows only, layer by layer
-    (the pulled halo rows of layers >= 2 receive none).  GCNII's input projection is computed in-graph for
-    halo rows too, so its weight gradient includes them.  `grad_out` is dLoss/dY_L [nb, F_L] in the storage
-    dtype.  Returns (Y_L, grads) with grads[l] = dW_l (or (dW1, dW2) for GIN) as float32, and grads["w_in"]
-    for GCNII."""
+def gas_batch_forward_kept(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, do_push=True):
+    """Forward as gas_batch_forward (GIN's MLP as two stored linears) with every activation the backward
+    pass reads kept.  Returns (Y_L, kept) with kept = (val, x0, h0, saved), saved[l] = (Z, hidden or None, Y)."""
     n_id = np.ascontiguousarray(n_id, dtype=np.int32)
     nv = n_id.size
     val = ops.gcn_norm(rowptr, col, n_id, deg) if model.op in ("gcn", "gcnii") else None
@@ -221,7 +216,45 @@ def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories,
         xn[:nb] = y
         xn[nb:] = ops.pull(histories[l - 1], n_id[nb:])
         x = xn
+    return y, (val, x0, h0, saved)
+
+
+def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, grad_out, do_push=True):
+    """Forward with kept activations, then the chain rule backwards.
+
+    Historical embeddings are constants: gradients flow through in-batch rows only, layer by layer
+    (the pulled halo rows of layers >= 2 receive none).  GCNII's input projection is computed in-graph for
+    halo rows too, so its weight gradient includes them.  `grad_out` is dLoss/dY_L [nb, F_L] in the storage
+    dtype.  Returns (Y_L, grads) with grads[l] = dW_l (or (dW1, dW2) for GIN) as float32, and grads["w_in"]
+    for GCNII."""
+    y, (val, x0, h0, saved) = gas_batch_forward_kept(model, n_id, rowptr, col, nb, deg, x_feat, histories, do_push)
     return y, gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, grad_out)
+
+
+def apply_sgd(model: Model, grads, lr, weight_decay=0.0):
+    """One gradient-descent update of every weight matrix, in place."""
+    for l in range(model.n_layers):
+        if model.op == "gin":
+            for w, dw in zip(model.weights[l], grads[l]):
+                ops.sgd_step(w, dw, lr, weight_decay)
+        else:
+            ops.sgd_step(model.weights[l], grads[l], lr, weight_decay)
+    if model.op == "gcnii":
+        ops.sgd_step(model.w_in, grads["w_in"], lr, weight_decay)
+
+
+def gas_train_step(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, labels, lr, weight_decay=0.0):
+    """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
+    softmax cross-entropy averaged over the labelled in-batch nodes (labels: one per node of the graph, < 0 =
+    unlabelled), backward with the histories held constant, gradient-descent update.  The model's weights and
+    the histories are updated in place.  Returns the mean loss before the update."""
+    y, (val, x0, h0, saved) = gas_batch_forward_kept(model, n_id, rowptr, col, nb, deg, x_feat, histories)
+    lab = np.ascontiguousarray(np.asarray(labels)[np.asarray(n_id[:nb], dtype=np.int64)], dtype=np.int32)
+    n_lab = int((lab >= 0).sum())
+    _, loss_sum, g = ops.softmax_xent(y, lab, scale=1.0 / max(1, n_lab))
+    grads = gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, g)
+    apply_sgd(model, grads, lr, weight_decay)
+    return loss_sum / max(1, n_lab)
 
 
 def gas_batch_backward(model: Model, n_id, rowptr, col, nb, val, x0, h0, saved, grad_out):

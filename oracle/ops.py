@@ -191,3 +191,23 @@ def linear_bwd_weight(z, gp, c_weight=1.0) -> np.ndarray:
                                    C.c_int32(z.shape[1]), C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_double(c_weight),
                                    _p(dw))
     return dw
+
+
+def softmax_xent(a, labels, scale=1.0):
+    """a [n, C] logits, labels int32[n] (< 0: row ignored) -> (loss_rows float32[n], loss_sum float, grad [n, C])."""
+    a, lda = _rows(a)
+    labels = _i32(labels)
+    assert labels.size == a.shape[0]
+    loss_rows = np.empty(a.shape[0], dtype=np.float32)
+    total = C.c_double(0.0)
+    g = np.empty(a.shape, dtype=a.dtype)
+    lib().oracle_softmax_xent(_p(a), C.c_int64(lda), C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
+                              _p(labels), C.c_double(scale), _p(loss_rows), C.byref(total), _p(g),
+                              C.c_int64(a.shape[1]))
+    return loss_rows, float(total.value), g
+
+
+def sgd_step(w, dw, lr, weight_decay=0.0) -> None:
+    """In place: w <- w - lr * (dw + weight_decay * w); w contiguous in its storage type, dw float32."""
+    assert w.flags.c_contiguous and dw.flags.c_contiguous and dw.dtype == np.float32 and dw.size == w.size
+    lib().oracle_sgd_step(_p(w), C.c_int64(w.size), C.c_int(_dt(w)), _p(dw), C.c_double(lr), C.c_double(weight_decay))

@@ -253,6 +253,30 @@ GAS_API gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void*
                                  float* dW, void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * Loss of a mini-batch and the parameter update that close the loop body of
+ * Algorithm 1 (the loss is taken over the in-batch nodes only, Section 1; the
+ * paper's tasks are node classification; Section 3 names L2 regularisation).
+ *
+ * gas_softmax_xent: for every row i with 0 <= labels[i] < n_classes
+ *     p_ic = softmax(A[i, :])_c,  loss_rows[i] = -log p_{i, labels[i]},
+ *     G[i, c] = scale * (p_ic - [c == labels[i]]);
+ * rows with a label outside that range (-1 = unlabelled) get loss 0 and a zero
+ * gradient row.  A, G: [n_rows, n_classes] of type dt (device), G != A;
+ * labels int32[n_rows]; loss_rows fp32[n_rows]; loss_sum: optional fp32[1],
+ * receives the sum of loss_rows added in a fixed order (double accumulation).
+ * Arithmetic in fp32.
+ *
+ * gas_sgd_step: W[i] <- W[i] - lr * (dW[i] + weight_decay * W[i]) for the n
+ * contiguous elements of W (type dt, device); dW fp32[n] (as written by
+ * gas_linear_bwd_weight).
+ */
+GAS_API gas_status gas_softmax_xent(const void* A, int64_t lda, int64_t n_rows, int32_t n_classes, gas_dtype dt,
+                            const int32_t* labels, float scale, float* loss_rows, float* loss_sum,
+                            void* G, int64_t ldg, void* stream);
+GAS_API gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* dW, float lr, float weight_decay,
+                        void* stream);
+
+/*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
  * flag back and waits for `stream`.
  */

@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step"]
 
 _lib = None
 
@@ -282,3 +282,23 @@ def gas_mlp2_push(z, w1, w2, y, idx, hist, b1=None, b2=None, relu_out=False):
                                _ptr(b1), _ptr(w2), C.c_int32(w2.shape[1]), _ptr(b2), C.c_int(_dt(z)),
                                C.c_int(int(relu_out)), yp, ldy, _ptr(idx, torch.int32), hp, C.c_int64(hist.shape[0]),
                                ldh, _stream()))
+
+
+def gas_softmax_xent(a, labels, grad, loss_rows, loss_sum=None, scale=1.0):
+    """Softmax cross-entropy per row and its gradient (scaled); rows with a label outside [0, C) are skipped."""
+    ap, lda = _mat(a)
+    gp, ldg = _mat(grad)
+    if grad.dtype != a.dtype or grad.shape != a.shape or labels.numel() != a.shape[0] or \
+            loss_rows.dtype != torch.float32 or loss_rows.numel() != a.shape[0] or not loss_rows.is_contiguous():
+        raise ValueError("gas_softmax_xent: shapes or dtypes do not match")
+    _check(lib().gas_softmax_xent(ap, lda, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
+                                  _ptr(labels, torch.int32), C.c_float(scale), _ptr(loss_rows, torch.float32),
+                                  _ptr(loss_sum, torch.float32), gp, ldg, _stream()))
+
+
+def gas_sgd_step(w, dw, lr, weight_decay=0.0):
+    """In place: w <- w - lr * (dw + weight_decay * w); dw float32 of the same shape."""
+    if not w.is_contiguous() or not dw.is_contiguous() or dw.dtype != torch.float32 or dw.numel() != w.numel():
+        raise ValueError("gas_sgd_step: w and dw must be contiguous and of equal size, dw float32")
+    _check(lib().gas_sgd_step(_ptr(w), C.c_int64(w.numel()), C.c_int(_dt(w)), _ptr(dw, torch.float32),
+                              C.c_float(lr), C.c_float(weight_decay), _stream()))

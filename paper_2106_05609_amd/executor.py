@@ -159,7 +159,8 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
     is computed in-graph for the halo rows too and its gradient includes them.  GIN's MLP runs as two stored
     linears here (the hidden activation is needed again by the backward pass).  Returns (Y_L, grads, kept) with
     grads[l] = dW_l (float32; a pair for GIN), grads["w_in"] for GCNII, and kept = the stored activations the
-    backward pass read (x0, h0, per layer (Z, hidden, Y)).  Every step is a gas_* call."""
+    backward pass read (x0, h0, per layer (Z, hidden, Y)).  grad_out is dLoss/dY_L [nb, F_L], or a function
+    that returns it given Y_L.  Every step is a gas_* call."""
     dev, dt = x_feat.device, x_feat.dtype
     nb, nv = bg.nb, bg.nv
     x0 = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
@@ -209,7 +210,7 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         return dw
 
     grads = {}
-    g = grad_out
+    g = grad_out(y) if callable(grad_out) else grad_out     # a loss: gradient at the output, from the output
     g_h0 = None
     for l in range(L, 0, -1):
         z, h, yl = saved[l - 1]
@@ -256,3 +257,36 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         B.gas_relu_bwd(gh0, h0, gp)
         grads["w_in"] = weight_grad(x0, gp)
     return y, grads, {"x0": x0, "h0": h0, "layers": saved}
+
+
+def apply_sgd(model: Model, grads, lr, weight_decay=0.0):
+    """One gradient-descent update of every weight matrix, in place (gas_sgd_step per matrix)."""
+    for l in range(model.n_layers):
+        if model.op == "gin":
+            for w, dw in zip(model.weights[l], grads[l]):
+                B.gas_sgd_step(w, dw, lr, weight_decay)
+        else:
+            B.gas_sgd_step(model.weights[l], grads[l], lr, weight_decay)
+    if model.op == "gcnii":
+        B.gas_sgd_step(model.w_in, grads["w_in"], lr, weight_decay)
+
+
+def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr, weight_decay=0.0, n_labelled=None):
+    """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
+    softmax cross-entropy averaged over the labelled in-batch nodes, backward with the histories held constant,
+    gradient-descent update of the weights (in place).  labels_batch: int32 [nb], the labels of the in-batch
+    nodes in batch order, < 0 = unlabelled; n_labelled: their count if the caller knows it (saves a device
+    read-back).  Returns (loss_sum as a 1-element float32 device tensor, n_labelled, logits, grads)."""
+    if n_labelled is None:
+        n_labelled = int((labels_batch >= 0).sum().item())
+    dev = x_feat.device
+    loss_rows = torch.empty(bg.nb, dtype=torch.float32, device=dev)
+    loss_sum = torch.empty(1, dtype=torch.float32, device=dev)
+
+    def loss_grad(y):
+        g = torch.empty_like(y)
+        B.gas_softmax_xent(y, labels_batch, g, loss_rows, loss_sum, scale=1.0 / max(1, n_labelled))
+        return g
+    y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad)
+    apply_sgd(model, grads, lr, weight_decay)
+    return loss_sum, n_labelled, y, grads

@@ -1,0 +1,152 @@
+"""GPU parity of the loss, the gradient-descent update and whole optimisation steps of Algorithm 1's loop
+body: call by call against the oracle, then epochs of mini-batch steps (weights, histories and losses after
+the epoch against the oracle's), then the property training must have on a learnable target."""
+import numpy as np
+import pytest
+import torch
+
+from gas_inputs import configs, batches, rng
+from oracle import ops as oops, model as omodel
+from tests.util import to_np, max_rel_err, oracle_model
+from tests.test_gpu_gas import _gpu_model, _gpu_batch
+from tests.test_oracle_train import learnable_workload
+
+pytestmark = pytest.mark.gpu
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def gas():
+    import paper_2106_05609_amd as g
+    g.lib()
+    return g
+
+
+def dev(t):
+    return t.to("cuda")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,C,ld", [(1000, 64, 64), (333, 100, 104), (50, 1, 1), (5000, 256, 256), (77, 4, 4),
+                                     (130, 300, 300), (0, 8, 8)])
+def test_softmax_xent_parity(gas, dtype, M, C, ld):
+    a = rng.normal_matrix(10, 700, M, ld, dtype=dtype) * 4.0
+    lab = rng.randint(10, 701, torch.arange(M), C + 1).to(torch.int32) - 1          # -1 (unlabelled) .. C-1
+    scale = 1.0 / max(1, M)
+    g = torch.full((M, ld), 7.0, dtype=dtype, device="cuda")
+    loss_rows = torch.full((M,), float("nan"), device="cuda")
+    loss_sum = torch.full((1,), float("nan"), device="cuda")
+    gas.gas_softmax_xent(dev(a)[:, :C], dev(lab), g[:, :C], loss_rows, loss_sum, scale=scale)
+    if M == 0:
+        assert float(loss_sum) == 0.0                  # the empty sum, and no kernel ran on no rows
+        return
+    want_rows, want_sum, want_g = oops.softmax_xent(to_np(a)[:, :C], to_np(lab), scale=scale)
+    assert np.abs(to_np(loss_rows) - want_rows).max() <= 1e-5 * max(1.0, np.abs(want_rows).max())
+    assert abs(float(loss_sum) - want_sum) <= 1e-5 * max(1.0, want_sum)
+    assert max_rel_err(to_np(g[:, :C]), want_g) <= TOL[dtype] or not want_g.any()
+    unl = to_np(lab) < 0
+    assert not to_np(g[:, :C])[unl].any() and not to_np(loss_rows)[unl].any()
+    if ld > C:
+        assert (g[:, C:] == 7.0).all()
+    # a label beyond the last class is skipped like an unlabelled row, never read out of the row
+    lab2 = lab.clone()
+    lab2[:] = C
+    gas.gas_softmax_xent(dev(a)[:, :C], dev(lab2), g[:, :C], loss_rows, loss_sum)
+    assert float(loss_sum) == 0.0 and not to_np(g[:, :C]).any()
+    with pytest.raises(gas.GasError):
+        gas.gas_softmax_xent(g[:, :C], dev(lab), g[:, :C], loss_rows)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(256, 256), (100, 47), (1, 1), (3, 1000)])
+def test_sgd_step_parity(gas, dtype, shape):
+    w = rng.glorot_uniform(10, 710, shape[0], shape[1], dtype=dtype)
+    dw = rng.normal_matrix(10, 711, shape[0], shape[1]) * 0.1
+    for lr, wd in ((0.05, 0.0), (0.3, 0.01), (0.0, 0.5)):
+        w_dev = dev(w.clone())
+        gas.gas_sgd_step(w_dev, dev(dw), lr, wd)
+        want = to_np(w).copy()
+        oops.sgd_step(want, to_np(dw), lr, wd)
+        if lr == 0.0:
+            assert np.array_equal(to_np(w_dev), to_np(w))
+        assert max_rel_err(to_np(w_dev), want) <= (2e-7 if dtype == torch.float32 else 2 ** -8)
+
+
+def _both_models(wl):
+    cfg = wl.cfg
+    hs_cpu = [to_np(h).copy() for h in configs.make_histories(cfg, init="zeros")]
+    hs_gpu = [h.to("cuda") for h in configs.make_histories(cfg, init="zeros")]
+    return oracle_model(wl), _gpu_model(wl), hs_cpu, hs_gpu
+
+
+def _weights(m):
+    out = []
+    for w in m.weights:
+        out += list(w) if isinstance(w, (tuple, list)) else [w]
+    if m.w_in is not None:
+        out.append(m.w_in)
+    return out
+
+
+@pytest.mark.parametrize("op,dtype", [("gcn", torch.float32), ("gin", torch.float32), ("gin", torch.bfloat16),
+                                       ("gcnii", torch.float32)])
+def test_training_epochs_match_oracle(gas, op, dtype):
+    """Epochs over all four batches: every step's loss, and the weights and histories afterwards.  Two epochs
+    in fp32; one, with a smaller step, in bf16, where a descent trajectory amplifies the storage rounding of
+    every weight and history row from step to step (the per-call bar is what the other tests hold)."""
+    from paper_2106_05609_amd import executor
+    wl, labels, _ = learnable_workload(op, dtype=dtype)
+    g = wl.graph
+    om, gm, hs_cpu, hs_gpu = _both_models(wl)
+    deg_dev, x_dev, lab_dev = g.deg.to("cuda"), wl.x.to("cuda"), labels.to("cuda")
+    lr, wd = (0.05 if op == "gin" else 0.5), 0.001
+    if dtype == torch.bfloat16:
+        lr = 0.01
+    tol = 2e-5 if dtype == torch.float32 else 2e-2
+    for epoch in range(2 if dtype == torch.float32 else 1):
+        for b in wl.batches:
+            sg = batches.batch_subgraph(g, b, wl.cfg.self_loops)
+            bg = _gpu_batch(wl, sg, deg_dev)
+            lab_b = lab_dev[bg.n_id[:sg.nb].long()].contiguous()
+            loss_sum, n_lab, _, _ = executor.train_step(gm, bg, x_dev, hs_gpu, lab_b, lr, wd)
+            want = omodel.gas_train_step(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
+                                         to_np(wl.x), hs_cpu, to_np(labels), lr, wd)
+            got = float(loss_sum) / n_lab
+            assert abs(got - want) <= (1e-4 if dtype == torch.float32 else 2e-2) * max(1.0, want), (epoch, got, want)
+    for a, b in zip(_weights(gm), _weights(om)):
+        assert max_rel_err(to_np(a), b) <= tol, max_rel_err(to_np(a), b)
+    for a, b in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), b) <= tol, max_rel_err(to_np(a), b)
+
+
+@pytest.mark.parametrize("op,dtype", [("gcn", torch.float32), ("gin", torch.bfloat16)])
+def test_training_on_the_gpu_learns(gas, op, dtype):
+    """What holds at any size: the loss falls and nodes the loss never saw are classified far above chance by
+    a forward pass with the trained weights."""
+    from paper_2106_05609_amd import executor
+    wl, labels, truth = learnable_workload(op, dtype=dtype)
+    g = wl.graph
+    _, gm, _, hs_gpu = _both_models(wl)
+    deg_dev, x_dev, lab_dev = g.deg.to("cuda"), wl.x.to("cuda"), labels.to("cuda")
+    bgs = []
+    for b in wl.batches:
+        sg = batches.batch_subgraph(g, b, wl.cfg.self_loops)
+        bgs.append((sg, _gpu_batch(wl, sg, deg_dev)))
+    losses = []
+    lr = 1.0 if op == "gcn" else 0.05
+    for epoch in range(20):
+        tot = 0.0
+        for sg, bg in bgs:
+            lab_b = lab_dev[bg.n_id[:sg.nb].long()].contiguous()
+            loss_sum, n_lab, _, _ = executor.train_step(gm, bg, x_dev, hs_gpu, lab_b, lr)
+            tot += float(loss_sum) / n_lab
+        losses.append(tot / len(bgs))
+    assert losses[-1] < 0.3 * losses[0], losses
+    hit = tot_n = 0
+    for sg, bg in bgs:
+        y = executor.forward_batch(gm, bg, x_dev, hs_gpu, do_push=False)
+        ids = bg.n_id[:sg.nb].long()
+        held = lab_dev[ids] < 0
+        hit += int(((y.float().argmax(dim=1) == truth.to("cuda")[ids]) & held).sum())
+        tot_n += int(held.sum())
+    assert hit / tot_n > 0.85, hit / tot_n

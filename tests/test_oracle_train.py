@@ -147,6 +147,8 @@ def learnable_workload(op="gcn", n=384, f=12, dtype=torch.float32):
     cfg.graph = dict(kind="sbm_bernoulli", p_in=0.1, p_out=0.005)
     cfg.self_loops = op != "gin"
     cfg.widths = [f + 3, f + 1, 4]
+    if op == "gcnii":                 # one width throughout: the f-wide output serves as logits, 4 of them used
+        cfg.widths, cfg.alpha = [f + 3, f, f, f], 0.1
     if op == "gin":
         cfg.gin_hidden, cfg.gin_eps = f + 5, 0.0
     wl = configs.build_workload(cfg)

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Timing of the backward pass of one middle layer (256 -> 256) at the sizes of
-the benchmark configurations: ReLU backward, input gradient, weight gradient
-and the backward aggregation, as the C-ABI calls a training step makes.
+the benchmark configurations: loss and its gradient, ReLU backward, input
+gradient, weight gradient and the weight update, as the C-ABI calls a training
+step makes.
 One JSON line on stdout, a table on stderr."""
 import argparse
 import json
@@ -34,9 +35,15 @@ def main():
     gy = rng.normal_matrix(0, 702, nb, F, dev, dt)
     w = rng.glorot_uniform(0, 703, F, F, dev, dt)
     gp, gz = torch.empty_like(gy), torch.empty_like(z)
-    dw = torch.empty((F, F), dtype=torch.float32, device=dev)
+    dw = torch.zeros((F, F), dtype=torch.float32, device=dev)
     ws = torch.empty(gas.gas_linear_bwd_weight_workspace(nb, F, F), dtype=torch.uint8, device=dev)
+    labels = (torch.arange(nb, device=dev) % F).to(torch.int32)
+    loss_rows = torch.empty(nb, dtype=torch.float32, device=dev)
+    loss_sum = torch.empty(1, dtype=torch.float32, device=dev)
     calls = {
+        "softmax_xent": (lambda: gas.gas_softmax_xent(z, labels, gz, loss_rows, loss_sum, scale=1.0 / nb),
+                         2 * nb * F * s + 12 * nb, 0.0),
+        "sgd_step": (lambda: gas.gas_sgd_step(w, dw, 1e-9), F * F * (2 * s + 4), 0.0),
         "relu_bwd": (lambda: gas.gas_relu_bwd(gy, y, gp), 3 * nb * F * s, 0.0),
         "linear_bwd_input": (lambda: gas.gas_linear_bwd_input(gp, w, gz), 2 * nb * F * s + F * F * s, 2.0 * nb * F * F),
         "linear_bwd_weight": (lambda: gas.gas_linear_bwd_weight(z, gp, dw, ws), 2 * nb * F * s + F * F * 4, 2.0 * nb * F * F),

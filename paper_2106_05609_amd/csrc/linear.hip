@@ -20,6 +20,8 @@
 //         regroups it in registers and writes eight 16-byte [n][k] pieces.
 // The accumulator of a 32x32 block keeps, in register r of lane (li, lh),
 // row 8*(r/4) + 4*lh + r%4 and column li.
+#include <type_traits>
+
 #include "common.h"
 
 namespace gas {
@@ -610,14 +612,17 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
     if constexpr (TWO) load_w_frags<KT2>(a.W2, a.H, a.N, 32 * wave + li, lh, w2f);
     // output columns of this lane: n(q, e) = 32*wave + 8*q + 4*lh + e, q, e in 0..3
     const int nbase = 32 * wave + 4 * lh;
-    float bias1[16], bias2[TWO ? 16 : 1];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int n = nbase + 8 * (r / 4) + (r % 4);
-        bias1[r] = (a.b1 && n < a.H) ? bf16_val(a.b1, n) : 0.f;
-        if constexpr (TWO) bias2[r] = (a.b2 && n < a.N) ? bf16_val(a.b2, n) : 0.f;
+    // biases as fp32 in LDS (read back four at a time in the epilogues: registers are what this kernel is short of)
+    float* bias1 = reinterpret_cast<float*>(Ys + kWsRows * LDY);            // [256]
+    float* bias2 = bias1 + 256;                                             // [256]
+    if (tid < 256) {
+        bias1[tid] = (a.b1 && tid < a.H) ? bf16_val(a.b1, tid) : 0.f;
+        bias2[tid] = (TWO && a.b2 && tid < a.N) ? bf16_val(a.b2, tid) : 0.f;
     }
 
+    // Loads are issued unconditionally from a clamped address and zeroed by a select afterwards: with no
+    // branch around them the compiler counts outstanding memory operations exactly, and a later wait for one
+    // load does not turn into a wait for everything in flight.
     u32x4 ra[NVA];
     auto fetch = [&](int64_t tile) {
 #pragma unroll
@@ -625,30 +630,45 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
             const int idx = tid + 512 * i;
             const int row = idx / VPR, k = 8 * (idx % VPR);
             const int64_t m = tile * kWsRows + row;
-            ra[i] = u32x4{0u, 0u, 0u, 0u};
-            if (idx < kWsRows * VPR && m < a.M && k < a.K)
-                ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.Z + m * a.ldz + k));
+            const bool ok = idx < kWsRows * VPR && m < a.M && k < a.K;
+            const uint16_t* src = ok ? a.Z + m * a.ldz + k : a.Z;
+            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, int64_t tile) {          // tile: the one fetch() was called for
 #pragma unroll
         for (int i = 0; i < NVA; ++i) {
             const int idx = tid + 512 * i;
+            const int row = idx / VPR, k = 8 * (idx % VPR);
+            const bool ok = tile * kWsRows + row < a.M && k < a.K;
             if (idx < kWsRows * VPR)
-                *reinterpret_cast<u32x4*>(As + (buf * kWsRows + idx / VPR) * LDA + 8 * (idx % VPR)) = ra[i];
+                *reinterpret_cast<u32x4*>(As + (buf * kWsRows + row) * LDA + k) = ok ? ra[i] : u32x4{0u, 0u, 0u, 0u};
         }
     };
 
+    // Order of memory operations per tile: the loads of the tile after next are issued BEFORE this tile's
+    // output stores and are consumed one iteration later, so they are in flight during the stores and the next
+    // tile's MFMAs, and waiting for them never waits for a store (loads and stores retire in issue order).
+    constexpr int NPI = (kWsRows * 32 + 511) / 512;   // output vectors per thread per tile at the widest row
     int64_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
         fetch(tile);
-        stage(0);
+        stage(0, tile);
+        if (tile + gridDim.x < a.n_tiles) fetch(tile + gridDim.x);
     }
     int buf = 0;
     for (; tile < a.n_tiles; tile += gridDim.x, buf ^= 1) {
         const int64_t next = tile + gridDim.x;
-        if (next < a.n_tiles) fetch(next);            // in flight during this tile's MFMAs
         __syncthreads();                               // (1) Z tile `buf` staged; previous tile fully consumed
+        int32_t prow[NPI] = {};                        // history slots of the rows this thread will store
+        if (a.push_idx) {
+            const int vpr = a.N >> 3;
+#pragma unroll
+            for (int i = 0; i < NPI; ++i) {
+                const int64_t m = tile * kWsRows + (tid + 512 * i) / vpr;
+                prow[i] = a.push_idx[m < a.M ? m : a.M - 1];
+            }
+        }
         const uint16_t* At = As + buf * kWsRows * LDA;
         f32x16 acc[MT];
 #pragma unroll
@@ -672,9 +692,10 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float v[4];
+                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias1 + nbase + 8 * q);
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        v[e] = (nbase + 8 * q + e < a.H) ? fmaxf(acc[t][4 * q + e] + bias1[4 * q + e], 0.f) : 0.f;
+                        v[e] = (nbase + 8 * q + e < a.H) ? fmaxf(acc[t][4 * q + e] + bq[e], 0.f) : 0.f;
                     if (nbase + 8 * q < 16 * KT2)
                         *reinterpret_cast<u32x2*>(Hs + (32 * t + li) * LDH + nbase + 8 * q) =
                             u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
@@ -699,9 +720,10 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float v[4];
+                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias2 + nbase + 8 * q);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        v[e] = acc[t][4 * q + e] + bias2[4 * q + e];
+                        v[e] = acc[t][4 * q + e] + bq[e];
                         if (a.relu_out) v[e] = fmaxf(v[e], 0.f);
                     }
                     *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
@@ -713,8 +735,9 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float v[4];
+                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias1 + nbase + 8 * q);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = a.c_w * acc[t][4 * q + e] + bias1[4 * q + e];
+                    for (int e = 0; e < 4; ++e) v[e] = a.c_w * acc[t][4 * q + e] + bq[e];
                     if (a.c_id != 0.f && nbase + 8 * q < a.N) {      // identity term straight from the staged Z tile (K == N)
                         const u32x2 z = *reinterpret_cast<const u32x2*>(At + (32 * t + li) * LDA + nbase + 8 * q);
                         v[0] += a.c_id * bf16_lo(z[0]); v[1] += a.c_id * bf16_hi(z[0]);
@@ -728,11 +751,21 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
                         u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
                 }
         }
-        if (next < a.n_tiles) stage(buf ^ 1);          // the other buffer: nobody reads it before the next (1)
+        // take delivery of the history slots before new loads are queued behind them: the stores below then
+        // need no wait that the loads just issued would have to satisfy first
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) asm volatile("" : "+v"(prow[i]));
+        if (next < a.n_tiles) {
+            stage(buf ^ 1, next);                      // the other buffer: nobody reads it before the next (1)
+            if (next + gridDim.x < a.n_tiles) fetch(next + gridDim.x);
+        }
         __syncthreads();                               // (3) output tile staged
         {
             const int vpr = a.N >> 3;                  // 16-byte vectors per output row
-            for (int idx = tid; idx < kWsRows * vpr; idx += 512) {
+#pragma unroll
+            for (int i = 0; i < NPI; ++i) {
+                const int idx = tid + 512 * i;
+                if (idx >= kWsRows * vpr) break;
                 const int row = idx / vpr, v = idx % vpr;
                 const int64_t m = tile * kWsRows + row;
                 if (m < a.M) {
@@ -748,16 +781,242 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
                     __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
                     if (a.push_idx)          // Push fused into the epilogue: the row goes to its history slot as well
                         __builtin_nontemporal_store(
-                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)a.push_idx[m] * a.ld_push + 8 * v));
+                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
                 }
             }
         }
     }
 }
 
+// Weight fragments for a 64-column block, through LDS: the [K][ncols] matrix is staged 128 rows at a time with
+// 16-byte loads, and a lane picks the 8 consecutive k of its column out of the staged chunk (the MFMA operand
+// wants the matrix transposed).  ncols is a multiple of 8 and W is 16-byte aligned.  All threads of the
+// workgroup call this; only those with `mine` keep fragments.
+constexpr int kLdW = 256 + 8;
+template <int KT, int KTM>
+__device__ __forceinline__ void load_w_block_lds(const uint16_t* W, int K, int ncols, uint16_t* Wl, bool mine, int cb,
+                                                 int li, int lh, int tid, bf16x8 (&w)[2][KTM]) {
+    constexpr int NCH = (KT + 7) / 8;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        __syncthreads();                               // the previous chunk has been read
+        for (int idx = tid; idx < 128 * 32; idx += 512) {
+            const int r = idx >> 5, v = idx & 31;
+            const int k = 128 * c + r;
+            u32x4 x = {0u, 0u, 0u, 0u};
+            if (k < K && 8 * v < ncols) x = *reinterpret_cast<const u32x4*>(W + (int64_t)k * ncols + 8 * v);
+            *reinterpret_cast<u32x4*>(Wl + r * kLdW + 8 * v) = x;
+        }
+        __syncthreads();
+        if (mine) {
+#pragma unroll
+            for (int kk = 8 * c; kk < 8 * c + 8 && kk < KT; ++kk)
+#pragma unroll
+                for (int ch = 0; ch < 2; ++ch) {
+                    const int col = 64 * cb + 32 * ch + li;
+                    u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t x = Wl[(16 * (kk - 8 * c) + 8 * lh + e) * kLdW + col];
+                        v[e >> 1] |= x << (16 * (e & 1));
+                    }
+                    w[ch][kk] = __builtin_bit_cast(bf16x8, v);
+                }
+        }
+    }
+    __syncthreads();
+}
+
+// Fused two-layer MLP, weights stationary, wavefronts specialised by layer.
+//
+// Wavefronts 0-3 hold W1 (64 hidden columns each), wavefronts 4-7 hold W2 (64 output columns each); every SIMD
+// gets one of each.  The two products are pipelined over tiles: in phase p the first group turns Z tile p into
+// hidden tile p (LDS, two buffers) while the second group turns hidden tile p-1 into output tile p-1, so the
+// each staged row is read from LDS by four wavefronts instead of eight.  The loads of Z tile p+1 are issued at the
+// start of the phase and travel during the products; between the phase's two barriers all wavefronts move data:
+// output tile p-1 from its staging tile to Y (and to the history rows), Z tile p+1 from registers to LDS.
+template <int KT1, int KT2>
+__global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
+    constexpr int LDA = 16 * KT1 + 8, LDH = 16 * KT2 + 8, LDY = 256 + 8;
+    constexpr int VPR = 2 * KT1;
+    constexpr int NVA = (kWsRows * VPR + 511) / 512;
+    constexpr int NPI = (kWsRows * 32 + 511) / 512;
+    constexpr int MT = kWsRows / 32;
+    constexpr int KTM = KT1 > KT2 ? KT1 : KT2;
+    static_assert(KT2 == 16, "the hidden and output staging tiles are 256 columns wide, one 64-column block per wavefront");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);                       // [64][LDA]
+    uint16_t* Hs = As + kWsRows * LDA;                                      // [2][64][LDH]
+    uint16_t* Ys = Hs + 2 * kWsRows * LDH;                                  // [64][LDY]
+    float* bias1 = reinterpret_cast<float*>(Ys + kWsRows * LDY);            // [256]
+    float* bias2 = bias1 + 256;                                             // [256]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int role = wave >> 2, cb = wave & 3;        // role 0: Z W1, role 1: H W2; 64-column block cb
+
+    bf16x8 w[2][KTM];
+    load_w_block_lds<KT1, KTM>(a.W1, a.K, a.H, As, role == 0, cb, li, lh, tid, w);
+    load_w_block_lds<KT2, KTM>(a.W2, a.H, a.N, As, role == 1, cb, li, lh, tid, w);
+    if (tid < 256) {
+        bias1[tid] = (a.b1 && tid < a.H) ? bf16_val(a.b1, tid) : 0.f;
+        bias2[tid] = (a.b2 && tid < a.N) ? bf16_val(a.b2, tid) : 0.f;
+    }
+
+    u32x4 ra[NVA];
+    // Per-thread offsets (row, column, LDS address) are recomputed from the thread index where they are used
+    // (the index is made opaque there): kept live across the products they would be spilled.
+    auto fetch = [&](int64_t tile, int tl) {          // unconditional loads from a clamped address
+#pragma unroll
+        for (int i = 0; i < NVA; ++i) {
+            const int idx = tl + 512 * i;
+            const int row = idx / VPR, k = 8 * (idx % VPR);
+            const int64_t m = tile * kWsRows + row;
+            const bool ok = idx < kWsRows * VPR && m < a.M && k < a.K;
+            const uint16_t* src = ok ? a.Z + m * a.ldz + k : a.Z;
+            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+        }
+    };
+    auto stage = [&](int64_t tile, int tl) {          // tile: the one fetch() was called for
+#pragma unroll
+        for (int i = 0; i < NVA; ++i) {
+            const int idx = tl + 512 * i;
+            const int row = idx / VPR, k = 8 * (idx % VPR);
+            const bool ok = tile * kWsRows + row < a.M && k < a.K;
+            if (idx < kWsRows * VPR)
+                *reinterpret_cast<u32x4*>(As + row * LDA + k) = ok ? ra[i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    // D[m][64cb .. 64cb+63] = act(X[m][:] Wcols + bias) for the 64 rows of a tile, X and D in LDS.  Transposed
+    // products: a lane ends up with 4 consecutive columns of one row per group of four accumulator registers.
+    auto product = [&](auto kt_tag, const uint16_t* X, int ldx, uint16_t* D, int ldd, const float* bias, int ncols,
+                       bool relu) {
+        constexpr int KT = decltype(kt_tag)::value;
+        const bool whole = 64 * cb + 64 <= ncols;      // every column of this block exists: no per-column select
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {                 // 32 rows at a time: two accumulator tiles live, not four
+            // the accumulators start from the bias of their columns (element 4q+e of a lane is column n0(q)+e)
+            f32x16 acc[2];
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias + 64 * cb + 32 * ch + 8 * q + 4 * lh);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[ch][4 * q + e] = bq[e];
+                }
+            // operand fragments are read from LDS PF steps ahead of the MFMAs that use them
+            constexpr int PF = KT < 4 ? KT : 4;
+            const uint16_t* xrow = X + (32 * t + li) * ldx + 8 * lh;
+            u32x4 fx[PF];
+#pragma unroll
+            for (int j = 0; j < PF; ++j) fx[j] = *reinterpret_cast<const u32x4*>(xrow + 16 * j);
+#pragma unroll
+            for (int kk = 0; kk < KT; ++kk) {
+                const bf16x8 cur = __builtin_bit_cast(bf16x8, fx[kk % PF]);
+                if (kk + PF < KT) fx[kk % PF] = *reinterpret_cast<const u32x4*>(xrow + 16 * (kk + PF));
+#pragma unroll
+                for (int ch = 0; ch < 2; ++ch)
+                    acc[ch] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[ch][kk], cur, acc[ch], 0, 0, 0);
+            }
+            uint16_t* drow = D + (32 * t + li) * ldd + 64 * cb + 4 * lh;
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[ch][4 * q + e];
+                        if (relu) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    if (!whole) {                      // columns beyond the width are zero operands later
+                        const int n0 = 64 * cb + 32 * ch + 8 * q + 4 * lh;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n0 + e >= ncols) v[e] = 0.f;
+                    }
+                    *reinterpret_cast<u32x2*>(drow + 32 * ch + 8 * q) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                }
+        }
+    };
+
+    const int64_t grid = gridDim.x, t0 = blockIdx.x;
+    const int64_t n_my = (a.n_tiles - t0 + grid - 1) / grid;      // tiles of this workgroup (>= 1)
+    fetch(t0, tid);
+    stage(t0, tid);
+    __syncthreads();
+    for (int64_t p = 0; p <= n_my; ++p) {
+        const int64_t t_out = t0 + (p - 1) * grid;                 // tile whose output leaves in this phase
+        int32_t prow[NPI] = {};
+        int tl = tid;
+        asm volatile("" : "+v"(tl));
+        if (a.push_idx && p >= 1) {
+            const int vpr = a.N >> 3;
+#pragma unroll
+            for (int i = 0; i < NPI; ++i) {
+                const int64_t m = t_out * kWsRows + (tl + 512 * i) / vpr;
+                prow[i] = a.push_idx[m < a.M ? m : a.M - 1];
+            }
+        }
+        // loads of the next Z tile: issued here, they travel while the matrix pipes work, and are staged
+        // between this phase's two barriers
+        if (p + 1 < n_my) fetch(t0 + (p + 1) * grid, tl);
+        if (role == 0) {
+            if (p < n_my)
+                product(std::integral_constant<int, KT1>{}, As, LDA, Hs + (p & 1) * kWsRows * LDH, LDH, bias1, a.H, true);
+        } else {
+            if (p >= 1)
+                product(std::integral_constant<int, KT2>{}, Hs + ((p - 1) & 1) * kWsRows * LDH, LDH, Ys, LDY, bias2, a.N,
+                        a.relu_out != 0);
+        }
+        __syncthreads();                               // Z tile consumed; hidden tile p and output tile p-1 complete
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) asm volatile("" : "+v"(prow[i]));   // delivered before new loads queue up
+        asm volatile("" : "+v"(tl));
+        if (p + 1 < n_my) stage(t0 + (p + 1) * grid, tl);
+        if (p >= 1) {
+            const int vpr = a.N >> 3;                  // 16-byte vectors per output row
+            int tq = (int)t_out;                       // opaque here: the store addresses are formed now, not
+            asm volatile("" : "+s"(tq));               // before the products (they would not fit in registers)
+#pragma unroll
+            for (int i = 0; i < NPI; ++i) {
+                const int idx = tl + 512 * i;
+                if (idx >= kWsRows * vpr) break;
+                const int row = idx / vpr, v = idx % vpr;
+                const int64_t m = (int64_t)tq * kWsRows + row;
+                if (m < a.M) {
+                    const u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
+                    if (a.push_idx)
+                        __builtin_nontemporal_store(
+                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                }
+            }
+        }
+        __syncthreads();                               // next Z tile staged, output staging tile free again
+    }
+}
+
+template <int KT1, int KT2>
+gas_status launch_ws_mlp(const WsArgs& a, hipStream_t s) {
+    constexpr int smem = 2 * (kWsRows * (16 * KT1 + 8) + 2 * kWsRows * (16 * KT2 + 8) + kWsRows * (256 + 8)) + 2 * 256 * 4;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_mlp_bf16_kernel<KT1, KT2>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    GAS_CHECK_HIP(attr);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    }
+    const int64_t blocks = a.n_tiles < cus ? a.n_tiles : cus;
+    hipLaunchKernelGGL((ws_mlp_bf16_kernel<KT1, KT2>), dim3((unsigned)blocks), dim3(512), smem, s, a);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
 template <int KT1, int KT2>
 gas_status launch_ws(const WsArgs& a, hipStream_t s) {
-    constexpr int smem = 2 * (2 * kWsRows * (16 * KT1 + 8) + (KT2 > 0 ? kWsRows * (16 * KT2 + 8) : 0) + kWsRows * (256 + 8));
+    constexpr int smem = 2 * (2 * kWsRows * (16 * KT1 + 8) + (KT2 > 0 ? kWsRows * (16 * KT2 + 8) : 0) + kWsRows * (256 + 8))
+                         + 2 * 256 * 4;                  // + the two bias vectors in fp32
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_bf16_kernel<KT1, KT2>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     GAS_CHECK_HIP(attr);
@@ -1129,8 +1388,8 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         return push_after(push, Y, ldy, n_rows, F_out, dt, s);
     }
     if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
-        (!mask || (aligned16(mask) && ldmask % 8 == 0)) &&
-        (!push.idx || (aligned16(push.hist) && push.ld_hist % 8 == 0))) {
+        (!mask || (aligned16(mask) && ldmask % 8 == 0))) {
+        const bool scatter = push.idx && aligned16(push.hist) && push.ld_hist % 8 == 0;
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
         w.W1 = static_cast<const uint16_t*>(W); w.b1 = static_cast<const uint16_t*>(bias);
@@ -1139,10 +1398,9 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         w.K = F_in; w.H = F_out; w.N = F_out;
         w.c_id = c_identity; w.c_w = c_weight; w.relu1 = relu; w.relu_out = 0;
         w.trans_w1 = trans_w; w.mask = static_cast<const uint16_t*>(mask); w.ldmask = ldmask;
-        w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist;
-        if (F_in <= 64) return launch_ws<4, 0>(w, s);
-        if (F_in <= 128) return launch_ws<8, 0>(w, s);
-        return launch_ws<16, 0>(w, s);
+        if (scatter) { w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist; }
+        const gas_status st = F_in <= 64 ? launch_ws<4, 0>(w, s) : (F_in <= 128 ? launch_ws<8, 0>(w, s) : launch_ws<16, 0>(w, s));
+        return (st != GAS_OK || scatter) ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
     }
     const gas_status st = F_out <= 64 ? launch_bf16<64>(a, s) : (F_out <= 128 ? launch_bf16<128>(a, s) : launch_bf16<256>(a, s));
     return st != GAS_OK ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
@@ -1295,8 +1553,9 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
         dim3 grid((unsigned)((n_rows + kMlpRowsF32 - 1) / kMlpRowsF32), (unsigned)gn);
         if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
         else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
-    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
-               (!push.idx || (aligned16(push.hist) && push.ld_hist % 8 == 0))) {
+    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+        // the kernel scatters the rows itself if the history rows take 16-byte stores; else the row copy follows
+        const bool scatter = push.idx && aligned16(push.hist) && push.ld_hist % 8 == 0;
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;
         w.W1 = static_cast<const uint16_t*>(W1); w.b1 = static_cast<const uint16_t*>(b1);
@@ -1305,9 +1564,9 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
         w.M = n_rows; w.n_tiles = (n_rows + kWsRows - 1) / kWsRows;
         w.K = F_in; w.H = F_hid; w.N = F_out;
         w.c_id = 0.f; w.c_w = 1.f; w.relu1 = 1; w.relu_out = relu_out;
-        w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist;
-        if (F_in <= 128) return launch_ws<8, 16>(w, s);
-        return launch_ws<16, 16>(w, s);
+        if (scatter) { w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist; }
+        const gas_status st = F_in <= 128 ? launch_ws_mlp<8, 16>(w, s) : launch_ws_mlp<16, 16>(w, s);
+        return (st != GAS_OK || scatter) ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
     } else if (vec) {
         constexpr int smem = 2 * (kMlpRowsBF16 * (kHidMax + 8 + kBKh + 8) + 256 * (kBKh + 8));
         static const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp2_bf16_kernel),

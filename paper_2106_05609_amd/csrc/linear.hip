@@ -541,11 +541,11 @@ __global__ __launch_bounds__(256) void mlp2_bf16_kernel(MlpArgs a) {
 // For feature widths up to 256 the whole weight matrix fits in the registers
 // of one workgroup: wavefront w of 8 keeps the MFMA B-fragments of columns
 // [32w, 32w+32) for every k (K/16 fragments of 8 bf16 per lane), loaded once.
-// The workgroup is persistent (one per compute unit) and streams 32-row tiles
+// The workgroup is persistent (one per compute unit) and streams 64-row tiles
 // of Z through LDS, so after start-up the only global traffic is Z in and Y
-// out: the transform runs at the HBM rate, not at the rate weights can be
-// re-staged.  With KT2 > 0 the same workgroup also keeps W2 and chains the
-// second product of the GIN MLP through an LDS-resident hidden tile.
+// out: the weights are never re-staged.  ws_bf16_kernel is the single product;
+// ws_mlp_bf16_kernel keeps W1 and W2 on separate wavefronts and chains the two
+// products of the GIN MLP through an LDS-resident hidden tile.
 struct WsArgs {
     const uint16_t* Z;  int64_t ldz;
     const uint16_t* W1; const uint16_t* b1;
@@ -591,34 +591,25 @@ __device__ __forceinline__ void load_w_frags(const uint16_t* W, int K, int ncols
 // other way round).  Then a lane holds, for ONE row m of the tile, 4 groups of
 // 4 consecutive output columns, which go to the [m][n] LDS tiles as 8-byte
 // stores after a packed hardware fp32->bf16 conversion.
-template <int KT1, int KT2>
+template <int KT1>
 __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
-    constexpr bool TWO = KT2 > 0;
     constexpr int LDA = 16 * KT1 + 8;                 // bf16 elements per LDS row of the Z tile
-    constexpr int LDH = 16 * (TWO ? KT2 : 1) + 8;     // ... of the hidden tile
     constexpr int LDY = 256 + 8;                      // ... of the output staging tile
     constexpr int VPR = 2 * KT1;                      // 16-byte vectors per Z-tile row
     constexpr int NVA = (kWsRows * VPR + 511) / 512;  // vectors per thread per tile
     constexpr int MT = kWsRows / 32;                  // 32-row blocks per tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
     uint16_t* As = reinterpret_cast<uint16_t*>(smem);                       // [2][64][LDA]
-    uint16_t* Hs = As + 2 * kWsRows * LDA;                                  // [64][LDH]
-    uint16_t* Ys = Hs + (TWO ? kWsRows * LDH : 0);                          // [64][LDY]
+    uint16_t* Ys = As + 2 * kWsRows * LDA;                                  // [64][LDY]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
 
     bf16x8 w1f[KT1];
-    bf16x8 w2f[TWO ? KT2 : 1];
-    load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f, !TWO && a.trans_w1 != 0);
-    if constexpr (TWO) load_w_frags<KT2>(a.W2, a.H, a.N, 32 * wave + li, lh, w2f);
+    load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f, a.trans_w1 != 0);
     // output columns of this lane: n(q, e) = 32*wave + 8*q + 4*lh + e, q, e in 0..3
     const int nbase = 32 * wave + 4 * lh;
-    // biases as fp32 in LDS (read back four at a time in the epilogues: registers are what this kernel is short of)
+    // bias as fp32 in LDS (read back four at a time in the epilogue: registers are what this kernel is short of)
     float* bias1 = reinterpret_cast<float*>(Ys + kWsRows * LDY);            // [256]
-    float* bias2 = bias1 + 256;                                             // [256]
-    if (tid < 256) {
-        bias1[tid] = (a.b1 && tid < a.H) ? bf16_val(a.b1, tid) : 0.f;
-        bias2[tid] = (TWO && a.b2 && tid < a.N) ? bf16_val(a.b2, tid) : 0.f;
-    }
+    if (tid < 256) bias1[tid] = (a.b1 && tid < a.H) ? bf16_val(a.b1, tid) : 0.f;
 
     // Loads are issued unconditionally from a clamped address and zeroed by a select afterwards: with no
     // branch around them the compiler counts outstanding memory operations exactly, and a later wait for one
@@ -685,72 +676,26 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1f[kk], fz, acc[t], 0, 0, 0);
                 }
         }
-        if constexpr (TWO) {
-            // hidden tile: relu(Z W1 + b1) in bf16; columns at and beyond H are zero
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v[4];
-                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias1 + nbase + 8 * q);
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
+                const f32x4 bq = *reinterpret_cast<const f32x4*>(bias1 + nbase + 8 * q);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        v[e] = (nbase + 8 * q + e < a.H) ? fmaxf(acc[t][4 * q + e] + bq[e], 0.f) : 0.f;
-                    if (nbase + 8 * q < 16 * KT2)
-                        *reinterpret_cast<u32x2*>(Hs + (32 * t + li) * LDH + nbase + 8 * q) =
-                            u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                for (int e = 0; e < 4; ++e) v[e] = a.c_w * acc[t][4 * q + e] + bq[e];
+                if (a.c_id != 0.f && nbase + 8 * q < a.N) {      // identity term straight from the staged Z tile (K == N)
+                    const u32x2 z = *reinterpret_cast<const u32x2*>(At + (32 * t + li) * LDA + nbase + 8 * q);
+                    v[0] += a.c_id * bf16_lo(z[0]); v[1] += a.c_id * bf16_hi(z[0]);
+                    v[2] += a.c_id * bf16_lo(z[1]); v[3] += a.c_id * bf16_hi(z[1]);
                 }
-            __syncthreads();                           // (2) hidden tile complete
+                if (a.relu1) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-            if (32 * wave < a.N) {
-#pragma unroll
-                for (int kk = 0; kk < KT2; ++kk)
-#pragma unroll
-                    for (int t = 0; t < MT; ++t) {
-                        const bf16x8 fh = __builtin_bit_cast(
-                            bf16x8, *reinterpret_cast<const u32x4*>(Hs + (32 * t + li) * LDH + 16 * kk + 8 * lh));
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2f[kk], fh, acc[t], 0, 0, 0);
-                    }
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
+                    u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
             }
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v[4];
-                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias2 + nbase + 8 * q);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        v[e] = acc[t][4 * q + e] + bq[e];
-                        if (a.relu_out) v[e] = fmaxf(v[e], 0.f);
-                    }
-                    *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
-                        u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                }
-        } else {
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v[4];
-                    const f32x4 bq = *reinterpret_cast<const f32x4*>(bias1 + nbase + 8 * q);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = a.c_w * acc[t][4 * q + e] + bq[e];
-                    if (a.c_id != 0.f && nbase + 8 * q < a.N) {      // identity term straight from the staged Z tile (K == N)
-                        const u32x2 z = *reinterpret_cast<const u32x2*>(At + (32 * t + li) * LDA + nbase + 8 * q);
-                        v[0] += a.c_id * bf16_lo(z[0]); v[1] += a.c_id * bf16_hi(z[0]);
-                        v[2] += a.c_id * bf16_lo(z[1]); v[3] += a.c_id * bf16_hi(z[1]);
-                    }
-                    if (a.relu1) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-                    }
-                    *reinterpret_cast<u32x2*>(Ys + (32 * t + li) * LDY + nbase + 8 * q) =
-                        u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                }
-        }
         // take delivery of the history slots before new loads are queued behind them: the stores below then
         // need no wait that the loads just issued would have to satisfy first
 #pragma unroll
@@ -1013,11 +958,10 @@ gas_status launch_ws_mlp(const WsArgs& a, hipStream_t s) {
     return GAS_OK;
 }
 
-template <int KT1, int KT2>
+template <int KT1>
 gas_status launch_ws(const WsArgs& a, hipStream_t s) {
-    constexpr int smem = 2 * (2 * kWsRows * (16 * KT1 + 8) + (KT2 > 0 ? kWsRows * (16 * KT2 + 8) : 0) + kWsRows * (256 + 8))
-                         + 2 * 256 * 4;                  // + the two bias vectors in fp32
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_bf16_kernel<KT1, KT2>),
+    constexpr int smem = 2 * (2 * kWsRows * (16 * KT1 + 8) + kWsRows * (256 + 8)) + 256 * 4;   // + the bias in fp32
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_bf16_kernel<KT1>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     GAS_CHECK_HIP(attr);
     int dev = 0, cus = 256;
@@ -1026,7 +970,7 @@ gas_status launch_ws(const WsArgs& a, hipStream_t s) {
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
     }
     const int64_t blocks = a.n_tiles < cus ? a.n_tiles : cus;
-    hipLaunchKernelGGL((ws_bf16_kernel<KT1, KT2>), dim3((unsigned)blocks), dim3(512), smem, s, a);
+    hipLaunchKernelGGL((ws_bf16_kernel<KT1>), dim3((unsigned)blocks), dim3(512), smem, s, a);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
@@ -1399,7 +1343,7 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         w.c_id = c_identity; w.c_w = c_weight; w.relu1 = relu; w.relu_out = 0;
         w.trans_w1 = trans_w; w.mask = static_cast<const uint16_t*>(mask); w.ldmask = ldmask;
         if (scatter) { w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist; }
-        const gas_status st = F_in <= 64 ? launch_ws<4, 0>(w, s) : (F_in <= 128 ? launch_ws<8, 0>(w, s) : launch_ws<16, 0>(w, s));
+        const gas_status st = F_in <= 64 ? launch_ws<4>(w, s) : (F_in <= 128 ? launch_ws<8>(w, s) : launch_ws<16>(w, s));
         return (st != GAS_OK || scatter) ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
     }
     const gas_status st = F_out <= 64 ? launch_bf16<64>(a, s) : (F_out <= 128 ? launch_bf16<128>(a, s) : launch_bf16<256>(a, s));

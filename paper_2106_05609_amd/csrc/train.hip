@@ -58,11 +58,74 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const char* A, int64_
     }
 }
 
-// sum of n floats in a fixed order: thread t adds elements t, t+1024, ... in double, then a tree over the block
+// Rows of at most 64 vectors of 16 bytes (512 bf16 or 256 fp32 classes), 16-byte aligned: a team of
+// 2^lpr_log2 lanes holds a whole row in registers (one vector per lane), so the logits are read once, the
+// exponentials are computed once and serve the loss and the gradient, and a wavefront takes 64 / team rows.
+template <bool BF>
+__global__ __launch_bounds__(256) void softmax_xent_rows_kernel(const char* A, int64_t lda, int64_t M, int C,
+                                                                const int32_t* labels, float scale, float* loss_rows,
+                                                                char* G, int64_t ldg, int lpr_log2) {
+    constexpr int EPV = BF ? 8 : 4;
+    constexpr int EB = BF ? 2 : 4;
+    const int lane = threadIdx.x & 63;
+    const int lpr = 1 << lpr_log2, rpw = 64 >> lpr_log2;
+    const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw + (lane >> lpr_log2);
+    const int c0 = (lane & (lpr - 1)) * EPV;
+    const bool active = row < M && c0 < C;
+    float x[EPV];
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (active) raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(A + (row * lda + c0) * EB));
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        if constexpr (BF) x[i] = (i & 1) ? bf16_hi(raw[i >> 1]) : bf16_lo(raw[i >> 1]);
+        else x[i] = __uint_as_float(raw[i]);
+        if (!active) x[i] = -INFINITY;
+    }
+    float mx = x[0];
+#pragma unroll
+    for (int i = 1; i < EPV; ++i) mx = fmaxf(mx, x[i]);
+    for (int o = lpr >> 1; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float e[EPV], den = 0.f;
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        e[i] = active ? expf(x[i] - mx) : 0.f;
+        den += e[i];
+    }
+    for (int o = lpr >> 1; o > 0; o >>= 1) den += __shfl_xor(den, o);
+    if (!active) return;
+    const int y = labels[row];
+    const bool labelled = y >= 0 && y < C;
+    const float inv = labelled ? scale / den : 0.f;
+    float g[EPV];
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) {
+        g[i] = e[i] * inv;
+        if (labelled && c0 + i == y) {
+            g[i] -= scale;
+            loss_rows[row] = -(x[i] - mx - logf(den));
+        }
+    }
+    if (!labelled && c0 == 0) loss_rows[row] = 0.f;
+    u32x4 out;
+    if constexpr (BF) out = u32x4{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]), pack_bf16(g[4], g[5]), pack_bf16(g[6], g[7])};
+    else out = u32x4{__float_as_uint(g[0]), __float_as_uint(g[1]), __float_as_uint(g[2]), __float_as_uint(g[3])};
+    __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(G + (row * ldg + c0) * EB));
+}
+
+// sum of n floats in a fixed order: thread t adds elements t, t+1024, ... in double (eight loads in flight),
+// then a tree over the block
 __global__ __launch_bounds__(1024) void sum_fixed_kernel(const float* x, int64_t n, float* out) {
     __shared__ double part[1024];
     double s = 0.0;
-    for (int64_t i = threadIdx.x; i < n; i += 1024) s += (double)x[i];
+    int64_t i = threadIdx.x;
+    for (; i + 7 * 1024 < n; i += 8 * 1024) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = x[i + 1024 * j];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += (double)v[j];
+    }
+    for (; i < n; i += 1024) s += (double)x[i];
     part[threadIdx.x] = s;
     __syncthreads();
     for (int w = 512; w > 0; w >>= 1) {
@@ -104,6 +167,28 @@ gas_status gas_softmax_xent(const void* A, int64_t lda, int64_t n_rows, int32_t 
         GAS_REQUIRE(A && labels && loss_rows && G, "gas_softmax_xent: null pointer");
         GAS_REQUIRE(lda >= n_classes && ldg >= n_classes, "gas_softmax_xent: row stride smaller than the row");
         GAS_REQUIRE(A != G, "gas_softmax_xent: the gradient must not alias the logits");
+        const int epv = dt == GAS_BF16 ? 8 : 4;
+        if (n_classes % epv == 0 && n_classes <= 64 * epv && lda % epv == 0 && ldg % epv == 0 && aligned16(A) &&
+            aligned16(G)) {
+            int lpr_log2 = 0;
+            while ((epv << lpr_log2) < n_classes) ++lpr_log2;
+            const int64_t rows_per_block = 4 * (64 >> lpr_log2);
+            const int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+            if (dt == GAS_BF16)
+                hipLaunchKernelGGL(softmax_xent_rows_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s,
+                                   static_cast<const char*>(A), lda, n_rows, n_classes, labels, scale, loss_rows,
+                                   static_cast<char*>(G), ldg, lpr_log2);
+            else
+                hipLaunchKernelGGL(softmax_xent_rows_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s,
+                                   static_cast<const char*>(A), lda, n_rows, n_classes, labels, scale, loss_rows,
+                                   static_cast<char*>(G), ldg, lpr_log2);
+            GAS_CHECK_HIP(hipGetLastError());
+            if (loss_sum) {
+                hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, loss_rows, n_rows, loss_sum);
+                GAS_CHECK_HIP(hipGetLastError());
+            }
+            return GAS_OK;
+        }
         const int64_t blocks = (n_rows + 3) / 4;
         GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_softmax_xent: too many rows for one launch");
         if (dt == GAS_BF16)

@@ -302,3 +302,45 @@ def gas_batch_backward(model: Model, n_id, rowptr, col, nb, val, x0, h0, saved, 
         gh0 = np.where(ops.to_f64(h0) > 0.0, g_h0, 0.0)
         grads["w_in"] = (ops.to_f64(x0).T @ gh0).astype(np.float32)
     return grads
+
+
+# ----------------------------------------------------------------------------
+# APPNP (paper, operator appendix): graph-agnostic prediction, then K propagation steps without weights
+# ----------------------------------------------------------------------------
+def appnp_batch_forward(w1, w2, alpha, n_steps, n_id, rowptr, col, nb, deg, x_feat, histories, do_push=True):
+    """h^(0) = relu(x W1) W2 for every node of V_b (it depends on the node's own features only, so it is exact
+    for halo rows too), then for l = 1..K:  h^(l)_v = alpha h^(0)_v + (1 - alpha) sum_w h^(l-1)_w / c_{w,v}
+    over N(v) and v itself, with the GCN coefficients.  Steps 1..K-1 are pushed to histories[l-1] and their
+    halo rows pulled back, as for any other operator of Algorithm 1.  Returns h^(K) of the in-batch nodes."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    val = ops.gcn_norm(rowptr, col, n_id, deg)
+    h0 = ops.mlp2(ops.pull(x_feat, n_id), w1, w2, relu_out=False)
+    x = h0
+    y = None
+    for l in range(1, n_steps + 1):
+        y = ops.spmm(rowptr, col, val, x, s_agg=1.0 - alpha, r=h0, s_res=alpha)
+        if l == n_steps:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        x = np.empty((nv, y.shape[1]), dtype=y.dtype)
+        x[:nb] = y
+        x[nb:] = ops.pull(histories[l - 1], n_id[nb:])
+    return y
+
+
+def appnp_full_batch(w1, w2, alpha, n_steps, rowptr, col, x_feat):
+    """The same model on the whole graph in float64 without storage rounding: list of h^(1..K)."""
+    n = len(rowptr) - 1
+    a = _adjacency(rowptr, col, n)
+    deg = np.asarray(a.sum(axis=1)).ravel()
+    dinv = 1.0 / np.sqrt(deg + 1.0)
+    a_hat = sp.diags(dinv) @ (a + sp.identity(n)) @ sp.diags(dinv)
+    f64 = ops.to_f64
+    h0 = np.maximum(f64(x_feat) @ f64(w1), 0.0) @ f64(w2)
+    h, out = h0, []
+    for _ in range(n_steps):
+        h = alpha * h0 + (1.0 - alpha) * (a_hat @ h)
+        out.append(h)
+    return out

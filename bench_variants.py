@@ -1,0 +1,88 @@
+#!/usr/bin/env python3
+"""Timing of operator variants of the layer step on a benchmark configuration's first batch.
+
+  appnp   one propagation step of APPNP (paper, operator appendix): pull + aggregation with the
+          alpha * h0 residual in its epilogue + push; no transform.  Also with the halo rows read in place.
+
+One JSON line on stdout, a table on stderr.  Bytes are algorithmic (indices and coefficients once, every needed
+feature row once, every output row once)."""
+import argparse
+import json
+import os
+import sys
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def timed(fn, reps):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def main():
+    p = argparse.ArgumentParser()
+    p.add_argument("--config", type=int, default=2)
+    p.add_argument("--scale", type=float, default=1.0)
+    p.add_argument("--reps", type=int, default=10)
+    p.add_argument("--width", type=int, default=0, help="feature width (default: the configuration's hidden width)")
+    args = p.parse_args()
+    if not torch.cuda.is_available():
+        sys.exit("bench_variants.py: no GPU visible")
+    import paper_2106_05609_amd as gas
+    from paper_2106_05609_amd import executor
+    from gas_inputs import configs, batches, rng
+    gas.lib()
+    dev = torch.device("cuda:0")
+    cfg = configs.config(args.config, args.scale)
+    g = configs.build_graph(cfg, device=dev)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    sg = batches.batch_subgraph(g, bl[0], True)
+    F, dt = args.width or cfg.widths[-2], cfg.dtype
+    s = 4 if dt == torch.float32 else 2
+    nb, nh, nv, nnz = sg.nb, sg.nh, sg.nv, sg.nnz
+    bg = executor.BatchGraph(nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row, max_F=F, normalise=True)
+    hist_in = rng.normal_matrix(cfg.seed, 200, cfg.n, F, dev, dt)
+    hist_out = torch.zeros((cfg.n, F), dtype=dt, device=dev)
+    x = rng.normal_matrix(cfg.seed, 210, nv, F, dev, dt)
+    h0 = rng.normal_matrix(cfg.seed, 212, nb, F, dev, dt)
+    y = torch.empty((nb, F), dtype=dt, device=dev)
+    alpha = 0.1
+    by = {"pull": nh * (2 * F * s + 4), "spmm": nnz * 8 + (nb + 1) * 4 + nv * F * s + 2 * nb * F * s,
+          "push": nb * (2 * F * s + 4)}
+    calls = {
+        "pull": lambda: gas.gas_pull(hist_in, bg.n_id[nb:], x[nb:]),
+        "spmm": lambda: gas.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, y, s_agg=1.0 - alpha, r=h0, s_res=alpha),
+        "spmm_hist": lambda: gas.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x[:nb], hist_in, y, s_agg=1.0 - alpha,
+                                               r=h0, s_res=alpha),
+        "push": lambda: gas.gas_push(y, bg.n_id[:nb], hist_out),
+    }
+    by["spmm_hist"] = by["spmm"]
+    out = {"workload": f"configs[{args.config}] {cfg.name}: one APPNP propagation step, first batch, width {F}, "
+                       f"{'f32' if s == 4 else 'bf16'}", "nb": nb, "nh": nh, "nnz_b": nnz, "calls": {}}
+    ms = {}
+    for name, fn in calls.items():
+        ms[name] = timed(fn, args.reps)
+        out["calls"][name] = {"ms": round(ms[name], 4), "alg_GB": round(by[name] / 1e9, 3),
+                              "GBps": round(by[name] / ms[name] / 1e6, 1)}
+        print(f"{name:10s} {ms[name]:8.3f} ms  {by[name] / 1e9:7.3f} GB  {by[name] / ms[name] / 1e6:8.1f} GB/s",
+              file=sys.stderr, flush=True)
+    out["step_ms"] = {"separate": round(ms["pull"] + ms["spmm"] + ms["push"], 4),
+                      "in_place": round(ms["spmm_hist"] + ms["push"], 4)}
+    out["edges_per_s"] = {k: round(nnz / (v * 1e-3), 1) for k, v in out["step_ms"].items()}
+    print(f"step: {out['step_ms']} ms, {out['edges_per_s']} edges/s", file=sys.stderr, flush=True)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

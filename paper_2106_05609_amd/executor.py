@@ -290,3 +290,35 @@ def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr
     y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad)
     apply_sgd(model, grads, lr, weight_decay)
     return loss_sum, n_labelled, y, grads
+
+
+def appnp_forward_batch(w1, w2, alpha, n_steps, bg: BatchGraph, x_feat, histories, do_push=True, fused=False):
+    """APPNP (paper, operator appendix) on one mini-batch: h0 = relu(x W1) W2 for every row of the mini-batch
+    tensor (graph-agnostic, so exact for halo rows), then n_steps propagation steps
+    h <- alpha h0 + (1 - alpha) A_hat h, each one aggregation call with the residual in its epilogue; steps
+    1..K-1 are pushed to histories[l-1] and their halo rows pulled back.  fused: from step 2 on the aggregation
+    reads the halo rows from the history table in place (no pull).  Returns h^(K) of the in-batch rows."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x0 = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x0)
+    h0 = torch.empty((nv, w2.shape[1]), dtype=dt, device=dev)
+    B.gas_mlp2(x0, w1, w2, h0, relu_out=False)
+    x, y = h0, None
+    for l in range(1, n_steps + 1):
+        last = l == n_steps
+        x_next = torch.empty((nb if (last or fused) else nv, h0.shape[1]), dtype=dt, device=dev)
+        y = x_next[:nb]
+        if fused and l > 1:
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, histories[l - 2], y, s_agg=1.0 - alpha, r=h0,
+                            s_res=alpha)
+        else:
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, y, s_agg=1.0 - alpha, r=h0, s_res=alpha)
+        if last:
+            break
+        if do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        if not fused and nv > nb:
+            B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
+        x = x_next
+    return y

@@ -143,3 +143,36 @@ def test_paper_overhead_workload_matches_oracle():
     for fn in (executor.forward_batch, executor.forward_batch_fused):
         y = fn(gm, bg, d(x), [d(h).clone() for h in hist])
         assert max_rel_err(to_np(y), want) <= 1e-5, fn.__name__
+
+
+@pytest.mark.parametrize("cfg_id,scale,dtype", [(1, 0.1, torch.float32), (2, 0.02, torch.float32), (1, 0.1, torch.bfloat16)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_appnp_matches_oracle(cfg_id, scale, dtype, fused):
+    """APPNP (operator appendix): graph-agnostic prediction, then 5 weight-free propagation steps through the
+    histories; outputs of two batches and the histories afterwards against the oracle."""
+    from gas_inputs import rng
+    from paper_2106_05609_amd import executor
+    cfg = configs.config(cfg_id, scale)
+    g = configs.build_graph(cfg)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    f_in, f_hid, f_out, K, alpha = 100, 256, 64, 5, 0.1
+    x = rng.normal_matrix(cfg.seed, 830, g.n, f_in, dtype=dtype)
+    w1 = rng.glorot_uniform(cfg.seed, 831, f_in if dtype == torch.float32 else 104, f_hid, dtype=dtype)
+    if dtype == torch.bfloat16:
+        x = rng.normal_matrix(cfg.seed, 830, g.n, 104, dtype=dtype)
+    w2 = rng.glorot_uniform(cfg.seed, 832, f_hid, f_out, dtype=dtype)
+    hist = [rng.normal_matrix(cfg.seed, 840 + l, g.n, f_out, dtype=dtype) for l in range(K - 1)]
+    hs_cpu = [to_np(h).copy() for h in hist]
+    hs_gpu = [h.to("cuda") for h in hist]
+    d = lambda t: t.to("cuda")
+    deg_dev = d(g.deg)
+    for b in (0, 1):
+        sg = batches.batch_subgraph(g, bl[b], True)
+        bg = executor.BatchGraph(sg.nb, d(sg.n_id), d(sg.rowptr), d(sg.col), deg_dev, d(sg.colptr), d(sg.row),
+                                 max_F=f_out, normalise=True)
+        y = executor.appnp_forward_batch(d(w1), d(w2), alpha, K, bg, d(x), hs_gpu, fused=fused)
+        want = omodel.appnp_batch_forward(to_np(w1), to_np(w2), alpha, K, to_np(sg.n_id), to_np(sg.rowptr),
+                                          to_np(sg.col), sg.nb, to_np(g.deg), to_np(x), hs_cpu)
+        assert max_rel_err(to_np(y), want) <= TOL[dtype], (b, max_rel_err(to_np(y), want))
+    for a, c in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), c) <= TOL[dtype]

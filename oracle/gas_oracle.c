@@ -307,3 +307,48 @@ void oracle_sgd_step(void* W, int64_t n, int dt, const float* dW, double lr, dou
         store_elem(W, i, dt, w - lr * ((double)dW[i] + weight_decay * w));
     }
 }
+
+/*
+ * PNA's neighbourhood aggregation (paper, operator appendix): the tensor product of the scalers
+ * [1, s(deg(v), 1), s(deg(v), -1)] with the aggregators [mean, min, max] over the neighbours of v, where
+ * s(d, a) = (log(d + 1) / delta)^a and delta is the mean of log(deg + 1) over the graph (passed in).
+ *
+ *   agg_j[v] = add[v] + (mean | min | max)_{w in N(v)} X[w]      j = 0, 1, 2, element-wise
+ *   out[v]   = [ agg_0, agg_1, agg_2,  s agg_0, s agg_1, s agg_2,  agg_0 / s, agg_1 / s, agg_2 / s ]
+ *
+ * with s = log(d_v + 1) / delta and d_v the number of entries of row v (all neighbours of an in-batch node are
+ * in the batch subgraph, so this is its degree in the full graph).  `add` (optional) is the part of a message
+ * that depends on the receiving node only and therefore commutes with all three aggregators.  A node without
+ * neighbours receives no message: its nine blocks are zero.
+ */
+void oracle_pna_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows, const void* X, int64_t ldx,
+                          int dt, int32_t F, const void* add, int64_t ldadd, double delta, void* out,
+                          int64_t ldout) {
+    #pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        int64_t b = rowptr[v], e = rowptr[v + 1];
+        double d = (double)(e - b);
+        double s = log(d + 1.0) / delta;
+        for (int32_t f = 0; f < F; ++f) {
+            double agg[3] = {0.0, 0.0, 0.0};
+            if (e > b) {
+                double sum = 0.0, mn = INFINITY, mx = -INFINITY;
+                for (int64_t k = b; k < e; ++k) {
+                    double x = load_elem(X, (int64_t)col[k] * ldx + f, dt);
+                    sum += x;
+                    if (x < mn) mn = x;
+                    if (x > mx) mx = x;
+                }
+                double q = add ? load_elem(add, v * ldadd + f, dt) : 0.0;
+                agg[0] = sum / d + q;
+                agg[1] = mn + q;
+                agg[2] = mx + q;
+            }
+            for (int j = 0; j < 3; ++j) {
+                store_elem(out, v * ldout + (int64_t)j * F + f, dt, agg[j]);
+                store_elem(out, v * ldout + (int64_t)(3 + j) * F + f, dt, e > b ? s * agg[j] : 0.0);
+                store_elem(out, v * ldout + (int64_t)(6 + j) * F + f, dt, e > b ? agg[j] / s : 0.0);
+            }
+        }
+    }
+}

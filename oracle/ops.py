@@ -211,3 +211,18 @@ def sgd_step(w, dw, lr, weight_decay=0.0) -> None:
     """In place: w <- w - lr * (dw + weight_decay * w); w contiguous in its storage type, dw float32."""
     assert w.flags.c_contiguous and dw.flags.c_contiguous and dw.dtype == np.float32 and dw.size == w.size
     lib().oracle_sgd_step(_p(w), C.c_int64(w.size), C.c_int(_dt(w)), _p(dw), C.c_double(lr), C.c_double(weight_decay))
+
+
+def pna_aggregate(rowptr, col, x, delta, add=None) -> np.ndarray:
+    """[n_rows, 9F]: scalers [1, s, 1/s] (x) aggregators [mean, min, max] over the neighbours, s = log(d+1)/delta."""
+    rowptr, col = _i32(rowptr), _i32(col)
+    x, ldx = _rows(x)
+    n_rows, f = rowptr.size - 1, x.shape[1]
+    ldadd = 0
+    if add is not None:
+        add, ldadd = _rows(add)
+        assert add.dtype == x.dtype and add.shape == (n_rows, f)
+    out = np.empty((n_rows, 9 * f), dtype=x.dtype)
+    lib().oracle_pna_aggregate(_p(rowptr), _p(col), C.c_int64(n_rows), _p(x), C.c_int64(ldx), C.c_int(_dt(x)),
+                               C.c_int32(f), _p(add), C.c_int64(ldadd), C.c_double(delta), _p(out), C.c_int64(9 * f))
+    return out

@@ -1,0 +1,88 @@
+"""Pins for the oracle's PNA aggregation (CPU only): mean against the row-normalised dense adjacency product,
+min and max against numpy's masked reductions over the dense adjacency, the degree scalers against their closed
+form on a regular graph (all equal to one) and on a star, the receiving-node term commuting with all three
+aggregators, and a node without neighbours."""
+import numpy as np
+
+from gas_inputs import rng
+from oracle import ops
+from tests.util import to_np, f64
+from tests.test_oracle_gas import _workload, _sub
+
+
+def _dense(rp, cl, nb, nv):
+    a = np.zeros((nb, nv), dtype=bool)
+    for v in range(nb):
+        a[v, cl[rp[v]:rp[v + 1]]] = True
+    return a
+
+
+def test_aggregators_match_dense_brute_force():
+    wl = _workload("gin", n=300, layers=2, f=8)                # no self-loops: N(v) only
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, wl.batches[2])
+    f = 7
+    x = to_np(rng.normal_matrix(41, 900, sg.nv, f))
+    q = to_np(rng.normal_matrix(41, 901, sg.nb, f))
+    deg = to_np(g.deg).astype(np.float64)
+    delta = float(np.log(deg + 1.0).mean())
+    out = ops.pna_aggregate(rp, cl, x, delta, add=q)
+    a = _dense(rp, cl, sg.nb, sg.nv)
+    d = a.sum(axis=1)
+    assert np.array_equal(d, deg[n_id[:sg.nb]])                # every neighbour of an in-batch node is in G_b
+    has = d > 0
+    xx = f64(x)
+    mean = np.where(has[:, None], (a.astype(np.float64) @ xx) / np.maximum(d, 1)[:, None] + f64(q), 0.0)
+    big = np.where(a[:, :, None], xx[None, :, :], np.inf)
+    mn = np.where(has[:, None], big.min(axis=1) + f64(q), 0.0)
+    mx = np.where(has[:, None], np.where(a[:, :, None], xx[None, :, :], -np.inf).max(axis=1) + f64(q), 0.0)
+    s = np.log(d + 1.0) / delta
+    blocks = [mean, mn, mx]
+    for j in range(3):
+        assert np.abs(out[:, j * f:(j + 1) * f] - blocks[j]).max() <= 1e-6 * np.abs(blocks[j]).max(), j
+        want = s[:, None] * blocks[j]
+        assert np.abs(out[:, (3 + j) * f:(4 + j) * f] - want).max() <= 1e-6 * np.abs(want).max(), j
+        want = np.where(has[:, None], blocks[j] / np.where(has, s, 1.0)[:, None], 0.0)
+        assert np.abs(out[:, (6 + j) * f:(7 + j) * f] - want).max() <= 1e-6 * np.abs(want).max(), j
+    # min <= mean <= max wherever there is a neighbour
+    assert (out[has, f:2 * f] <= out[has, :f] + 1e-6).all() and (out[has, :f] <= out[has, 2 * f:3 * f] + 1e-6).all()
+
+
+def test_scalers_closed_forms_and_isolated_node():
+    # a ring: every degree is 2, delta = log 3, so s = 1 and the three scaler blocks coincide
+    n, f = 12, 5
+    rp = np.arange(0, 2 * n + 1, 2, dtype=np.int32)
+    cl = np.stack([(np.arange(n) - 1) % n, (np.arange(n) + 1) % n], axis=1).astype(np.int32)
+    cl.sort(axis=1)
+    x = to_np(rng.normal_matrix(42, 910, n, f))
+    out = ops.pna_aggregate(rp, cl.ravel(), x, float(np.log(3.0)))
+    assert np.array_equal(out[:, :3 * f], out[:, 3 * f:6 * f]) and np.array_equal(out[:, :3 * f], out[:, 6 * f:])
+    left, right = f64(x)[(np.arange(n) - 1) % n], f64(x)[(np.arange(n) + 1) % n]
+    assert np.abs(out[:, :f] - (left + right) / 2).max() <= 1e-7
+    assert np.array_equal(out[:, f:2 * f], np.minimum(left, right).astype(np.float32))
+    assert np.array_equal(out[:, 2 * f:3 * f], np.maximum(left, right).astype(np.float32))
+    # a star with 4 leaves plus an isolated node: centre sees all leaves, a leaf sees only the centre
+    rp = np.array([0, 4, 5, 6, 7, 8, 8], dtype=np.int32)
+    cl = np.array([1, 2, 3, 4, 0, 0, 0, 0], dtype=np.int32)
+    x = np.array([[10.0], [1.0], [2.0], [3.0], [6.0], [99.0]], np.float32)
+    delta = 0.7
+    out = ops.pna_aggregate(rp, cl, x, delta)
+    s_c, s_l = np.log(5.0) / delta, np.log(2.0) / delta
+    want_c = [3.0, 1.0, 6.0, 3.0 * s_c, 1.0 * s_c, 6.0 * s_c, 3.0 / s_c, 1.0 / s_c, 6.0 / s_c]
+    assert np.allclose(out[0], want_c, rtol=1e-6)
+    assert np.allclose(out[1], [10.0] * 3 + [10.0 * s_l] * 3 + [10.0 / s_l] * 3, rtol=1e-6)
+    assert not out[5].any()                                     # no neighbour, no message
+
+
+def test_bf16_storage_rounds_once():
+    import torch
+    wl = _workload("gin", n=200, layers=2, f=8)
+    sg, n_id, rp, cl = _sub(wl, wl.batches[0])
+    f = 8
+    xb = rng.normal_matrix(43, 920, sg.nv, f, dtype=torch.bfloat16)
+    out = ops.pna_aggregate(rp, cl, to_np(xb), 1.3)
+    ref = ops.pna_aggregate(rp, cl, to_np(xb.float()), 1.3)    # same inputs, fp32 storage
+    # min and max of bf16 values are bf16 values: exact; the others are within half a bf16 ulp of the fp32 result
+    assert np.array_equal(f64(out[:, f:3 * f]), f64(ref[:, f:3 * f]))
+    err = np.abs(f64(out) - f64(ref))
+    assert (err <= 2.0 ** -8 * np.abs(f64(ref)) + 1e-30).all()

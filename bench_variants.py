@@ -3,6 +3,8 @@
 
   appnp   one propagation step of APPNP (paper, operator appendix): pull + aggregation with the
           alpha * h0 residual in its epilogue + push; no transform.  Also with the halo rows read in place.
+  pna     PNA's neighbourhood aggregation (same appendix): mean, min and max with the three degree scalers in
+          one pass over the gathered rows (9 output blocks per row).
 
 One JSON line on stdout, a table on stderr.  Bytes are algorithmic (indices and coefficients once, every needed
 feature row once, every output row once)."""
@@ -77,6 +79,15 @@ def main():
                               "GBps": round(by[name] / ms[name] / 1e6, 1)}
         print(f"{name:10s} {ms[name]:8.3f} ms  {by[name] / 1e9:7.3f} GB  {by[name] / ms[name] / 1e6:8.1f} GB/s",
               file=sys.stderr, flush=True)
+    # PNA aggregation over the same batch subgraph (self-loops excluded from the pattern would change nnz by nb only)
+    delta = float(torch.log(g.deg.double() + 1.0).mean())
+    out9 = torch.empty((nb, 9 * F), dtype=dt, device=dev)
+    t = timed(lambda: gas.gas_pna_aggregate(bg.rowptr, bg.col, x, out9, delta, add=h0), args.reps)
+    nbytes = nnz * 4 + (nb + 1) * 4 + nv * F * s + nb * F * s + 9 * nb * F * s
+    out["pna_aggregate"] = {"ms": round(t, 4), "alg_GB": round(nbytes / 1e9, 3), "GBps": round(nbytes / t / 1e6, 1),
+                            "gathered_GBps": round(nnz * F * s / t / 1e6, 1)}
+    print(f"pna_aggr   {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s  (gathers {nnz * F * s / t / 1e6:.0f} GB/s)",
+          file=sys.stderr, flush=True)
     out["step_ms"] = {"separate": round(ms["pull"] + ms["spmm"] + ms["push"], 4),
                       "in_place": round(ms["spmm_hist"] + ms["push"], 4)}
     out["edges_per_s"] = {k: round(nnz / (v * 1e-3), 1) for k, v in out["step_ms"].items()}

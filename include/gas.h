@@ -277,6 +277,24 @@ GAS_API gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* d
                         void* stream);
 
 /*
+ * PNA's neighbourhood aggregation (operator appendix): for every row v of the
+ * batch subgraph, in one pass over the gathered rows,
+ *     agg_0 = mean, agg_1 = min, agg_2 = max  over X[col[k], 0:F], k in row v,
+ *     each plus add[v, 0:F] if add is given (the part of a message that depends
+ *     on the receiving node only),
+ * and out[v] = [agg_0 agg_1 agg_2 | s agg_0 .. | agg_0 / s ..] (9 F columns),
+ * s = log(d_v + 1) / delta, d_v = rowptr[v+1] - rowptr[v]; delta > 0 is the
+ * mean of log(deg + 1) over the graph.  Rows without entries give zeros.
+ * rowptr int32[n_rows+1], col int32[nnz] in range of X's rows; X, add, out of
+ * type dt (device), out must not alias them.  Deterministic (entries folded
+ * in index order).
+ */
+GAS_API gas_status gas_pna_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+                             const void* X, int64_t ldx, gas_dtype dt, int32_t F,
+                             const void* add, int64_t ldadd, float delta,
+                             void* out, int64_t ldout, void* stream);
+
+/*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
  * flag back and waits for `stream`.
  */

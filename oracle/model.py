@@ -344,3 +344,40 @@ def appnp_full_batch(w1, w2, alpha, n_steps, rowptr, col, x_feat):
         h = alpha * h0 + (1.0 - alpha) * (a_hat @ h)
         out.append(h)
     return out
+
+
+# ----------------------------------------------------------------------------
+# PNA (paper, operator appendix)
+# ----------------------------------------------------------------------------
+def pna_layer(x, nb, rowptr, col, w1, w2, delta, relu):
+    """h'_v = W2 [h_v, (+)_w W1 [h_v, h_w]] for the in-batch rows.  W1 is [2F, F1] (rows 0..F-1 multiply the
+    receiving node, rows F.. the neighbour), W2 is [F + 9 F1, F_out].  A message is W1a h_v + W1b h_w and its
+    first part is the same for every neighbour, so it commutes with mean, min and max: the neighbour part is
+    computed once per node of V_b, aggregated, and the receiving-node part added afterwards."""
+    f = x.shape[1]
+    w1a, w1b = np.ascontiguousarray(w1[:f]), np.ascontiguousarray(w1[f:])
+    p = ops.linear(x, w1b)                          # every node of V_b as a neighbour
+    q = ops.linear(np.ascontiguousarray(x[:nb]), w1a)
+    a9 = ops.pna_aggregate(rowptr, col, p, delta, add=q)
+    cat = np.concatenate([x[:nb], a9], axis=1)
+    return ops.linear(cat, w2, relu=relu)
+
+
+def pna_batch_forward(weights, delta, n_id, rowptr, col, nb, x_feat, histories, do_push=True):
+    """All layers of a PNA model for one mini-batch in the order of Algorithm 1; weights[l] = (W1, W2)."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    x = ops.pull(x_feat, n_id)
+    L = len(weights)
+    y = None
+    for l in range(1, L + 1):
+        w1, w2 = weights[l - 1]
+        y = pna_layer(x, nb, rowptr, col, w1, w2, delta, relu=l < L)
+        if l == L:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        x = np.empty((nv, y.shape[1]), dtype=y.dtype)
+        x[:nb] = y
+        x[nb:] = ops.pull(histories[l - 1], n_id[nb:])
+    return y

@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate"]
 
 _lib = None
 
@@ -302,3 +302,17 @@ def gas_sgd_step(w, dw, lr, weight_decay=0.0):
         raise ValueError("gas_sgd_step: w and dw must be contiguous and of equal size, dw float32")
     _check(lib().gas_sgd_step(_ptr(w), C.c_int64(w.numel()), C.c_int(_dt(w)), _ptr(dw, torch.float32),
                               C.c_float(lr), C.c_float(weight_decay), _stream()))
+
+
+def gas_pna_aggregate(rowptr, col, x, out, delta, add=None):
+    """out [n_rows, 9F] = scalers [1, s, 1/s] (x) aggregators [mean, min, max] over the neighbours (+ add)."""
+    xp, ldx = _mat(x)
+    op, ldo = _mat(out)
+    ap, lda = (C.c_void_p(0), C.c_int64(0)) if add is None else _mat(add)
+    n_rows = rowptr.numel() - 1
+    if out.dtype != x.dtype or out.shape[0] < n_rows or out.shape[1] != 9 * x.shape[1] or \
+            (add is not None and (add.dtype != x.dtype or add.shape[1] != x.shape[1] or add.shape[0] < n_rows)):
+        raise ValueError("gas_pna_aggregate: shapes or dtypes do not match")
+    _check(lib().gas_pna_aggregate(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows), xp, ldx,
+                                   C.c_int(_dt(x)), C.c_int32(x.shape[1]), ap, lda, C.c_float(delta), op, ldo,
+                                   _stream()))

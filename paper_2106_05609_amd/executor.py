@@ -322,3 +322,48 @@ def appnp_forward_batch(w1, w2, alpha, n_steps, bg: BatchGraph, x_feat, historie
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
         x = x_next
     return y
+
+
+def pna_layer(x, nb, rowptr, col, w1, w2, delta, relu, y=None):
+    """One PNA layer (paper, operator appendix) for the in-batch rows: h'_v = W2 [h_v, (+)_w W1 [h_v, h_w]].
+    x: mini-batch tensor [nv, F]; w1 [2F, F1] (rows 0..F-1 multiply the receiving node, rows F.. the neighbour),
+    w2 [F + 9 F1, F_out].  The neighbour part of a message is computed once per node (gas_linear over all of
+    V_b), aggregated by mean, min and max in one pass with the degree scalers (gas_pna_aggregate), the
+    receiving-node part is added inside that call, and the concatenation with h_v is laid out in one buffer
+    that the second gas_linear reads."""
+    dev, dt = x.device, x.dtype
+    f, f1 = x.shape[1], w1.shape[1]
+    p = torch.empty((x.shape[0], f1), dtype=dt, device=dev)
+    B.gas_linear(x, w1[f:], p)
+    q = torch.empty((nb, f1), dtype=dt, device=dev)
+    B.gas_linear(x[:nb], w1[:f], q)
+    cat = torch.empty((nb, f + 9 * f1), dtype=dt, device=dev)
+    B.gas_pull(x, None, cat[:, :f], base=0, n=nb)                 # h_v into the first F columns (a strided row copy)
+    B.gas_pna_aggregate(rowptr, col, p, cat[:, f:], delta, add=q)
+    if y is None:
+        y = torch.empty((nb, w2.shape[1]), dtype=dt, device=dev)
+    B.gas_linear(cat, w2, y, relu=relu)
+    return y
+
+
+def pna_forward_batch(weights, delta, bg: BatchGraph, x_feat, histories, do_push=True):
+    """All layers of a PNA model for one mini-batch in the order of Algorithm 1; weights[l] = (W1, W2)."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    L = len(weights)
+    y = None
+    for l in range(1, L + 1):
+        w1, w2 = weights[l - 1]
+        last = l == L
+        x_next = torch.empty((nb if last else nv, w2.shape[1]), dtype=dt, device=dev)
+        y = pna_layer(x, nb, bg.rowptr, bg.col, w1, w2, delta, relu=not last, y=x_next[:nb])
+        if last:
+            break
+        if do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        if nv > nb:
+            B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
+        x = x_next
+    return y

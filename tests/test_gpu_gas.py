@@ -176,3 +176,35 @@ def test_appnp_matches_oracle(cfg_id, scale, dtype, fused):
         assert max_rel_err(to_np(y), want) <= TOL[dtype], (b, max_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
         assert max_rel_err(to_np(a), c) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("cfg_id,scale,dtype,f,f1", [(1, 0.1, torch.float32, 64, 32), (2, 0.01, torch.float32, 100, 28),
+                                                      (4, 0.0005, torch.bfloat16, 64, 64)])
+def test_pna_model_matches_oracle(cfg_id, scale, dtype, f, f1):
+    """Three PNA layers (operator appendix) through the histories, two batches, against the oracle."""
+    from gas_inputs import rng
+    from paper_2106_05609_amd import executor
+    cfg = configs.config(cfg_id, scale)
+    g = configs.build_graph(cfg)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    L = 3
+    x = rng.normal_matrix(cfg.seed, 860, g.n, f, dtype=dtype)
+    ws = [(rng.glorot_uniform(cfg.seed, 861 + 2 * l, 2 * f, f1, dtype=dtype),
+           rng.glorot_uniform(cfg.seed, 862 + 2 * l, f + 9 * f1, f, dtype=dtype)) for l in range(L)]
+    hist = [rng.normal_matrix(cfg.seed, 870 + l, g.n, f, dtype=dtype) for l in range(L - 1)]
+    hs_cpu = [to_np(h).copy() for h in hist]
+    hs_gpu = [h.to("cuda") for h in hist]
+    delta = float(torch.log(g.deg.double() + 1.0).mean())
+    d = lambda t: t.to("cuda")
+    ws_gpu = [(d(a), d(b)) for a, b in ws]
+    ws_cpu = [(to_np(a), to_np(b)) for a, b in ws]
+    tol = TOL[dtype] * (3 if dtype == torch.float32 else 1)      # three layers of three GEMMs each on top of the sums
+    for b in (0, 1):
+        sg = batches.batch_subgraph(g, bl[b], False)
+        bg = executor.BatchGraph(sg.nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=f, normalise=False)
+        y = executor.pna_forward_batch(ws_gpu, delta, bg, d(x), hs_gpu)
+        want = omodel.pna_batch_forward(ws_cpu, delta, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x),
+                                        hs_cpu)
+        assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
+    for a, c in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), c) <= tol

@@ -325,3 +325,37 @@ def test_transform_with_fused_push(gas, dtype, M, K, H, N, ld_hist):
     if M:
         with pytest.raises(gas.GasError):
             gas.gas_linear_push(z, w, y, idx, y, bias=b2)            # the table must not be the output
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name,F,ld_pad", [("powerlaw", 256, 0), ("gin", 64, 8), ("sbm", 100, 0), ("powerlaw", 7, 0),
+                                           ("gin", 520, 0), ("sbm", 8, 0)])
+def test_pna_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
+    """Scalers x aggregators of PNA (operator appendix) in one pass: every block against the oracle; the
+    min and max blocks of a call without the receiving-node term are bit-exact (they select stored values)."""
+    cfg, g, sg = graphs_small[name]
+    nb, nv = sg.nb, sg.nv
+    x = rng.normal_matrix(11, 950, nv, F + ld_pad, dtype=dtype)
+    q = rng.normal_matrix(11, 951, nb, F, dtype=dtype)
+    delta = float(torch.log(g.deg.double() + 1.0).mean())
+    d_ptr, d_col = dev(sg.rowptr), dev(sg.col)
+    for add in (None, q):
+        out = torch.full((nb, 9 * F + ld_pad), float("nan"), dtype=dtype, device="cuda")
+        gas.gas_pna_aggregate(d_ptr, d_col, dev(x)[:, :F], out[:, :9 * F], delta, add=None if add is None else dev(add))
+        want = oops.pna_aggregate(to_np(sg.rowptr), to_np(sg.col), to_np(x)[:, :F], delta,
+                                  add=None if add is None else to_np(add))
+        got = to_np(out[:, :9 * F])
+        for j in range(9):
+            blk = slice(j * F, (j + 1) * F)
+            assert max_rel_err(got[:, blk], want[:, blk]) <= TOL[dtype], (j, max_rel_err(got[:, blk], want[:, blk]))
+        if add is None:
+            assert np.array_equal(got[:, F:3 * F], want[:, F:3 * F])
+    # a row without neighbours gives zeros; an empty problem is fine
+    ptr = torch.tensor([0, 0, 2], dtype=torch.int32, device="cuda")
+    col = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    out = torch.full((2, 9 * F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_pna_aggregate(ptr, col, dev(x)[:, :F], out, delta)
+    assert not to_np(out[0]).any() and not torch.isnan(out.float()).any()
+    gas.gas_pna_aggregate(ptr[:1], col[:0], dev(x)[:, :F], out[:0], delta)
+    with pytest.raises(gas.GasError):
+        gas.gas_pna_aggregate(ptr, col, dev(x)[:, :F], out, 0.0)

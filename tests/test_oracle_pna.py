@@ -86,3 +86,57 @@ def test_bf16_storage_rounds_once():
     assert np.array_equal(f64(out[:, f:3 * f]), f64(ref[:, f:3 * f]))
     err = np.abs(f64(out) - f64(ref))
     assert (err <= 2.0 ** -8 * np.abs(f64(ref)) + 1e-30).all()
+
+
+def test_layer_equals_the_formula_written_out_per_message():
+    """The operator appendix's formula evaluated literally: every message W1 [h_v, h_w] built on its own, then
+    aggregated, scaled, concatenated and multiplied by W2, in float64."""
+    from oracle import model as omodel
+    wl = _workload("gin", n=160, layers=2, f=8)
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, wl.batches[1])
+    f, f1, f_out = 6, 5, 4
+    x = to_np(rng.normal_matrix(44, 930, sg.nv, f))
+    w1 = to_np(rng.glorot_uniform(44, 931, 2 * f, f1))
+    w2 = to_np(rng.glorot_uniform(44, 932, f + 9 * f1, f_out))
+    delta = float(np.log(to_np(g.deg).astype(np.float64) + 1.0).mean())
+    y = omodel.pna_layer(x, sg.nb, rp, cl, w1, w2, delta, relu=True)
+    xx, ww1, ww2 = f64(x), f64(w1), f64(w2)
+    want = np.zeros((sg.nb, f_out))
+    for v in range(sg.nb):
+        nbrs = cl[rp[v]:rp[v + 1]]
+        if len(nbrs):
+            msgs = np.stack([np.concatenate([xx[v], xx[w]]) @ ww1 for w in nbrs])
+            aggs = np.concatenate([msgs.mean(axis=0), msgs.min(axis=0), msgs.max(axis=0)])
+            s = np.log(len(nbrs) + 1.0) / delta
+            big = np.concatenate([aggs, s * aggs, aggs / s])
+        else:
+            big = np.zeros(9 * f1)
+        want[v] = np.maximum(np.concatenate([xx[v], big]) @ ww2, 0.0)
+    assert np.abs(f64(y) - want).max() <= 3e-6 * np.abs(want).max()
+    assert (want > 0).any()
+
+
+def test_pna_whole_graph_batch_needs_no_history():
+    from oracle import model as omodel
+    import torch
+    wl = _workload("gin", n=160, layers=2, f=8)
+    g = wl.graph
+    f, f1 = 6, 5
+    x = to_np(rng.normal_matrix(45, 940, g.n, f))
+    ws = [(to_np(rng.glorot_uniform(45, 941 + 2 * l, 2 * f, f1)), to_np(rng.glorot_uniform(45, 942 + 2 * l, f + 9 * f1, f)))
+          for l in range(3)]
+    delta = float(np.log(to_np(g.deg).astype(np.float64) + 1.0).mean())
+    sg, n_id, rp, cl = _sub(wl, torch.cat(wl.batches))
+    junk = [to_np(rng.normal_matrix(45, 950 + l, g.n, f)) for l in range(2)]
+    zero = [np.zeros((g.n, f), np.float32) for _ in range(2)]
+    a = omodel.pna_batch_forward(ws, delta, n_id, rp, cl, sg.nb, x, junk)
+    b = omodel.pna_batch_forward(ws, delta, n_id, rp, cl, sg.nb, x, zero)
+    assert np.array_equal(a, b)                                  # no halo: histories are written, never read
+    # a proper batch with the whole-graph run's own histories reproduces its rows
+    sg1, n_id1, rp1, cl1 = _sub(wl, wl.batches[0])
+    assert sg1.nh > 0
+    y1 = omodel.pna_batch_forward(ws, delta, n_id1, rp1, cl1, sg1.nb, x, [h.copy() for h in zero], do_push=False)
+    order = np.argsort(n_id[:sg.nb])
+    full_rows = a[order][n_id1[:sg1.nb]]
+    assert np.abs(y1 - full_rows).max() <= 5e-6 * np.abs(full_rows).max()

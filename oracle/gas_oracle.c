@@ -352,3 +352,47 @@ void oracle_pna_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_r
         }
     }
 }
+
+/*
+ * GAT's anisotropic aggregation (paper, operator appendix), one head: for every row v of the batch subgraph,
+ * whose entries list N(v) and v itself,
+ *     e_k      = LeakyReLU(a_dst . P[v] + a_src . P[col[k]])          (negative slope given)
+ *     alpha_k  = exp(e_k) / sum_k' exp(e_k')                          (softmax over the row's entries)
+ *     Z[v]     = sum_k alpha_k P[col[k]]
+ * with P = H W computed beforehand for every node of V_b.  a = [a_dst, a_src] is the attention vector split into
+ * the part that meets the receiving node and the part that meets the neighbour.  A row without entries gives
+ * zeros.  Written as the definition: scores, their maximum, the normalised weights, the weighted sum.
+ */
+void oracle_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows, const void* P, int64_t ldp,
+                          int dt, int32_t F, const void* a_dst, const void* a_src, double negative_slope,
+                          void* Z, int64_t ldz) {
+    #pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        int64_t b = rowptr[v], e = rowptr[v + 1];
+        if (e == b) {
+            for (int32_t f = 0; f < F; ++f) store_elem(Z, v * ldz + f, dt, 0.0);
+            continue;
+        }
+        double sv = 0.0;
+        for (int32_t f = 0; f < F; ++f) sv += load_elem(a_dst, f, dt) * load_elem(P, v * ldp + f, dt);
+        double* score = (double*)malloc(sizeof(double) * (size_t)(e - b));
+        double mx = -INFINITY;
+        for (int64_t k = b; k < e; ++k) {
+            double sw = 0.0;
+            for (int32_t f = 0; f < F; ++f) sw += load_elem(a_src, f, dt) * load_elem(P, (int64_t)col[k] * ldp + f, dt);
+            double x = sv + sw;
+            x = x > 0.0 ? x : negative_slope * x;
+            score[k - b] = x;
+            if (x > mx) mx = x;
+        }
+        double den = 0.0;
+        for (int64_t k = b; k < e; ++k) den += exp(score[k - b] - mx);
+        for (int32_t f = 0; f < F; ++f) {
+            double acc = 0.0;
+            for (int64_t k = b; k < e; ++k)
+                acc += exp(score[k - b] - mx) / den * load_elem(P, (int64_t)col[k] * ldp + f, dt);
+            store_elem(Z, v * ldz + f, dt, acc);
+        }
+        free(score);
+    }
+}

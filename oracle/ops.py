@@ -226,3 +226,16 @@ def pna_aggregate(rowptr, col, x, delta, add=None) -> np.ndarray:
     lib().oracle_pna_aggregate(_p(rowptr), _p(col), C.c_int64(n_rows), _p(x), C.c_int64(ldx), C.c_int(_dt(x)),
                                C.c_int32(f), _p(add), C.c_int64(ldadd), C.c_double(delta), _p(out), C.c_int64(9 * f))
     return out
+
+
+def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2) -> np.ndarray:
+    """Z[v] = sum_k softmax_k(LeakyReLU(a_dst.P[v] + a_src.P[col k])) P[col k] over the entries of row v."""
+    rowptr, col = _i32(rowptr), _i32(col)
+    p, ldp = _rows(p)
+    n_rows, f = rowptr.size - 1, p.shape[1]
+    a_dst, a_src = np.ascontiguousarray(a_dst), np.ascontiguousarray(a_src)
+    assert a_dst.dtype == p.dtype == a_src.dtype and a_dst.size == f == a_src.size
+    z = np.empty((n_rows, f), dtype=p.dtype)
+    lib().oracle_gat_aggregate(_p(rowptr), _p(col), C.c_int64(n_rows), _p(p), C.c_int64(ldp), C.c_int(_dt(p)),
+                               C.c_int32(f), _p(a_dst), _p(a_src), C.c_double(negative_slope), _p(z), C.c_int64(f))
+    return z

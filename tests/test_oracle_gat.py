@@ -1,0 +1,65 @@
+"""Pins for the oracle's GAT aggregation (CPU only): dense brute force with torch's own softmax and leaky_relu in
+float64, the zero attention vector (uniform weights: the mean over N(v) and v), invariance to a shift of the
+receiving node's score, weights that sum to one, and the limit of a dominating neighbour."""
+import numpy as np
+import torch
+
+from gas_inputs import rng
+from oracle import ops
+from tests.util import to_np, f64
+from tests.test_oracle_gas import _workload, _sub
+
+
+def _case(f=9, op="gcn"):
+    wl = _workload(op, n=240, layers=2, f=8)       # gcn: the pattern carries the self-loops
+    sg, n_id, rp, cl = _sub(wl, wl.batches[1])
+    p = to_np(rng.normal_matrix(51, 1000, sg.nv, f))
+    a_dst = to_np(rng.normal(51, 1001, 0, f))
+    a_src = to_np(rng.normal(51, 1002, 0, f))
+    return sg, rp, cl, p, a_dst, a_src
+
+
+def test_matches_dense_softmax_in_float64():
+    sg, rp, cl, p, a_dst, a_src = _case()
+    z = ops.gat_aggregate(rp, cl, p, a_dst, a_src, 0.2)
+    pp = torch.from_numpy(f64(p))
+    s_dst = pp[:sg.nb] @ torch.from_numpy(f64(a_dst))
+    s_src = pp @ torch.from_numpy(f64(a_src))
+    e = torch.nn.functional.leaky_relu(s_dst[:, None] + s_src[None, :], 0.2)
+    mask = torch.zeros((sg.nb, sg.nv), dtype=torch.bool)
+    for v in range(sg.nb):
+        mask[v, cl[rp[v]:rp[v + 1]]] = True
+    assert mask[torch.arange(sg.nb), torch.arange(sg.nb)].all()            # v itself is among the entries
+    alpha = torch.softmax(e.masked_fill(~mask, float("-inf")), dim=1)
+    want = (alpha @ pp).numpy()
+    assert np.abs(z - want).max() <= 1e-6 * np.abs(want).max()
+    assert torch.allclose(alpha.sum(dim=1), torch.ones(sg.nb, dtype=torch.float64))
+
+
+def test_zero_attention_vector_is_the_mean_and_shift_invariance():
+    sg, rp, cl, p, a_dst, a_src = _case()
+    zero = np.zeros_like(a_dst)
+    z = ops.gat_aggregate(rp, cl, p, zero, zero)
+    for v in (0, 5, sg.nb - 1):
+        want = f64(p)[cl[rp[v]:rp[v + 1]]].mean(axis=0)
+        assert np.abs(z[v] - want).max() <= 1e-6
+    # with slope 1 the activation is the identity and the receiving node's score cancels in the softmax
+    z1 = ops.gat_aggregate(rp, cl, p, a_dst, a_src, 1.0)
+    z2 = ops.gat_aggregate(rp, cl, p, 3.0 * a_dst, a_src, 1.0)
+    assert np.abs(z1 - z2).max() <= 2e-6 * np.abs(z1).max()
+    # with the usual slope it does not cancel
+    z3 = ops.gat_aggregate(rp, cl, p, a_dst, a_src, 0.2)
+    z4 = ops.gat_aggregate(rp, cl, p, 3.0 * a_dst, a_src, 0.2)
+    assert np.abs(z3 - z4).max() > 1e-3
+
+
+def test_dominating_neighbour_and_empty_row():
+    # 3 source rows; row 0 lists all of them, row 1 is empty; a_src makes source 2 win by a wide margin
+    rp = np.array([0, 3, 3], dtype=np.int32)
+    cl = np.array([0, 1, 2], dtype=np.int32)
+    p = np.array([[1.0, 0.0], [0.0, 1.0], [50.0, 7.0]], np.float32)
+    z = ops.gat_aggregate(rp, cl, p, np.zeros(2, np.float32), np.array([2.0, 0.0], np.float32))
+    assert np.allclose(z[0], [50.0, 7.0], rtol=1e-6) and not z[1].any()
+    # very large scores neither overflow nor lose the answer
+    z = ops.gat_aggregate(rp, cl, p * 100, np.zeros(2, np.float32), np.array([2.0, 0.0], np.float32))
+    assert np.isfinite(z).all() and np.allclose(z[0], [5000.0, 700.0], rtol=1e-6)

@@ -5,6 +5,8 @@
           alpha * h0 residual in its epilogue + push; no transform.  Also with the halo rows read in place.
   pna     PNA's neighbourhood aggregation (same appendix): mean, min and max with the three degree scalers in
           one pass over the gathered rows (9 output blocks per row).
+  gat     GAT's aggregation (same appendix, one head): scores, softmax over the row's entries and the weighted
+          sum in one pass over the gathered rows.
 
 One JSON line on stdout, a table on stderr.  Bytes are algorithmic (indices and coefficients once, every needed
 feature row once, every output row once)."""
@@ -87,6 +89,14 @@ def main():
     out["pna_aggregate"] = {"ms": round(t, 4), "alg_GB": round(nbytes / 1e9, 3), "GBps": round(nbytes / t / 1e6, 1),
                             "gathered_GBps": round(nnz * F * s / t / 1e6, 1)}
     print(f"pna_aggr   {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s  (gathers {nnz * F * s / t / 1e6:.0f} GB/s)",
+          file=sys.stderr, flush=True)
+    a_dst = rng.normal(cfg.seed, 213, 0, F, dev, dt) * 0.1
+    a_src = rng.normal(cfg.seed, 214, 0, F, dev, dt) * 0.1
+    t = timed(lambda: gas.gas_gat_aggregate(bg.rowptr, bg.col, x, a_dst, a_src, y, 0.2, relu=True), args.reps)
+    nbytes = nnz * 4 + (nb + 1) * 4 + nv * F * s + nb * F * s
+    out["gat_aggregate"] = {"ms": round(t, 4), "alg_GB": round(nbytes / 1e9, 3), "GBps": round(nbytes / t / 1e6, 1),
+                            "gathered_GBps": round(nnz * F * s / t / 1e6, 1)}
+    print(f"gat_aggr   {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s  (gathers {nnz * F * s / t / 1e6:.0f} GB/s)",
           file=sys.stderr, flush=True)
     out["step_ms"] = {"separate": round(ms["pull"] + ms["spmm"] + ms["push"], 4),
                       "in_place": round(ms["spmm_hist"] + ms["push"], 4)}

@@ -295,6 +295,22 @@ GAS_API gas_status gas_pna_aggregate(const int32_t* rowptr, const int32_t* col, 
                              void* out, int64_t ldout, void* stream);
 
 /*
+ * GAT's anisotropic aggregation (operator appendix), one head: for every row
+ * v of the batch subgraph (its entries list N(v) and v itself),
+ *     e_k = LeakyReLU(a_dst . P[v] + a_src . P[col[k]])  (negative_slope),
+ *     Z[v] = act(sum_k softmax_k(e)_k P[col[k]]),  act = ReLU if relu != 0,
+ * P = H W [n_cols, F] computed beforehand (rows 0..n_rows-1 are the in-batch
+ * nodes); a_dst, a_src: the two halves of the attention vector, [F] of type
+ * dt.  Scores, softmax and the weighted sum take one pass over the gathered
+ * rows (fp32 arithmetic, entries folded in index order: deterministic).
+ * Rows without entries give zeros.  F <= 1024.  Z must not alias P.
+ */
+GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+                             const void* P, int64_t ldp, gas_dtype dt, int32_t F,
+                             const void* a_dst, const void* a_src, float negative_slope, int relu,
+                             void* Z, int64_t ldz, void* stream);
+
+/*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
  * flag back and waits for `stream`.
  */

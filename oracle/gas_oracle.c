@@ -358,14 +358,14 @@ void oracle_pna_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_r
  * whose entries list N(v) and v itself,
  *     e_k      = LeakyReLU(a_dst . P[v] + a_src . P[col[k]])          (negative slope given)
  *     alpha_k  = exp(e_k) / sum_k' exp(e_k')                          (softmax over the row's entries)
- *     Z[v]     = sum_k alpha_k P[col[k]]
+ *     Z[v]     = sum_k alpha_k P[col[k]]          (followed by ReLU if asked: the activation between layers)
  * with P = H W computed beforehand for every node of V_b.  a = [a_dst, a_src] is the attention vector split into
  * the part that meets the receiving node and the part that meets the neighbour.  A row without entries gives
  * zeros.  Written as the definition: scores, their maximum, the normalised weights, the weighted sum.
  */
 void oracle_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows, const void* P, int64_t ldp,
                           int dt, int32_t F, const void* a_dst, const void* a_src, double negative_slope,
-                          void* Z, int64_t ldz) {
+                          int relu, void* Z, int64_t ldz) {
     #pragma omp parallel for schedule(dynamic, 64)
     for (int64_t v = 0; v < n_rows; ++v) {
         int64_t b = rowptr[v], e = rowptr[v + 1];
@@ -391,7 +391,7 @@ void oracle_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_r
             double acc = 0.0;
             for (int64_t k = b; k < e; ++k)
                 acc += exp(score[k - b] - mx) / den * load_elem(P, (int64_t)col[k] * ldp + f, dt);
-            store_elem(Z, v * ldz + f, dt, acc);
+            store_elem(Z, v * ldz + f, dt, (relu && acc < 0.0) ? 0.0 : acc);
         }
         free(score);
     }

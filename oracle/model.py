@@ -381,3 +381,29 @@ def pna_batch_forward(weights, delta, n_id, rowptr, col, nb, x_feat, histories, 
         x[:nb] = y
         x[nb:] = ops.pull(histories[l - 1], n_id[nb:])
     return y
+
+
+# ----------------------------------------------------------------------------
+# GAT (paper, operator appendix), one head
+# ----------------------------------------------------------------------------
+def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negative_slope=0.2, do_push=True):
+    """All layers of a one-head GAT for one mini-batch in the order of Algorithm 1; weights[l] = (W, a_dst, a_src).
+    rowptr/col: the batch subgraph WITH self-loops (the sums run over N(v) and v).  Per layer: P = X W for every
+    node of V_b, attention-weighted aggregation for the in-batch rows, ReLU on all layers but the last."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    x = ops.pull(x_feat, n_id)
+    L = len(weights)
+    y = None
+    for l in range(1, L + 1):
+        w, a_dst, a_src = weights[l - 1]
+        p = ops.linear(x, w)
+        y = ops.gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope, relu=l < L)
+        if l == L:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        x = np.empty((nv, y.shape[1]), dtype=y.dtype)
+        x[:nb] = y
+        x[nb:] = ops.pull(histories[l - 1], n_id[nb:])
+    return y

@@ -228,7 +228,7 @@ def pna_aggregate(rowptr, col, x, delta, add=None) -> np.ndarray:
     return out
 
 
-def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2) -> np.ndarray:
+def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2, relu=False) -> np.ndarray:
     """Z[v] = sum_k softmax_k(LeakyReLU(a_dst.P[v] + a_src.P[col k])) P[col k] over the entries of row v."""
     rowptr, col = _i32(rowptr), _i32(col)
     p, ldp = _rows(p)
@@ -237,5 +237,5 @@ def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2) -> np.ndarra
     assert a_dst.dtype == p.dtype == a_src.dtype and a_dst.size == f == a_src.size
     z = np.empty((n_rows, f), dtype=p.dtype)
     lib().oracle_gat_aggregate(_p(rowptr), _p(col), C.c_int64(n_rows), _p(p), C.c_int64(ldp), C.c_int(_dt(p)),
-                               C.c_int32(f), _p(a_dst), _p(a_src), C.c_double(negative_slope), _p(z), C.c_int64(f))
+                               C.c_int32(f), _p(a_dst), _p(a_src), C.c_double(negative_slope), C.c_int(int(relu)), _p(z), C.c_int64(f))
     return z

@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate"]
 
 _lib = None
 
@@ -316,3 +316,16 @@ def gas_pna_aggregate(rowptr, col, x, out, delta, add=None):
     _check(lib().gas_pna_aggregate(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows), xp, ldx,
                                    C.c_int(_dt(x)), C.c_int32(x.shape[1]), ap, lda, C.c_float(delta), op, ldo,
                                    _stream()))
+
+
+def gas_gat_aggregate(rowptr, col, p, a_dst, a_src, z, negative_slope=0.2, relu=False):
+    """z[v] = sum_k softmax_k(LeakyReLU(a_dst.p[v] + a_src.p[col k])) p[col k] over the entries of row v."""
+    pp, ldp = _mat(p)
+    zp, ldz = _mat(z)
+    n_rows = rowptr.numel() - 1
+    if z.dtype != p.dtype or a_dst.dtype != p.dtype or a_src.dtype != p.dtype or z.shape[1] != p.shape[1] or \
+            z.shape[0] < n_rows or a_dst.numel() != p.shape[1] or a_src.numel() != p.shape[1]:
+        raise ValueError("gas_gat_aggregate: shapes or dtypes do not match")
+    _check(lib().gas_gat_aggregate(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows), pp, ldp,
+                                   C.c_int(_dt(p)), C.c_int32(p.shape[1]), _ptr(a_dst), _ptr(a_src),
+                                   C.c_float(negative_slope), C.c_int(int(relu)), zp, ldz, _stream()))

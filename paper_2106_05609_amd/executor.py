@@ -367,3 +367,32 @@ def pna_forward_batch(weights, delta, bg: BatchGraph, x_feat, histories, do_push
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
         x = x_next
     return y
+
+
+def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope=0.2, do_push=True):
+    """All layers of a one-head GAT (paper, operator appendix) for one mini-batch in the order of Algorithm 1;
+    weights[l] = (W, a_dst, a_src); bg: the batch subgraph with self-loops.  Per layer: P = X W for every row of
+    the mini-batch tensor (gas_linear), then scores, softmax and weighted sum in one pass (gas_gat_aggregate,
+    ReLU in its epilogue on all layers but the last), push, pull."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    L = len(weights)
+    y = None
+    for l in range(1, L + 1):
+        w, a_dst, a_src = weights[l - 1]
+        last = l == L
+        p = torch.empty((nv, w.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x, w, p)
+        x_next = torch.empty((nb if last else nv, w.shape[1]), dtype=dt, device=dev)
+        y = x_next[:nb]
+        B.gas_gat_aggregate(bg.rowptr, bg.col, p, a_dst, a_src, y, negative_slope, relu=not last)
+        if last:
+            break
+        if do_push:
+            B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+        if nv > nb:
+            B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
+        x = x_next
+    return y

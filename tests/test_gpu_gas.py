@@ -208,3 +208,33 @@ def test_pna_model_matches_oracle(cfg_id, scale, dtype, f, f1):
         assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
         assert max_rel_err(to_np(a), c) <= tol
+
+
+@pytest.mark.parametrize("cfg_id,scale,dtype,f", [(1, 0.1, torch.float32, 64), (2, 0.01, torch.float32, 100),
+                                                   (4, 0.0005, torch.bfloat16, 128)])
+def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
+    """Three one-head GAT layers (operator appendix) through the histories, two batches, against the oracle."""
+    from gas_inputs import rng
+    from paper_2106_05609_amd import executor
+    cfg = configs.config(cfg_id, scale)
+    g = configs.build_graph(cfg)
+    bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
+    L = 3
+    x = rng.normal_matrix(cfg.seed, 880, g.n, f, dtype=dtype)
+    ws = [(rng.glorot_uniform(cfg.seed, 881 + 3 * l, f, f, dtype=dtype), rng.normal(cfg.seed, 882 + 3 * l, 0, f, dtype=dtype) * 0.3,
+           rng.normal(cfg.seed, 883 + 3 * l, 0, f, dtype=dtype) * 0.3) for l in range(L)]
+    hist = [rng.normal_matrix(cfg.seed, 890 + l, g.n, f, dtype=dtype) for l in range(L - 1)]
+    hs_cpu = [to_np(h).copy() for h in hist]
+    hs_gpu = [h.to("cuda") for h in hist]
+    d = lambda t: t.to("cuda")
+    ws_gpu = [tuple(d(t) for t in w) for w in ws]
+    ws_cpu = [tuple(to_np(t) for t in w) for w in ws]
+    tol = TOL[dtype] * (2 if dtype == torch.float32 else 1)
+    for b in (0, 1):
+        sg = batches.batch_subgraph(g, bl[b], True)
+        bg = executor.BatchGraph(sg.nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=f, normalise=False)
+        y = executor.gat_forward_batch(ws_gpu, bg, d(x), hs_gpu)
+        want = omodel.gat_batch_forward(ws_cpu, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x), hs_cpu)
+        assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
+    for a, c in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), c) <= tol

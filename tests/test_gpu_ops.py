@@ -359,3 +359,32 @@ def test_pna_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
     gas.gas_pna_aggregate(ptr[:1], col[:0], dev(x)[:, :F], out[:0], delta)
     with pytest.raises(gas.GasError):
         gas.gas_pna_aggregate(ptr, col, dev(x)[:, :F], out, 0.0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name,F,ld_pad", [("powerlaw", 256, 0), ("sbm", 64, 8), ("powerlaw", 100, 0), ("sbm", 7, 0),
+                                           ("powerlaw", 520, 0), ("gin", 128, 0)])
+def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
+    """GAT's scores, softmax and weighted sum in one pass (operator appendix) against the oracle's three-step form."""
+    cfg, g, sg = graphs_small[name]
+    nb, nv = sg.nb, sg.nv
+    p = rng.normal_matrix(12, 960, nv, F + ld_pad, dtype=dtype)
+    a_dst = rng.normal(12, 961, 0, F, dtype=dtype) * 0.3
+    a_src = rng.normal(12, 962, 0, F, dtype=dtype) * 0.3
+    z = torch.full((nb, F + ld_pad), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_gat_aggregate(dev(sg.rowptr), dev(sg.col), dev(p)[:, :F], dev(a_dst), dev(a_src), z[:, :F])
+    want = oops.gat_aggregate(to_np(sg.rowptr), to_np(sg.col), to_np(p)[:, :F], to_np(a_dst), to_np(a_src))
+    assert max_rel_err(to_np(z[:, :F]), want) <= TOL[dtype], max_rel_err(to_np(z[:, :F]), want)
+    # same call again: same bits (entries are folded in index order)
+    z2 = torch.full((nb, F + ld_pad), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_gat_aggregate(dev(sg.rowptr), dev(sg.col), dev(p)[:, :F], dev(a_dst), dev(a_src), z2[:, :F])
+    assert torch.equal(z[:, :F].view(torch.int32 if dtype == torch.float32 else torch.int16),
+                       z2[:, :F].view(torch.int32 if dtype == torch.float32 else torch.int16))
+    # rows without entries give zeros
+    ptr = torch.tensor([0, 0, 2], dtype=torch.int32, device="cuda")
+    col = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    out = torch.full((2, F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_gat_aggregate(ptr, col, dev(p)[:, :F], dev(a_dst), dev(a_src), out)
+    assert not to_np(out[0]).any() and not torch.isnan(out.float()).any()
+    with pytest.raises(gas.GasError):
+        gas.gas_gat_aggregate(ptr, col, out, dev(a_dst), dev(a_src), out)

@@ -63,3 +63,33 @@ def test_dominating_neighbour_and_empty_row():
     # very large scores neither overflow nor lose the answer
     z = ops.gat_aggregate(rp, cl, p * 100, np.zeros(2, np.float32), np.array([2.0, 0.0], np.float32))
     assert np.isfinite(z).all() and np.allclose(z[0], [5000.0, 700.0], rtol=1e-6)
+
+
+def test_gat_model_whole_graph_equals_dense_layers():
+    """Two layers on a batch that is the whole graph against the same model written densely with torch in float64."""
+    from oracle import model as omodel
+    wl = _workload("gcn", n=200, layers=2, f=8)
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, torch.cat(wl.batches))
+    f = [10, 7, 5]
+    x = to_np(rng.normal_matrix(52, 1010, g.n, f[0]))
+    ws = [(to_np(rng.glorot_uniform(52, 1011 + 3 * l, f[l], f[l + 1])), to_np(rng.normal(52, 1012 + 3 * l, 0, f[l + 1])),
+           to_np(rng.normal(52, 1013 + 3 * l, 0, f[l + 1]))) for l in range(2)]
+    hist = [np.zeros((g.n, f[1]), np.float32)]
+    y = omodel.gat_batch_forward(ws, n_id, rp, cl, sg.nb, x, hist)
+    mask = torch.zeros((g.n, g.n), dtype=torch.bool)
+    for v in range(sg.nb):
+        mask[n_id[v], n_id[cl[rp[v]:rp[v + 1]]]] = True
+    h = torch.from_numpy(f64(x))
+    for l, (w, a_dst, a_src) in enumerate(ws):
+        p = h @ torch.from_numpy(f64(w))
+        e = torch.nn.functional.leaky_relu((p @ torch.from_numpy(f64(a_dst)))[:, None] + (p @ torch.from_numpy(f64(a_src)))[None, :], 0.2)
+        h = torch.softmax(e.masked_fill(~mask, float("-inf")), dim=1) @ p
+        if l == 0:
+            h = torch.relu(h)
+    want = h.numpy()[n_id[:sg.nb]]
+    assert np.abs(y - want).max() <= 5e-6 * np.abs(want).max()
+    # the history now holds layer 1 of every node: a proper batch reproduces its rows from it
+    sg1, n_id1, rp1, cl1 = _sub(wl, wl.batches[0])
+    y1 = omodel.gat_batch_forward(ws, n_id1, rp1, cl1, sg1.nb, x, [hist[0].copy()], do_push=False)
+    assert np.abs(y1 - h.numpy()[n_id1[:sg1.nb]]).max() <= 5e-6 * np.abs(want).max()

@@ -100,3 +100,12 @@ def permutation(seed: int, stream: int, n: int) -> torch.Tensor:
     idx = torch.arange(n, dtype=torch.int64)
     h = _lsr(bits(seed, stream, idx), 1)
     return torch.argsort(h * 1, stable=True)
+
+
+def ball_matrix(seed: int, stream: int, n: int, f: int, radius: float, device="cpu", dtype=torch.float32) -> torch.Tensor:
+    """n points drawn uniformly from the closed ball of the given radius in R^f, one per row: a Gaussian
+    direction scaled to length radius * u^(1/f)."""
+    g = normal_matrix(seed, stream, n, f, device, torch.float32).double()
+    u = uniform01(seed, stream + 1, torch.arange(n, dtype=torch.int64, device=device))
+    r = radius * u ** (1.0 / f)
+    return (g / g.norm(dim=1, keepdim=True).clamp_min(1e-300) * r[:, None]).to(dtype)

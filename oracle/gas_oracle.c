@@ -396,3 +396,31 @@ void oracle_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_r
         free(score);
     }
 }
+
+/*
+ * Pieces of the auxiliary loss of the paper's Eq. (3), L_reg = || f(h) - f(h + eps) ||: the perturbed input
+ * Y = X + alpha E (E holds the drawn perturbations, one row per node) and the Euclidean distance between the
+ * rows of two layer outputs, dist[i] = || A[i, :] - B[i, :] ||_2, with its sum over the rows in double.
+ */
+void oracle_axpy(const void* X, int64_t ldx, const void* E, int64_t lde, int64_t n_rows, int32_t F, int dt,
+                 double alpha, void* Y, int64_t ldy) {
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t f = 0; f < F; ++f)
+            store_elem(Y, i * ldy + f, dt, load_elem(X, i * ldx + f, dt) + alpha * load_elem(E, i * lde + f, dt));
+}
+
+void oracle_row_distance(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows, int32_t F, int dt,
+                         float* dist, double* dist_sum) {
+    double total = 0.0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double s = 0.0;
+        for (int32_t f = 0; f < F; ++f) {
+            double d = load_elem(A, i * lda + f, dt) - load_elem(B, i * ldb + f, dt);
+            s += d * d;
+        }
+        s = sqrt(s);
+        dist[i] = (float)s;
+        total += s;
+    }
+    if (dist_sum) *dist_sum = total;
+}

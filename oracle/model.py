@@ -407,3 +407,31 @@ def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negativ
         x[:nb] = y
         x[nb:] = ops.pull(histories[l - 1], n_id[nb:])
     return y
+
+
+# ----------------------------------------------------------------------------
+# local Lipschitz regulariser (paper, Eq. 3)
+# ----------------------------------------------------------------------------
+def layer_forward(model: Model, l, x, h0, rowptr, col, val, nb):
+    """Layer l (1-based) of the model applied to a mini-batch tensor x [nv, F]: output for the in-batch rows."""
+    last = l == model.n_layers
+    if model.op == "gcn":
+        return ops.linear(ops.spmm(rowptr, col, val, x), model.weights[l - 1], relu=not last)
+    if model.op == "gin":
+        w1, w2 = model.weights[l - 1]
+        return ops.mlp2(ops.spmm(rowptr, col, None, x, diag=1.0 + model.gin_eps), w1, w2, relu_out=not last)
+    if model.op == "gcnii":
+        z = ops.spmm(rowptr, col, val, x, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+        b = model.betas[l - 1]
+        return ops.linear(z, model.weights[l - 1], c_identity=1.0 - b, c_weight=b, relu=not last)
+    raise ValueError(model.op)
+
+
+def lipschitz_reg(model: Model, l, x, eps, rowptr, col, val, nb, h0=None):
+    """Eq. (3) for layer l on one mini-batch: the mean over the in-batch nodes of || f(x)_v - f(x + eps)_v ||_2,
+    where x is the mini-batch tensor the layer reads (in-batch rows and pulled halo rows alike are perturbed:
+    the layer is a function of all of them) and eps holds one drawn perturbation per row."""
+    y = layer_forward(model, l, x, h0, rowptr, col, val, nb)
+    y2 = layer_forward(model, l, ops.axpy(x, eps, 1.0), h0, rowptr, col, val, nb)
+    _, total = ops.row_distance(y, y2)
+    return total / max(1, nb)

@@ -239,3 +239,26 @@ def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2, relu=False) 
     lib().oracle_gat_aggregate(_p(rowptr), _p(col), C.c_int64(n_rows), _p(p), C.c_int64(ldp), C.c_int(_dt(p)),
                                C.c_int32(f), _p(a_dst), _p(a_src), C.c_double(negative_slope), C.c_int(int(relu)), _p(z), C.c_int64(f))
     return z
+
+
+def axpy(x, e, alpha) -> np.ndarray:
+    """x + alpha * e, row-major [n, F], rounded once to the storage type."""
+    x, ldx = _rows(x)
+    e, lde = _rows(e)
+    assert x.shape == e.shape and x.dtype == e.dtype
+    y = np.empty(x.shape, dtype=x.dtype)
+    lib().oracle_axpy(_p(x), C.c_int64(ldx), _p(e), C.c_int64(lde), C.c_int64(x.shape[0]), C.c_int32(x.shape[1]),
+                      C.c_int(_dt(x)), C.c_double(alpha), _p(y), C.c_int64(x.shape[1]))
+    return y
+
+
+def row_distance(a, b):
+    """(dist float32[n], sum of dist): dist[i] = ||a[i] - b[i]||_2."""
+    a, lda = _rows(a)
+    b, ldb = _rows(b)
+    assert a.shape == b.shape and a.dtype == b.dtype
+    dist = np.empty(a.shape[0], dtype=np.float32)
+    total = C.c_double(0.0)
+    lib().oracle_row_distance(_p(a), C.c_int64(lda), _p(b), C.c_int64(ldb), C.c_int64(a.shape[0]), C.c_int32(a.shape[1]),
+                              C.c_int(_dt(a)), _p(dist), C.byref(total))
+    return dist, float(total.value)

@@ -1,0 +1,58 @@
+"""Pins for the pieces of the paper's Eq. (3) in the oracle (CPU only): the perturbed input and the row distance
+against numpy, the drawn perturbations inside their ball, and the regulariser of a linear layer, whose difference
+f(x + eps) - f(x) = A_hat eps W is known in closed form."""
+import numpy as np
+import torch
+
+from gas_inputs import rng
+from oracle import ops, model as omodel
+from tests.util import to_np, f64, oracle_model
+from tests.test_oracle_gas import _workload, _sub
+
+
+def test_axpy_and_row_distance_match_numpy():
+    x = to_np(rng.normal_matrix(61, 1100, 40, 9))
+    e = to_np(rng.normal_matrix(61, 1101, 40, 9))
+    y = ops.axpy(x, e, 0.25)
+    assert np.array_equal(y, (f64(x) + 0.25 * f64(e)).astype(np.float32))
+    d, total = ops.row_distance(x, y)
+    want = np.linalg.norm(f64(x) - f64(y), axis=1)
+    assert np.abs(d - want).max() <= 1e-7 * want.max() and abs(total - want.sum()) <= 1e-12 * want.sum()
+    assert ops.row_distance(x, x)[1] == 0.0
+    # 3-4-5
+    d, _ = ops.row_distance(np.array([[0.0, 0.0]], np.float32), np.array([[3.0, 4.0]], np.float32))
+    assert d[0] == 5.0
+    xb = rng.normal_matrix(61, 1102, 16, 8, dtype=torch.bfloat16)
+    eb = rng.normal_matrix(61, 1103, 16, 8, dtype=torch.bfloat16)
+    yb = ops.axpy(to_np(xb), to_np(eb), 0.5)
+    assert np.array_equal(yb, to_np((xb.double() + 0.5 * eb.double()).to(torch.bfloat16)))
+
+
+def test_perturbations_lie_in_the_ball():
+    e = rng.ball_matrix(62, 1110, 5000, 6, 0.3)
+    r = e.double().norm(dim=1)
+    assert float(r.max()) <= 0.3 * (1 + 1e-6)
+    # uniform in the ball: P(r <= 0.3 * 2^(-1/6)) = 1/2, and the mean of every coordinate is 0
+    assert abs(float((r <= 0.3 * 2 ** (-1 / 6)).double().mean()) - 0.5) < 0.03
+    assert float(e.double().mean(dim=0).abs().max()) < 0.01
+
+
+def test_regulariser_of_a_linear_layer_has_a_closed_form():
+    wl = _workload("gcn", n=200, layers=2, f=8)
+    g, m = wl.graph, oracle_model(wl)
+    sg, n_id, rp, cl = _sub(wl, wl.batches[1])
+    val = ops.gcn_norm(rp, cl, n_id, to_np(g.deg))
+    f_in = m.weights[-1].shape[0]
+    x = to_np(rng.normal_matrix(63, 1120, sg.nv, f_in))
+    eps = to_np(rng.ball_matrix(63, 1121, sg.nv, f_in, 0.1))
+    got = omodel.lipschitz_reg(m, m.n_layers, x, eps, rp, cl, val, sg.nb)      # the last layer has no ReLU: linear
+    a = omodel.dense_adjacency(n_id, rp, cl, val, sg.nb)
+    diff = a @ f64(eps) @ f64(m.weights[-1])
+    want = np.linalg.norm(diff, axis=1).mean()
+    assert abs(got - want) <= 2e-4 * want          # the two outputs are rounded to fp32 before they are subtracted
+    assert omodel.lipschitz_reg(m, m.n_layers, x, np.zeros_like(eps), rp, cl, val, sg.nb) == 0.0
+    # a non-linear layer: bounded by the linear map's norm times the perturbation (ReLU is 1-Lipschitz)
+    got1 = omodel.lipschitz_reg(m, 1, to_np(rng.normal_matrix(63, 1122, sg.nv, m.weights[0].shape[0])),
+                                to_np(rng.ball_matrix(63, 1123, sg.nv, m.weights[0].shape[0], 0.1)), rp, cl, val, sg.nb)
+    bound = 0.1 * np.linalg.norm(a, 2) * np.linalg.norm(f64(m.weights[0]), 2) * np.sqrt(sg.nv) / sg.nb * np.sqrt(sg.nb)
+    assert 0.0 < got1 <= bound

@@ -311,6 +311,19 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
                              void* Z, int64_t ldz, void* stream);
 
 /*
+ * Pieces of the auxiliary loss of Eq. (3), || f(h) - f(h + eps) ||, which is
+ * a second forward pass of a layer on a perturbed input:
+ * gas_axpy:          Y = X + alpha E, element-wise over [n_rows, F] of type dt
+ *                    (E: the drawn perturbations, one row per node; Y may be X);
+ * gas_row_distance:  dist[i] = || A[i, :] - B[i, :] ||_2 (fp32[n_rows]), and,
+ *                    if dist_sum is given (fp32[1]), their sum in a fixed order.
+ */
+GAS_API gas_status gas_axpy(const void* X, int64_t ldx, const void* E, int64_t lde, int64_t n_rows, int32_t F,
+                    gas_dtype dt, float alpha, void* Y, int64_t ldy, void* stream);
+GAS_API gas_status gas_row_distance(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows,
+                            int32_t F, gas_dtype dt, float* dist, float* dist_sum, void* stream);
+
+/*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
  * flag back and waits for `stream`.
  */

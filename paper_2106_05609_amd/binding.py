@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate", "gas_axpy", "gas_row_distance"]
 
 _lib = None
 
@@ -329,3 +329,25 @@ def gas_gat_aggregate(rowptr, col, p, a_dst, a_src, z, negative_slope=0.2, relu=
     _check(lib().gas_gat_aggregate(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows), pp, ldp,
                                    C.c_int(_dt(p)), C.c_int32(p.shape[1]), _ptr(a_dst), _ptr(a_src),
                                    C.c_float(negative_slope), C.c_int(int(relu)), zp, ldz, _stream()))
+
+
+def gas_axpy(x, e, y, alpha=1.0):
+    """y = x + alpha * e over [n, F] (y may be x)."""
+    xp, ldx = _mat(x)
+    ep, lde = _mat(e)
+    yp, ldy = _mat(y)
+    if x.shape != e.shape or x.shape != y.shape or x.dtype != e.dtype or x.dtype != y.dtype:
+        raise ValueError("gas_axpy: shapes or dtypes do not match")
+    _check(lib().gas_axpy(xp, ldx, ep, lde, C.c_int64(x.shape[0]), C.c_int32(x.shape[1]), C.c_int(_dt(x)),
+                          C.c_float(alpha), yp, ldy, _stream()))
+
+
+def gas_row_distance(a, b, dist, dist_sum=None):
+    """dist[i] = ||a[i] - b[i]||_2 (float32 [n]); dist_sum (float32 [1]) receives their sum."""
+    ap, lda = _mat(a)
+    bp, ldb = _mat(b)
+    if a.shape != b.shape or a.dtype != b.dtype or dist.dtype != torch.float32 or dist.numel() != a.shape[0] or \
+            not dist.is_contiguous():
+        raise ValueError("gas_row_distance: shapes or dtypes do not match")
+    _check(lib().gas_row_distance(ap, lda, bp, ldb, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
+                                  _ptr(dist, torch.float32), _ptr(dist_sum, torch.float32), _stream()))

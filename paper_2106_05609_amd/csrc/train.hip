@@ -150,6 +150,58 @@ __global__ __launch_bounds__(256) void sgd_kernel(char* W, const float* dW, int6
     }
 }
 
+// Y = X + alpha E, element-wise over [M, F] (the perturbed input of Eq. (3))
+template <bool BF>
+__global__ __launch_bounds__(256) void axpy_kernel(const char* X, int64_t ldx, const char* E, int64_t lde, char* Y,
+                                                   int64_t ldy, int64_t M, int F, float alpha, int vec) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    constexpr int EB = BF ? 2 : 4;
+    if (vec > 0) {                                    // vec: 16-byte pieces per row
+        if (idx >= M * vec) return;
+        const int64_t m = idx / vec;
+        const int v = (int)(idx % vec);
+        const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(X + m * ldx * EB) + v);
+        const u32x4 e = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(E + m * lde * EB) + v);
+        u32x4 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if constexpr (BF)
+                o[q] = pack_bf16(bf16_lo(x[q]) + alpha * bf16_lo(e[q]), bf16_hi(x[q]) + alpha * bf16_hi(e[q]));
+            else
+                o[q] = __float_as_uint(__uint_as_float(x[q]) + alpha * __uint_as_float(e[q]));
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(Y + m * ldy * EB) + v);
+    } else {
+        if (idx >= M * F) return;
+        const int64_t m = idx / F;
+        const int f = (int)(idx % F);
+        if constexpr (BF) {
+            const float x = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(X)[m * ldx + f] << 16);
+            const float e = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(E)[m * lde + f] << 16);
+            reinterpret_cast<uint16_t*>(Y)[m * ldy + f] = (uint16_t)f32_to_bf16(x + alpha * e);
+        } else {
+            reinterpret_cast<float*>(Y)[m * ldy + f] =
+                reinterpret_cast<const float*>(X)[m * ldx + f] + alpha * reinterpret_cast<const float*>(E)[m * lde + f];
+        }
+    }
+}
+
+// dist[m] = || A[m, :] - B[m, :] ||_2: one wavefront per row, lanes stride over the row
+template <bool BF>
+__global__ __launch_bounds__(256) void row_distance_kernel(const char* A, int64_t lda, const char* B, int64_t ldb,
+                                                           int64_t M, int F, float* dist) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    float s = 0.f;
+    for (int f = lane; f < F; f += 64) {
+        const float d = load_logit<BF>(A, row * lda + f) - load_logit<BF>(B, row * ldb + f);
+        s += d * d;
+    }
+    s = wave_sum(s);
+    if (lane == 0) dist[row] = sqrtf(s);
+}
+
 }  // namespace
 }  // namespace gas
 
@@ -223,6 +275,56 @@ gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* dW, float
         hipLaunchKernelGGL(sgd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                            static_cast<char*>(W), dW, n, lr, weight_decay);
     GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+gas_status gas_axpy(const void* X, int64_t ldx, const void* E, int64_t lde, int64_t n_rows, int32_t F, gas_dtype dt,
+                    float alpha, void* Y, int64_t ldy, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_axpy: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_axpy: n_rows=%lld F=%d", (long long)n_rows, F);
+    if (n_rows == 0) return GAS_OK;
+    GAS_REQUIRE(X && E && Y, "gas_axpy: null pointer");
+    GAS_REQUIRE(ldx >= F && lde >= F && ldy >= F, "gas_axpy: row stride smaller than the row");
+    const int q = dt == GAS_BF16 ? 8 : 4;
+    const bool vec = F % q == 0 && ldx % q == 0 && lde % q == 0 && ldy % q == 0 && aligned16(X) && aligned16(E) && aligned16(Y);
+    const int v = vec ? F / q : 0;
+    const int64_t total = n_rows * (int64_t)(vec ? v : F);
+    const int64_t blocks = (total + 255) / 256;
+    GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_axpy: problem too large for one launch");
+    if (dt == GAS_BF16)
+        hipLaunchKernelGGL(axpy_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<const char*>(X), ldx, static_cast<const char*>(E), lde, static_cast<char*>(Y), ldy,
+                           n_rows, F, alpha, v);
+    else
+        hipLaunchKernelGGL(axpy_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<const char*>(X), ldx, static_cast<const char*>(E), lde, static_cast<char*>(Y), ldy,
+                           n_rows, F, alpha, v);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+gas_status gas_row_distance(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows, int32_t F,
+                            gas_dtype dt, float* dist, float* dist_sum, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_row_distance: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_row_distance: n_rows=%lld F=%d", (long long)n_rows, F);
+    hipStream_t s = (hipStream_t)stream;
+    if (n_rows > 0) {
+        GAS_REQUIRE(A && B && dist, "gas_row_distance: null pointer");
+        GAS_REQUIRE(lda >= F && ldb >= F, "gas_row_distance: row stride smaller than the row");
+        const int64_t blocks = (n_rows + 3) / 4;
+        GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_row_distance: too many rows for one launch");
+        if (dt == GAS_BF16)
+            hipLaunchKernelGGL(row_distance_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, dist);
+        else
+            hipLaunchKernelGGL(row_distance_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, dist);
+        GAS_CHECK_HIP(hipGetLastError());
+    }
+    if (dist_sum) {
+        hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, dist, n_rows, dist_sum);
+        GAS_CHECK_HIP(hipGetLastError());
+    }
     return GAS_OK;
 }
 

@@ -396,3 +396,42 @@ def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
         x = x_next
     return y
+
+
+def layer_forward(model: Model, l, bg: BatchGraph, x, h0=None, y=None):
+    """Layer l (1-based) of the model applied to a mini-batch tensor x [nv, F]: output for the in-batch rows."""
+    dev, dt = x.device, x.dtype
+    nb = bg.nb
+    last = l == model.n_layers
+    z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
+    if y is None:
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+    if model.op == "gcn":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+        B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+    elif model.op == "gin":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
+        w1, w2 = model.weights[l - 1]
+        B.gas_mlp2(z, w1, w2, y, relu_out=not last)
+    elif model.op == "gcnii":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+        beta = gcnii_beta(l)
+        B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
+    else:
+        raise ValueError(model.op)
+    return y
+
+
+def lipschitz_reg(model: Model, l, bg: BatchGraph, x, eps, h0=None):
+    """Eq. (3) for layer l on one mini-batch: the layer applied to the mini-batch tensor x and to x + eps (one
+    drawn perturbation per row, in-batch and halo rows alike), and the mean over the in-batch nodes of the
+    distance between the two output rows.  Returns (sum of distances as a 1-element device tensor, nb)."""
+    dev = x.device
+    y = layer_forward(model, l, bg, x, h0)
+    xp = torch.empty_like(x)
+    B.gas_axpy(x, eps, xp, 1.0)
+    y2 = layer_forward(model, l, bg, xp, h0)
+    dist = torch.empty(bg.nb, dtype=torch.float32, device=dev)
+    total = torch.empty(1, dtype=torch.float32, device=dev)
+    B.gas_row_distance(y, y2, dist, total)
+    return total, bg.nb

@@ -5,6 +5,8 @@
           alpha * h0 residual in its epilogue + push; no transform.  Also with the halo rows read in place.
   pna     PNA's neighbourhood aggregation (same appendix): mean, min and max with the three degree scalers in
           one pass over the gathered rows (9 output blocks per row).
+  host    pull and push against a history table in pinned host memory (rows moved over the host link by the
+          copy kernel itself), alone and on a second stream beside the aggregation.
   gat     GAT's aggregation (same appendix, one head): scores, softmax over the row's entries and the weighted
           sum in one pass over the gathered rows.
 
@@ -40,6 +42,7 @@ def main():
     p.add_argument("--scale", type=float, default=1.0)
     p.add_argument("--reps", type=int, default=10)
     p.add_argument("--width", type=int, default=0, help="feature width (default: the configuration's hidden width)")
+    p.add_argument("--host-rows", type=int, default=1 << 21, help="rows of the pinned host table (0: skip)")
     args = p.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_variants.py: no GPU visible")
@@ -98,6 +101,31 @@ def main():
                             "gathered_GBps": round(nnz * F * s / t / 1e6, 1)}
     print(f"gat_aggr   {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s  (gathers {nnz * F * s / t / 1e6:.0f} GB/s)",
           file=sys.stderr, flush=True)
+    if args.host_rows > 0:
+        hr = min(args.host_rows, cfg.n)
+        table = gas.HostTable(torch.zeros((hr, F), dtype=dt).pin_memory())
+        m = min(nh, 1 << 20)                                  # rows per transfer
+        hidx = (rng.permutation(cfg.seed, 215, hr)[:m]).to(torch.int32).to(dev)
+        stage = torch.empty((m, F), dtype=dt, device=dev)
+        t_pull = timed(lambda: gas.gas_pull(table, hidx, stage), args.reps)
+        t_push = timed(lambda: gas.gas_push(stage, hidx, table), args.reps)
+        side = torch.cuda.Stream()
+
+        def both():
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                gas.gas_pull(table, hidx, stage)
+            calls["spmm_hist"]()
+            torch.cuda.current_stream().wait_stream(side)
+        t_both = timed(both, args.reps)
+        gb = m * F * s / 1e9
+        out["host_table"] = {"rows_per_transfer": m, "GB": round(gb, 3), "pull_ms": round(t_pull, 3),
+                             "pull_GBps": round(gb / t_pull * 1e3, 1), "push_ms": round(t_push, 3),
+                             "push_GBps": round(gb / t_push * 1e3, 1), "spmm_hist_ms": round(ms["spmm_hist"], 3),
+                             "pull_beside_spmm_hist_ms": round(t_both, 3)}
+        print(f"host table: pull {t_pull:.3f} ms ({gb / t_pull * 1e3:.1f} GB/s), push {t_push:.3f} ms "
+              f"({gb / t_push * 1e3:.1f} GB/s); pull on a second stream beside spmm_hist: {t_both:.3f} ms "
+              f"(spmm_hist alone {ms['spmm_hist']:.3f})", file=sys.stderr, flush=True)
     out["step_ms"] = {"separate": round(ms["pull"] + ms["spmm"] + ms["push"], 4),
                       "in_place": round(ms["spmm_hist"] + ms["push"], 4)}
     out["edges_per_s"] = {k: round(nnz / (v * 1e-3), 1) for k, v in out["step_ms"].items()}

@@ -324,6 +324,28 @@ GAS_API gas_status gas_row_distance(const void* A, int64_t lda, const void* B, i
                             int32_t F, gas_dtype dt, float* dist, float* dist_sum, void* stream);
 
 /*
+ * Histories outside HBM (the paper keeps them in host memory and overlaps
+ * the transfers with computation, Section 4): gas_pull and gas_push accept a
+ * table in pinned host memory once its device-side address is known; the
+ * copy kernel then moves the rows over the host link itself, with no staging
+ * copy and no host thread, and overlaps with other work when launched on a
+ * stream of its own.  gas_host_table_pointer returns that address for memory
+ * allocated with hipHostMalloc (torch's pin_memory), or GAS_ERR_ARG if the
+ * device cannot address it (never pass such a pointer to a kernel).
+ * gas_pull_host / gas_push_host: gas_pull / gas_push with `hist` such an
+ * address; same arguments and result, launched on a small grid (the host
+ * link needs few requests in flight) so that kernels of other streams keep
+ * the compute units.
+ */
+GAS_API gas_status gas_host_table_pointer(const void* host_ptr, void** device_ptr);
+GAS_API gas_status gas_pull_host(const void* hist, int64_t n_hist_rows, int64_t ld_hist,
+                         const int32_t* idx, int64_t base, int64_t n, int32_t F, gas_dtype dt,
+                         void* dst, int64_t ld_dst, void* stream);
+GAS_API gas_status gas_push_host(const void* src, int64_t ld_src, const int32_t* idx, int64_t base,
+                         int64_t n, int32_t F, gas_dtype dt,
+                         void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+
+/*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a
  * flag back and waits for `stream`.
  */

@@ -14,7 +14,7 @@ OK = 0
 
 EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
            "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate", "gas_axpy", "gas_row_distance"]
+           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate", "gas_axpy", "gas_row_distance", "gas_host_table_pointer", "gas_pull_host", "gas_push_host"]
 
 _lib = None
 
@@ -89,7 +89,8 @@ def gas_pull(hist, idx, dst, base=0, n=None):
     dp, ldd = _mat(dst)
     if dst.dtype != hist.dtype or dst.shape[1] != hist.shape[1] or dst.shape[0] < n:
         raise ValueError("gas_pull: dst does not match")
-    _check(lib().gas_pull(hp, C.c_int64(hist.shape[0]), ldh, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n),
+    fn = lib().gas_pull_host if isinstance(hist, HostTable) else lib().gas_pull
+    _check(fn(hp, C.c_int64(hist.shape[0]), ldh, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n),
                           C.c_int32(hist.shape[1]), C.c_int(_dt(hist)), dp, ldd, _stream()))
 
 
@@ -100,7 +101,8 @@ def gas_push(src, idx, hist, base=0, n=None):
     sp, lds = _mat(src)
     if src.dtype != hist.dtype or src.shape[1] != hist.shape[1] or src.shape[0] < n:
         raise ValueError("gas_push: src does not match")
-    _check(lib().gas_push(sp, lds, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n), C.c_int32(hist.shape[1]),
+    fn = lib().gas_push_host if isinstance(hist, HostTable) else lib().gas_push
+    _check(fn(sp, lds, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n), C.c_int32(hist.shape[1]),
                           C.c_int(_dt(hist)), hp, C.c_int64(hist.shape[0]), ldh, _stream()))
 
 
@@ -351,3 +353,25 @@ def gas_row_distance(a, b, dist, dist_sum=None):
         raise ValueError("gas_row_distance: shapes or dtypes do not match")
     _check(lib().gas_row_distance(ap, lda, bp, ldb, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
                                   _ptr(dist, torch.float32), _ptr(dist_sum, torch.float32), _stream()))
+
+
+class HostTable:
+    """A history table in pinned host memory, usable as the `hist` argument of gas_pull / gas_push: it carries
+    the device-side address of the allocation and looks like a 2-D tensor to the marshalling code."""
+
+    def __init__(self, t: torch.Tensor):
+        if t.is_cuda or not t.is_pinned() or t.dim() != 2 or not t.is_contiguous():
+            raise ValueError("HostTable: need a contiguous 2-D tensor in pinned host memory")
+        dev = C.c_void_p(0)
+        _check(lib().gas_host_table_pointer(C.c_void_p(t.data_ptr()), C.byref(dev)))
+        self.tensor, self._dev = t, dev.value
+        self.shape, self.dtype = t.shape, t.dtype
+
+    def data_ptr(self):
+        return self._dev
+
+    def dim(self):
+        return 2
+
+    def stride(self, i):
+        return self.tensor.stride(i)

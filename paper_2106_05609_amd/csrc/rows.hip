@@ -34,36 +34,39 @@ template <typename V>
 __global__ __launch_bounds__(kCopyThreads) void copy_rows_kernel(
     const char* __restrict__ src, int64_t src_stride, const int32_t* __restrict__ src_idx, int64_t src_base,
     char* __restrict__ dst, int64_t dst_stride, const int32_t* __restrict__ dst_idx, int64_t dst_base,
-    int64_t n, int units, int g_log2) {
+    int64_t n, int units, int g_log2, int64_t n_blocks) {
     const int team = threadIdx.x >> g_log2;
     const int lane = threadIdx.x & ((1 << g_log2) - 1);
     const int teams = kCopyThreads >> g_log2;
-    const int64_t r0 = (int64_t)blockIdx.x * teams * kCopyUnroll + team;
-    int64_t srow[kCopyUnroll], drow[kCopyUnroll];
+    // one pass when the grid covers all row blocks (tables in HBM); a small grid striding over them otherwise
+    for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        const int64_t r0 = blk * teams * kCopyUnroll + team;
+        int64_t srow[kCopyUnroll], drow[kCopyUnroll];
 #pragma unroll
-    for (int j = 0; j < kCopyUnroll; ++j) {
-        const int64_t r = r0 + (int64_t)j * teams;
-        const bool ok = r < n;
-        srow[j] = ok ? (src_idx ? (int64_t)src_idx[r] : src_base + r) : -1;
-        drow[j] = ok ? (dst_idx ? (int64_t)dst_idx[r] : dst_base + r) : -1;
-    }
-    for (int u = lane; u < units; u += (1 << g_log2)) {
-        V tmp[kCopyUnroll];
+        for (int j = 0; j < kCopyUnroll; ++j) {
+            const int64_t r = r0 + (int64_t)j * teams;
+            const bool ok = r < n;
+            srow[j] = ok ? (src_idx ? (int64_t)src_idx[r] : src_base + r) : -1;
+            drow[j] = ok ? (dst_idx ? (int64_t)dst_idx[r] : dst_base + r) : -1;
+        }
+        for (int u = lane; u < units; u += (1 << g_log2)) {
+            V tmp[kCopyUnroll];
 #pragma unroll
-        for (int j = 0; j < kCopyUnroll; ++j)
-            if (srow[j] >= 0)
-                tmp[j] = __builtin_nontemporal_load(
-                    reinterpret_cast<const V*>(src + srow[j] * src_stride) + u);
+            for (int j = 0; j < kCopyUnroll; ++j)
+                if (srow[j] >= 0)
+                    tmp[j] = __builtin_nontemporal_load(
+                        reinterpret_cast<const V*>(src + srow[j] * src_stride) + u);
 #pragma unroll
-        for (int j = 0; j < kCopyUnroll; ++j)
-            if (srow[j] >= 0)
-                __builtin_nontemporal_store(tmp[j], reinterpret_cast<V*>(dst + drow[j] * dst_stride) + u);
+            for (int j = 0; j < kCopyUnroll; ++j)
+                if (srow[j] >= 0)
+                    __builtin_nontemporal_store(tmp[j], reinterpret_cast<V*>(dst + drow[j] * dst_stride) + u);
+        }
     }
 }
 
 gas_status launch_copy(const void* src, int64_t ld_src, const int32_t* src_idx, int64_t src_base,
                        void* dst, int64_t ld_dst, const int32_t* dst_idx, int64_t dst_base,
-                       int64_t n, int32_t F, gas_dtype dt, hipStream_t stream) {
+                       int64_t n, int32_t F, gas_dtype dt, hipStream_t stream, int64_t max_blocks = 0) {
     if (n == 0) return GAS_OK;
     const int eb = elem_bytes(dt);
     const int64_t row_bytes = (int64_t)F * eb, ss = ld_src * eb, ds = ld_dst * eb;
@@ -78,18 +81,18 @@ gas_status launch_copy(const void* src, int64_t ld_src, const int32_t* src_idx, 
     const int64_t rows_per_block = (int64_t)teams * kCopyUnroll;
     const int64_t blocks = (n + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7FFFFFFF) return fail(GAS_ERR_ARG, "too many rows for one launch: %lld", (long long)n);
-    dim3 grid((unsigned)blocks), block(kCopyThreads);
+    dim3 grid((unsigned)((max_blocks > 0 && max_blocks < blocks) ? max_blocks : blocks)), block(kCopyThreads);
     const char* s = static_cast<const char*>(src);
     char* d = static_cast<char*>(dst);
     if (vec == 16)
         hipLaunchKernelGGL(copy_rows_kernel<u32x4>, grid, block, 0, stream, s, ss, src_idx, src_base, d, ds,
-                           dst_idx, dst_base, n, units, g_log2);
+                           dst_idx, dst_base, n, units, g_log2, blocks);
     else if (vec == 4)
         hipLaunchKernelGGL(copy_rows_kernel<uint32_t>, grid, block, 0, stream, s, ss, src_idx, src_base, d, ds,
-                           dst_idx, dst_base, n, units, g_log2);
+                           dst_idx, dst_base, n, units, g_log2, blocks);
     else
         hipLaunchKernelGGL(copy_rows_kernel<uint16_t>, grid, block, 0, stream, s, ss, src_idx, src_base, d, ds,
-                           dst_idx, dst_base, n, units, g_log2);
+                           dst_idx, dst_base, n, units, g_log2, blocks);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
@@ -129,8 +132,13 @@ const char* gas_last_error(void) { return last_error_buffer(); }
 
 int gas_version(void) { return 100; }
 
-gas_status gas_pull(const void* hist, int64_t n_hist_rows, int64_t ld_hist, const int32_t* idx, int64_t base,
-                    int64_t n, int32_t F, gas_dtype dt, void* dst, int64_t ld_dst, void* stream) {
+// A transfer over the host link needs few requests in flight to run at the link's rate; a small grid leaves the
+// compute units to the kernels of other streams (the overlap the paper's transfer scheme is about).
+static constexpr int64_t kHostLinkBlocks = 64;
+
+static gas_status run_pull(const void* hist, int64_t n_hist_rows, int64_t ld_hist, const int32_t* idx, int64_t base,
+                           int64_t n, int32_t F, gas_dtype dt, void* dst, int64_t ld_dst, void* stream,
+                           int64_t max_blocks) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_pull: unknown dtype %d", (int)dt);
     GAS_REQUIRE(n >= 0 && F > 0 && n_hist_rows >= 0, "gas_pull: n=%lld F=%d n_hist_rows=%lld", (long long)n, F,
                 (long long)n_hist_rows);
@@ -139,11 +147,22 @@ gas_status gas_pull(const void* hist, int64_t n_hist_rows, int64_t ld_hist, cons
     GAS_REQUIRE(ld_hist >= F && ld_dst >= F, "gas_pull: row stride smaller than F");
     if (!idx) GAS_REQUIRE(base >= 0 && base + n <= n_hist_rows, "gas_pull: range [%lld, %lld) outside the table",
                           (long long)base, (long long)(base + n));
-    return launch_copy(hist, ld_hist, idx, base, dst, ld_dst, nullptr, 0, n, F, dt, (hipStream_t)stream);
+    return launch_copy(hist, ld_hist, idx, base, dst, ld_dst, nullptr, 0, n, F, dt, (hipStream_t)stream, max_blocks);
 }
 
-gas_status gas_push(const void* src, int64_t ld_src, const int32_t* idx, int64_t base, int64_t n, int32_t F,
-                    gas_dtype dt, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream) {
+gas_status gas_pull(const void* hist, int64_t n_hist_rows, int64_t ld_hist, const int32_t* idx, int64_t base,
+                    int64_t n, int32_t F, gas_dtype dt, void* dst, int64_t ld_dst, void* stream) {
+    return run_pull(hist, n_hist_rows, ld_hist, idx, base, n, F, dt, dst, ld_dst, stream, 0);
+}
+
+gas_status gas_pull_host(const void* hist, int64_t n_hist_rows, int64_t ld_hist, const int32_t* idx, int64_t base,
+                         int64_t n, int32_t F, gas_dtype dt, void* dst, int64_t ld_dst, void* stream) {
+    return run_pull(hist, n_hist_rows, ld_hist, idx, base, n, F, dt, dst, ld_dst, stream, kHostLinkBlocks);
+}
+
+static gas_status run_push(const void* src, int64_t ld_src, const int32_t* idx, int64_t base, int64_t n, int32_t F,
+                           gas_dtype dt, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream,
+                           int64_t max_blocks) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_push: unknown dtype %d", (int)dt);
     GAS_REQUIRE(n >= 0 && F > 0 && n_hist_rows >= 0, "gas_push: n=%lld F=%d n_hist_rows=%lld", (long long)n, F,
                 (long long)n_hist_rows);
@@ -152,7 +171,17 @@ gas_status gas_push(const void* src, int64_t ld_src, const int32_t* idx, int64_t
     GAS_REQUIRE(ld_hist >= F && ld_src >= F, "gas_push: row stride smaller than F");
     if (!idx) GAS_REQUIRE(base >= 0 && base + n <= n_hist_rows, "gas_push: range [%lld, %lld) outside the table",
                           (long long)base, (long long)(base + n));
-    return launch_copy(src, ld_src, nullptr, 0, hist, ld_hist, idx, base, n, F, dt, (hipStream_t)stream);
+    return launch_copy(src, ld_src, nullptr, 0, hist, ld_hist, idx, base, n, F, dt, (hipStream_t)stream, max_blocks);
+}
+
+gas_status gas_push(const void* src, int64_t ld_src, const int32_t* idx, int64_t base, int64_t n, int32_t F,
+                    gas_dtype dt, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream) {
+    return run_push(src, ld_src, idx, base, n, F, dt, hist, n_hist_rows, ld_hist, stream, 0);
+}
+
+gas_status gas_push_host(const void* src, int64_t ld_src, const int32_t* idx, int64_t base, int64_t n, int32_t F,
+                         gas_dtype dt, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream) {
+    return run_push(src, ld_src, idx, base, n, F, dt, hist, n_hist_rows, ld_hist, stream, kHostLinkBlocks);
 }
 
 gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t n_rows, const int32_t* n_id,
@@ -187,6 +216,19 @@ gas_status gas_validate_indices(const int32_t* idx, int64_t n, int64_t limit, vo
     (void)hipFree(d_flag);
     if (e != hipSuccess) return fail(GAS_ERR_HIP, "gas_validate_indices: %s", hipGetErrorString(e));
     if (h_flag) return fail(GAS_ERR_RANGE, "gas_validate_indices: an index lies outside [0, %lld)", (long long)limit);
+    return GAS_OK;
+}
+
+gas_status gas_host_table_pointer(const void* host_ptr, void** device_ptr) {
+    GAS_REQUIRE(host_ptr && device_ptr, "gas_host_table_pointer: null pointer");
+    void* d = nullptr;
+    const hipError_t e = hipHostGetDevicePointer(&d, const_cast<void*>(host_ptr), 0);
+    if (e != hipSuccess || !d) {
+        (void)hipGetLastError();                       // the failed query must not be reported by a later call
+        return fail(GAS_ERR_ARG, "gas_host_table_pointer: not pinned host memory that this device can address (%s)",
+                    hipGetErrorString(e));
+    }
+    *device_ptr = d;
     return GAS_OK;
 }
 

@@ -388,3 +388,25 @@ def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
     assert not to_np(out[0]).any() and not torch.isnan(out.float()).any()
     with pytest.raises(gas.GasError):
         gas.gas_gat_aggregate(ptr, col, out, dev(a_dst), dev(a_src), out)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_pull_push_with_a_history_table_in_pinned_host_memory(gas, dtype):
+    """Histories outside HBM: the row-copy kernel reads and writes a pinned host table through its device-side
+    address; same bits as indexing the table on the host."""
+    n, F, m = 20000, 256, 7000
+    table = rng.normal_matrix(15, 1300, n, F, dtype=dtype).pin_memory()
+    ht = gas.HostTable(table)
+    idx = rng.permutation(15, 1301, n)[:m].to(torch.int32)
+    out = torch.full((m, F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_pull(ht, dev(idx), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(out), oops.pull(to_np(table), to_np(idx)))
+    fresh = rng.normal_matrix(15, 1302, m, F, dtype=dtype)
+    want = to_np(table).copy()
+    oops.push(to_np(fresh), to_np(idx), want)
+    gas.gas_push(dev(fresh), dev(idx), ht)
+    torch.cuda.synchronize()                           # the host reads the table only after the kernel has finished
+    assert np.array_equal(to_np(table), want)
+    with pytest.raises((gas.GasError, ValueError)):
+        gas.HostTable(torch.zeros((4, 4)))              # pageable memory: refused before any kernel sees it

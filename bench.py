@@ -139,8 +139,14 @@ def main():
         for n in names:
             if fused and n == "pull":
                 continue                         # no such launch: the aggregation reads the history itself
-            gbs = bytes_of[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
             key = {"spmm": "spmm_hist", "linear": "linear_alone", "push": "push_in_epilogue"}.get(n, n) if fused else n
+            if per[n] < 0.02 and fused and n == "push":
+                # the transform is not bound by its stores: the extra output copy costs nothing measurable
+                kern[key] = {"ms": round(per[n], 4), "alg_GB": round(bytes_of[n] / 1e9, 4), "alg_GBps": None,
+                             "pct_hbm_peak": None}
+                log(f"[bench] {tag:8s} {key:16s} {per[n]:8.3f} ms  alg {bytes_of[n] / 1e9:7.3f} GB  (hidden in the transform)")
+                continue
+            gbs = bytes_of[n] / (max(per[n], 1e-6) * 1e-3) / 1e9
             kern[key] = {"ms": round(per[n], 4), "alg_GB": round(bytes_of[n] / 1e9, 4), "alg_GBps": round(gbs, 1),
                          "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2)}
             log(f"[bench] {tag:8s} {key:16s} {per[n]:8.3f} ms  alg {bytes_of[n] / 1e9:7.3f} GB  {gbs:8.1f} GB/s  "

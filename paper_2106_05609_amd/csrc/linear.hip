@@ -780,7 +780,9 @@ __device__ __forceinline__ void load_w_block_lds(const uint16_t* W, int K, int n
 // each staged row is read from LDS by four wavefronts instead of eight.  The loads of Z tile p+1 are issued at the
 // start of the phase and travel during the products; between the phase's two barriers all wavefronts move data:
 // output tile p-1 from its staging tile to Y (and to the history rows), Z tile p+1 from registers to LDS.
-template <int KT1, int KT2>
+// EXACT: K = 16 KT1 and H = N = 256, i.e. every column of every tile exists: the checks on the input columns and
+// the output width are compiled out.
+template <int KT1, int KT2, bool EXACT>
 __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
     constexpr int LDA = 16 * KT1 + 8, LDH = 16 * KT2 + 8, LDY = 256 + 8;
     constexpr int VPR = 2 * KT1;
@@ -795,7 +797,8 @@ __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
     uint16_t* Ys = Hs + 2 * kWsRows * LDH;                                  // [64][LDY]
     float* bias1 = reinterpret_cast<float*>(Ys + kWsRows * LDY);            // [256]
     float* bias2 = bias1 + 256;                                             // [256]
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // the same in every lane, and known to be
     const int role = wave >> 2, cb = wave & 3;        // role 0: Z W1, role 1: H W2; 64-column block cb
 
     bf16x8 w[2][KTM];
@@ -808,34 +811,47 @@ __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
 
     u32x4 ra[NVA];
     // Per-thread offsets (row, column, LDS address) are recomputed from the thread index where they are used
-    // (the index is made opaque there): kept live across the products they would be spilled.
-    auto fetch = [&](int64_t tile, int tl) {          // unconditional loads from a clamped address
+    // (the index is made opaque there): kept live across the products they would be spilled.  Addresses are a
+    // tile base that is the same for every lane plus a 32-bit offset; a tile that lies wholly inside the matrix
+    // (all but the last, when the width is a multiple of the MFMA depth) takes a path without per-lane checks.
+    const bool k_whole = EXACT || a.K == 16 * KT1;
+    auto fetch = [&](int64_t tile, int tl) {          // unconditional loads; clamped addresses where checks are needed
+        const uint16_t* base = a.Z + tile * kWsRows * a.ldz;
+        const bool full = k_whole && (tile + 1) * kWsRows <= a.M;
 #pragma unroll
         for (int i = 0; i < NVA; ++i) {
             const int idx = tl + 512 * i;
             const int row = idx / VPR, k = 8 * (idx % VPR);
-            const int64_t m = tile * kWsRows + row;
-            const bool ok = idx < kWsRows * VPR && m < a.M && k < a.K;
-            const uint16_t* src = ok ? a.Z + m * a.ldz + k : a.Z;
-            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            uint32_t off = (uint32_t)row * (uint32_t)a.ldz + (uint32_t)k;
+            if (!full) {
+                const bool ok = idx < kWsRows * VPR && tile * kWsRows + row < a.M && k < a.K;
+                off = ok ? off : 0u;
+            } else if (kWsRows * VPR % 512 != 0 && idx >= kWsRows * VPR) {
+                off = 0u;
+            }
+            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
         }
     };
     auto stage = [&](int64_t tile, int tl) {          // tile: the one fetch() was called for
+        const bool full = k_whole && (tile + 1) * kWsRows <= a.M;
 #pragma unroll
         for (int i = 0; i < NVA; ++i) {
             const int idx = tl + 512 * i;
             const int row = idx / VPR, k = 8 * (idx % VPR);
-            const bool ok = tile * kWsRows + row < a.M && k < a.K;
-            if (idx < kWsRows * VPR)
-                *reinterpret_cast<u32x4*>(As + row * LDA + k) = ok ? ra[i] : u32x4{0u, 0u, 0u, 0u};
+            u32x4 v = ra[i];
+            if (!full) {
+                const bool ok = tile * kWsRows + row < a.M && k < a.K;
+                v = ok ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+            if (idx < kWsRows * VPR) *reinterpret_cast<u32x4*>(As + row * LDA + k) = v;
         }
     };
     // D[m][64cb .. 64cb+63] = act(X[m][:] Wcols + bias) for the 64 rows of a tile, X and D in LDS.  Transposed
     // products: a lane ends up with 4 consecutive columns of one row per group of four accumulator registers.
-    auto product = [&](auto kt_tag, const uint16_t* X, int ldx, uint16_t* D, int ldd, const float* bias, int ncols,
-                       bool relu) {
+    // Columns beyond the width need no check: their weight fragments and biases were loaded as zeros, so they come
+    // out as exact zeros (and are zero operands of the next product).
+    auto product = [&](auto kt_tag, const uint16_t* X, int ldx, uint16_t* D, int ldd, const float* bias, bool relu) {
         constexpr int KT = decltype(kt_tag)::value;
-        const bool whole = 64 * cb + 64 <= ncols;      // every column of this block exists: no per-column select
 #pragma unroll
         for (int t = 0; t < MT; ++t) {                 // 32 rows at a time: two accumulator tiles live, not four
             // the accumulators start from the bias of their columns (element 4q+e of a lane is column n0(q)+e)
@@ -873,67 +889,66 @@ __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
                         v[e] = acc[ch][4 * q + e];
                         if (relu) v[e] = fmaxf(v[e], 0.f);
                     }
-                    if (!whole) {                      // columns beyond the width are zero operands later
-                        const int n0 = 64 * cb + 32 * ch + 8 * q + 4 * lh;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n0 + e >= ncols) v[e] = 0.f;
-                    }
                     *reinterpret_cast<u32x2*>(drow + 32 * ch + 8 * q) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
                 }
         }
     };
 
-    const int64_t grid = gridDim.x, t0 = blockIdx.x;
-    const int64_t n_my = (a.n_tiles - t0 + grid - 1) / grid;      // tiles of this workgroup (>= 1)
+    const int grid = (int)gridDim.x, t0 = (int)blockIdx.x;
+    const int n_my = (int)((a.n_tiles - t0 + grid - 1) / grid);   // tiles of this workgroup (>= 1)
     fetch(t0, tid);
     stage(t0, tid);
     __syncthreads();
-    for (int64_t p = 0; p <= n_my; ++p) {
-        const int64_t t_out = t0 + (p - 1) * grid;                 // tile whose output leaves in this phase
+    for (int p = 0; p <= n_my; ++p) {
+        const int64_t t_out = t0 + (int64_t)(p - 1) * grid;        // tile whose output leaves in this phase
         int32_t prow[NPI] = {};
         int tl = tid;
         asm volatile("" : "+v"(tl));
+        // output vector (row, v) of a thread: row = tl / 32 + 16 i, v = tl % 32 (the staging tile is 32 vectors wide;
+        // narrower outputs leave the lanes beyond their width idle)
+        const bool out_full = p >= 1 && (t_out + 1) * kWsRows <= a.M;
         if (a.push_idx && p >= 1) {
-            const int vpr = a.N >> 3;
+            const int32_t* pi = a.push_idx + t_out * kWsRows;
 #pragma unroll
             for (int i = 0; i < NPI; ++i) {
-                const int64_t m = t_out * kWsRows + (tl + 512 * i) / vpr;
-                prow[i] = a.push_idx[m < a.M ? m : a.M - 1];
+                int row = (tl >> 5) + 16 * i;
+                if (!out_full) row = t_out * kWsRows + row < a.M ? row : 0;
+                prow[i] = pi[row];
             }
         }
         // loads of the next Z tile: issued here, they travel while the matrix pipes work, and are staged
         // between this phase's two barriers
-        if (p + 1 < n_my) fetch(t0 + (p + 1) * grid, tl);
+        if (p + 1 < n_my) fetch(t0 + (int64_t)(p + 1) * grid, tl);
         if (role == 0) {
             if (p < n_my)
-                product(std::integral_constant<int, KT1>{}, As, LDA, Hs + (p & 1) * kWsRows * LDH, LDH, bias1, a.H, true);
+                product(std::integral_constant<int, KT1>{}, As, LDA, Hs + (p & 1) * kWsRows * LDH, LDH, bias1, true);
         } else {
             if (p >= 1)
-                product(std::integral_constant<int, KT2>{}, Hs + ((p - 1) & 1) * kWsRows * LDH, LDH, Ys, LDY, bias2, a.N,
+                product(std::integral_constant<int, KT2>{}, Hs + ((p - 1) & 1) * kWsRows * LDH, LDH, Ys, LDY, bias2,
                         a.relu_out != 0);
         }
         __syncthreads();                               // Z tile consumed; hidden tile p and output tile p-1 complete
 #pragma unroll
         for (int i = 0; i < NPI; ++i) asm volatile("" : "+v"(prow[i]));   // delivered before new loads queue up
         asm volatile("" : "+v"(tl));
-        if (p + 1 < n_my) stage(t0 + (p + 1) * grid, tl);
+        if (p + 1 < n_my) stage(t0 + (int64_t)(p + 1) * grid, tl);
         if (p >= 1) {
-            const int vpr = a.N >> 3;                  // 16-byte vectors per output row
-            int tq = (int)t_out;                       // opaque here: the store addresses are formed now, not
-            asm volatile("" : "+s"(tq));               // before the products (they would not fit in registers)
+            const int vpr = EXACT ? 32 : a.N >> 3;     // 16-byte vectors per output row
+            const int tq = __builtin_amdgcn_readfirstlane((int)t_out);   // the tile index, in a scalar register
+            uint16_t* ybase = a.Y + (int64_t)tq * kWsRows * a.ldy;
+            const int v = tl & 31;
+            if (v < vpr) {
 #pragma unroll
-            for (int i = 0; i < NPI; ++i) {
-                const int idx = tl + 512 * i;
-                if (idx >= kWsRows * vpr) break;
-                const int row = idx / vpr, v = idx % vpr;
-                const int64_t m = (int64_t)tq * kWsRows + row;
-                if (m < a.M) {
-                    const u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
-                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
-                    if (a.push_idx)
+                for (int i = 0; i < NPI; ++i) {
+                    const int row = (tl >> 5) + 16 * i;
+                    if (out_full || (int64_t)tq * kWsRows + row < a.M) {
+                        const u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
                         __builtin_nontemporal_store(
-                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                            o, reinterpret_cast<u32x4*>(ybase + ((uint32_t)row * (uint32_t)a.ldy + 8u * v)));
+                        if (a.push_idx)
+                            __builtin_nontemporal_store(
+                                o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                    }
                 }
             }
         }
@@ -944,16 +959,22 @@ __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
 template <int KT1, int KT2>
 gas_status launch_ws_mlp(const WsArgs& a, hipStream_t s) {
     constexpr int smem = 2 * (kWsRows * (16 * KT1 + 8) + 2 * kWsRows * (16 * KT2 + 8) + kWsRows * (256 + 8)) + 2 * 256 * 4;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_mlp_bf16_kernel<KT1, KT2>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    GAS_CHECK_HIP(attr);
+    static const hipError_t attr1 = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_mlp_bf16_kernel<KT1, KT2, true>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static const hipError_t attr2 = hipFuncSetAttribute(reinterpret_cast<const void*>(ws_mlp_bf16_kernel<KT1, KT2, false>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    GAS_CHECK_HIP(attr1);
+    GAS_CHECK_HIP(attr2);
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {
         int v = 0;
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
     }
     const int64_t blocks = a.n_tiles < cus ? a.n_tiles : cus;
-    hipLaunchKernelGGL((ws_mlp_bf16_kernel<KT1, KT2>), dim3((unsigned)blocks), dim3(512), smem, s, a);
+    if (a.K == 16 * KT1 && a.H == 256 && a.N == 256)
+        hipLaunchKernelGGL((ws_mlp_bf16_kernel<KT1, KT2, true>), dim3((unsigned)blocks), dim3(512), smem, s, a);
+    else
+        hipLaunchKernelGGL((ws_mlp_bf16_kernel<KT1, KT2, false>), dim3((unsigned)blocks), dim3(512), smem, s, a);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
@@ -1497,7 +1518,8 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
         dim3 grid((unsigned)((n_rows + kMlpRowsF32 - 1) / kMlpRowsF32), (unsigned)gn);
         if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
         else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
-    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096) {
+    } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
+               ldz < (1 << 24) && ldy < (1 << 24)) {      // offsets inside a 64-row tile are 32-bit
         // the kernel scatters the rows itself if the history rows take 16-byte stores; else the row copy follows
         const bool scatter = push.idx && aligned16(push.hist) && push.ld_hist % 8 == 0;
         WsArgs w{};

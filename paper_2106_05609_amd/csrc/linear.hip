@@ -601,7 +601,8 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     uint16_t* As = reinterpret_cast<uint16_t*>(smem);                       // [2][64][LDA]
     uint16_t* Ys = As + 2 * kWsRows * LDA;                                  // [64][LDY]
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // the same in every lane, and known to be
 
     bf16x8 w1f[KT1];
     load_w_frags<KT1>(a.W1, a.K, a.H, 32 * wave + li, lh, w1f, a.trans_w1 != 0);
@@ -615,25 +616,36 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
     // branch around them the compiler counts outstanding memory operations exactly, and a later wait for one
     // load does not turn into a wait for everything in flight.
     u32x4 ra[NVA];
+    const bool k_whole = a.K == 16 * KT1;
     auto fetch = [&](int64_t tile) {
+        const uint16_t* base = a.Z + tile * kWsRows * a.ldz;      // the same for every lane; offsets are 32-bit
+        const bool full = k_whole && (tile + 1) * kWsRows <= a.M;
 #pragma unroll
         for (int i = 0; i < NVA; ++i) {
             const int idx = tid + 512 * i;
             const int row = idx / VPR, k = 8 * (idx % VPR);
-            const int64_t m = tile * kWsRows + row;
-            const bool ok = idx < kWsRows * VPR && m < a.M && k < a.K;
-            const uint16_t* src = ok ? a.Z + m * a.ldz + k : a.Z;
-            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+            uint32_t off = (uint32_t)row * (uint32_t)a.ldz + (uint32_t)k;
+            if (!full) {
+                const bool ok = idx < kWsRows * VPR && tile * kWsRows + row < a.M && k < a.K;
+                off = ok ? off : 0u;
+            } else if (kWsRows * VPR % 512 != 0 && idx >= kWsRows * VPR) {
+                off = 0u;
+            }
+            ra[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
         }
     };
     auto stage = [&](int buf, int64_t tile) {          // tile: the one fetch() was called for
+        const bool full = k_whole && (tile + 1) * kWsRows <= a.M;
 #pragma unroll
         for (int i = 0; i < NVA; ++i) {
             const int idx = tid + 512 * i;
             const int row = idx / VPR, k = 8 * (idx % VPR);
-            const bool ok = tile * kWsRows + row < a.M && k < a.K;
-            if (idx < kWsRows * VPR)
-                *reinterpret_cast<u32x4*>(As + (buf * kWsRows + row) * LDA + k) = ok ? ra[i] : u32x4{0u, 0u, 0u, 0u};
+            u32x4 v = ra[i];
+            if (!full) {
+                const bool ok = tile * kWsRows + row < a.M && k < a.K;
+                v = ok ? v : u32x4{0u, 0u, 0u, 0u};
+            }
+            if (idx < kWsRows * VPR) *reinterpret_cast<u32x4*>(As + (buf * kWsRows + row) * LDA + k) = v;
         }
     };
 
@@ -651,13 +663,17 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
     for (; tile < a.n_tiles; tile += gridDim.x, buf ^= 1) {
         const int64_t next = tile + gridDim.x;
         __syncthreads();                               // (1) Z tile `buf` staged; previous tile fully consumed
+        // output vector (row, v) of a thread: row = tid / 32 + 16 i, v = tid % 32 (the staging tile is 32 vectors
+        // wide; narrower outputs leave the lanes beyond their width idle)
+        const bool out_full = (tile + 1) * kWsRows <= a.M;
         int32_t prow[NPI] = {};                        // history slots of the rows this thread will store
         if (a.push_idx) {
-            const int vpr = a.N >> 3;
+            const int32_t* pi = a.push_idx + tile * kWsRows;
 #pragma unroll
             for (int i = 0; i < NPI; ++i) {
-                const int64_t m = tile * kWsRows + (tid + 512 * i) / vpr;
-                prow[i] = a.push_idx[m < a.M ? m : a.M - 1];
+                int row = (tid >> 5) + 16 * i;
+                if (!out_full) row = tile * kWsRows + row < a.M ? row : 0;
+                prow[i] = pi[row];
             }
         }
         const uint16_t* At = As + buf * kWsRows * LDA;
@@ -707,26 +723,29 @@ __global__ __launch_bounds__(512) void ws_bf16_kernel(WsArgs a) {
         __syncthreads();                               // (3) output tile staged
         {
             const int vpr = a.N >> 3;                  // 16-byte vectors per output row
+            uint16_t* ybase = a.Y + tile * kWsRows * a.ldy;
+            const uint16_t* mbase = a.mask ? a.mask + tile * kWsRows * a.ldmask : nullptr;
+            const int v = tid & 31;
+            if (v < vpr) {
 #pragma unroll
-            for (int i = 0; i < NPI; ++i) {
-                const int idx = tid + 512 * i;
-                if (idx >= kWsRows * vpr) break;
-                const int row = idx / vpr, v = idx % vpr;
-                const int64_t m = tile * kWsRows + row;
-                if (m < a.M) {
-                    u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
-                    if (a.mask) {
-                        const u32x4 k = *reinterpret_cast<const u32x4*>(a.mask + m * a.ldmask + 8 * v);
+                for (int i = 0; i < NPI; ++i) {
+                    const int row = (tid >> 5) + 16 * i;
+                    if (out_full || tile * kWsRows + row < a.M) {
+                        u32x4 o = *reinterpret_cast<const u32x4*>(Ys + row * LDY + 8 * v);
+                        if (mbase) {
+                            const u32x4 km = *reinterpret_cast<const u32x4*>(mbase + ((uint32_t)row * (uint32_t)a.ldmask + 8u * v));
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            if (!(bf16_lo(k[q]) > 0.f)) o[q] &= 0xFFFF0000u;
-                            if (!(bf16_hi(k[q]) > 0.f)) o[q] &= 0x0000FFFFu;
+                            for (int q = 0; q < 4; ++q) {
+                                if (!(bf16_lo(km[q]) > 0.f)) o[q] &= 0xFFFF0000u;
+                                if (!(bf16_hi(km[q]) > 0.f)) o[q] &= 0x0000FFFFu;
+                            }
                         }
-                    }
-                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(a.Y + m * a.ldy + 8 * v));
-                    if (a.push_idx)          // Push fused into the epilogue: the row goes to its history slot as well
                         __builtin_nontemporal_store(
-                            o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                            o, reinterpret_cast<u32x4*>(ybase + ((uint32_t)row * (uint32_t)a.ldy + 8u * v)));
+                        if (a.push_idx)      // Push fused into the epilogue: the row goes to its history slot as well
+                            __builtin_nontemporal_store(
+                                o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                    }
                 }
             }
         }
@@ -1353,7 +1372,7 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
         return push_after(push, Y, ldy, n_rows, F_out, dt, s);
     }
     if (F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
-        (!mask || (aligned16(mask) && ldmask % 8 == 0))) {
+        (!mask || (aligned16(mask) && ldmask % 8 == 0)) && ldz < (1 << 24) && ldy < (1 << 24) && ldmask < (1 << 24)) {
         const bool scatter = push.idx && aligned16(push.hist) && push.ld_hist % 8 == 0;
         WsArgs w{};
         w.Z = static_cast<const uint16_t*>(Z); w.ldz = ldz;

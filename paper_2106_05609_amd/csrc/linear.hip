@@ -213,29 +213,51 @@ __global__ __launch_bounds__(256) void linear_f32_kernel(LinArgs a) {
         }
         mfma_tile_f32<TM, TN, BN>(&As[0][0], kLdA, wm0, 0, Bs, wn0, li, lh, acc);
     }
+    // Epilogue: one output row at a time (register r of tile i), its address formed once; the optional terms
+    // (identity, mask, push) are decided once per kernel, not once per element.
     float* Y = reinterpret_cast<float*>(a.Y);
     const float* bias = reinterpret_cast<const float*>(a.bias);
     const float* mask = reinterpret_cast<const float*>(a.mask);
     float* PH = reinterpret_cast<float*>(a.push_hist);
+    const int nl = n0 + wn0 + li;                      // column of tile j = nl + 32 j
+    float bv[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j) bv[j] = (bias && nl + 32 * j < a.N) ? bias[nl + 32 * j] : 0.f;
+    auto rows = [&](auto cid_tag, auto mask_tag, auto push_tag) {
+        constexpr bool CID = decltype(cid_tag)::value, MASK = decltype(mask_tag)::value, PUSH = decltype(push_tag)::value;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn0 + 32 * j + li;
-            if (n >= a.N) continue;
-            const float bv = bias ? bias[n] : 0.f;
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * lh + (r % 4);
                 if (m >= a.M) continue;
-                float y = a.c_w * acc[i][j][r] + bv;
-                if (a.c_id != 0.f) y += a.c_id * Z[m * a.ldz + n];
-                if (a.relu) y = fmaxf(y, 0.f);
-                if (mask && !(mask[m * a.ldmask + n] > 0.f)) y = 0.f;
-                Y[m * a.ldy + n] = y;
-                if (a.push_idx) PH[(int64_t)a.push_idx[m] * a.ld_push + n] = y;   // Push in the epilogue
+                float* yrow = Y + m * a.ldy + nl;
+                const float* zrow = CID ? Z + m * a.ldz + nl : nullptr;
+                const float* krow = MASK ? mask + m * a.ldmask + nl : nullptr;
+                float* hrow = PUSH ? PH + (int64_t)a.push_idx[m] * a.ld_push + nl : nullptr;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if (nl + 32 * j >= a.N) continue;
+                    float y = a.c_w * acc[i][j][r] + bv[j];
+                    if constexpr (CID) y += a.c_id * zrow[32 * j];
+                    if (a.relu) y = fmaxf(y, 0.f);
+                    if constexpr (MASK) { if (!(krow[32 * j] > 0.f)) y = 0.f; }
+                    yrow[32 * j] = y;
+                    if constexpr (PUSH) hrow[32 * j] = y;      // Push in the epilogue
+                }
             }
-        }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    const bool cid = a.c_id != 0.f;
+    if (!cid && !mask && !a.push_idx) rows(F{}, F{}, F{});
+    else if (!cid && !mask) rows(F{}, F{}, T{});
+    else if (cid && !mask && !a.push_idx) rows(T{}, F{}, F{});
+    else if (cid && !mask) rows(T{}, F{}, T{});
+    else if (!cid && !a.push_idx) rows(F{}, T{}, F{});
+    else if (!a.push_idx) rows(T{}, T{}, F{});
+    else if (!cid) rows(F{}, T{}, T{});
+    else rows(T{}, T{}, T{});
 }
 
 // fp32 fused MLP: 32 rows per workgroup; wavefront w owns hidden / output

@@ -153,7 +153,9 @@ def main():
                 f"{100 * gbs / HBM_PEAK_GBS:5.1f}% of peak")
         sk = "spmm_hist" if fused else "spmm"
         lk = "linear_alone" if fused else "linear"
+        mfma_peak = 157.3 if dt == torch.float32 else 2500.0        # dense MFMA TFLOP/s of the operand type
         kern[lk]["TFLOPs"] = round(flops / (per["linear"] * 1e-3) / 1e12, 2)
+        kern[lk]["mfma_util"] = round(kern[lk]["TFLOPs"] / mfma_peak, 4)
         if fused:
             kern["linear_push"] = {"ms": round(per["linear_push"], 4),
                                    "TFLOPs": round(flops / (per["linear_push"] * 1e-3) / 1e12, 2)}
@@ -183,6 +185,7 @@ def main():
     fused_head = "in-place" in res
     per = head.pop("per")
     spmm_gbs = by["spmm"] / (per["spmm"] * 1e-3) / 1e9
+    traffic = load_traffic(args.config, args.scale)
     out = {
         "metric": "GAS layer step: edges aggregated/sec + achieved HBM GB/s (% of peak), 1 GPU",
         "value": head["value"], "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -199,7 +202,10 @@ def main():
         "roofline": {"kernel": ("gas_spmm_hist" if fused_head else "gas_spmm")
                                + " = spmm_chunk_kernel + spmm_heavy_reduce_kernel + spmm_rows_kernel", "bound": "hbm",
                      "achieved": round(spmm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(spmm_gbs / HBM_PEAK_GBS, 4), "traffic": load_traffic(args.config, args.scale)},
+                     "frac": round(spmm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     # the two other figures of the aggregation: the measured traffic and the gathered bytes per second
+                     "traffic_GBps": None if traffic is None else round(traffic / (per["spmm"] * 1e-3) / 1e9, 1),
+                     "gathered_GBps": round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)},
     }
     if fused_head and "separate" in res:
         res["separate"].pop("per")

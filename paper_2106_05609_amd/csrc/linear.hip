@@ -1242,6 +1242,68 @@ __global__ __launch_bounds__(256) void dw_bf16_kernel(DwArgs a) {
         }
 }
 
+// bf16, both widths at most 256: one workgroup of eight wavefronts owns the whole [K][N] partial of its slab, so
+// Z and G are read once (the 128 x 128 kernel above reads each of them once per tile column / row).  Wavefront
+// (wk, wn) of a 4 x 2 arrangement accumulates rows 64 wk.. of dW and columns 128 wn..: eight 32 x 32 tiles.
+__global__ __launch_bounds__(512) void dw_bf16_wide_kernel(DwArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];               // above the 64 KB static limit
+    uint16_t (*Zt)[kLdh] = reinterpret_cast<uint16_t (*)[kLdh]>(smem);        // [256 features][64 rows + pad]
+    uint16_t (*Gt)[kLdh] = Zt + 256;
+    const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
+    const uint16_t* G = reinterpret_cast<const uint16_t*>(a.G);
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slab = blockIdx.x;
+    const int64_t m_begin = (int64_t)slab * kDwSlab;
+    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 128;
+    f32x16 acc[2][4];
+    zero_acc(acc);
+    // a 64(row) x 256(feature) tile is 8 x 32 blocks of 8 x 8: threads 0-255 take Z's, threads 256-511 G's
+    const bool mine_z = tid < 256;
+    const int t = tid & 255, rb = t / 32, fb = t % 32;
+    const uint16_t* src = mine_z ? Z : G;
+    const int64_t ld = mine_z ? a.ldz : a.ldg;
+    const int f = 8 * fb, flim = mine_z ? a.K : a.N;
+    u32x4 r[8];
+    auto fetch = [&](int64_t m0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int64_t m = m0 + 8 * rb + i;
+            const bool ok = m < m_end && f < flim;
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ok ? src + m * ld + f : src));
+            r[i] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    fetch(m_begin);
+    for (int64_t m0 = m_begin; m0 < m_end; m0 += kBKh) {
+        __syncthreads();
+        {
+            u32x4 tt[8];
+            transpose8x8_bf16(r, tt);
+            uint16_t (*dst)[kLdh] = mine_z ? Zt : Gt;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(&dst[8 * fb + c][8 * rb]) = tt[c];
+        }
+        __syncthreads();
+        if (m0 + kBKh < m_end) fetch(m0 + kBKh);
+        mfma_tile_bf16<2, 4>(&Zt[0][0], kLdh, wk0, 0, Gt, wn0, li, lh, acc);
+    }
+    float* out = a.partial + (int64_t)slab * a.K * a.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = wn0 + 32 * j + li;
+            if (n >= a.N) continue;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                const int k = wk0 + 32 * i + 8 * (rr / 4) + 4 * lh + (rr % 4);
+                if (k < a.K) out[(int64_t)k * a.N + n] = acc[i][j][rr];
+            }
+        }
+}
+
 // element-wise path for bf16 operands that are not 16-byte aligned: one thread per (slab, k, j)
 __global__ __launch_bounds__(256) void dw_bf16_generic_kernel(DwArgs a) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1480,7 +1542,13 @@ gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int
         else hipLaunchKernelGGL(dw_f32_kernel<false>, grid, dim3(256), 0, s, a);
     } else {
         const bool vec = aligned16(Z) && aligned16(GP) && ldz % 8 == 0 && ldgp % 8 == 0 && F_in % 8 == 0 && F_out % 8 == 0;
-        if (vec) {
+        if (vec && F_in <= 256 && F_out <= 256 && F_in > 128 && F_out > 128) {
+            constexpr int smem = 2 * 256 * kLdh * 2;
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_bf16_wide_kernel),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            GAS_CHECK_HIP(attr);
+            hipLaunchKernelGGL(dw_bf16_wide_kernel, dim3((unsigned)n_slabs), dim3(512), smem, s, a);
+        } else if (vec) {
             hipLaunchKernelGGL(dw_bf16_kernel, grid, dim3(256), 0, s, a);
         } else {
             const int64_t blocks = (per * n_slabs + 255) / 256;

@@ -64,7 +64,7 @@ def test_linear_bwd_input_parity(gas, dtype, M, K, N):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("M,K,N", [(10000, 256, 256), (4097, 128, 256), (5000, 100, 64), (300, 15, 20), (9000, 72, 200),
-                                    (1, 8, 8)])
+                                    (1, 8, 8), (5000, 200, 136), (8193, 256, 192)])
 def test_linear_bwd_weight_parity(gas, dtype, M, K, N):
     z = rng.normal_matrix(9, 620, M, K, dtype=dtype)
     gp = rng.normal_matrix(9, 621, M, N, dtype=dtype)

@@ -19,6 +19,7 @@ def main():
     p.add_argument("--config", type=int, default=2)
     p.add_argument("--scale", type=float, default=1.0)
     p.add_argument("--epochs", type=int, default=2, help="timed epochs after one warm-up epoch")
+    p.add_argument("--separate", action="store_true", help="pull the halo rows instead of reading them in place")
     p.add_argument("--lr", type=float, default=0.0, help="step size (default: 0.01 for GCN; 1e-10 for GIN, whose unnormalised sums of N(0,1) features give logits of order 1e5)")
     args = p.parse_args()
     if not torch.cuda.is_available():
@@ -55,7 +56,7 @@ def main():
         tot = torch.zeros(1, device=dev)
         n = 0
         for bg, lab_b, n_lab, _ in bgs:
-            loss_sum, _, _, _ = executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab)
+            loss_sum, _, _, _ = executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab, fused=not args.separate)
             tot += loss_sum
             n += n_lab
         return tot, n

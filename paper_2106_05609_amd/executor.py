@@ -153,18 +153,22 @@ def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True,
     return (y, layers) if keep_layers else y
 
 
-def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_push=True):
+def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_push=True, fused=False):
     """Forward with the activations kept, then the backward pass through all layers (no optimiser step).
     Historical embeddings are constants, so gradients travel along in-batch rows only; GCNII's input projection
     is computed in-graph for the halo rows too and its gradient includes them.  GIN's MLP runs as two stored
     linears here (the hidden activation is needed again by the backward pass).  Returns (Y_L, grads, kept) with
     grads[l] = dW_l (float32; a pair for GIN), grads["w_in"] for GCNII, and kept = the stored activations the
     backward pass read (x0, h0, per layer (Z, hidden, Y)).  grad_out is dLoss/dY_L [nb, F_L], or a function
-    that returns it given Y_L.  Every step is a gas_* call."""
+    that returns it given Y_L.  fused (GCN, GIN): the forward aggregations read their halo rows from the feature
+    table / the history tables in place (gas_spmm_hist) and nothing is pulled; same bits.  Every step is a
+    gas_* call."""
     dev, dt = x_feat.device, x_feat.dtype
     nb, nv = bg.nb, bg.nv
-    x0 = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
-    B.gas_pull(x_feat, bg.n_id, x0)
+    if fused and model.op == "gcnii":
+        raise ValueError("GCNII's first layer aggregates the projected features, which no table holds: fused=False")
+    x0 = torch.empty((nb if fused else nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id[:nb] if fused else bg.n_id, x0)
     x, h0 = x0, None
     if model.op == "gcnii":
         h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
@@ -177,14 +181,21 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         last = l == L
         f_in, f_out = x.shape[1], model.out_width(l - 1)
         z = torch.empty((nb, f_in), dtype=dt, device=dev)
-        x_next = torch.empty((nb if last else nv, f_out), dtype=dt, device=dev)
+        x_next = torch.empty((nb if (last or fused) else nv, f_out), dtype=dt, device=dev)
         y = x_next[:nb]
         h = None
+        table = (x_feat if l == 1 else histories[l - 2]) if fused else None
         if model.op == "gcn":
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+            if fused:
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z)
+            else:
+                B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
             B.gas_linear(z, model.weights[l - 1], y, relu=not last)
         elif model.op == "gin":
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
+            if fused:
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, x, table, z, diag=1.0 + model.gin_eps)
+            else:
+                B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
             w1, w2 = model.weights[l - 1]
             h = torch.empty((nb, w1.shape[1]), dtype=dt, device=dev)
             B.gas_linear(z, w1, h, relu=True)
@@ -198,7 +209,7 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             break
         if do_push:
             B.gas_push(y, bg.n_id[:nb], histories[l - 1])
-        if nv > nb:
+        if nv > nb and not fused:
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
         x = x_next
     # ---- backward
@@ -271,7 +282,8 @@ def apply_sgd(model: Model, grads, lr, weight_decay=0.0):
         B.gas_sgd_step(model.w_in, grads["w_in"], lr, weight_decay)
 
 
-def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr, weight_decay=0.0, n_labelled=None):
+def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr, weight_decay=0.0, n_labelled=None,
+               fused=False):
     """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
     softmax cross-entropy averaged over the labelled in-batch nodes, backward with the histories held constant,
     gradient-descent update of the weights (in place).  labels_batch: int32 [nb], the labels of the in-batch
@@ -287,7 +299,7 @@ def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr
         g = torch.empty_like(y)
         B.gas_softmax_xent(y, labels_batch, g, loss_rows, loss_sum, scale=1.0 / max(1, n_labelled))
         return g
-    y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad)
+    y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad, fused=fused)
     apply_sgd(model, grads, lr, weight_decay)
     return loss_sum, n_labelled, y, grads
 

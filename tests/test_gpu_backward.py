@@ -123,3 +123,29 @@ def test_batch_backward_matches_oracle(cfg_id, scale, dtype):
             assert max_rel_err(to_np(grads_gpu[l]), grads_cpu[l]) <= gtol, (l, max_rel_err(to_np(grads_gpu[l]), grads_cpu[l]))
     if cfg.op == "gcnii":
         assert max_rel_err(to_np(grads_gpu["w_in"]), grads_cpu["w_in"]) <= gtol
+
+
+@pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (4, 0.001)])
+def test_training_forward_in_place_gives_the_same_bits(cfg_id, scale):
+    """train_batch with the halo rows read in place (no pull): outputs, gradients and histories bit for bit."""
+    from paper_2106_05609_amd import executor
+    cfg = configs.config(cfg_id, scale)
+    wl = configs.build_workload(cfg)
+    g = wl.graph
+    gm = _gpu_model(wl)
+    sg = batches.batch_subgraph(g, wl.batches[0], cfg.self_loops)
+    bg = _gpu_batch(wl, sg, g.deg.to("cuda"))
+    grad_out = rng.normal_matrix(cfg.seed, 640, sg.nb, cfg.widths[-1], dtype=cfg.dtype).to("cuda")
+    res = []
+    for fused in (False, True):
+        hs = [h.to("cuda") for h in configs.make_histories(cfg, init="normal")]
+        y, grads, _ = executor.train_batch(gm, bg, wl.x.to("cuda"), hs, grad_out, fused=fused)
+        res.append((y, grads, hs))
+    (y0, g0, h0), (y1, g1, h1) = res
+    assert torch.equal(y0, y1)
+    for l in range(gm.n_layers):
+        a, b = g0[l], g1[l]
+        for u, v in zip(a if isinstance(a, tuple) else (a,), b if isinstance(b, tuple) else (b,)):
+            assert torch.equal(u, v)
+    for u, v in zip(h0, h1):
+        assert torch.equal(u, v)

@@ -12,9 +12,15 @@ LIB_PATH = os.path.join(_HERE, "libgas.so")
 F32, BF16 = 0, 1
 OK = 0
 
-EXPORTS = ["gas_last_error", "gas_version", "gas_pull", "gas_push", "gas_gcn_norm", "gas_plan_create",
-           "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t", "gas_linear", "gas_mlp2", "gas_validate_indices", "gas_relu_bwd", "gas_linear_bwd_input",
-           "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_push", "gas_mlp2_push", "gas_softmax_xent", "gas_sgd_step", "gas_pna_aggregate", "gas_gat_aggregate", "gas_axpy", "gas_row_distance", "gas_host_table_pointer", "gas_pull_host", "gas_push_host"]
+EXPORTS = [
+    "gas_last_error", "gas_version", "gas_validate_indices",
+    "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
+    "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
+    "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push",
+    "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
+    "gas_softmax_xent", "gas_sgd_step", "gas_axpy", "gas_row_distance",
+    "gas_pna_aggregate", "gas_gat_aggregate",
+]
 
 _lib = None
 
@@ -91,7 +97,7 @@ def gas_pull(hist, idx, dst, base=0, n=None):
         raise ValueError("gas_pull: dst does not match")
     fn = lib().gas_pull_host if isinstance(hist, HostTable) else lib().gas_pull
     _check(fn(hp, C.c_int64(hist.shape[0]), ldh, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n),
-                          C.c_int32(hist.shape[1]), C.c_int(_dt(hist)), dp, ldd, _stream()))
+              C.c_int32(hist.shape[1]), C.c_int(_dt(hist)), dp, ldd, _stream()))
 
 
 def gas_push(src, idx, hist, base=0, n=None):
@@ -103,7 +109,7 @@ def gas_push(src, idx, hist, base=0, n=None):
         raise ValueError("gas_push: src does not match")
     fn = lib().gas_push_host if isinstance(hist, HostTable) else lib().gas_push
     _check(fn(sp, lds, _ptr(idx, torch.int32), C.c_int64(base), C.c_int64(n), C.c_int32(hist.shape[1]),
-                          C.c_int(_dt(hist)), hp, C.c_int64(hist.shape[0]), ldh, _stream()))
+              C.c_int(_dt(hist)), hp, C.c_int64(hist.shape[0]), ldh, _stream()))
 
 
 def gas_gcn_norm(ptr, ind, n_id, deg, val):

@@ -21,6 +21,8 @@ def main():
     p = argparse.ArgumentParser()
     p.add_argument("--configs", type=int, nargs="+", default=[3, 0, 1])
     p.add_argument("--reps", type=int, default=20)
+    p.add_argument("--in-place", action="store_true",
+                   help="the in-place forward: halo rows read by the aggregation, push in the transform's epilogue")
     args = p.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_graph.py: no GPU visible")
@@ -40,7 +42,9 @@ def main():
         bg = executor.BatchGraph(sg.nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row,
                                  max_F=max(cfg.widths + [cfg.gin_hidden]), normalise=cfg.op != "gin")
         hist = configs.make_histories(cfg, device=dev, init="normal")
-        fwd = lambda: executor.forward_batch(gm, bg, wl.x, hist)
+        run = executor.forward_batch_fused if args.in_place else executor.forward_batch
+        bg.src                                           # built once, before any capture (it allocates)
+        fwd = lambda: run(gm, bg, wl.x, hist)
         y_eager = fwd().clone()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -70,7 +74,7 @@ def main():
         torch.cuda.synchronize()
         ms_graph = (time.perf_counter() - t0) / args.reps * 1e3
         n_layers = gm.n_layers
-        rec = {"config": c, "name": cfg.name, "layers": n_layers, "nb": sg.nb, "eager_ms": round(ms_eager, 4),
+        rec = {"config": c, "name": cfg.name, "in_place": args.in_place, "layers": n_layers, "nb": sg.nb, "eager_ms": round(ms_eager, 4),
                "graph_ms": round(ms_graph, 4), "speedup": round(ms_eager / ms_graph, 2), "replays_bit_identical": ok}
         out["runs"].append(rec)
         print(f"configs[{c}] {cfg.name:14s} {n_layers:3d} layers  eager {ms_eager:8.3f} ms  graph {ms_graph:8.3f} ms  "

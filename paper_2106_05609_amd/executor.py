@@ -72,11 +72,13 @@ def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push
     aggregation (gas_spmm_hist) instead of being pulled into the mini-batch
     tensor, and the Push taken in the transform's epilogue: per layer
     aggregate(X_batch, H[l-1]) -> transform, rows stored to H[l] as well.
-    Layer 1 reads its halo rows from the feature table the same way."""
+    Layer 1 reads its halo rows from the feature table the same way.  GCNII: its first layer aggregates the
+    projected features of all of V_b, which no table holds, so that layer gathers from the mini-batch tensor; from
+    layer 2 on the halo rows come from the history tables in place."""
     dev, dt = x_feat.device, x_feat.dtype
     nb = bg.nb
     if model.op == "gcnii":
-        raise ValueError("GCNII's first layer aggregates the projected features, which no table holds: use forward_batch")
+        return _forward_gcnii_fused(model, bg, x_feat, histories, do_push)
     x = torch.empty((nb, x_feat.shape[1]), dtype=dt, device=dev)
     B.gas_pull(x_feat, bg.n_id[:nb], x)
     L = model.n_layers
@@ -100,6 +102,34 @@ def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push
                 B.gas_mlp2_push(z, w1, w2, y, bg.n_id[:nb], histories[l - 1], relu_out=True)
             else:
                 B.gas_mlp2(z, w1, w2, y, relu_out=not last)
+        x = y
+    return y
+
+
+def _forward_gcnii_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push):
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x0 = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x0)
+    h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
+    B.gas_linear(x0, model.w_in, h0, relu=True)
+    x, y = h0, None
+    L = model.n_layers
+    for l in range(1, L + 1):
+        last = l == L
+        z = torch.empty((nb, h0.shape[1]), dtype=dt, device=dev)
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+        if l == 1:
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+        else:
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, histories[l - 2], z, s_agg=1.0 - model.alpha, r=h0,
+                            s_res=model.alpha)
+        beta = gcnii_beta(l)
+        if not last and do_push:
+            B.gas_linear_push(z, model.weights[l - 1], y, bg.n_id[:nb], histories[l - 1], c_identity=1.0 - beta,
+                              c_weight=beta, relu=True)
+        else:
+            B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
         x = y
     return y
 

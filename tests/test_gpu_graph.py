@@ -9,7 +9,7 @@ from tests.test_gpu_gas import _gpu_model, _gpu_batch
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg_id,scale,fused", [(0, 1.0, False), (0, 1.0, True), (3, 0.05, False), (4, 0.0005, True)])
+@pytest.mark.parametrize("cfg_id,scale,fused", [(0, 1.0, False), (0, 1.0, True), (3, 0.05, False), (3, 0.05, True), (4, 0.0005, True)])
 def test_forward_replays_bit_identical(cfg_id, scale, fused):
     from paper_2106_05609_amd import executor
     cfg = configs.config(cfg_id, scale)

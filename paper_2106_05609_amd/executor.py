@@ -134,6 +134,24 @@ def _forward_gcnii_fused(model: Model, bg: BatchGraph, x_feat, histories, do_pus
     return y
 
 
+def _aggregate_transform(model: Model, l, bg: BatchGraph, x, h0, z, y):
+    """Layer l (1-based) on the mini-batch tensor x: aggregation into z, transform into y (ReLU unless last)."""
+    last = l == model.n_layers
+    if model.op == "gcn":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
+        B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+    elif model.op == "gin":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
+        w1, w2 = model.weights[l - 1]
+        B.gas_mlp2(z, w1, w2, y, relu_out=not last)
+    elif model.op == "gcnii":
+        B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+        beta = gcnii_beta(l)
+        B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
+    else:
+        raise ValueError(model.op)
+
+
 def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True, keep_layers=False):
     """Run all layers for one batch.  Returns the last layer's [nb, F] output
     (and the list of mini-batch tensors if keep_layers)."""
@@ -158,19 +176,7 @@ def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True,
         else:
             x_next = torch.empty((nv, f_out), dtype=dt, device=dev)
             y = x_next[:nb]
-        if model.op == "gcn":
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z)
-            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
-        elif model.op == "gin":
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
-            w1, w2 = model.weights[l - 1]
-            B.gas_mlp2(z, w1, w2, y, relu_out=not last)
-        elif model.op == "gcnii":
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
-            beta = gcnii_beta(l)
-            B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
-        else:
-            raise ValueError(model.op)
+        _aggregate_transform(model, l, bg, x, h0, z, y)
         if last:
             break
         if do_push:
@@ -181,6 +187,107 @@ def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True,
         if keep_layers:
             layers.append(x)
     return (y, layers) if keep_layers else y
+
+
+class HostPipeline:
+    """Streams for histories kept in host memory (Section 4 of the paper: history access runs beside the
+    computation).  One stream carries the pulls, one the pushes, both at the default priority.  The mini-batch
+    tensors the transfers touch belong to the pipeline: two sets, used by alternate batches, so that a batch can
+    compute while the pushes of the one before still read its tensors.  Events: `table_pushed[l]`, the end of the
+    last push into table l (a later pull from that table waits for it); `set_pushed[i]` / `set_read[i]`, the end
+    of the pushes / of the computation that last read set i (the next writers of that set wait for them)."""
+
+    def __init__(self, device):
+        self.pull = torch.cuda.Stream(device)
+        self.push = torch.cuda.Stream(device)
+        self.turn = 0
+        self.table_pushed = {}
+        self.set_pushed = [None, None]
+        self.set_read = [None, None]
+        self._buffers = {}
+        self._fresh = False
+
+    def buffer(self, l, rows, width, dtype, device):
+        """The mini-batch tensor of the current set that layer l writes and layer l + 1 reads; grown when a
+        batch needs more rows."""
+        key = (self.turn, l, width, dtype)
+        t = self._buffers.get(key)
+        if t is None or t.shape[0] < rows:
+            if t is not None:                    # the transfer streams may still be using the old tensor
+                t.record_stream(self.pull)
+                t.record_stream(self.push)
+            t = self._buffers[key] = torch.empty((rows, width), dtype=dtype, device=device)
+            self._fresh = True                   # memory the compute stream may still be using
+        return t[:rows]
+
+    def join(self):
+        """Make the current stream wait for every transfer issued so far."""
+        cur = torch.cuda.current_stream()
+        cur.wait_stream(self.pull)
+        cur.wait_stream(self.push)
+
+
+def forward_batch_host(model: Model, bg: BatchGraph, x_feat, histories, pipe: HostPipeline, do_push=True):
+    """forward_batch for history tables in pinned host memory (binding.HostTable), with the transfers taken off
+    the compute stream: the halo rows of every layer are pulled ahead on pipe.pull (they were pushed by earlier
+    batches, so none depends on this batch's computation) and each layer's output is pushed on pipe.push while
+    the next layer computes.  A layer waits only for its own halo rows, a pull only for the earlier pushes into
+    its own table.  Same bits as forward_batch: in-batch and halo rows of a table are disjoint, so the order of
+    this batch's pushes and pulls is immaterial (Algorithm 1).  The caller calls pipe.join() before it reads the
+    tables or uses them outside this function."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    L = model.n_layers
+    cur = torch.cuda.current_stream()
+    turn = pipe.turn = pipe.turn ^ 1
+    pipe._fresh = False
+    xs = [None] + [pipe.buffer(l, nv, model.out_width(l - 1), dt, dev) for l in range(1, L)]
+    pulled = [None] * L
+    if nv > nb:
+        with torch.cuda.stream(pipe.pull):
+            if pipe._fresh or pipe.set_read[turn] is None:
+                pipe.pull.wait_stream(cur)
+            else:
+                pipe.pull.wait_event(pipe.set_read[turn])
+            for l in range(1, L):
+                if l - 1 in pipe.table_pushed:
+                    pipe.pull.wait_event(pipe.table_pushed[l - 1])
+                B.gas_pull(histories[l - 1], bg.n_id[nb:], xs[l][nb:])
+                pulled[l] = torch.cuda.Event()
+                pulled[l].record(pipe.pull)
+    if pipe.set_pushed[turn] is not None:
+        cur.wait_event(pipe.set_pushed[turn])    # pushes that still read the rows the layers overwrite
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    h0 = None
+    if model.op == "gcnii":
+        h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x, model.w_in, h0, relu=True)
+        x = h0
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev) if last else xs[l][:nb]
+        if l > 1 and pulled[l - 1] is not None:
+            cur.wait_event(pulled[l - 1])
+        _aggregate_transform(model, l, bg, x, h0, z, y)
+        if last:
+            break
+        if do_push:
+            done = torch.cuda.Event()
+            done.record(cur)
+            with torch.cuda.stream(pipe.push):
+                pipe.push.wait_event(done)
+                B.gas_push(y, bg.n_id[:nb], histories[l - 1])
+                pipe.table_pushed[l - 1] = torch.cuda.Event()
+                pipe.table_pushed[l - 1].record(pipe.push)
+        x = xs[l]
+    pipe.set_read[turn] = torch.cuda.Event()
+    pipe.set_read[turn].record(cur)
+    if do_push and L > 1:
+        pipe.set_pushed[turn] = pipe.table_pushed[L - 2]
+    return y
 
 
 def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_push=True, fused=False):

@@ -241,3 +241,43 @@ def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
         assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
         assert max_rel_err(to_np(a), c) <= tol
+
+
+@pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (4, 0.001), (3, 0.1)])
+def test_host_histories_with_concurrent_transfers(cfg_id, scale):
+    """Histories in pinned host memory, pulled ahead and pushed behind the computation on their own streams
+    (Section 4): two sweeps over all batches give, bit for bit, the outputs and tables of the run with the
+    tables in device memory, and the oracle's within tolerance."""
+    from paper_2106_05609_amd import executor
+    import paper_2106_05609_amd as gas
+    cfg0 = configs.config(cfg_id, scale)
+    if cfg0.op == "gcnii":
+        cfg0.widths = cfg0.widths[:6]
+    wl = configs.build_workload(cfg0)
+    cfg, g = wl.cfg, wl.graph
+    init = [h for h in configs.make_histories(cfg, init="normal")]
+    hs_cpu = [to_np(h).copy() for h in init]
+    hs_dev = [h.to("cuda") for h in init]
+    pinned = [h.clone().pin_memory() for h in init]
+    hs_host = [gas.HostTable(t) for t in pinned]
+    om, gm = oracle_model(wl), _gpu_model(wl)
+    x_dev, deg_dev = wl.x.to("cuda"), g.deg.to("cuda")
+    pipe = executor.HostPipeline(torch.device("cuda"))
+    order = list(range(min(4, len(wl.batches)))) * 2
+    bgs = {}
+    for k, b in enumerate(order):
+        if b not in bgs:
+            sg = batches.batch_subgraph(g, wl.batches[b], cfg.self_loops)
+            bgs[b] = (sg, _gpu_batch(wl, sg, deg_dev))
+        sg, bg = bgs[b]
+        y_dev = executor.forward_batch(gm, bg, x_dev, hs_dev)
+        y_host = executor.forward_batch_host(gm, bg, x_dev, hs_host, pipe)
+        assert torch.equal(y_dev, y_host), (k, b)
+        if k < 2:
+            y_cpu = omodel.gas_batch_forward(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
+                                             to_np(wl.x), hs_cpu)
+            assert max_rel_err(to_np(y_host), y_cpu) <= TOL[cfg.dtype]
+    pipe.join()
+    torch.cuda.synchronize()
+    for a, t in zip(hs_dev, pinned):
+        assert torch.equal(a.cpu(), t)

@@ -46,3 +46,76 @@ def test_argument_errors_are_reported_before_any_launch():
                       ctypes.c_int(0), ctypes.c_float(0.5), ctypes.c_float(0.5), ctypes.c_int(0), ctypes.c_void_p(32),
                       ctypes.c_int64(4), None)
     assert st == -1 and b"identity" in L.gas_last_error()
+
+
+def _signatures():
+    text = open(os.path.join(ROOT, "include", "gas.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    sigs = {}
+    for m in re.finditer(r"GAS_API\s+gas_status\s+(gas_\w+)\s*\(([^;]*?)\)\s*;", text, flags=re.S):
+        params = [re.sub(r"\s+", " ", p).strip() for p in m.group(2).split(",")]
+        sigs[m.group(1)] = params
+    return sigs
+
+
+def _args(params, pointer, dtype, size):
+    """ctypes arguments for a parameter list: every pointer = `pointer`, every dtype = `dtype`, the first
+    int64 count = `size`, other integers 4, floats 1."""
+    out, first = [], True
+    for p in params:
+        name = p.split()[-1].lstrip("*")
+        if "*" in p:
+            out.append(None if pointer is None else ctypes.c_void_p(pointer))
+        elif p.startswith("gas_dtype"):
+            out.append(ctypes.c_int(dtype))
+        elif p.startswith("float"):
+            out.append(ctypes.c_float(1.0))
+        elif p.startswith("int64_t"):
+            counts = name in ("n", "n_rows", "nnz")
+            out.append(ctypes.c_int64(size if counts and first else 4))
+            first = first and not counts
+        elif p.startswith("int32_t"):
+            out.append(ctypes.c_int32(4))
+        elif p.startswith("int "):
+            out.append(ctypes.c_int(0))
+        else:
+            raise AssertionError(f"unhandled parameter {p!r}")
+    return out
+
+
+def test_every_entry_point_rejects_bad_arguments_without_launching():
+    """Null pointers, an unknown dtype and a negative count: each call returns an error status and leaves a
+    message; nothing is launched (there is no GPU here), nothing crashes."""
+    L = binding.lib()
+    sigs = _signatures()
+    assert len(sigs) >= 25
+    for name, params in sigs.items():
+        fn = getattr(L, name)
+        fn.restype = ctypes.c_int
+        st = fn(*_args(params, None, 0, 4))
+        assert st < 0, f"{name} accepted null pointers"
+        assert len(L.gas_last_error()) > 0, name
+        takes_plan = any("gas_plan" in p for p in params)
+        if takes_plan:
+            continue                      # a non-null dummy plan would be dereferenced
+        if any(p.startswith("gas_dtype") for p in params):
+            st = fn(*_args(params, 4096, 7, 4))
+            assert st < 0, f"{name} accepted dtype 7"
+        if any(p.split()[-1] in ("n", "n_rows", "nnz") for p in params if p.startswith("int64_t")):
+            st = fn(*_args(params, 4096, 0, -1))
+            assert st < 0, f"{name} accepted a negative count"
+
+
+def test_a_zero_count_is_a_no_op():
+    """n = 0 (an empty batch, an empty halo) succeeds without touching any pointer; the weight gradient is the
+    exception, since an empty batch still has to produce a zero matrix."""
+    L = binding.lib()
+    for name, params in _signatures().items():
+        if any("gas_plan" in p for p in params):
+            continue
+        if not any(p.split()[-1] in ("n", "n_rows", "nnz") for p in params if p.startswith("int64_t")):
+            continue
+        fn = getattr(L, name)
+        fn.restype = ctypes.c_int
+        st = fn(*_args(params, None, 0, 0))
+        assert st == (-1 if name == "gas_linear_bwd_weight" else 0), name

@@ -225,6 +225,37 @@ GAS_API gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int
                          const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
 
 /*
+ * One whole layer in one launch, for narrow layers (Algorithm 1's loop body
+ * for the in-batch nodes: aggregate over G_b with both sources of Eq. 2,
+ * transform, Push):
+ *     Z[v, :] = s_agg * ( sum_k val[k] * S(src[k]) + diag * X[v, :] ) + s_res * R[v, :]
+ *     Y[v, :] = act( c_identity * Z[v, :] + c_weight * (Z W)[v, :] + bias )
+ *     push_hist[push_idx[v], :] = Y[v, :]                (if push_idx != NULL)
+ * with S(s) = X[s, :] for s >= 0 and hist[-1-s, :] for s < 0, exactly as in
+ * gas_spmm_hist (hist may be NULL when no index is negative: then src is the
+ * plain column array and X the whole mini-batch tensor) and the transform of
+ * gas_linear.  The aggregated tile stays on the chip, Z is never written.
+ * Needs no plan.  Meant for deep narrow models (the 64-layer GCNII of the
+ * paper's experiments), which are bound by launches: rows of any length are
+ * handled, but long rows are not split, so wide or heavy-tailed layers should
+ * use gas_spmm_hist + gas_linear_push.
+ * Restrictions: GAS_F32 only (GAS_ERR_DTYPE otherwise); F_in and F_out
+ * multiples of 4, at most 128; X, hist, R, W 16-byte aligned with row strides
+ * that are multiples of 4 elements (GAS_ERR_ARG otherwise, nothing is
+ * launched).  val may be NULL (all ones), R and bias may be NULL.  Results are
+ * deterministic (fixed summation order) and agree with the two-call form to
+ * rounding (the order of the row sum differs).
+ */
+GAS_API gas_status gas_spmm_linear(const int32_t* rowptr, const int32_t* src, const float* val, int64_t n_rows,
+                           const void* X, int64_t ldx, const void* hist, int64_t n_hist_rows, int64_t ld_hist,
+                           gas_dtype dt, int32_t F_in, float diag, float s_agg,
+                           const void* R, int64_t ldr, float s_res,
+                           const void* W, int32_t F_out, const void* bias,
+                           float c_identity, float c_weight, int relu, void* Y, int64_t ldy,
+                           const int32_t* push_idx, void* push_hist, int64_t n_push_rows, int64_t ld_push,
+                           void* stream);
+
+/*
  * Backward pass of the transform (chain rule on the operator equations; the
  * paper takes gradients through its layers, Section 2 advantage (1), without
  * spelling them out).  With P = c_identity * Z + c_weight * (Z W) and Y = relu(P):

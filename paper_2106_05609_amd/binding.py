@@ -16,7 +16,7 @@ EXPORTS = [
     "gas_last_error", "gas_version", "gas_validate_indices",
     "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
     "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
-    "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push",
+    "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
     "gas_softmax_xent", "gas_sgd_step", "gas_axpy", "gas_row_distance",
     "gas_pna_aggregate", "gas_gat_aggregate",
@@ -275,6 +275,36 @@ def gas_linear_push(z, w, y, idx, hist, bias=None, c_identity=0.0, c_weight=1.0,
                                  _ptr(bias), C.c_int(_dt(z)), C.c_float(c_identity), C.c_float(c_weight),
                                  C.c_int(int(relu)), yp, ldy, _ptr(idx, torch.int32), hp, C.c_int64(hist.shape[0]), ldh,
                                  _stream()))
+
+
+def spmm_linear_supported(x, f_out) -> bool:
+    """Whether gas_spmm_linear takes this layer (fp32, widths multiples of 4 up to 128)."""
+    f_in = x.shape[1]
+    return x.dtype == torch.float32 and f_in % 4 == 0 and f_out % 4 == 0 and max(f_in, f_out) <= 128
+
+
+def gas_spmm_linear(rowptr, src, val, x, w, y, hist=None, diag=0.0, s_agg=1.0, r=None, s_res=0.0, bias=None,
+                    c_identity=0.0, c_weight=1.0, relu=False, push_idx=None, push_hist=None):
+    """One layer in one launch: aggregation of the rows of y (sources: rows of x, or rows of hist for negative
+    indices), transform by w, optional store of every output row to push_hist[push_idx[i]]."""
+    n_rows = y.shape[0]
+    xp, ldx = _mat(x)
+    yp, ldy = _mat(y)
+    hp, ldh = (C.c_void_p(0), C.c_int64(0)) if hist is None else _mat(hist)
+    rp, ldr = (C.c_void_p(0), C.c_int64(0)) if r is None else _mat(r)
+    pp, ldp = (C.c_void_p(0), C.c_int64(0)) if push_hist is None else _mat(push_hist)
+    if w.dtype != x.dtype or y.dtype != x.dtype or w.shape[0] != x.shape[1] or y.shape[1] != w.shape[1] or \
+            rowptr.numel() != n_rows + 1 or (hist is not None and (hist.dtype != x.dtype or hist.shape[1] != x.shape[1])) or \
+            (r is not None and (r.dtype != x.dtype or r.shape[1] != x.shape[1] or r.shape[0] < n_rows)) or \
+            (push_hist is not None and (push_hist.dtype != x.dtype or push_hist.shape[1] != w.shape[1] or
+                                        push_idx is None or push_idx.numel() != n_rows)):
+        raise ValueError("gas_spmm_linear: shapes or dtypes do not match")
+    _check(lib().gas_spmm_linear(
+        _ptr(rowptr, torch.int32), _ptr(src, torch.int32), _ptr(val, torch.float32), C.c_int64(n_rows), xp, ldx, hp,
+        C.c_int64(0 if hist is None else hist.shape[0]), ldh, C.c_int(_dt(x)), C.c_int32(x.shape[1]), C.c_float(diag),
+        C.c_float(s_agg), rp, ldr, C.c_float(s_res), _ptr(w), C.c_int32(w.shape[1]), _ptr(bias), C.c_float(c_identity),
+        C.c_float(c_weight), C.c_int(int(relu)), yp, ldy, _ptr(push_idx, torch.int32), pp,
+        C.c_int64(0 if push_hist is None else push_hist.shape[0]), ldp, _stream()))
 
 
 def gas_mlp2_push(z, w1, w2, y, idx, hist, b1=None, b2=None, relu_out=False):

@@ -25,6 +25,7 @@ class BatchGraph:
         self.nb, self.nv = int(nb), int(n_id.numel())
         self.n_id, self.rowptr, self.col = n_id, rowptr, col
         self.nnz = int(col.numel())
+        self.max_row = int((rowptr[1:] - rowptr[:-1]).max().item()) if self.nb > 0 else 0
         self.plan = B.gas_plan_create(rowptr, self.nnz, max_F, ind=col)
         self.val = None
         if normalise:
@@ -63,6 +64,11 @@ class Model:
         return (w[1] if self.op == "gin" else w).shape[1]
 
 
+# Rows longer than this keep the two-kernel form, whose plan splits them over wavefronts; the one-launch layer
+# gives a row to one team of lanes.
+ONE_LAUNCH_MAX_ROW = 512
+
+
 def gcnii_beta(layer: int) -> float:
     return math.log(0.5 / layer + 1.0)
 
@@ -74,7 +80,8 @@ def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push
     aggregate(X_batch, H[l-1]) -> transform, rows stored to H[l] as well.
     Layer 1 reads its halo rows from the feature table the same way.  GCNII: its first layer aggregates the
     projected features of all of V_b, which no table holds, so that layer gathers from the mini-batch tensor; from
-    layer 2 on the halo rows come from the history tables in place."""
+    layer 2 on the halo rows come from the history tables in place.  Narrow fp32 layers of GCN and GCNII (widths
+    up to 128, no row above ONE_LAUNCH_MAX_ROW entries) take one launch each (gas_spmm_linear)."""
     dev, dt = x_feat.device, x_feat.dtype
     nb = bg.nb
     if model.op == "gcnii":
@@ -86,9 +93,15 @@ def forward_batch_fused(model: Model, bg: BatchGraph, x_feat, histories, do_push
     for l in range(1, L + 1):
         last = l == L
         table = x_feat if l == 1 else histories[l - 2]
-        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
         y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
         push = not last and do_push          # the transform stores its rows to the next history table as well
+        if model.op == "gcn" and B.spmm_linear_supported(x, y.shape[1]) and bg.max_row <= ONE_LAUNCH_MAX_ROW:
+            # narrow layers: aggregation, transform and Push in one launch
+            B.gas_spmm_linear(bg.rowptr, bg.src, bg.val, x, model.weights[l - 1], y, hist=table, relu=not last,
+                              push_idx=bg.n_id[:nb] if push else None, push_hist=histories[l - 1] if push else None)
+            x = y
+            continue
+        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
         if model.op == "gcn":
             B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z)
             if push:
@@ -117,15 +130,24 @@ def _forward_gcnii_fused(model: Model, bg: BatchGraph, x_feat, histories, do_pus
     L = model.n_layers
     for l in range(1, L + 1):
         last = l == L
-        z = torch.empty((nb, h0.shape[1]), dtype=dt, device=dev)
         y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+        beta = gcnii_beta(l)
+        push = not last and do_push
+        if B.spmm_linear_supported(x, y.shape[1]) and bg.max_row <= ONE_LAUNCH_MAX_ROW:
+            # narrow layers: aggregation, transform and Push in one launch
+            B.gas_spmm_linear(bg.rowptr, bg.col if l == 1 else bg.src, bg.val, x, model.weights[l - 1], y,
+                              hist=None if l == 1 else histories[l - 2], s_agg=1.0 - model.alpha, r=h0,
+                              s_res=model.alpha, c_identity=1.0 - beta, c_weight=beta, relu=not last,
+                              push_idx=bg.n_id[:nb] if push else None, push_hist=histories[l - 1] if push else None)
+            x = y
+            continue
+        z = torch.empty((nb, h0.shape[1]), dtype=dt, device=dev)
         if l == 1:
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
         else:
             B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, histories[l - 2], z, s_agg=1.0 - model.alpha, r=h0,
                             s_res=model.alpha)
-        beta = gcnii_beta(l)
-        if not last and do_push:
+        if push:
             B.gas_linear_push(z, model.weights[l - 1], y, bg.n_id[:nb], histories[l - 1], c_identity=1.0 - beta,
                               c_weight=beta, relu=True)
         else:

@@ -101,9 +101,10 @@ def test_gin_fp32_small():
     _run_both(wl, [1], "normal")
 
 
-@pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (2, 0.02), (4, 0.001), (3, 0.1)])
+@pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (2, 0.02), (4, 0.001), (3, 0.1), (3, 1.0), (0, 1.0)])
 def test_fused_execution_matches_oracle(cfg_id, scale):
-    """Algorithm 1 with the halo rows read in place by the aggregation: same outputs and histories."""
+    """Algorithm 1 with the halo rows read in place by the aggregation: same outputs and histories.  The narrow
+    fp32 configurations (0 and 3) take the one-launch layer (gas_spmm_linear), the wide ones the two-kernel form."""
     from paper_2106_05609_amd import executor
     cfg0 = configs.config(cfg_id, scale)
     if cfg0.op == "gcnii":

@@ -290,6 +290,76 @@ def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     assert max_rel_err(to_np(z), want) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("name,K,N,variant", [("sbm", 64, 64, "gcnii"), ("sbm", 128, 64, "gcn"), ("powerlaw", 100, 36, "gcn"),
+                                               ("powerlaw", 128, 128, "gcnii"), ("gin", 8, 4, "gin"), ("sbm", 64, 64, "plain")])
+def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, variant):
+    """gas_spmm_linear: Eq. (2)'s aggregation with both sources, the transform and the Push in one launch, against
+    the oracle's pull + aggregation + transform + push; rows that are not pushed keep their contents."""
+    cfg, g, sg = graphs_small[name]
+    nb, nv = sg.nb, sg.nv
+    ptr_np, col_np, nid_np = to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id)
+    hist = rng.normal_matrix(9, 380, g.n, K)
+    xb = rng.normal_matrix(9, 381, nb, K)
+    w = rng.glorot_uniform(9, 382, K, N)
+    bias = rng.normal(9, 383, 0, N) if variant == "gcn" else None
+    val = oops.gcn_norm(ptr_np, col_np, nid_np, to_np(g.deg)) if variant != "gin" else None
+    kw = dict(diag=1.1) if variant == "gin" else {}
+    r = None
+    if variant == "gcnii":
+        r = rng.normal_matrix(9, 384, nb, K)
+        kw.update(s_agg=0.9, s_res=0.1)
+    lin = dict(c_identity=0.7, c_weight=0.3) if variant == "gcnii" and K == N else {}
+    relu = variant != "plain"
+    # oracle: pull, aggregate, transform, push
+    xo = np.concatenate([to_np(xb), oops.pull(to_np(hist), nid_np[nb:])])
+    z = oops.spmm(ptr_np, col_np, val, xo, r=None if r is None else to_np(r), **kw)
+    want = oops.linear(z, to_np(w), bias=None if bias is None else to_np(bias), relu=relu, **lin)
+    table0 = rng.normal_matrix(9, 385, g.n, N)
+    want_table = to_np(table0).copy()
+    oops.push(want, nid_np[:nb], want_table)
+    # library: one call, halo rows read from the history table in place
+    d_ptr, d_col, d_nid = dev(sg.rowptr), dev(sg.col), dev(sg.n_id)
+    src = torch.empty_like(d_col)
+    gas.gas_fuse_sources(d_col, nb, d_nid, src)
+    dval = None if val is None else dev(torch.from_numpy(val))
+    y = torch.full((nb, N), float("nan"), device="cuda")
+    table = dev(table0).clone()
+    gas.gas_spmm_linear(d_ptr, src, dval, dev(xb), dev(w), y, hist=dev(hist), r=None if r is None else dev(r),
+                        bias=None if bias is None else dev(bias), relu=relu, push_idx=d_nid[:nb], push_hist=table,
+                        **kw, **lin)
+    assert max_rel_err(to_np(y), want) <= 1e-5
+    assert np.array_equal(to_np(table)[nid_np[:nb]], to_np(y))
+    keep = np.ones(g.n, dtype=bool)
+    keep[nid_np[:nb]] = False
+    assert np.array_equal(to_np(table)[keep], want_table[keep])
+    # the other form: plain column indices into the whole mini-batch tensor, no history table, no push
+    y2 = torch.full((nb, N), float("nan"), device="cuda")
+    gas.gas_spmm_linear(d_ptr, d_col, dval, dev(torch.from_numpy(xo)), dev(w), y2, r=None if r is None else dev(r),
+                        bias=None if bias is None else dev(bias), relu=relu, **kw, **lin)
+    assert np.array_equal(to_np(y2).view(np.uint8), to_np(y).view(np.uint8))       # same sources, same order
+    # run to run
+    y3 = torch.empty_like(y2)
+    gas.gas_spmm_linear(d_ptr, d_col, dval, dev(torch.from_numpy(xo)), dev(w), y3, r=None if r is None else dev(r),
+                        bias=None if bias is None else dev(bias), relu=relu, **kw, **lin)
+    assert torch.equal(y2, y3)
+
+
+def test_layer_in_one_launch_limits(gas):
+    """Shapes the one-launch layer does not take are refused before anything is launched."""
+    ptr = dev(torch.tensor([0, 1, 2], dtype=torch.int32))
+    col = dev(torch.tensor([0, 1], dtype=torch.int32))
+    for k, n, dtype in [(256, 64, torch.float32), (64, 132, torch.float32), (30, 32, torch.float32),
+                        (64, 64, torch.bfloat16)]:
+        x = torch.zeros((2, k), dtype=dtype, device="cuda")
+        w = torch.zeros((k, n), dtype=dtype, device="cuda")
+        y = torch.zeros((2, n), dtype=dtype, device="cuda")
+        assert not gas.spmm_linear_supported(x, n)
+        with pytest.raises(gas.GasError):
+            gas.gas_spmm_linear(ptr, col, None, x, w, y)
+    x = torch.zeros((2, 64), device="cuda")
+    gas.gas_spmm_linear(ptr[:1], col[:0], None, x[:0], torch.zeros((64, 64), device="cuda"), x[:0].clone())   # empty: no-op
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("M,K,H,N,ld_hist", [(5000, 256, 256, 256, 256), (4100, 128, 256, 64, 72), (300, 64, 96, 40, 40),
                                              (4097, 256, 256, 256, 260), (0, 32, 32, 32, 32)])

@@ -105,7 +105,11 @@ GAS_API gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t 
  * inside this call, which therefore waits for `stream`.  ind (device,
  * int32[nnz], each row ascending) may be NULL; when given it is used to cut
  * and order the chunks of heavy rows by column range (better cache reuse of
- * the gathered rows) and is copied to the host as well.  Either the local
+ * the gathered rows), and to see whether the pattern is clustered (most
+ * entries of a row name rows near it, as in a batch of partition clusters):
+ * then each of the eight XCDs is given one contiguous range of rows, so a
+ * cluster is gathered into one L2 instead of eight.  It is copied to the
+ * host as well.  Either the local
  * column ids or the source indices of gas_fuse_sources may be passed.  max_F
  * is the widest feature dimension the plan will be used with (sizes the
  * workspace).  A plan must not be used by two streams at the same time.

@@ -39,6 +39,8 @@ struct gas_plan {
     float* d_partial = nullptr;        // [n_chunks, max_F]
     int32_t* d_group = nullptr;        // [2 * n_groups] first and end row of every group of light rows
     int64_t n_groups = 0;
+    int xcd_ranges = 0;                // light-row groups are handed out in one contiguous range per XCD
+    int64_t xcd_start[9] = {0};        // first group of every XCD's range (and the end), equal cost per range
     int device = 0;
 };
 
@@ -71,6 +73,8 @@ struct SpmmArgs {
     float* partial;
     const int32_t* group;       // row groups of the light rows (wave-per-row path)
     int64_t n_groups;
+    int xcd_ranges;       // grouped light rows: one contiguous range of groups per XCD, [xcd_start[x], xcd_start[x+1])
+    int64_t xcd_start[9];
 };
 
 template <bool XBF>
@@ -448,8 +452,16 @@ __global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_chunk_kernel(SpmmArgs
 template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
 __global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_rows_kernel(SpmmArgs a) {
     if constexpr (VB > 0) {
-        const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-        if (g < a.n_groups) light_group<VB, XBF, ZBF>(a, g);
+        // Workgroups go to the eight XCDs in turn and each XCD has its own L2: with xcd_ranges every XCD takes one
+        // contiguous range of the groups (equal cost per range), so rows of one cluster of the partition gather
+        // into one L2, not eight.  The plan turns this on where the pattern is clustered.
+        int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), g_end = a.n_groups;
+        if (a.xcd_ranges) {
+            const int x = blockIdx.x & 7;
+            g = a.xcd_start[x] + (int64_t)(blockIdx.x >> 3) * 4 + (threadIdx.x >> 6);
+            g_end = a.xcd_start[x + 1];
+        }
+        if (g < g_end) light_group<VB, XBF, ZBF>(a, g);
     } else {
         constexpr int E = Unit<XBF>::E;
         const int lane = threadIdx.x & 63;
@@ -549,7 +561,12 @@ gas_status dispatch_chunks(const SpmmArgs& a, hipStream_t s) {
 template <int G, int UPT, int U, bool XBF, bool ZBF, int VB = 0>
 gas_status launch_rows(const SpmmArgs& a, hipStream_t s) {
     const int64_t items = VB > 0 ? a.n_groups : a.n_rows;
-    const int64_t blocks = (items + 3) / 4;
+    int64_t blocks = (items + 3) / 4;
+    if (VB > 0 && a.xcd_ranges) {
+        int64_t longest = 0;
+        for (int x = 0; x < 8; ++x) longest = std::max(longest, a.xcd_start[x + 1] - a.xcd_start[x]);
+        blocks = 8 * ((longest + 3) / 4);
+    }
     if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
     if (blocks > 0)
         hipLaunchKernelGGL((spmm_rows_kernel<G, UPT, U, XBF, ZBF, VB>), dim3((unsigned)blocks), dim3(256), 0, s, a);
@@ -614,6 +631,8 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
     a.partial = plan->d_partial;
     a.group = plan->d_group; a.n_groups = plan->n_groups;
+    a.xcd_ranges = plan->xcd_ranges;
+    for (int x = 0; x < 9; ++x) a.xcd_start[x] = plan->xcd_start[x];
     const bool vec = (F * xb) % 16 == 0 && aligned16(X) && a.x_stride % 16 == 0 && aligned16(Z) &&
                      a.z_stride % 16 == 0 && (!R || (aligned16(R) && a.r_stride % 16 == 0)) &&
                      (!H || (aligned16(H) && a.h_stride % 16 == 0));
@@ -694,21 +713,25 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
         const int64_t len = h_ptr[r + 1] - h_ptr[r];
         if (len > p->threshold) { ++n_heavy_rows; heavy_entries += len; }
     }
-    if (ind && window > 0 && n_heavy_rows > 0) {
+    const int xcd_mode = env_int("GAS_SPMM_XCD", 2, 0, 2);       // 0 never, 1 always, 2 where the pattern is clustered
+    const bool windowed = ind && window > 0 && n_heavy_rows > 0;
+    if (windowed || (ind && xcd_mode == 2 && nnz > 0)) {
         h_ind.resize((size_t)nnz);
         hipError_t e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
         int64_t max_col = 0;
-        for (int64_t r = 0; r < n_rows; ++r)
+        for (int64_t r = 0; windowed && r < n_rows; ++r)
             if (h_ptr[r + 1] - h_ptr[r] > p->threshold) {      // rows are ascending: look at both ends
                 for (int32_t k : {h_ptr[r], h_ptr[r + 1] - 1}) {
                     const int64_t v = h_ind[k] >= 0 ? h_ind[k] : -1 - (int64_t)h_ind[k];
                     if (v > max_col) max_col = v;
                 }
             }
-        const int64_t keep32 = (max_col + 1) * 32 / (heavy_entries / n_heavy_rows);
-        if (keep32 > window) window = keep32;
+        if (windowed) {
+            const int64_t keep32 = (max_col + 1) * 32 / (heavy_entries / n_heavy_rows);
+            if (keep32 > window) window = keep32;
+        }
     }
     std::vector<int32_t> chunk, heavy_row, heavy_first, group, chunk_window;
     const bool grouping = env_int("GAS_SPMM_GROUPS", 1, 0, 1) != 0;
@@ -735,7 +758,7 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
         if (e - b > p->threshold) {
             heavy_row.push_back((int32_t)r);
             heavy_first.push_back((int32_t)(chunk.size() / 3));
-            if (h_ind.empty()) {
+            if (!windowed) {
                 for (int32_t c = b; c < e; c += p->chunk) {
                     chunk.push_back((int32_t)(chunk.size() / 3));      // slot of the partial sum
                     chunk.push_back(c);
@@ -772,6 +795,32 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
         chunk.swap(sorted);
     }
     if (!group.empty()) {
+        // Ranges of groups of equal cost (entries gathered + rows written), one per XCD; used when the pattern is
+        // clustered: GAS_SPMM_XCD=1 always, 0 never, otherwise when at least 30 % of the entries of light rows name
+        // a row of their own range (a partition into clusters does that, a graph without communities stays near 0).
+        const int64_t ng = (int64_t)group.size() / 2;
+        std::vector<int64_t> cost((size_t)ng + 1, 0);
+        for (int64_t i = 0; i < ng; ++i)
+            cost[i + 1] = cost[i] + (h_ptr[group[2 * i + 1]] - h_ptr[group[2 * i]]) + (group[2 * i + 1] - group[2 * i]);
+        for (int x = 0; x <= 8; ++x) {
+            const int64_t target = cost[ng] * x / 8;
+            p->xcd_start[x] = x == 8 ? ng : std::lower_bound(cost.begin(), cost.end(), target) - cost.begin();
+        }
+        p->xcd_ranges = xcd_mode == 1;
+        if (xcd_mode == 2 && !h_ind.empty()) {
+            int64_t local = 0, seen = 0;
+            for (int x = 0; x < 8; ++x) {
+                if (p->xcd_start[x] >= p->xcd_start[x + 1]) continue;
+                const int64_t r0 = group[2 * p->xcd_start[x]], r1 = group[2 * (p->xcd_start[x + 1] - 1) + 1];
+                const int64_t step = std::max<int64_t>(1, (p->xcd_start[x + 1] - p->xcd_start[x]) / 4096);   // sample
+                for (int64_t i = p->xcd_start[x]; i < p->xcd_start[x + 1]; i += step)
+                    for (int32_t k = h_ptr[group[2 * i]]; k < h_ptr[group[2 * i + 1]]; ++k) {
+                        ++seen;
+                        local += h_ind[k] >= r0 && h_ind[k] < r1;
+                    }
+            }
+            p->xcd_ranges = seen > 0 && 10 * local >= 3 * seen;
+        }
         const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
         p->n_groups = (int64_t)group.size() / 2;
         hipError_t e = hipMalloc(&p->d_group, bounds.size() * sizeof(int32_t));

@@ -290,6 +290,27 @@ def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     assert max_rel_err(to_np(z), want) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("name", ["sbm", "powerlaw"])
+def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name, monkeypatch):
+    """Handing the light rows to the XCDs in contiguous ranges changes which workgroup does a row, not the sum."""
+    cfg, g, sg = graphs_small[name]
+    F = 256
+    x = dev(rng.normal_matrix(10, 390, sg.nv, F))
+    val = dev(torch.from_numpy(oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg))))
+    out = []
+    for mode in ("0", "1", "2"):
+        monkeypatch.setenv("GAS_SPMM_XCD", mode)
+        plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col))
+        z = torch.full((sg.nb, F), float("nan"), device="cuda")
+        gas.gas_spmm(plan, dev(sg.rowptr), dev(sg.col), val, x, z)
+        out.append(to_np(z))
+        gas.gas_plan_destroy(plan)
+    assert np.array_equal(out[0].view(np.uint8), out[1].view(np.uint8))
+    assert np.array_equal(out[0].view(np.uint8), out[2].view(np.uint8))
+    want = oops.spmm(to_np(sg.rowptr), to_np(sg.col), to_np(val), to_np(x))
+    assert max_rel_err(out[1], want) <= 1e-5
+
+
 @pytest.mark.parametrize("name,K,N,variant", [("sbm", 64, 64, "gcnii"), ("sbm", 128, 64, "gcn"), ("powerlaw", 100, 36, "gcn"),
                                                ("powerlaw", 128, 128, "gcnii"), ("gin", 8, 4, "gin"), ("sbm", 64, 64, "plain")])
 def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, variant):

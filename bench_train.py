@@ -1,7 +1,10 @@
 #!/usr/bin/env python3
 """One epoch of Algorithm 1 on a benchmark configuration: for every mini-batch, forward through all layers with
 Push/Pull of the histories, softmax cross-entropy on the in-batch nodes, backward with the histories held constant,
-gradient-descent update.  Every step is a C-ABI call (executor.train_step).  One JSON line on stdout."""
+gradient-descent update.  Every step is a C-ABI call (executor.train_step).  With --graph every mini-batch's whole
+training step (it neither allocates behind the allocator's back nor waits) is also captured as a HIP graph; the
+epochs are then timed both ways from the same state and the weights and histories afterwards must be the same bits.
+One JSON line on stdout."""
 import argparse
 import json
 import os
@@ -20,6 +23,7 @@ def main():
     p.add_argument("--scale", type=float, default=1.0)
     p.add_argument("--epochs", type=int, default=2, help="timed epochs after one warm-up epoch")
     p.add_argument("--separate", action="store_true", help="pull the halo rows instead of reading them in place")
+    p.add_argument("--graph", action="store_true", help="also replay every mini-batch's training step as a HIP graph")
     p.add_argument("--lr", type=float, default=0.0, help="step size (default: 0.01 for GCN; 1e-10 for GIN, whose unnormalised sums of N(0,1) features give logits of order 1e5)")
     args = p.parse_args()
     if not torch.cuda.is_available():
@@ -31,15 +35,14 @@ def main():
     dev = torch.device("cuda:0")
     cfg = configs.config(args.config, args.scale)
     lr = args.lr if args.lr > 0 else (1e-10 if cfg.op == "gin" else 0.01)
-    if cfg.op == "gcnii":
-        sys.exit("bench_train.py: use a GCN or GIN configuration (0, 1, 2, 4)")
+    fused = not args.separate and cfg.op != "gcnii"   # GCNII's first layer aggregates projected features: pulled
     t0 = time.time()
     wl = configs.build_workload(cfg, device=dev)
     g = wl.graph
     n_classes = cfg.widths[-1]
     labels = configs.block_labels(g, min(n_classes, 16), cfg.seed, unlabelled=0.5).to(dev)
     ws = [(a.clone(), b.clone()) for a, b in wl.weights] if cfg.op == "gin" else [w.clone() for w in wl.weights]
-    gm = executor.Model(cfg.op, ws, None, cfg.alpha, cfg.gin_eps)
+    gm = executor.Model(cfg.op, ws, wl.w_in.clone() if cfg.op == "gcnii" else None, cfg.alpha, cfg.gin_eps)
     hist = configs.make_histories(cfg, device=dev, init="zeros")
     bgs = []
     for b in wl.batches:
@@ -56,7 +59,7 @@ def main():
         tot = torch.zeros(1, device=dev)
         n = 0
         for bg, lab_b, n_lab, _ in bgs:
-            loss_sum, _, _, _ = executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab, fused=not args.separate)
+            loss_sum, _, _, _ = executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab, fused=fused)
             tot += loss_sum
             n += n_lab
         return tot, n
@@ -71,9 +74,53 @@ def main():
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / args.epochs
     edges = sum(nnz for *_, nnz in bgs) * len(ws)                 # entries aggregated per epoch, forward
+    graph = None
+    if args.graph:
+        state = [w for pair in ws for w in (pair if isinstance(pair, tuple) else (pair,))] + list(hist)
+        if gm.w_in is not None:
+            state.append(gm.w_in)
+        for bg, *_ in bgs:
+            if fused:
+                bg.src                                            # built before any capture (it allocates)
+            if cfg.op == "gcnii":
+                bg.plan_t_all
+
+        def run_epochs(step_fns):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.epochs):
+                for f in step_fns:
+                    f()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / args.epochs
+        start = [t.clone() for t in state]
+        eager_fns = [(lambda bg=bg, lab_b=lab_b, n_lab=n_lab: executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab,
+                                                                                  fused=fused))
+                     for bg, lab_b, n_lab, _ in bgs]
+        sec_eager = run_epochs(eager_fns)
+        after_eager = [t.clone() for t in state]
+        for t, t0_ in zip(state, start):
+            t.copy_(t0_)
+        graphs, pool = [], None
+        for f in eager_fns:                                       # capture only: nothing runs, the state stays put
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, pool=pool):
+                f()
+            pool = pool or gr.pool()
+            graphs.append(gr)
+        sec_graph = run_epochs([gr.replay for gr in graphs])
+        same = all(torch.equal(a, b) for a, b in zip(state, after_eager))
+        graph = {"epoch_s_eager": round(sec_eager, 5), "epoch_s_graph": round(sec_graph, 5),
+                 "speedup": round(sec_eager / sec_graph, 2), "state_bit_identical": same}
+        print(f"[train] from one state: eager epoch {sec_eager * 1e3:.2f} ms, graph replay {sec_graph * 1e3:.2f} ms "
+              f"(x{sec_eager / sec_graph:.2f}), weights and histories identical: {same}", file=sys.stderr, flush=True)
+        if not same:
+            sys.exit("bench_train.py: the replayed epochs left different weights or histories")
     out = {"workload": f"configs[{args.config}] {cfg.name}: one training epoch over {len(bgs)} mini-batches, {len(ws)} layers",
            "epoch_s": round(sec, 4), "forward_edges_per_s": round(edges / sec, 1), "nodes_per_s": round(g.n / sec, 1),
            "mean_loss_per_epoch": [round(x, 5) for x in losses], "dtype": "f32" if cfg.dtype == torch.float32 else "bf16"}
+    if graph:
+        out["graph_replay"] = graph
     print(f"[train] epoch {sec * 1e3:.1f} ms, {edges / sec / 1e9:.2f} G forward edges/s, losses {out['mean_loss_per_epoch']}",
           file=sys.stderr, flush=True)
     print(json.dumps(out))

@@ -1091,8 +1091,17 @@ __global__ __launch_bounds__(256) void mlp2_generic_kernel(MlpArgs a) {
 // Weight gradient dW[k, j] = c_w * sum_m Z[m, k] * G[m, j]: the reduction runs over the rows.  The rows are cut
 // into slabs; a workgroup forms the 128 x 128 tile (tk, tj) of the partial product of one slab in fp32 and
 // writes it to the workspace; dw_reduce_kernel adds the slabs in slab order (fixed order, no atomics).
-constexpr int kDwSlab = 4096;      // rows per slab
 constexpr int kDwTile = 128;
+
+// Rows per slab: a function of the shape alone (the workspace size and the order of the sum follow from it).
+// About four workgroups per compute unit, at most 4096 rows (long slabs amortise the partial tile they write),
+// at least 128: a small batch then still spreads over the chip instead of queueing in a handful of workgroups.
+static int64_t dw_slab_rows(int64_t M, int K, int N) {
+    const int64_t tiles = (int64_t)((K + kDwTile - 1) / kDwTile) * ((N + kDwTile - 1) / kDwTile);
+    int64_t slab = (M * tiles + 1023) / 1024;
+    slab = (slab + 63) / 64 * 64;
+    return slab < 128 ? 128 : (slab > 4096 ? 4096 : slab);
+}
 
 struct DwArgs {
     const char* Z;  int64_t ldz;
@@ -1103,6 +1112,7 @@ struct DwArgs {
     float* partial;                 // [n_slabs][K][N]
     float* dW;                      // [K][N]
     int n_slabs;
+    int slab;                       // rows per slab
 };
 
 // fp32: both operands are read as single dwords from row-major LDS tiles (lanes run along the feature index).
@@ -1115,8 +1125,8 @@ __global__ __launch_bounds__(256) void dw_f32_kernel(DwArgs a) {
     const float* G = reinterpret_cast<const float*>(a.G);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
     const int slab = blockIdx.x, k0 = blockIdx.y * kDwTile, n0 = blockIdx.z * kDwTile;
-    const int64_t m_begin = (int64_t)slab * kDwSlab;
-    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int64_t m_begin = (int64_t)slab * a.slab;
+    const int64_t m_end = m_begin + a.slab < a.M ? m_begin + a.slab : a.M;
     const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
     f32x16 acc[2][2];
     zero_acc(acc);
@@ -1193,8 +1203,8 @@ __global__ __launch_bounds__(256) void dw_bf16_kernel(DwArgs a) {
     const uint16_t* G = reinterpret_cast<const uint16_t*>(a.G);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
     const int slab = blockIdx.x, k0 = blockIdx.y * kDwTile, n0 = blockIdx.z * kDwTile;
-    const int64_t m_begin = (int64_t)slab * kDwSlab;
-    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int64_t m_begin = (int64_t)slab * a.slab;
+    const int64_t m_end = m_begin + a.slab < a.M ? m_begin + a.slab : a.M;
     const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
     f32x16 acc[2][2];
     zero_acc(acc);
@@ -1254,8 +1264,8 @@ __global__ __launch_bounds__(512) void dw_bf16_wide_kernel(DwArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slab = blockIdx.x;
-    const int64_t m_begin = (int64_t)slab * kDwSlab;
-    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int64_t m_begin = (int64_t)slab * a.slab;
+    const int64_t m_end = m_begin + a.slab < a.M ? m_begin + a.slab : a.M;
     const int wk0 = (wave >> 1) * 64, wn0 = (wave & 1) * 128;
     f32x16 acc[2][4];
     zero_acc(acc);
@@ -1313,20 +1323,40 @@ __global__ __launch_bounds__(256) void dw_bf16_generic_kernel(DwArgs a) {
     const int k = (int)((idx % per) / a.N), n = (int)(idx % a.N);
     const uint16_t* Z = reinterpret_cast<const uint16_t*>(a.Z);
     const uint16_t* G = reinterpret_cast<const uint16_t*>(a.G);
-    const int64_t m_begin = (int64_t)slab * kDwSlab;
-    const int64_t m_end = m_begin + kDwSlab < a.M ? m_begin + kDwSlab : a.M;
+    const int64_t m_begin = (int64_t)slab * a.slab;
+    const int64_t m_end = m_begin + a.slab < a.M ? m_begin + a.slab : a.M;
     float s = 0.f;
     for (int64_t m = m_begin; m < m_end; ++m) s = fmaf(bf16_val(Z, m * a.ldz + k), bf16_val(G, m * a.ldg + n), s);
     a.partial[idx] = s;
 }
 
+// dW = c_w * (sum of the slabs' partial tiles).  A workgroup owns 32 consecutive outputs; eight threads per output
+// each add every eighth slab in slab order, four loads in flight, and the eight sums are added in a fixed order.
+constexpr int kDwReduceOut = 32, kDwReduceWays = 8;
 __global__ __launch_bounds__(256) void dw_reduce_kernel(DwArgs a) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    __shared__ float part[kDwReduceWays][kDwReduceOut];
+    const int o = threadIdx.x % kDwReduceOut, way = threadIdx.x / kDwReduceOut;
+    const int64_t idx = (int64_t)blockIdx.x * kDwReduceOut + o;
     const int64_t per = (int64_t)a.K * a.N;
-    if (idx >= per) return;
     float s = 0.f;
-    for (int sl = 0; sl < a.n_slabs; ++sl) s += a.partial[(int64_t)sl * per + idx];
-    a.dW[idx] = a.c_w * s;
+    if (idx < per) {
+        const float* p = a.partial + idx;
+        int sl = way;
+        for (; sl + 3 * kDwReduceWays < a.n_slabs; sl += 4 * kDwReduceWays) {
+            const float v0 = p[(int64_t)sl * per], v1 = p[(int64_t)(sl + kDwReduceWays) * per],
+                        v2 = p[(int64_t)(sl + 2 * kDwReduceWays) * per], v3 = p[(int64_t)(sl + 3 * kDwReduceWays) * per];
+            s = ((s + v0) + v1) + v2 + v3;
+        }
+        for (; sl < a.n_slabs; sl += kDwReduceWays) s += p[(int64_t)sl * per];
+    }
+    part[way][o] = s;
+    __syncthreads();
+    if (way == 0 && idx < per) {
+        float t = part[0][o];
+#pragma unroll
+        for (int w = 1; w < kDwReduceWays; ++w) t += part[w][o];
+        a.dW[idx] = a.c_w * t;
+    }
 }
 
 // ReLU backward, element-wise: GP = GY where Y > 0, else 0
@@ -1502,7 +1532,8 @@ gas_status gas_linear_bwd_input(const void* GP, int64_t ldgp, int64_t n_rows, in
 
 int64_t gas_linear_bwd_weight_workspace(int64_t n_rows, int32_t F_in, int32_t F_out) {
     if (n_rows <= 0 || F_in <= 0 || F_out <= 0) return 0;
-    return ((n_rows + kDwSlab - 1) / kDwSlab) * (int64_t)F_in * F_out * (int64_t)sizeof(float);
+    const int64_t slab = dw_slab_rows(n_rows, F_in, F_out);
+    return ((n_rows + slab - 1) / slab) * (int64_t)F_in * F_out * (int64_t)sizeof(float);
 }
 
 gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
@@ -1518,11 +1549,12 @@ gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int
     a.G = static_cast<const char*>(GP); a.ldg = ldgp;
     a.M = n_rows; a.K = F_in; a.N = F_out; a.c_w = c_weight;
     a.partial = static_cast<float*>(workspace); a.dW = dW;
-    const int64_t n_slabs = (n_rows + kDwSlab - 1) / kDwSlab;
+    a.slab = (int)dw_slab_rows(n_rows, F_in, F_out);
+    const int64_t n_slabs = (n_rows + a.slab - 1) / a.slab;
     GAS_REQUIRE(n_slabs <= 0x7FFFFFFFLL, "gas_linear_bwd_weight: too many rows");
     a.n_slabs = (int)n_slabs;
     const int64_t per = (int64_t)F_in * F_out;
-    const unsigned rblocks = (unsigned)((per + 255) / 256);
+    const unsigned rblocks = (unsigned)((per + kDwReduceOut - 1) / kDwReduceOut);
     if (n_rows == 0) {                                   // empty sum: dW = 0
         hipLaunchKernelGGL(dw_reduce_kernel, dim3(rblocks), dim3(256), 0, s, a);
         GAS_CHECK_HIP(hipGetLastError());

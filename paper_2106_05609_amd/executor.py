@@ -32,6 +32,7 @@ class BatchGraph:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
             B.gas_gcn_norm(rowptr, col, n_id, deg, self.val)
         self._src = None
+        self._plan_t_all, self._max_F = None, max_F
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
         if colptr is not None:
             # backward over the in-batch columns only: histories are constants
@@ -41,6 +42,14 @@ class BatchGraph:
                 self.val_t = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
                 B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t)
 
+
+    @property
+    def plan_t_all(self):
+        """Plan of the backward aggregation over ALL columns, halo included (GCNII's first layer: the gradient of
+        the projected features of every node of V_b); built on first use, once per batch."""
+        if self._plan_t_all is None:
+            self._plan_t_all = B.gas_plan_create(self.colptr, self.nnz, self._max_F, ind=self.row)
+        return self._plan_t_all
 
     @property
     def src(self):
@@ -408,9 +417,8 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             g_h0[:nb] += model.alpha * gz.float()        # small accumulation on the side (fp32), not a hot-path step
         if l == 1:
             if model.op == "gcnii":
-                plan_all = B.gas_plan_create(bg.colptr, bg.nnz, gz.shape[1], ind=bg.row)
                 gx = torch.empty((nv, gz.shape[1]), dtype=dt, device=dev)
-                B.gas_spmm_t(plan_all, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
+                B.gas_spmm_t(bg.plan_t_all, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
                 g_h0 += gx.float()
             break
         gx = torch.empty((nb, gz.shape[1]), dtype=dt, device=dev)

@@ -70,7 +70,8 @@ def test_linear_bwd_weight_parity(gas, dtype, M, K, N):
     gp = rng.normal_matrix(9, 621, M, N, dtype=dtype)
     dw = torch.full((K, N), float("nan"), device="cuda")
     nbytes = gas.gas_linear_bwd_weight_workspace(M, K, N)
-    assert nbytes == -(-M // 4096) * K * N * 4
+    # one fp32 partial per slab of rows; slabs hold between 128 and 4096 rows, depending on the shape only
+    assert nbytes % (K * N * 4) == 0 and -(-M // 4096) <= nbytes // (K * N * 4) <= -(-M // 128)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     gas.gas_linear_bwd_weight(dev(z), dev(gp), dw, ws, c_weight=0.5)
     want = oops.linear_bwd_weight(to_np(z), to_np(gp), c_weight=0.5)

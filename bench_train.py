@@ -35,7 +35,7 @@ def main():
     dev = torch.device("cuda:0")
     cfg = configs.config(args.config, args.scale)
     lr = args.lr if args.lr > 0 else (1e-10 if cfg.op == "gin" else 0.01)
-    fused = not args.separate and cfg.op != "gcnii"   # GCNII's first layer aggregates projected features: pulled
+    fused = not args.separate
     t0 = time.time()
     wl = configs.build_workload(cfg, device=dev)
     g = wl.graph

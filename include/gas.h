@@ -238,13 +238,15 @@ GAS_API gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int
  * with S(s) = X[s, :] for s >= 0 and hist[-1-s, :] for s < 0, exactly as in
  * gas_spmm_hist (hist may be NULL when no index is negative: then src is the
  * plain column array and X the whole mini-batch tensor) and the transform of
- * gas_linear.  The aggregated tile stays on the chip, Z is never written.
+ * gas_linear.  The aggregated tile stays on the chip; Z is written only if
+ * Z_out != NULL ([n_rows, F_in], row stride ldz_out: a training pass reads it
+ * again for the weight gradient).
  * Needs no plan.  Meant for deep narrow models (the 64-layer GCNII of the
  * paper's experiments), which are bound by launches: rows of any length are
  * handled, but long rows are not split, so wide or heavy-tailed layers should
  * use gas_spmm_hist + gas_linear_push.
  * Restrictions: GAS_F32 only (GAS_ERR_DTYPE otherwise); F_in and F_out
- * multiples of 4, at most 128; X, hist, R, W 16-byte aligned with row strides
+ * multiples of 4, at most 128; X, hist, R, W, Z_out 16-byte aligned with row strides
  * that are multiples of 4 elements (GAS_ERR_ARG otherwise, nothing is
  * launched).  val may be NULL (all ones), R and bias may be NULL.  Results are
  * deterministic (fixed summation order) and agree with the two-call form to
@@ -256,6 +258,7 @@ GAS_API gas_status gas_spmm_linear(const int32_t* rowptr, const int32_t* src, co
                            const void* R, int64_t ldr, float s_res,
                            const void* W, int32_t F_out, const void* bias,
                            float c_identity, float c_weight, int relu, void* Y, int64_t ldy,
+                           void* Z_out, int64_t ldz_out,
                            const int32_t* push_idx, void* push_hist, int64_t n_push_rows, int64_t ld_push,
                            void* stream);
 

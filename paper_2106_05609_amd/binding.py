@@ -284,7 +284,7 @@ def spmm_linear_supported(x, f_out) -> bool:
 
 
 def gas_spmm_linear(rowptr, src, val, x, w, y, hist=None, diag=0.0, s_agg=1.0, r=None, s_res=0.0, bias=None,
-                    c_identity=0.0, c_weight=1.0, relu=False, push_idx=None, push_hist=None):
+                    c_identity=0.0, c_weight=1.0, relu=False, push_idx=None, push_hist=None, z_out=None):
     """One layer in one launch: aggregation of the rows of y (sources: rows of x, or rows of hist for negative
     indices), transform by w, optional store of every output row to push_hist[push_idx[i]]."""
     n_rows = y.shape[0]
@@ -293,6 +293,9 @@ def gas_spmm_linear(rowptr, src, val, x, w, y, hist=None, diag=0.0, s_agg=1.0, r
     hp, ldh = (C.c_void_p(0), C.c_int64(0)) if hist is None else _mat(hist)
     rp, ldr = (C.c_void_p(0), C.c_int64(0)) if r is None else _mat(r)
     pp, ldp = (C.c_void_p(0), C.c_int64(0)) if push_hist is None else _mat(push_hist)
+    zp, ldzo = (C.c_void_p(0), C.c_int64(0)) if z_out is None else _mat(z_out)
+    if z_out is not None and (z_out.dtype != x.dtype or z_out.shape[1] != x.shape[1] or z_out.shape[0] < n_rows):
+        raise ValueError("gas_spmm_linear: z_out does not match")
     if w.dtype != x.dtype or y.dtype != x.dtype or w.shape[0] != x.shape[1] or y.shape[1] != w.shape[1] or \
             rowptr.numel() != n_rows + 1 or (hist is not None and (hist.dtype != x.dtype or hist.shape[1] != x.shape[1])) or \
             (r is not None and (r.dtype != x.dtype or r.shape[1] != x.shape[1] or r.shape[0] < n_rows)) or \
@@ -303,7 +306,7 @@ def gas_spmm_linear(rowptr, src, val, x, w, y, hist=None, diag=0.0, s_agg=1.0, r
         _ptr(rowptr, torch.int32), _ptr(src, torch.int32), _ptr(val, torch.float32), C.c_int64(n_rows), xp, ldx, hp,
         C.c_int64(0 if hist is None else hist.shape[0]), ldh, C.c_int(_dt(x)), C.c_int32(x.shape[1]), C.c_float(diag),
         C.c_float(s_agg), rp, ldr, C.c_float(s_res), _ptr(w), C.c_int32(w.shape[1]), _ptr(bias), C.c_float(c_identity),
-        C.c_float(c_weight), C.c_int(int(relu)), yp, ldy, _ptr(push_idx, torch.int32), pp,
+        C.c_float(c_weight), C.c_int(int(relu)), yp, ldy, zp, ldzo, _ptr(push_idx, torch.int32), pp,
         C.c_int64(0 if push_hist is None else push_hist.shape[0]), ldp, _stream()))
 
 

@@ -22,6 +22,7 @@ struct FusedArgs {
     const float* R; int64_t ldr;
     const float* W; const float* bias;
     float* Y; int64_t ldy;
+    float* Zout; int64_t ldzo;       // optional copy of the aggregated rows (a training pass reads them again)
     const int32_t* push_idx; float* PH; int64_t ldp;
     int K, N, Kp, Np;                // widths, and the widths padded to the MFMA's steps (8 and 32)
     int g_log2;                      // lanes per row in the aggregation = 1 << g_log2 (>= K / 8)
@@ -159,6 +160,15 @@ __global__ __launch_bounds__(kThreads) void spmm_linear_f32_kernel(FusedArgs a) 
             if (piece1) finish(acc1, j + G);
         }
         __syncthreads();                 // Zs (and, the first time, Ws) complete
+        if (a.Zout) {                    // the aggregated rows as gas_spmm would have stored them
+            const int kq4 = a.K / 4;
+            for (int idx = tid; idx < kRows * kq4; idx += kThreads) {
+                const int row = idx / kq4, c = 4 * (idx % kq4);
+                if (m_tile + row < a.n_rows)
+                    *reinterpret_cast<f32x4*>(a.Zout + (m_tile + row) * a.ldzo + c) =
+                        *reinterpret_cast<const f32x4*>(Zs + row * ldz + c);
+            }
+        }
         // ---- 2. transform of the tile
         if (32 * wave < a.Np) {
             f32x16 acc;
@@ -222,8 +232,8 @@ gas_status gas_spmm_linear(const int32_t* rowptr, const int32_t* src, const floa
                            int64_t ldx, const void* hist, int64_t n_hist_rows, int64_t ld_hist, gas_dtype dt,
                            int32_t F_in, float diag, float s_agg, const void* R, int64_t ldr, float s_res,
                            const void* W, int32_t F_out, const void* bias, float c_identity, float c_weight, int relu,
-                           void* Y, int64_t ldy, const int32_t* push_idx, void* push_hist, int64_t n_push_rows,
-                           int64_t ld_push, void* stream) {
+                           void* Y, int64_t ldy, void* Z_out, int64_t ldz_out, const int32_t* push_idx,
+                           void* push_hist, int64_t n_push_rows, int64_t ld_push, void* stream) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_spmm_linear: unknown dtype %d", (int)dt);
     if (dt != GAS_F32) return fail(GAS_ERR_DTYPE, "gas_spmm_linear: fp32 only (use gas_spmm_hist + gas_linear_push)");
     GAS_REQUIRE(n_rows >= 0 && n_rows < 0x7FFFFFFFLL, "gas_spmm_linear: n_rows=%lld", (long long)n_rows);
@@ -238,8 +248,9 @@ gas_status gas_spmm_linear(const int32_t* rowptr, const int32_t* src, const floa
     GAS_REQUIRE(c_identity == 0.f || F_in == F_out, "gas_spmm_linear: the identity term needs F_in == F_out");
     GAS_REQUIRE((push_idx == nullptr) == (push_hist == nullptr), "gas_spmm_linear: push_idx and push_hist go together");
     GAS_REQUIRE(!push_hist || ld_push >= F_out, "gas_spmm_linear: row stride of the push table smaller than F_out");
+    GAS_REQUIRE(!Z_out || ldz_out >= F_in, "gas_spmm_linear: row stride of Z_out smaller than F_in");
     const bool al = aligned16(X) && ldx % 4 == 0 && aligned16(W) && (!hist || (aligned16(hist) && ld_hist % 4 == 0)) &&
-                    (!R || (aligned16(R) && ldr % 4 == 0));
+                    (!R || (aligned16(R) && ldr % 4 == 0)) && (!Z_out || (aligned16(Z_out) && ldz_out % 4 == 0));
     GAS_REQUIRE(al, "gas_spmm_linear: rows must be 16-byte aligned (use gas_spmm_hist + gas_linear_push)");
 
     FusedArgs a{};
@@ -250,6 +261,7 @@ gas_status gas_spmm_linear(const int32_t* rowptr, const int32_t* src, const floa
     a.R = reinterpret_cast<const float*>(R); a.ldr = ldr;
     a.W = reinterpret_cast<const float*>(W); a.bias = reinterpret_cast<const float*>(bias);
     a.Y = reinterpret_cast<float*>(Y); a.ldy = ldy;
+    a.Zout = reinterpret_cast<float*>(Z_out); a.ldzo = ldz_out;
     a.push_idx = push_idx; a.PH = reinterpret_cast<float*>(push_hist); a.ldp = ld_push;
     a.K = F_in; a.N = F_out; a.Kp = (F_in + 7) & ~7; a.Np = (F_out + 31) & ~31;
     a.g_log2 = 3;

@@ -328,15 +328,16 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
     linears here (the hidden activation is needed again by the backward pass).  Returns (Y_L, grads, kept) with
     grads[l] = dW_l (float32; a pair for GIN), grads["w_in"] for GCNII, and kept = the stored activations the
     backward pass read (x0, h0, per layer (Z, hidden, Y)).  grad_out is dLoss/dY_L [nb, F_L], or a function
-    that returns it given Y_L.  fused (GCN, GIN): the forward aggregations read their halo rows from the feature
-    table / the history tables in place (gas_spmm_hist) and nothing is pulled; same bits.  Every step is a
-    gas_* call."""
+    that returns it given Y_L.  fused: the forward aggregations read their halo rows from the feature table / the
+    history tables in place (gas_spmm_hist) and nothing is pulled; same bits.  GCNII's first layer gathers the
+    projected features from the mini-batch tensor, its later layers from the histories.  Narrow fp32 layers of
+    GCN and GCNII then take one launch each (gas_spmm_linear with Z kept; the row sums are taken in another order,
+    so these agree with the other form to rounding, not bit for bit).  Every step is a gas_* call."""
     dev, dt = x_feat.device, x_feat.dtype
     nb, nv = bg.nb, bg.nv
-    if fused and model.op == "gcnii":
-        raise ValueError("GCNII's first layer aggregates the projected features, which no table holds: fused=False")
-    x0 = torch.empty((nb if fused else nv, x_feat.shape[1]), dtype=dt, device=dev)
-    B.gas_pull(x_feat, bg.n_id[:nb] if fused else bg.n_id, x0)
+    all_rows = not fused or model.op == "gcnii"      # GCNII projects the features of every node of V_b
+    x0 = torch.empty((nv if all_rows else nb, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id if all_rows else bg.n_id[:nb], x0)
     x, h0 = x0, None
     if model.op == "gcnii":
         h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
@@ -353,6 +354,24 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         y = x_next[:nb]
         h = None
         table = (x_feat if l == 1 else histories[l - 2]) if fused else None
+        if fused and model.op == "gcnii" and l == 1:
+            table = None                                  # layer 1 gathers the projected features from h0 itself
+        one_launch = (fused and model.op in ("gcn", "gcnii") and B.spmm_linear_supported(x, f_out)
+                      and bg.max_row <= ONE_LAUNCH_MAX_ROW)
+        if one_launch:
+            # narrow layers: aggregation, transform and Push in one launch; Z is kept for the weight gradient
+            push = not last and do_push
+            beta = gcnii_beta(l) if model.op == "gcnii" else 1.0
+            kw = dict(s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha, c_identity=1.0 - beta,
+                      c_weight=beta) if model.op == "gcnii" else {}
+            B.gas_spmm_linear(bg.rowptr, bg.col if table is None else bg.src, bg.val, x, model.weights[l - 1], y,
+                              hist=table, relu=not last, z_out=z, push_idx=bg.n_id[:nb] if push else None,
+                              push_hist=histories[l - 1] if push else None, **kw)
+            saved.append((z, h, y))
+            if last:
+                break
+            x = x_next
+            continue
         if model.op == "gcn":
             if fused:
                 B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z)
@@ -369,7 +388,11 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             B.gas_linear(z, w1, h, relu=True)
             B.gas_linear(h, w2, y, relu=not last)
         else:
-            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            if table is not None:
+                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z, s_agg=1.0 - model.alpha, r=h0,
+                                s_res=model.alpha)
+            else:
+                B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, x, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
             beta = gcnii_beta(l)
             B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
         saved.append((z, h, y))

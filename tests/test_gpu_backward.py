@@ -84,9 +84,12 @@ def test_linear_bwd_weight_parity(gas, dtype, M, K, N):
         gas.gas_linear_bwd_weight(dev(z), dev(gp), dw, ws[: max(0, nbytes - 4)], c_weight=0.5)
 
 
-@pytest.mark.parametrize("cfg_id,scale,dtype", [(1, 0.1, None), (2, 0.02, None), (3, 0.05, None), (4, 0.001, None),
-                                                 (4, 0.0006, torch.float32)])
-def test_batch_backward_matches_oracle(cfg_id, scale, dtype):
+@pytest.mark.parametrize("cfg_id,scale,dtype,fused", [(1, 0.1, None, False), (2, 0.02, None, False), (3, 0.05, None, False),
+                                                       (4, 0.001, None, False), (4, 0.0006, torch.float32, False),
+                                                       (3, 0.05, None, True), (3, 1.0, None, True), (0, 1.0, None, True),
+                                                       (2, 0.02, None, True)])
+def test_batch_backward_matches_oracle(cfg_id, scale, dtype, fused):
+    """fused: halo rows read in place; configs 0 and 3 (narrow fp32) then run each layer's forward as one launch."""
     from paper_2106_05609_amd import executor
     cfg = configs.config(cfg_id, scale)
     if dtype is not None:
@@ -102,7 +105,7 @@ def test_batch_backward_matches_oracle(cfg_id, scale, dtype):
     bg = _gpu_batch(wl, sg, g.deg.to("cuda"))
     f_out = cfg.widths[-1]
     grad_out = rng.normal_matrix(cfg.seed, 630, sg.nb, f_out, dtype=cfg.dtype)
-    y_gpu, grads_gpu, kept = executor.train_batch(gm, bg, wl.x.to("cuda"), hs_gpu, grad_out.to("cuda"))
+    y_gpu, grads_gpu, kept = executor.train_batch(gm, bg, wl.x.to("cuda"), hs_gpu, grad_out.to("cuda"), fused=fused)
     n_id, rp, cl = to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col)
     y_cpu, _ = omodel.gas_batch_train(om, n_id, rp, cl, sg.nb, to_np(g.deg), to_np(wl.x), hs_cpu, to_np(grad_out))
     tol = TOL[cfg.dtype]

@@ -231,19 +231,32 @@ def gas_batch_train(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories,
     return y, gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, grad_out)
 
 
-def apply_sgd(model: Model, grads, lr, weight_decay=0.0):
-    """One gradient-descent update of every weight matrix, in place."""
+def _all_grads(model: Model, grads):
+    """(weight, gradient) pairs in a fixed order: layer by layer (GIN: W1 then W2), GCNII's projection last."""
+    out = []
     for l in range(model.n_layers):
         if model.op == "gin":
-            for w, dw in zip(model.weights[l], grads[l]):
-                ops.sgd_step(w, dw, lr, weight_decay)
+            out += list(zip(model.weights[l], grads[l]))
         else:
-            ops.sgd_step(model.weights[l], grads[l], lr, weight_decay)
+            out.append((model.weights[l], grads[l]))
     if model.op == "gcnii":
-        ops.sgd_step(model.w_in, grads["w_in"], lr, weight_decay)
+        out.append((model.w_in, grads["w_in"]))
+    return out
 
 
-def gas_train_step(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, labels, lr, weight_decay=0.0):
+def apply_sgd(model: Model, grads, lr, weight_decay=0.0, max_norm=None):
+    """One gradient-descent update of every weight matrix, in place; with max_norm the gradients are first
+    clipped by their global L2 norm (paper, Section 4)."""
+    pairs = _all_grads(model, grads)
+    scale = 1.0 if max_norm is None else ops.clip_scale([ops.sq_norm(dw) for _, dw in pairs], max_norm)
+    for w, dw in pairs:
+        if scale != 1.0:
+            dw = (dw.astype(np.float64) * scale).astype(np.float32)
+        ops.sgd_step(w, np.ascontiguousarray(dw), lr, weight_decay)
+
+
+def gas_train_step(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, labels, lr, weight_decay=0.0,
+                   max_norm=None):
     """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
     softmax cross-entropy averaged over the labelled in-batch nodes (labels: one per node of the graph, < 0 =
     unlabelled), backward with the histories held constant, gradient-descent update.  The model's weights and
@@ -253,7 +266,7 @@ def gas_train_step(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, 
     n_lab = int((lab >= 0).sum())
     _, loss_sum, g = ops.softmax_xent(y, lab, scale=1.0 / max(1, n_lab))
     grads = gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, g)
-    apply_sgd(model, grads, lr, weight_decay)
+    apply_sgd(model, grads, lr, weight_decay, max_norm)
     return loss_sum / max(1, n_lab)
 
 

@@ -213,6 +213,19 @@ def sgd_step(w, dw, lr, weight_decay=0.0) -> None:
     lib().oracle_sgd_step(_p(w), C.c_int64(w.size), C.c_int(_dt(w)), _p(dw), C.c_double(lr), C.c_double(weight_decay))
 
 
+def sq_norm(dw) -> float:
+    """Sum of the squares of a gradient (plain definition, float64)."""
+    return float(np.sum(np.asarray(dw, dtype=np.float64) ** 2))
+
+
+def clip_scale(sq_norms, max_norm) -> float:
+    """Gradient clipping by the global L2 norm (paper, Section 4: clipping keeps the parameters, and with them the
+    histories, from changing too fast): every gradient is multiplied by min(1, max_norm / (||g|| + 1e-6)), where
+    ||g|| is the norm of all gradients taken together."""
+    total = float(np.sqrt(np.sum(np.asarray(sq_norms, dtype=np.float64))))
+    return min(1.0, max_norm / (total + 1e-6))
+
+
 def pna_aggregate(rowptr, col, x, delta, add=None) -> np.ndarray:
     """[n_rows, 9F]: scalers [1, s, 1/s] (x) aggregators [mean, min, max] over the neighbours, s = log(d+1)/delta."""
     rowptr, col = _i32(rowptr), _i32(col)

@@ -96,6 +96,36 @@ def test_sgd_step_closed_form():
     assert np.array_equal(wbn, to_np(want))
 
 
+def test_gradient_clipping_matches_the_library_routine_and_its_closed_forms():
+    """Clipping by the global norm (Section 4): the scale and the clipped update against torch's clip_grad_norm_
+    followed by a plain step, in float64; a norm below the bound changes nothing; above it the clipped gradients
+    have exactly the bound as their norm."""
+    shapes = [(13, 7), (7, 5), (5, 5)]
+    ws = [to_np(rng.normal_matrix(23, 620 + i, *sh)) for i, sh in enumerate(shapes)]
+    dws = [to_np(rng.normal_matrix(23, 630 + i, *sh)) * (3.0 + i) for i, sh in enumerate(shapes)]
+    total = float(np.sqrt(sum((f64(d) ** 2).sum() for d in dws)))
+    for max_norm in (0.5, total * 2.0):
+        params = [torch.from_numpy(f64(w)).requires_grad_() for w in ws]
+        for p, d in zip(params, dws):
+            p.grad = torch.from_numpy(f64(d)).clone()
+        torch.nn.utils.clip_grad_norm_(params, max_norm)
+        scale = ops.clip_scale([ops.sq_norm(d) for d in dws], max_norm)
+        for p, d in zip(params, dws):
+            assert np.abs(p.grad.numpy() - scale * f64(d)).max() <= 1e-12 * np.abs(f64(d)).max()
+        if max_norm > total:
+            assert scale == 1.0
+        else:
+            clipped = float(np.sqrt(sum(((scale * f64(d)) ** 2).sum() for d in dws)))
+            assert abs(clipped - max_norm) <= 1e-5 * max_norm
+        # the model-level update: every matrix moves by lr * scale * gradient
+        m = omodel.Model("gcn", [w.copy() for w in ws])
+        omodel.apply_sgd(m, {i: d for i, d in enumerate(dws)}, 0.1, 0.0, max_norm)
+        for w_new, w0, p in zip(m.weights, ws, params):
+            want = (f64(w0) - 0.1 * p.grad.numpy()).astype(np.float32)
+            assert np.abs(f64(w_new) - f64(want)).max() <= 2e-7 * max(1.0, np.abs(f64(want)).max())
+    assert abs(ops.sq_norm(np.array([3.0, 4.0], dtype=np.float32)) - 25.0) == 0.0
+
+
 @pytest.mark.parametrize("op", ["gcn", "gin", "gcnii"])
 def test_whole_graph_step_is_one_full_batch_gradient_descent_step(op):
     """With the whole graph as the batch there is no halo and no history is read: the step must be plain

@@ -315,6 +315,23 @@ GAS_API gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* d
                         void* stream);
 
 /*
+ * Gradient clipping by the global norm (Section 3 of the paper: clipping keeps
+ * the parameters, and so the histories, from changing too fast).
+ * gas_sq_norm: out[0] = sum of x[i]^2, i in [0, n) (fp64 accumulation in a
+ * fixed order, one fp32 result); called once per gradient of the step, the
+ * results side by side in one float array.
+ * gas_sgd_step_clipped: gas_sgd_step with every gradient multiplied by
+ *     c = min(1, max_norm / (sqrt(sum_k sq_norms[k]) + 1e-6)),
+ * sq_norms (device, float[n_norms]) holding the squared norms of ALL gradients
+ * of the step, so that the same c is applied to every weight matrix; c is
+ * formed on the device (nothing is read back).  max_norm > 0.
+ */
+GAS_API gas_status gas_sq_norm(const float* x, int64_t n, float* out, void* stream);
+GAS_API gas_status gas_sgd_step_clipped(void* W, int64_t n, gas_dtype dt, const float* dW, float lr,
+                                float weight_decay, const float* sq_norms, int32_t n_norms, float max_norm,
+                                void* stream);
+
+/*
  * PNA's neighbourhood aggregation (operator appendix): for every row v of the
  * batch subgraph, in one pass over the gathered rows,
  *     agg_0 = mean, agg_1 = min, agg_2 = max  over X[col[k], 0:F], k in row v,

@@ -246,7 +246,7 @@ def _all_grads(model: Model, grads):
 
 def apply_sgd(model: Model, grads, lr, weight_decay=0.0, max_norm=None):
     """One gradient-descent update of every weight matrix, in place; with max_norm the gradients are first
-    clipped by their global L2 norm (paper, Section 4)."""
+    clipped by their global L2 norm (paper, Section 3)."""
     pairs = _all_grads(model, grads)
     scale = 1.0 if max_norm is None else ops.clip_scale([ops.sq_norm(dw) for _, dw in pairs], max_norm)
     for w, dw in pairs:

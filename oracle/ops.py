@@ -219,7 +219,7 @@ def sq_norm(dw) -> float:
 
 
 def clip_scale(sq_norms, max_norm) -> float:
-    """Gradient clipping by the global L2 norm (paper, Section 4: clipping keeps the parameters, and with them the
+    """Gradient clipping by the global L2 norm (paper, Section 3: clipping keeps the parameters, and with them the
     histories, from changing too fast): every gradient is multiplied by min(1, max_norm / (||g|| + 1e-6)), where
     ||g|| is the norm of all gradients taken together."""
     total = float(np.sqrt(np.sum(np.asarray(sq_norms, dtype=np.float64))))

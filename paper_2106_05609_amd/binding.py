@@ -18,7 +18,7 @@ EXPORTS = [
     "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
-    "gas_softmax_xent", "gas_sgd_step", "gas_axpy", "gas_row_distance",
+    "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance",
     "gas_pna_aggregate", "gas_gat_aggregate",
 ]
 
@@ -343,6 +343,24 @@ def gas_sgd_step(w, dw, lr, weight_decay=0.0):
         raise ValueError("gas_sgd_step: w and dw must be contiguous and of equal size, dw float32")
     _check(lib().gas_sgd_step(_ptr(w), C.c_int64(w.numel()), C.c_int(_dt(w)), _ptr(dw, torch.float32),
                               C.c_float(lr), C.c_float(weight_decay), _stream()))
+
+
+def gas_sq_norm(x, out):
+    """out[0] = sum of the squares of x (float32, contiguous); out: a 1-element float32 view."""
+    if not x.is_contiguous() or x.dtype != torch.float32 or out.dtype != torch.float32 or out.numel() < 1:
+        raise ValueError("gas_sq_norm: x float32 contiguous, out float32")
+    _check(lib().gas_sq_norm(_ptr(x, torch.float32), C.c_int64(x.numel()), _ptr(out, torch.float32), _stream()))
+
+
+def gas_sgd_step_clipped(w, dw, lr, sq_norms, max_norm, weight_decay=0.0):
+    """gas_sgd_step with dw scaled by min(1, max_norm / (sqrt(sum(sq_norms)) + 1e-6)), formed on the device."""
+    if not w.is_contiguous() or not dw.is_contiguous() or dw.dtype != torch.float32 or dw.numel() != w.numel():
+        raise ValueError("gas_sgd_step_clipped: w and dw must be contiguous and of equal size, dw float32")
+    if sq_norms.dtype != torch.float32 or not sq_norms.is_contiguous():
+        raise ValueError("gas_sgd_step_clipped: sq_norms float32 contiguous")
+    _check(lib().gas_sgd_step_clipped(_ptr(w), C.c_int64(w.numel()), C.c_int(_dt(w)), _ptr(dw, torch.float32),
+                                      C.c_float(lr), C.c_float(weight_decay), _ptr(sq_norms, torch.float32),
+                                      C.c_int32(sq_norms.numel()), C.c_float(max_norm), _stream()))
 
 
 def gas_pna_aggregate(rowptr, col, x, out, delta, add=None):

@@ -135,18 +135,55 @@ __global__ __launch_bounds__(1024) void sum_fixed_kernel(const float* x, int64_t
     if (threadIdx.x == 0) out[0] = (float)part[0];
 }
 
+// sum of the squares of n floats, same order and precision as sum_fixed_kernel
+__global__ __launch_bounds__(1024) void sq_sum_fixed_kernel(const float* x, int64_t n, float* out) {
+    __shared__ double part[1024];
+    double s = 0.0;
+    int64_t i = threadIdx.x;
+    for (; i + 7 * 1024 < n; i += 8 * 1024) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = x[i + 1024 * j];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += (double)v[j] * (double)v[j];
+    }
+    for (; i < n; i += 1024) s += (double)x[i] * (double)x[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = (float)part[0];
+}
+
+// W <- W - lr * (c * dW + wd * W).  c = 1, or with sq_norms (the squared norms of ALL gradients of the step) the
+// clipping factor min(1, max_norm / (sqrt(sum) + 1e-6)), formed once per workgroup in index order.
 template <bool BF>
-__global__ __launch_bounds__(256) void sgd_kernel(char* W, const float* dW, int64_t n, float lr, float wd) {
+__global__ __launch_bounds__(256) void sgd_kernel(char* W, const float* dW, int64_t n, float lr, float wd,
+                                                  const float* sq_norms, int n_norms, float max_norm) {
+    __shared__ float c_shared;
+    float c = 1.f;
+    if (sq_norms) {
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int k = 0; k < n_norms; ++k) t += (double)sq_norms[k];
+            c_shared = fminf(1.f, (float)((double)max_norm / (sqrt(t) + 1e-6)));
+        }
+        __syncthreads();
+        c = c_shared;
+    }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
+    const float g = sq_norms ? c * dW[i] : dW[i];
     if constexpr (BF) {
         uint16_t* w = reinterpret_cast<uint16_t*>(W);
         const float v = __uint_as_float((uint32_t)w[i] << 16);
-        w[i] = (uint16_t)f32_to_bf16(v - lr * (dW[i] + wd * v));
+        w[i] = (uint16_t)f32_to_bf16(v - lr * (g + wd * v));
     } else {
         float* w = reinterpret_cast<float*>(W);
         const float v = w[i];
-        w[i] = v - lr * (dW[i] + wd * v);
+        w[i] = v - lr * (g + wd * v);
     }
 }
 
@@ -260,8 +297,17 @@ gas_status gas_softmax_xent(const void* A, int64_t lda, int64_t n_rows, int32_t 
     return GAS_OK;
 }
 
-gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* dW, float lr, float weight_decay,
-                        void* stream) {
+gas_status gas_sq_norm(const float* x, int64_t n, float* out, void* stream) {
+    GAS_REQUIRE(n >= 0, "gas_sq_norm: n=%lld", (long long)n);
+    GAS_REQUIRE(out, "gas_sq_norm: null output");
+    GAS_REQUIRE(x || n == 0, "gas_sq_norm: null pointer");
+    hipLaunchKernelGGL(sq_sum_fixed_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, x, n, out);
+    GAS_CHECK_HIP(hipGetLastError());
+    return GAS_OK;
+}
+
+static gas_status run_sgd(void* W, int64_t n, gas_dtype dt, const float* dW, float lr, float weight_decay,
+                          const float* sq_norms, int n_norms, float max_norm, void* stream) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_sgd_step: unknown dtype %d", (int)dt);
     GAS_REQUIRE(n >= 0, "gas_sgd_step: n=%lld", (long long)n);
     if (n == 0) return GAS_OK;
@@ -270,12 +316,25 @@ gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* dW, float
     GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_sgd_step: too many elements for one launch");
     if (dt == GAS_BF16)
         hipLaunchKernelGGL(sgd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                           static_cast<char*>(W), dW, n, lr, weight_decay);
+                           static_cast<char*>(W), dW, n, lr, weight_decay, sq_norms, n_norms, max_norm);
     else
         hipLaunchKernelGGL(sgd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                           static_cast<char*>(W), dW, n, lr, weight_decay);
+                           static_cast<char*>(W), dW, n, lr, weight_decay, sq_norms, n_norms, max_norm);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
+}
+
+gas_status gas_sgd_step(void* W, int64_t n, gas_dtype dt, const float* dW, float lr, float weight_decay,
+                        void* stream) {
+    return run_sgd(W, n, dt, dW, lr, weight_decay, nullptr, 0, 0.f, stream);
+}
+
+gas_status gas_sgd_step_clipped(void* W, int64_t n, gas_dtype dt, const float* dW, float lr, float weight_decay,
+                                const float* sq_norms, int32_t n_norms, float max_norm, void* stream) {
+    GAS_REQUIRE(n < 0 || n == 0 || (sq_norms && n_norms > 0 && max_norm > 0.f),
+                "gas_sgd_step_clipped: sq_norms=%p n_norms=%d max_norm=%g", (const void*)sq_norms, n_norms,
+                (double)max_norm);
+    return run_sgd(W, n, dt, dW, lr, weight_decay, sq_norms, n_norms, max_norm, stream);
 }
 
 gas_status gas_axpy(const void* X, int64_t ldx, const void* E, int64_t lde, int64_t n_rows, int32_t F, gas_dtype dt,

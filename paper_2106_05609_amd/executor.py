@@ -460,20 +460,31 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
     return y, grads, {"x0": x0, "h0": h0, "layers": saved}
 
 
-def apply_sgd(model: Model, grads, lr, weight_decay=0.0):
-    """One gradient-descent update of every weight matrix, in place (gas_sgd_step per matrix)."""
+def apply_sgd(model: Model, grads, lr, weight_decay=0.0, max_norm=None):
+    """One gradient-descent update of every weight matrix, in place (gas_sgd_step per matrix).  max_norm: the
+    gradients are first clipped by their global L2 norm (paper, Section 3): one gas_sq_norm per gradient, then
+    gas_sgd_step_clipped, which forms the common factor on the device."""
+    pairs = []
     for l in range(model.n_layers):
         if model.op == "gin":
-            for w, dw in zip(model.weights[l], grads[l]):
-                B.gas_sgd_step(w, dw, lr, weight_decay)
+            pairs += list(zip(model.weights[l], grads[l]))
         else:
-            B.gas_sgd_step(model.weights[l], grads[l], lr, weight_decay)
+            pairs.append((model.weights[l], grads[l]))
     if model.op == "gcnii":
-        B.gas_sgd_step(model.w_in, grads["w_in"], lr, weight_decay)
+        pairs.append((model.w_in, grads["w_in"]))
+    if max_norm is None:
+        for w, dw in pairs:
+            B.gas_sgd_step(w, dw, lr, weight_decay)
+        return
+    sq = torch.empty(len(pairs), dtype=torch.float32, device=pairs[0][0].device)
+    for k, (_, dw) in enumerate(pairs):
+        B.gas_sq_norm(dw, sq[k:k + 1])
+    for w, dw in pairs:
+        B.gas_sgd_step_clipped(w, dw, lr, sq, max_norm, weight_decay)
 
 
 def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr, weight_decay=0.0, n_labelled=None,
-               fused=False):
+               fused=False, max_norm=None):
     """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
     softmax cross-entropy averaged over the labelled in-batch nodes, backward with the histories held constant,
     gradient-descent update of the weights (in place).  labels_batch: int32 [nb], the labels of the in-batch
@@ -490,7 +501,7 @@ def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr
         B.gas_softmax_xent(y, labels_batch, g, loss_rows, loss_sum, scale=1.0 / max(1, n_labelled))
         return g
     y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad, fused=fused)
-    apply_sgd(model, grads, lr, weight_decay)
+    apply_sgd(model, grads, lr, weight_decay, max_norm)
     return loss_sum, n_labelled, y, grads
 
 

@@ -107,8 +107,8 @@ def test_every_entry_point_rejects_bad_arguments_without_launching():
 
 
 def test_a_zero_count_is_a_no_op():
-    """n = 0 (an empty batch, an empty halo) succeeds without touching any pointer; the weight gradient is the
-    exception, since an empty batch still has to produce a zero matrix."""
+    """n = 0 (an empty batch, an empty halo) succeeds without touching any pointer; the weight gradient and the
+    squared norm are the exceptions, since an empty sum still has to be written (a zero matrix, a zero)."""
     L = binding.lib()
     for name, params in _signatures().items():
         if any("gas_plan" in p for p in params):
@@ -118,4 +118,4 @@ def test_a_zero_count_is_a_no_op():
         fn = getattr(L, name)
         fn.restype = ctypes.c_int
         st = fn(*_args(params, None, 0, 0))
-        assert st == (-1 if name == "gas_linear_bwd_weight" else 0), name
+        assert st == (-1 if name in ("gas_linear_bwd_weight", "gas_sq_norm") else 0), name

@@ -119,6 +119,54 @@ def test_training_epochs_match_oracle(gas, op, dtype):
         assert max_rel_err(to_np(a), b) <= tol, max_rel_err(to_np(a), b)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gradient_clipping_parity(gas, dtype):
+    """Section 3's gradient clipping: squared norms, the common factor formed on the device, the clipped update."""
+    shapes = [(256, 256), (100, 36), (8, 8), (1, 5)]
+    ws = [rng.normal_matrix(15, 700 + i, *sh, dtype=dtype) for i, sh in enumerate(shapes)]
+    dws = [rng.normal_matrix(15, 710 + i, *sh) * (0.5 + i) for i, sh in enumerate(shapes)]
+    sq = torch.full((len(shapes),), float("nan"), device="cuda")
+    for k, d in enumerate(dws):
+        gas.gas_sq_norm(d.to("cuda"), sq[k:k + 1])
+    want_sq = np.array([oops.sq_norm(to_np(d)) for d in dws])
+    assert np.abs(to_np(sq) - want_sq).max() <= 1e-6 * want_sq.max()
+    total = float(np.sqrt(want_sq.sum()))
+    for max_norm in (0.25 * total, 4.0 * total):
+        scale = oops.clip_scale(want_sq, max_norm)
+        for w, d in zip(ws, dws):
+            wd = w.to("cuda").clone()
+            gas.gas_sgd_step_clipped(wd, d.to("cuda"), 0.1, sq, max_norm, weight_decay=0.01)
+            wo = to_np(w).copy()
+            oops.sgd_step(wo, np.ascontiguousarray((to_np(d).astype(np.float64) * scale).astype(np.float32)), 0.1, 0.01)
+            assert max_rel_err(to_np(wd), wo) <= TOL[dtype]
+            if max_norm > total:                     # no clipping: the bits of the plain step
+                wp = w.to("cuda").clone()
+                gas.gas_sgd_step(wp, d.to("cuda"), 0.1, weight_decay=0.01)
+                assert torch.equal(wp, wd)
+    with pytest.raises(gas.GasError):
+        gas.gas_sgd_step_clipped(ws[0].to("cuda"), dws[0].to("cuda"), 0.1, sq, 0.0)
+
+
+def test_training_step_with_clipping_matches_oracle(gas):
+    from paper_2106_05609_amd import executor
+    wl, labels, _ = learnable_workload("gcn", dtype=torch.float32)
+    g = wl.graph
+    om, gm, hs_cpu, hs_gpu = _both_models(wl)
+    deg_dev, x_dev, lab_dev = g.deg.to("cuda"), wl.x.to("cuda"), labels.to("cuda")
+    for b in wl.batches[:2]:
+        sg = batches.batch_subgraph(g, b, wl.cfg.self_loops)
+        bg = _gpu_batch(wl, sg, deg_dev)
+        lab_b = lab_dev[bg.n_id[:sg.nb].long()].contiguous()
+        loss_sum, n_lab, _, grads = executor.train_step(gm, bg, x_dev, hs_gpu, lab_b, 0.5, 0.001, max_norm=0.05)
+        norm = float(np.sqrt(sum(oops.sq_norm(to_np(grads[l])) for l in range(gm.n_layers))))
+        assert norm > 0.05                           # the bound is active in this case
+        want = omodel.gas_train_step(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
+                                     to_np(wl.x), hs_cpu, to_np(labels), 0.5, 0.001, max_norm=0.05)
+        assert abs(float(loss_sum) / n_lab - want) <= 1e-4 * max(1.0, want)
+    for a, b in zip(_weights(gm), _weights(om)):
+        assert max_rel_err(to_np(a), b) <= 2e-5
+
+
 @pytest.mark.parametrize("op,dtype", [("gcn", torch.float32), ("gin", torch.bfloat16)])
 def test_training_on_the_gpu_learns(gas, op, dtype):
     """What holds at any size: the loss falls and nodes the loss never saw are classified far above chance by

@@ -97,7 +97,7 @@ def test_sgd_step_closed_form():
 
 
 def test_gradient_clipping_matches_the_library_routine_and_its_closed_forms():
-    """Clipping by the global norm (Section 4): the scale and the clipped update against torch's clip_grad_norm_
+    """Clipping by the global norm (Section 3): the scale and the clipped update against torch's clip_grad_norm_
     followed by a plain step, in float64; a norm below the bound changes nothing; above it the clipped gradients
     have exactly the bound as their norm."""
     shapes = [(13, 7), (7, 5), (5, 5)]

@@ -424,3 +424,24 @@ void oracle_row_distance(const void* A, int64_t lda, const void* B, int64_t ldb,
     }
     if (dist_sum) *dist_sum = total;
 }
+
+/*
+ * Gradient of scale * sum_i ||A[i] - B[i]||_2 with respect to A (Eq. 3's distance; the gradient with respect to
+ * B is its negative): row i is scale * (A[i] - B[i]) / ||A[i] - B[i]||_2, zero where the rows are equal.
+ */
+void oracle_row_distance_bwd(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows, int32_t F, int dt,
+                             double scale, void* G, int64_t ldg) {
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double s = 0.0;
+        for (int32_t f = 0; f < F; ++f) {
+            double d = load_elem(A, i * lda + f, dt) - load_elem(B, i * ldb + f, dt);
+            s += d * d;
+        }
+        s = sqrt(s);
+        for (int32_t f = 0; f < F; ++f) {
+            double d = load_elem(A, i * lda + f, dt) - load_elem(B, i * ldb + f, dt);
+            store_elem(G, i * ldg + f, dt, s > 0.0 ? scale * d / s : 0.0);
+        }
+    }
+}
+

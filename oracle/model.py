@@ -448,3 +448,45 @@ def lipschitz_reg(model: Model, l, x, eps, rowptr, col, val, nb, h0=None):
     y2 = layer_forward(model, l, ops.axpy(x, eps, 1.0), h0, rowptr, col, val, nb)
     _, total = ops.row_distance(y, y2)
     return total / max(1, nb)
+
+
+def lipschitz_reg_grad(model: Model, l, x, eps, rowptr, col, val, nb, h0=None):
+    """Eq. (3) for layer l and its gradient with respect to that layer's weights, the layer's input held fixed:
+    returns (loss, dW) with loss as in lipschitz_reg and dW of the layer's weight matrix (a pair for GIN).  Both
+    evaluations of the layer are differentiated: with u_v = (y_v - y'_v) / (nb ||y_v - y'_v||) the output
+    gradients are u and -u, and each passes back through its own evaluation's activations."""
+    last = l == model.n_layers
+    x2 = ops.axpy(x, eps, 1.0)
+    grads = None
+    outs = []
+    for xx in (x, x2):
+        if model.op == "gcn":
+            z = ops.spmm(rowptr, col, val, xx)
+            outs.append((z, None, ops.linear(z, model.weights[l - 1], relu=not last)))
+        elif model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            z = ops.spmm(rowptr, col, None, xx, diag=1.0 + model.gin_eps)
+            h = ops.linear(z, w1, relu=True)
+            outs.append((z, h, ops.linear(h, w2, relu=not last)))
+        else:
+            b = model.betas[l - 1]
+            z = ops.spmm(rowptr, col, val, xx, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            outs.append((z, None, ops.linear(z, model.weights[l - 1], c_identity=1.0 - b, c_weight=b, relu=not last)))
+    (_, _, y), (_, _, y2) = outs
+    _, total = ops.row_distance(y, y2)
+    u = ops.row_distance_bwd(y, y2, 1.0 / max(1, nb))
+    for sign, (z, h, yy) in zip((1.0, -1.0), outs):
+        g = u if last else ops.relu_bwd(u, yy)
+        if model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            dw2 = ops.linear_bwd_weight(h, g, c_weight=sign)
+            gh = ops.linear_bwd_input(g, w2, mask=h)
+            part = (ops.linear_bwd_weight(z, gh, c_weight=sign), dw2)
+            grads = part if grads is None else tuple((a.astype(np.float64) + b).astype(np.float32)
+                                                     for a, b in zip(grads, part))
+        else:
+            c = model.betas[l - 1] if model.op == "gcnii" else 1.0
+            part = ops.linear_bwd_weight(z, g, c_weight=sign * c)
+            grads = part if grads is None else (grads.astype(np.float64) + part).astype(np.float32)
+    return total / max(1, nb), grads
+

@@ -275,3 +275,15 @@ def row_distance(a, b):
     lib().oracle_row_distance(_p(a), C.c_int64(lda), _p(b), C.c_int64(ldb), C.c_int64(a.shape[0]), C.c_int32(a.shape[1]),
                               C.c_int(_dt(a)), _p(dist), C.byref(total))
     return dist, float(total.value)
+
+
+def row_distance_bwd(a, b, scale=1.0) -> np.ndarray:
+    """Gradient of scale * sum_i ||a[i] - b[i]||_2 with respect to a (that with respect to b is its negative):
+    row i is scale * (a[i] - b[i]) / ||a[i] - b[i]||_2, and zero where the two rows are equal.  In a's type."""
+    a, lda = _rows(a)
+    b, ldb = _rows(b)
+    assert a.shape == b.shape and a.dtype == b.dtype
+    g = np.empty(a.shape, dtype=a.dtype)
+    lib().oracle_row_distance_bwd(_p(a), C.c_int64(lda), _p(b), C.c_int64(ldb), C.c_int64(a.shape[0]),
+                                  C.c_int32(a.shape[1]), C.c_int(_dt(a)), C.c_double(scale), _p(g), C.c_int64(a.shape[1]))
+    return g

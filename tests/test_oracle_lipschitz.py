@@ -56,3 +56,66 @@ def test_regulariser_of_a_linear_layer_has_a_closed_form():
                                 to_np(rng.ball_matrix(63, 1123, sg.nv, m.weights[0].shape[0], 0.1)), rp, cl, val, sg.nb)
     bound = 0.1 * np.linalg.norm(a, 2) * np.linalg.norm(f64(m.weights[0]), 2) * np.sqrt(sg.nv) / sg.nb * np.sqrt(sg.nb)
     assert 0.0 < got1 <= bound
+
+
+def test_row_distance_gradient_matches_autograd_and_its_closed_forms():
+    a = to_np(rng.normal_matrix(64, 1130, 30, 7))
+    b = to_np(rng.normal_matrix(64, 1131, 30, 7))
+    b[3] = a[3]                                              # equal rows: zero gradient
+    ta = torch.from_numpy(f64(a)).requires_grad_()
+    (0.25 * (ta - torch.from_numpy(f64(b))).norm(dim=1).sum()).backward()
+    g = ops.row_distance_bwd(a, b, 0.25)
+    want = ta.grad.numpy()
+    want[3] = 0.0
+    assert np.abs(f64(g) - want).max() <= 1e-7
+    assert not g[3].any()
+    # every non-zero row of the gradient has norm `scale`
+    n = np.linalg.norm(f64(g), axis=1)
+    assert np.abs(np.delete(n, 3) - 0.25).max() <= 1e-6
+    # 3-4-5
+    g = ops.row_distance_bwd(np.array([[3.0, 4.0]], np.float32), np.array([[0.0, 0.0]], np.float32), 1.0)
+    assert np.abs(g - np.array([[0.6, 0.8]], np.float32)).max() <= 1e-7
+
+
+import pytest
+
+
+@pytest.mark.parametrize("op,layer", [("gcn", 1), ("gcn", 2), ("gin", 1), ("gcnii", 2)])
+def test_regulariser_gradient_matches_autograd(op, layer):
+    """Eq. (3) differentiated with respect to the layer's weights (input held fixed) against float64 autograd of
+    the same expression written with a dense adjacency."""
+    wl = _workload(op, n=160, layers=2, f=8)
+    g, m = wl.graph, oracle_model(wl)
+    sg, n_id, rp, cl = _sub(wl, wl.batches[0])
+    val = ops.gcn_norm(rp, cl, n_id, to_np(g.deg)) if op != "gin" else None
+    f_in = (m.weights[layer - 1][0] if op == "gin" else m.weights[layer - 1]).shape[0]
+    x = to_np(rng.normal_matrix(65, 1140, sg.nv, f_in))
+    eps = to_np(rng.ball_matrix(65, 1141, sg.nv, f_in, 0.2))
+    h0 = to_np(torch.relu(rng.normal_matrix(65, 1142, sg.nv, f_in))) if op == "gcnii" else None
+    loss, dw = omodel.lipschitz_reg_grad(m, layer, x, eps, rp, cl, val, sg.nb, h0)
+    # (GIN: the gradient needs the hidden activation stored, the plain evaluation keeps it unrounded)
+    assert abs(loss - omodel.lipschitz_reg(m, layer, x, eps, rp, cl, val, sg.nb, h0)) <= 1e-6 * loss
+    # autograd replica
+    a = torch.from_numpy(omodel.dense_adjacency(n_id, rp, cl, val if val is not None else np.ones(len(cl), np.float32), sg.nb))
+    last = layer == m.n_layers
+    ws = [torch.from_numpy(f64(w)).requires_grad_() for w in (m.weights[layer - 1] if op == "gin" else [m.weights[layer - 1]])]
+
+    def f(xx):
+        xx = torch.from_numpy(f64(xx))
+        if op == "gcn":
+            y = (a @ xx) @ ws[0]
+        elif op == "gin":
+            z = a @ xx + (1.0 + m.gin_eps) * xx[:sg.nb]
+            y = torch.relu(z @ ws[0]) @ ws[1]
+        else:
+            b = m.betas[layer - 1]
+            z = (1.0 - m.alpha) * (a @ xx) + m.alpha * torch.from_numpy(f64(h0))[:sg.nb]
+            y = (1.0 - b) * z + b * (z @ ws[0])
+        return y if last else torch.relu(y)
+    l_t = (f(x) - f((f64(x) + f64(eps)).astype(np.float32))).norm(dim=1).mean()    # x + eps is stored in fp32
+    l_t.backward()
+    assert abs(loss - float(l_t.detach())) <= 1e-5 * float(l_t.detach())
+    got = dw if op == "gin" else (dw,)
+    for gg, w in zip(got, ws):
+        want = w.grad.numpy()
+        assert np.abs(f64(gg) - want).max() <= 2e-5 * np.abs(want).max(), np.abs(f64(gg) - want).max() / np.abs(want).max()

@@ -379,6 +379,15 @@ GAS_API gas_status gas_row_distance(const void* A, int64_t lda, const void* B, i
                             int32_t F, gas_dtype dt, float* dist, float* dist_sum, void* stream);
 
 /*
+ * Gradient of the distance of Eq. (3): G[i, :] = scale * (A[i, :] - B[i, :]) / ||A[i, :] - B[i, :]||_2, zero where
+ * the two rows are equal; this is d/dA of scale * sum_i ||A[i] - B[i]||_2, and d/dB is its negative.  A, B, G:
+ * [n_rows, F] of type dt.  With it the regulariser's gradient with respect to a layer's weights is two passes of
+ * the layer's backward calls (one per evaluation, output gradients G and -G).
+ */
+GAS_API gas_status gas_row_distance_bwd(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows,
+                                int32_t F, gas_dtype dt, float scale, void* G, int64_t ldg, void* stream);
+
+/*
  * Histories outside HBM (the paper keeps them in host memory and overlaps
  * the transfers with computation, Section 4): gas_pull and gas_push accept a
  * table in pinned host memory once its device-side address is known; the

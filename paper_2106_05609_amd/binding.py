@@ -18,7 +18,7 @@ EXPORTS = [
     "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
-    "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance",
+    "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
     "gas_pna_aggregate", "gas_gat_aggregate",
 ]
 
@@ -410,6 +410,17 @@ def gas_row_distance(a, b, dist, dist_sum=None):
         raise ValueError("gas_row_distance: shapes or dtypes do not match")
     _check(lib().gas_row_distance(ap, lda, bp, ldb, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
                                   _ptr(dist, torch.float32), _ptr(dist_sum, torch.float32), _stream()))
+
+
+def gas_row_distance_bwd(a, b, g, scale=1.0):
+    """g[i] = scale * (a[i] - b[i]) / ||a[i] - b[i]||_2 (zero where the rows are equal)."""
+    ap, lda = _mat(a)
+    bp, ldb = _mat(b)
+    gp, ldg = _mat(g)
+    if a.shape != b.shape or g.shape != a.shape or not (a.dtype == b.dtype == g.dtype):
+        raise ValueError("gas_row_distance_bwd: shapes or dtypes do not match")
+    _check(lib().gas_row_distance_bwd(ap, lda, bp, ldb, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
+                                      C.c_float(scale), gp, ldg, _stream()))
 
 
 class HostTable:

@@ -239,6 +239,28 @@ __global__ __launch_bounds__(256) void row_distance_kernel(const char* A, int64_
     if (lane == 0) dist[row] = sqrtf(s);
 }
 
+// G[m, :] = scale * (A[m, :] - B[m, :]) / || A[m, :] - B[m, :] ||_2 (zero where the rows are equal): one wavefront
+// per row, two passes over the row (the second one out of the cache)
+template <bool BF>
+__global__ __launch_bounds__(256) void row_distance_bwd_kernel(const char* A, int64_t lda, const char* B, int64_t ldb,
+                                                               int64_t M, int F, float scale, char* G, int64_t ldg) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    float s = 0.f;
+    for (int f = lane; f < F; f += 64) {
+        const float d = load_logit<BF>(A, row * lda + f) - load_logit<BF>(B, row * ldb + f);
+        s += d * d;
+    }
+    s = wave_sum(s);
+    const float c = s > 0.f ? scale / sqrtf(s) : 0.f;
+    for (int f = lane; f < F; f += 64) {
+        const float g = c * (load_logit<BF>(A, row * lda + f) - load_logit<BF>(B, row * ldb + f));
+        if constexpr (BF) reinterpret_cast<uint16_t*>(G)[row * ldg + f] = (uint16_t)f32_to_bf16(g);
+        else reinterpret_cast<float*>(G)[row * ldg + f] = g;
+    }
+}
+
 }  // namespace
 }  // namespace gas
 
@@ -384,6 +406,27 @@ gas_status gas_row_distance(const void* A, int64_t lda, const void* B, int64_t l
         hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, dist, n_rows, dist_sum);
         GAS_CHECK_HIP(hipGetLastError());
     }
+    return GAS_OK;
+}
+
+gas_status gas_row_distance_bwd(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows, int32_t F,
+                                gas_dtype dt, float scale, void* G, int64_t ldg, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_row_distance_bwd: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_row_distance_bwd: n_rows=%lld F=%d", (long long)n_rows, F);
+    if (n_rows == 0) return GAS_OK;
+    GAS_REQUIRE(A && B && G, "gas_row_distance_bwd: null pointer");
+    GAS_REQUIRE(lda >= F && ldb >= F && ldg >= F, "gas_row_distance_bwd: row stride smaller than the row");
+    const int64_t blocks = (n_rows + 3) / 4;
+    GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_row_distance_bwd: too many rows for one launch");
+    if (dt == GAS_BF16)
+        hipLaunchKernelGGL(row_distance_bwd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, scale,
+                           static_cast<char*>(G), ldg);
+    else
+        hipLaunchKernelGGL(row_distance_bwd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, scale,
+                           static_cast<char*>(G), ldg);
+    GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
 }
 

@@ -648,3 +648,72 @@ def lipschitz_reg(model: Model, l, bg: BatchGraph, x, eps, h0=None):
     total = torch.empty(1, dtype=torch.float32, device=dev)
     B.gas_row_distance(y, y2, dist, total)
     return total, bg.nb
+
+
+def lipschitz_reg_grad(model: Model, l, bg: BatchGraph, x, eps, h0=None):
+    """Eq. (3) for layer l and its gradient with respect to that layer's weights (the layer's input held fixed).
+    Both evaluations of the layer are differentiated: with u_v = (y_v - y'_v) / (nb ||y_v - y'_v||)
+    (gas_row_distance_bwd) the output gradients are u and -u; each goes back through its own evaluation's stored
+    activations (gas_relu_bwd, gas_linear_bwd_input for GIN's hidden layer, gas_linear_bwd_weight), and the two
+    weight gradients are added.  Returns (sum of distances as a 1-element device tensor, nb, dW) with dW float32
+    (a pair for GIN), scaled for the MEAN over the in-batch nodes."""
+    dev, dt = x.device, x.dtype
+    nb = bg.nb
+    last = l == model.n_layers
+    xp = torch.empty_like(x)
+    B.gas_axpy(x, eps, xp, 1.0)
+    outs = []
+    for xx in (x, xp):
+        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev)
+        h = None
+        if model.op == "gcn":
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, xx, z)
+            B.gas_linear(z, model.weights[l - 1], y, relu=not last)
+        elif model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, xx, z, diag=1.0 + model.gin_eps)
+            h = torch.empty((nb, w1.shape[1]), dtype=dt, device=dev)
+            B.gas_linear(z, w1, h, relu=True)            # stored: the backward pass reads the hidden activation
+            B.gas_linear(h, w2, y, relu=not last)
+        else:
+            beta = gcnii_beta(l)
+            B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, xx, z, s_agg=1.0 - model.alpha, r=h0, s_res=model.alpha)
+            B.gas_linear(z, model.weights[l - 1], y, c_identity=1.0 - beta, c_weight=beta, relu=not last)
+        outs.append((z, h, y))
+    y, y2 = outs[0][2], outs[1][2]
+    dist = torch.empty(nb, dtype=torch.float32, device=dev)
+    total = torch.empty(1, dtype=torch.float32, device=dev)
+    B.gas_row_distance(y, y2, dist, total)
+    u = torch.empty_like(y)
+    B.gas_row_distance_bwd(y, y2, u, 1.0 / max(1, nb))
+
+    def weight_grad(zz, gg, c):
+        dw = torch.empty((zz.shape[1], gg.shape[1]), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(1, B.gas_linear_bwd_weight_workspace(zz.shape[0], zz.shape[1], gg.shape[1])),
+                         dtype=torch.uint8, device=dev)
+        B.gas_linear_bwd_weight(zz, gg, dw, ws, c_weight=c)
+        return dw
+
+    def add(a, b):
+        B.gas_axpy(a, b, a, 1.0)                         # float32 matrices, in place
+        return a
+
+    grads = None
+    for sign, (z, h, yy) in zip((1.0, -1.0), outs):
+        g = u
+        if not last:
+            g = torch.empty_like(u)
+            B.gas_relu_bwd(u, yy, g)
+        if model.op == "gin":
+            w1, w2 = model.weights[l - 1]
+            dw2 = weight_grad(h, g, sign)
+            gh = torch.empty_like(h)
+            B.gas_linear_bwd_input(g, w2, gh, mask=h)
+            part = (weight_grad(z, gh, sign), dw2)
+            grads = part if grads is None else tuple(add(a, b) for a, b in zip(grads, part))
+        else:
+            c = gcnii_beta(l) if model.op == "gcnii" else 1.0
+            part = weight_grad(z, g, sign * c)
+            grads = part if grads is None else add(grads, part)
+    return total, nb, grads

@@ -248,3 +248,45 @@ def test_lipschitz_regulariser_matches_oracle(gas, op, dtype, layer):
     y = omodel.layer_forward(om, layer, to_np(x), None if h0 is None else to_np(h0), rp, cl, val, sg.nb)
     scale = np.abs(oops.to_f64(y)).max() * np.sqrt(y.shape[1])
     assert want > 0 and abs(got - want) <= TOL[dtype] * scale, (got, want, scale)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,F,ld", [(1000, 256, 256), (333, 100, 104), (50, 7, 7), (0, 8, 8)])
+def test_row_distance_gradient_parity(gas, dtype, M, F, ld):
+    a = rng.normal_matrix(16, 1300, M, ld, dtype=dtype)
+    b = rng.normal_matrix(16, 1301, M, ld, dtype=dtype)
+    if M > 5:
+        b[5] = a[5]                                          # equal rows: zero gradient, no division by zero
+    g = torch.full((M, ld), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_row_distance_bwd(a.to("cuda")[:, :F], b.to("cuda")[:, :F], g[:, :F], scale=0.125)
+    if M == 0:
+        return
+    want = oops.row_distance_bwd(to_np(a)[:, :F], to_np(b)[:, :F], 0.125)
+    assert max_rel_err(to_np(g[:, :F]), want) <= TOL[dtype]
+    assert not to_np(g[5, :F].float()).any()
+
+
+@pytest.mark.parametrize("op,layer", [("gcn", 1), ("gcn", 2), ("gin", 1), ("gcnii", 2)])
+def test_lipschitz_regulariser_gradient_matches_oracle(gas, op, layer):
+    """Eq. (3) differentiated with respect to the layer's weights: loss and gradient against the oracle (itself
+    pinned to float64 autograd).  fp32: the gradient divides by the distance of two rounded outputs, which in
+    bf16 storage is known to a few per cent only, so the bf16 bar is held call by call instead."""
+    from paper_2106_05609_amd import executor
+    wl, _, _ = learnable_workload(op, dtype=torch.float32)
+    g = wl.graph
+    om, gm = oracle_model(wl), _gpu_model(wl)
+    sg = batches.batch_subgraph(g, wl.batches[1], wl.cfg.self_loops)
+    bg = _gpu_batch(wl, sg, g.deg.to("cuda"))
+    n_id, rp, cl = to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col)
+    val = oops.gcn_norm(rp, cl, n_id, to_np(g.deg)) if op != "gin" else None
+    f_in = (om.weights[layer - 1][0] if op == "gin" else om.weights[layer - 1]).shape[0]
+    x = rng.normal_matrix(17, 1310, sg.nv, f_in)
+    eps = rng.ball_matrix(17, 1311, sg.nv, f_in, 0.5)
+    h0 = torch.relu(rng.normal_matrix(17, 1312, sg.nv, f_in)) if op == "gcnii" else None
+    total, nb, dw = executor.lipschitz_reg_grad(gm, layer, bg, x.to("cuda"), eps.to("cuda"),
+                                                None if h0 is None else h0.to("cuda"))
+    loss, want = omodel.lipschitz_reg_grad(om, layer, to_np(x), to_np(eps), rp, cl, val, sg.nb,
+                                           None if h0 is None else to_np(h0))
+    assert abs(float(total) / nb - loss) <= 1e-4 * loss
+    for a, b in zip(dw if op == "gin" else (dw,), want if op == "gin" else (want,)):
+        assert max_rel_err(to_np(a), b) <= 2e-4, max_rel_err(to_np(a), b)

@@ -255,17 +255,43 @@ def apply_sgd(model: Model, grads, lr, weight_decay=0.0, max_norm=None):
         ops.sgd_step(w, np.ascontiguousarray(dw), lr, weight_decay)
 
 
+def layer_input(model: Model, l, n_id, nb, x0, h0, saved, histories):
+    """The mini-batch tensor layer l read in a forward pass whose activations were kept: the features (GCNII: the
+    projected features) for l = 1, else layer l-1's output for the in-batch rows and the halo rows as they stand in
+    history table l-1 (this batch's pushes do not touch halo rows, so they are what the layer pulled)."""
+    if l == 1:
+        return h0 if model.op == "gcnii" else x0
+    y = saved[l - 2][2]
+    x = np.empty((n_id.size, y.shape[1]), dtype=y.dtype)
+    x[:nb] = y
+    x[nb:] = ops.pull(histories[l - 2], n_id[nb:])
+    return x
+
+
 def gas_train_step(model: Model, n_id, rowptr, col, nb, deg, x_feat, histories, labels, lr, weight_decay=0.0,
-                   max_norm=None):
+                   max_norm=None, reg_weight=0.0, reg_eps=None):
     """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
     softmax cross-entropy averaged over the labelled in-batch nodes (labels: one per node of the graph, < 0 =
     unlabelled), backward with the histories held constant, gradient-descent update.  The model's weights and
-    the histories are updated in place.  Returns the mean loss before the update."""
+    the histories are updated in place.  reg_weight: the local Lipschitz regulariser of Eq. (3) is added for every
+    layer, differentiated with respect to that layer's weights.  Returns the mean loss (without the regulariser)
+    before the update."""
     y, (val, x0, h0, saved) = gas_batch_forward_kept(model, n_id, rowptr, col, nb, deg, x_feat, histories)
     lab = np.ascontiguousarray(np.asarray(labels)[np.asarray(n_id[:nb], dtype=np.int64)], dtype=np.int32)
     n_lab = int((lab >= 0).sum())
     _, loss_sum, g = ops.softmax_xent(y, lab, scale=1.0 / max(1, n_lab))
     grads = gas_batch_backward(model, n_id, rowptr, col, nb, val, x0, h0, saved, g)
+    if reg_weight != 0.0:
+        # loss + reg_weight * sum over the layers of Eq. (3); reg_eps[l-1] holds layer l's drawn perturbations
+        n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+        for l in range(1, model.n_layers + 1):
+            x = layer_input(model, l, n_id, nb, x0, h0, saved, histories)
+            _, dw = lipschitz_reg_grad(model, l, x, reg_eps[l - 1], rowptr, col, val, nb, h0)
+            if model.op == "gin":
+                grads[l - 1] = tuple((a.astype(np.float64) + reg_weight * b).astype(np.float32)
+                                     for a, b in zip(grads[l - 1], dw))
+            else:
+                grads[l - 1] = (grads[l - 1].astype(np.float64) + reg_weight * dw).astype(np.float32)
     apply_sgd(model, grads, lr, weight_decay, max_norm)
     return loss_sum / max(1, n_lab)
 

@@ -119,3 +119,36 @@ def test_regulariser_gradient_matches_autograd(op, layer):
     for gg, w in zip(got, ws):
         want = w.grad.numpy()
         assert np.abs(f64(gg) - want).max() <= 2e-5 * np.abs(want).max(), np.abs(f64(gg) - want).max() / np.abs(want).max()
+
+
+def test_training_step_with_the_regulariser_adds_its_gradient():
+    """loss + lambda * sum_l Eq. (3): the step's weights differ from the plain step's by -lr * lambda * the
+    regulariser's gradient at the kept activations, layer by layer."""
+    wl = _workload("gcn", n=160, layers=2, f=8)
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, wl.batches[0])
+    labels = (np.arange(g.n) % 4).astype(np.int32)
+    widths = wl.cfg.widths                                   # [f + 3, f + 1, f - 2]
+    hist0 = [to_np(rng.normal_matrix(66, 1150, g.n, widths[1]))]
+    eps = [to_np(rng.ball_matrix(66, 1151 + l, sg.nv, widths[l], 0.2)) for l in range(2)]
+    lr, lam = 0.3, 0.7
+    def own_model():                                         # a model with its own copies of the weights
+        m = oracle_model(wl)
+        m.weights = [w.copy() for w in m.weights]
+        return m
+    plain, reg = own_model(), own_model()
+    h_a, h_b = [h.copy() for h in hist0], [h.copy() for h in hist0]
+    omodel.gas_train_step(plain, n_id, rp, cl, sg.nb, to_np(g.deg), to_np(wl.x), h_a, labels, lr)
+    omodel.gas_train_step(reg, n_id, rp, cl, sg.nb, to_np(g.deg), to_np(wl.x), h_b, labels, lr, reg_weight=lam, reg_eps=eps)
+    # the regulariser's gradients at the same (pre-update) activations
+    fresh = own_model()
+    h_c = [h.copy() for h in hist0]
+    _, (val, x0, h0, saved) = omodel.gas_batch_forward_kept(fresh, n_id, rp, cl, sg.nb, to_np(g.deg), to_np(wl.x), h_c)
+    for l in (1, 2):
+        x = omodel.layer_input(fresh, l, np.ascontiguousarray(n_id, dtype=np.int32), sg.nb, x0, h0, saved, h_c)
+        _, dw = omodel.lipschitz_reg_grad(fresh, l, x, eps[l - 1], rp, cl, val, sg.nb)
+        assert np.abs(dw).max() > 0
+        diff = f64(plain.weights[l - 1]) - f64(reg.weights[l - 1])
+        assert np.abs(diff - lr * lam * f64(dw)).max() <= 2e-6 * max(1.0, np.abs(lr * lam * f64(dw)).max())
+    for a, b in zip(h_a, h_b):
+        assert np.array_equal(a, b)                          # the forward pass (and so the pushes) is the same

@@ -483,13 +483,28 @@ def apply_sgd(model: Model, grads, lr, weight_decay=0.0, max_norm=None):
         B.gas_sgd_step_clipped(w, dw, lr, sq, max_norm, weight_decay)
 
 
+def layer_input(model: Model, l, bg: BatchGraph, kept, histories):
+    """The mini-batch tensor [nv, F] layer l read in a pass whose activations were kept (train_batch, not fused):
+    the features (GCNII: the projected features) for l = 1, else layer l-1's output for the in-batch rows and the
+    halo rows as they stand in history table l-1 (this batch's pushes do not touch them)."""
+    if l == 1:
+        return kept["h0"] if model.op == "gcnii" else kept["x0"]
+    y = kept["layers"][l - 2][2]
+    x = torch.empty((bg.nv, y.shape[1]), dtype=y.dtype, device=y.device)
+    x[:bg.nb].copy_(y)
+    if bg.nv > bg.nb:
+        B.gas_pull(histories[l - 2], bg.n_id[bg.nb:], x[bg.nb:])
+    return x
+
+
 def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr, weight_decay=0.0, n_labelled=None,
-               fused=False, max_norm=None):
+               fused=False, max_norm=None, reg_weight=0.0, reg_eps=None):
     """One optimisation step of Algorithm 1's loop body on one mini-batch: forward with Push/Pull per layer,
     softmax cross-entropy averaged over the labelled in-batch nodes, backward with the histories held constant,
     gradient-descent update of the weights (in place).  labels_batch: int32 [nb], the labels of the in-batch
     nodes in batch order, < 0 = unlabelled; n_labelled: their count if the caller knows it (saves a device
-    read-back).  Returns (loss_sum as a 1-element float32 device tensor, n_labelled, logits, grads)."""
+    read-back).  reg_weight: the local Lipschitz regulariser of Eq. (3) is added for every layer (lipschitz_reg_grad
+    on the layer's kept input).  Returns (loss_sum as a 1-element float32 device tensor, n_labelled, logits, grads)."""
     if n_labelled is None:
         n_labelled = int((labels_batch >= 0).sum().item())
     dev = x_feat.device
@@ -500,7 +515,17 @@ def train_step(model: Model, bg: BatchGraph, x_feat, histories, labels_batch, lr
         g = torch.empty_like(y)
         B.gas_softmax_xent(y, labels_batch, g, loss_rows, loss_sum, scale=1.0 / max(1, n_labelled))
         return g
-    y, grads, _ = train_batch(model, bg, x_feat, histories, loss_grad, fused=fused)
+    y, grads, kept = train_batch(model, bg, x_feat, histories, loss_grad, fused=fused)
+    if reg_weight != 0.0:
+        # loss + reg_weight * sum over the layers of Eq. (3), each differentiated with respect to its layer's
+        # weights; reg_eps[l-1]: layer l's drawn perturbations [nv, F_in]
+        if fused:
+            raise ValueError("the regulariser perturbs the whole mini-batch tensor of every layer: fused=False")
+        for l in range(1, model.n_layers + 1):
+            _, _, dw = lipschitz_reg_grad(model, l, bg, layer_input(model, l, bg, kept, histories), reg_eps[l - 1],
+                                          kept["h0"])
+            for a, b in zip(grads[l - 1] if model.op == "gin" else (grads[l - 1],), dw if model.op == "gin" else (dw,)):
+                B.gas_axpy(a, b, a, reg_weight)
     apply_sgd(model, grads, lr, weight_decay, max_norm)
     return loss_sum, n_labelled, y, grads
 

@@ -290,3 +290,30 @@ def test_lipschitz_regulariser_gradient_matches_oracle(gas, op, layer):
     assert abs(float(total) / nb - loss) <= 1e-4 * loss
     for a, b in zip(dw if op == "gin" else (dw,), want if op == "gin" else (want,)):
         assert max_rel_err(to_np(a), b) <= 2e-4, max_rel_err(to_np(a), b)
+
+
+@pytest.mark.parametrize("op", ["gcn", "gin"])
+def test_training_step_with_the_regulariser_matches_oracle(gas, op):
+    """loss + lambda * sum_l Eq. (3) in the training step: two steps on two batches, weights and histories."""
+    from paper_2106_05609_amd import executor
+    wl, labels, _ = learnable_workload(op, dtype=torch.float32)
+    g = wl.graph
+    om, gm, hs_cpu, hs_gpu = _both_models(wl)
+    deg_dev, x_dev, lab_dev = g.deg.to("cuda"), wl.x.to("cuda"), labels.to("cuda")
+    lr, lam = (0.05 if op == "gin" else 0.5), 0.3
+    for k, b in enumerate(wl.batches[:2]):
+        sg = batches.batch_subgraph(g, b, wl.cfg.self_loops)
+        bg = _gpu_batch(wl, sg, deg_dev)
+        lab_b = lab_dev[bg.n_id[:sg.nb].long()].contiguous()
+        widths = [(w[0] if op == "gin" else w).shape[0] for w in om.weights]
+        eps = [rng.ball_matrix(18, 1400 + 10 * k + l, sg.nv, f, 0.3) for l, f in enumerate(widths)]
+        loss_sum, n_lab, _, _ = executor.train_step(gm, bg, x_dev, hs_gpu, lab_b, lr, reg_weight=lam,
+                                                    reg_eps=[e.to("cuda") for e in eps])
+        want = omodel.gas_train_step(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
+                                     to_np(wl.x), hs_cpu, to_np(labels), lr, reg_weight=lam,
+                                     reg_eps=[to_np(e) for e in eps])
+        assert abs(float(loss_sum) / n_lab - want) <= 1e-4 * max(1.0, want)
+    for a, b in zip(_weights(gm), _weights(om)):
+        assert max_rel_err(to_np(a), b) <= 1e-4, max_rel_err(to_np(a), b)
+    for a, b in zip(hs_gpu, hs_cpu):
+        assert max_rel_err(to_np(a), b) <= 2e-5

@@ -229,6 +229,19 @@ GAS_API gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int
                          const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
 
 /*
+ * The GIN update for a training pass: gas_mlp2_push (idx == NULL and hist == NULL: no Push) which also stores the
+ * hidden activation relu(Z W1 + b1) to H_out [n_rows, F_hid] (type dt, row stride ldh_out): the backward pass reads
+ * it (weight gradient of W2, ReLU mask).  Where the fused kernel applies (bf16, widths up to 256, 16-byte aligned
+ * rows, at least 4096 rows) the hidden tile is stored from LDS on its way; elsewhere the call runs as two stored
+ * linears.  H_out must not alias Z or Y.
+ */
+GAS_API gas_status gas_mlp2_keep(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in,
+                         const void* W1, int32_t F_hid, const void* b1,
+                         const void* W2, int32_t F_out, const void* b2, gas_dtype dt,
+                         int relu_out, void* Y, int64_t ldy, void* H_out, int64_t ldh_out,
+                         const int32_t* idx, void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+
+/*
  * One whole layer in one launch, for narrow layers (Algorithm 1's loop body
  * for the in-batch nodes: aggregate over G_b with both sources of Eq. 2,
  * transform, Push):

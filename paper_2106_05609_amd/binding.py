@@ -16,7 +16,7 @@ EXPORTS = [
     "gas_last_error", "gas_version", "gas_validate_indices",
     "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
     "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
-    "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_spmm_linear",
+    "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
     "gas_pna_aggregate", "gas_gat_aggregate",
@@ -275,6 +275,23 @@ def gas_linear_push(z, w, y, idx, hist, bias=None, c_identity=0.0, c_weight=1.0,
                                  _ptr(bias), C.c_int(_dt(z)), C.c_float(c_identity), C.c_float(c_weight),
                                  C.c_int(int(relu)), yp, ldy, _ptr(idx, torch.int32), hp, C.c_int64(hist.shape[0]), ldh,
                                  _stream()))
+
+
+def gas_mlp2_keep(z, w1, w2, y, h_out, idx=None, hist=None, b1=None, b2=None, relu_out=False):
+    """gas_mlp2 that also stores the hidden activation relu(z w1 + b1) to h_out, and (idx, hist given) pushes y."""
+    zp, ldz = _mat(z)
+    yp, ldy = _mat(y)
+    hp, ldh = _mat(h_out)
+    tp, ldt = (C.c_void_p(0), C.c_int64(0)) if hist is None else _mat(hist)
+    if not (w1.dtype == w2.dtype == z.dtype == y.dtype == h_out.dtype) or w1.shape[0] != z.shape[1] or \
+            w2.shape[0] != w1.shape[1] or y.shape != (z.shape[0], w2.shape[1]) or \
+            h_out.shape != (z.shape[0], w1.shape[1]) or (hist is None) != (idx is None) or \
+            (hist is not None and (hist.dtype != z.dtype or hist.shape[1] != w2.shape[1] or idx.numel() != z.shape[0])):
+        raise ValueError("gas_mlp2_keep: shapes or dtypes do not match")
+    _check(lib().gas_mlp2_keep(zp, ldz, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]), _ptr(w1), C.c_int32(w1.shape[1]),
+                               _ptr(b1), _ptr(w2), C.c_int32(w2.shape[1]), _ptr(b2), C.c_int(_dt(z)),
+                               C.c_int(int(relu_out)), yp, ldy, hp, ldh, _ptr(idx, torch.int32), tp,
+                               C.c_int64(0 if hist is None else hist.shape[0]), ldt, _stream()))
 
 
 def spmm_linear_supported(x, f_out) -> bool:

@@ -581,6 +581,7 @@ struct WsArgs {
     const uint16_t* mask; int64_t ldmask;  // optional [M, N]: outputs where mask <= 0 are set to zero
     const int32_t* push_idx;               // optional: output row m is also stored to push_hist[push_idx[m], :]
     uint16_t* push_hist; int64_t ld_push;
+    uint16_t* H_out; int64_t ldh_out;      // optional (fused MLP): the hidden activation is stored as well
 };
 
 constexpr int kWsRows = 64;
@@ -989,6 +990,23 @@ __global__ __launch_bounds__(512) void ws_mlp_bf16_kernel(WsArgs a) {
                         if (a.push_idx)
                             __builtin_nontemporal_store(
                                 o, reinterpret_cast<u32x4*>(a.push_hist + (int64_t)prow[i] * a.ld_push + 8 * v));
+                    }
+                }
+            }
+            if (a.H_out) {
+                // a training pass reads the hidden activation again: tile p-1 of it is complete and not written
+                // before the next phase, so it leaves from its LDS buffer the same way
+                const int hvpr = EXACT ? 32 : a.H >> 3;
+                const uint16_t* hs = Hs + ((p - 1) & 1) * kWsRows * LDH;
+                uint16_t* hbase = a.H_out + (int64_t)tq * kWsRows * a.ldh_out;
+                if (v < hvpr) {
+#pragma unroll
+                    for (int i = 0; i < NPI; ++i) {
+                        const int row = (tl >> 5) + 16 * i;
+                        if (out_full || (int64_t)tq * kWsRows + row < a.M)
+                            __builtin_nontemporal_store(
+                                *reinterpret_cast<const u32x4*>(hs + row * LDH + 8 * v),
+                                reinterpret_cast<u32x4*>(hbase + ((uint32_t)row * (uint32_t)a.ldh_out + 8u * v)));
                     }
                 }
             }
@@ -1622,8 +1640,11 @@ gas_status gas_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy
 
 static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
                            const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
-                           void* Y, int64_t ldy, void* stream, const PushTarget& push) {
+                           void* Y, int64_t ldy, void* stream, const PushTarget& push, void* H_out = nullptr,
+                           int64_t ldh_out = 0) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_mlp2: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(!H_out || ldh_out >= F_hid, "gas_mlp2_keep: row stride of the hidden activation smaller than F_hid");
+    GAS_REQUIRE(!H_out || (H_out != Y && H_out != Z), "gas_mlp2_keep: the hidden activation aliases Z or Y");
     if (push.idx) {
         GAS_REQUIRE(push.hist && push.ld_hist >= F_out && push.n_hist_rows > 0, "gas_mlp2_push: bad history table");
         GAS_REQUIRE(push.hist != Y, "gas_mlp2_push: the history table aliases the output");
@@ -1646,6 +1667,17 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
     const int q = dt == GAS_F32 ? 4 : 8;    // elements per 16 bytes
     const bool vec = aligned16(Z) && aligned16(W1) && aligned16(W2) && ldz % q == 0 && F_in % q == 0 &&
                      F_hid % q == 0 && F_out % q == 0;
+    const bool ws_path = dt == GAS_BF16 && vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 &&
+                         n_rows >= 4096 && ldz < (1 << 24) && ldy < (1 << 24) && H_out && aligned16(H_out) &&
+                         ldh_out % 8 == 0 && ldh_out < (1 << 24);
+    if (H_out && !ws_path) {
+        // only the weights-stationary kernel stores the hidden activation on its way: elsewhere two stored linears
+        gas_status st = run_linear("gas_mlp2_keep", Z, ldz, n_rows, F_in, W1, 0, F_hid, b1, dt, 0.f, 1.f, 1, nullptr, 0,
+                                   H_out, ldh_out, s);
+        if (st != GAS_OK) return st;
+        return run_linear("gas_mlp2_keep", H_out, ldh_out, n_rows, F_hid, W2, 0, F_out, b2, dt, 0.f, 1.f, relu_out,
+                          nullptr, 0, Y, ldy, s, push);
+    }
     const int gn = (F_out + 255) / 256;
     if (n_rows > 0x7FFFFFFFLL || gn > 65535) return fail(GAS_ERR_ARG, "gas_mlp2: problem too large for one launch");
     if (dt == GAS_F32) {
@@ -1660,7 +1692,8 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
         if (vec) hipLaunchKernelGGL(mlp2_f32_kernel<true>, grid, dim3(256), smem, s, a);
         else hipLaunchKernelGGL(mlp2_f32_kernel<false>, grid, dim3(256), smem, s, a);
     } else if (vec && F_in <= 256 && F_out <= 256 && aligned16(Y) && ldy % 8 == 0 && n_rows >= 4096 &&
-               ldz < (1 << 24) && ldy < (1 << 24)) {      // offsets inside a 64-row tile are 32-bit
+               ldz < (1 << 24) && ldy < (1 << 24) &&      // offsets inside a 64-row tile are 32-bit
+               (!H_out || (aligned16(H_out) && ldh_out % 8 == 0 && ldh_out < (1 << 24)))) {
         // the kernel scatters the rows itself if the history rows take 16-byte stores; else the row copy follows
         const bool scatter = push.idx && aligned16(push.hist) && push.ld_hist % 8 == 0;
         WsArgs w{};
@@ -1672,6 +1705,7 @@ static gas_status run_mlp2(const void* Z, int64_t ldz, int64_t n_rows, int32_t F
         w.K = F_in; w.H = F_hid; w.N = F_out;
         w.c_id = 0.f; w.c_w = 1.f; w.relu1 = 1; w.relu_out = relu_out;
         if (scatter) { w.push_idx = push.idx; w.push_hist = static_cast<uint16_t*>(push.hist); w.ld_push = push.ld_hist; }
+        w.H_out = static_cast<uint16_t*>(H_out); w.ldh_out = ldh_out;
         const gas_status st = F_in <= 128 ? launch_ws_mlp<8, 16>(w, s) : launch_ws_mlp<16, 16>(w, s);
         return (st != GAS_OK || scatter) ? st : push_after(push, Y, ldy, n_rows, F_out, dt, s);
     } else if (vec) {
@@ -1702,6 +1736,17 @@ gas_status gas_mlp2_push(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_i
     PushTarget p;
     p.idx = idx; p.hist = hist; p.n_hist_rows = n_hist_rows; p.ld_hist = ld_hist;
     return run_mlp2(Z, ldz, n_rows, F_in, W1, F_hid, b1, W2, F_out, b2, dt, relu_out, Y, ldy, stream, p);
+}
+
+gas_status gas_mlp2_keep(const void* Z, int64_t ldz, int64_t n_rows, int32_t F_in, const void* W1, int32_t F_hid,
+                         const void* b1, const void* W2, int32_t F_out, const void* b2, gas_dtype dt, int relu_out,
+                         void* Y, int64_t ldy, void* H_out, int64_t ldh_out, const int32_t* idx, void* hist,
+                         int64_t n_hist_rows, int64_t ld_hist, void* stream) {
+    GAS_REQUIRE(H_out || n_rows == 0, "gas_mlp2_keep: null hidden activation");
+    GAS_REQUIRE((idx == nullptr) == (hist == nullptr), "gas_mlp2_keep: idx and hist go together");
+    PushTarget p;
+    p.idx = idx; p.hist = hist; p.n_hist_rows = n_hist_rows; p.ld_hist = ld_hist;
+    return run_mlp2(Z, ldz, n_rows, F_in, W1, F_hid, b1, W2, F_out, b2, dt, relu_out, Y, ldy, stream, p, H_out, ldh_out);
 }
 
 }  // extern "C"

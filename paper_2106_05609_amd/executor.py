@@ -324,8 +324,8 @@ def forward_batch_host(model: Model, bg: BatchGraph, x_feat, histories, pipe: Ho
 def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_push=True, fused=False):
     """Forward with the activations kept, then the backward pass through all layers (no optimiser step).
     Historical embeddings are constants, so gradients travel along in-batch rows only; GCNII's input projection
-    is computed in-graph for the halo rows too and its gradient includes them.  GIN's MLP runs as two stored
-    linears here (the hidden activation is needed again by the backward pass).  Returns (Y_L, grads, kept) with
+    is computed in-graph for the halo rows too and its gradient includes them.  GIN's MLP stores its hidden
+    activation here (gas_mlp2_keep: the backward pass reads it again).  Returns (Y_L, grads, kept) with
     grads[l] = dW_l (float32; a pair for GIN), grads["w_in"] for GCNII, and kept = the stored activations the
     backward pass read (x0, h0, per layer (Z, hidden, Y)).  grad_out is dLoss/dY_L [nb, F_L], or a function
     that returns it given Y_L.  fused: the forward aggregations read their halo rows from the feature table / the
@@ -352,7 +352,7 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         z = torch.empty((nb, f_in), dtype=dt, device=dev)
         x_next = torch.empty((nb if (last or fused) else nv, f_out), dtype=dt, device=dev)
         y = x_next[:nb]
-        h = None
+        h, pushed = None, False
         table = (x_feat if l == 1 else histories[l - 2]) if fused else None
         if fused and model.op == "gcnii" and l == 1:
             table = None                                  # layer 1 gathers the projected features from h0 itself
@@ -385,8 +385,11 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
                 B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, x, z, diag=1.0 + model.gin_eps)
             w1, w2 = model.weights[l - 1]
             h = torch.empty((nb, w1.shape[1]), dtype=dt, device=dev)
-            B.gas_linear(z, w1, h, relu=True)
-            B.gas_linear(h, w2, y, relu=not last)
+            # both products in one call, the hidden activation stored for the backward pass, the Push in its epilogue
+            push = not last and do_push
+            B.gas_mlp2_keep(z, w1, w2, y, h, idx=bg.n_id[:nb] if push else None,
+                            hist=histories[l - 1] if push else None, relu_out=not last)
+            pushed = push
         else:
             if table is not None:
                 B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, x, table, z, s_agg=1.0 - model.alpha, r=h0,
@@ -398,7 +401,7 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
         saved.append((z, h, y))
         if last:
             break
-        if do_push:
+        if do_push and not pushed:
             B.gas_push(y, bg.n_id[:nb], histories[l - 1])
         if nv > nb and not fused:
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])

@@ -290,6 +290,44 @@ def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     assert max_rel_err(to_np(z), want) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,K,H,N,push", [(5000, 256, 256, 256, True), (4100, 128, 256, 64, False), (4097, 256, 200, 256, True),
+                                          (300, 64, 96, 40, True), (0, 32, 32, 32, False)])
+def test_mlp_that_keeps_its_hidden_activation(gas, dtype, M, K, H, N, push):
+    """gas_mlp2_keep: the GIN update of a training pass, hidden activation stored (from LDS where the fused kernel
+    runs, by two stored linears elsewhere), output pushed; against the oracle's two linears and its push."""
+    n_hist = 2 * M + 7
+    z = rng.normal_matrix(11, 400, M, K, dtype=dtype)
+    w1 = rng.glorot_uniform(11, 401, K, H, dtype=dtype)
+    w2 = rng.glorot_uniform(11, 402, H, N, dtype=dtype)
+    b1 = rng.normal(11, 403, 0, H, dtype=dtype)
+    idx = rng.permutation(11, 404, n_hist)[:M].to(torch.int32)
+    table0 = rng.normal_matrix(11, 405, n_hist, N, dtype=dtype)
+    y = torch.full((M, N), float("nan"), dtype=dtype, device="cuda")
+    h = torch.full((M, H), float("nan"), dtype=dtype, device="cuda")
+    table = dev(table0).clone()
+    gas.gas_mlp2_keep(dev(z), dev(w1), dev(w2), y, h, idx=dev(idx) if push else None, hist=table if push else None,
+                      b1=dev(b1), relu_out=True)
+    if M == 0:
+        return
+    dt = oops.F32 if dtype == torch.float32 else oops.BF16
+    want_h = oops.linear(to_np(z), to_np(w1), bias=to_np(b1), relu=True, out_dt=dt)
+    assert max_rel_err(to_np(h), want_h) <= TOL[dtype]
+    # the second product on the hidden activation the library stored (a unit within rounding of zero may fall on
+    # either side of the ReLU in two correct passes)
+    want_y = oops.linear(to_np(h), to_np(w2), relu=True, out_dt=dt)
+    assert max_rel_err(to_np(y), want_y) <= TOL[dtype]
+    want_table = to_np(table0).copy()
+    if push:
+        oops.push(to_np(y), to_np(idx), want_table)
+    assert np.array_equal(to_np(table).view(np.uint8), want_table.view(np.uint8))
+    # and the plain fused call gives the same output bits where the same kernel runs
+    if dtype == torch.bfloat16 and M >= 4096:
+        y2 = torch.empty_like(y)
+        gas.gas_mlp2(dev(z), dev(w1), dev(w2), y2, b1=dev(b1), relu_out=True)
+        assert torch.equal(y, y2)
+
+
 @pytest.mark.parametrize("name", ["sbm", "powerlaw"])
 def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name, monkeypatch):
     """Handing the light rows to the XCDs in contiguous ranges changes which workgroup does a row, not the sum."""

@@ -614,6 +614,20 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     GAS_REQUIRE(ldx >= F && ldz >= F && (!R || ldr >= F) && (!H || ldh >= F), "%s: row stride smaller than F", who);
     GAS_REQUIRE(Z != X && Z != R, "%s: output aliases an input", who);
     const int xb = elem_bytes(dt_x), zb = elem_bytes(dt_z);
+    // Rows longer than 4096 bytes (a wide input layer) are aggregated panel by panel: the sum is separate for
+    // every feature column, so a panel of columns is an aggregation of its own over the same pattern.
+    const int64_t panel = 4096 / xb;
+    if ((int64_t)F > panel) {
+        for (int64_t f0 = 0; f0 < F; f0 += panel) {
+            const int32_t fw = (int32_t)std::min<int64_t>(panel, F - f0);
+            const gas_status st = run_spmm(who, plan, ptr, ind, val, diag, n_diag, static_cast<const char*>(X) + f0 * xb,
+                                           ldx, H ? static_cast<const char*>(H) + f0 * xb : nullptr, ldh, dt_x, fw, s_agg,
+                                           R ? static_cast<const char*>(R) + f0 * xb : nullptr, ldr, s_res,
+                                           static_cast<char*>(Z) + f0 * zb, ldz, dt_z, s);
+            if (st != GAS_OK) return st;
+        }
+        return GAS_OK;
+    }
     SpmmArgs a;
     a.ptr = ptr; a.ind = ind; a.val = val;
     a.X = static_cast<const char*>(X); a.x_stride = ldx * xb;

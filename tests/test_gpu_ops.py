@@ -121,14 +121,14 @@ def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld
     return err
 
 
-@pytest.mark.parametrize("F", [64, 100, 128, 256, 512, 12, 1024, 7])
+@pytest.mark.parametrize("F", [64, 100, 128, 256, 512, 12, 1024, 7, 1436, 2050])      # the last two: rows above 4096 bytes
 def test_spmm_fp32_gcn(gas, graphs_small, F):
     for name in ("sbm", "powerlaw"):
         cfg, g, sg = graphs_small[name]
         assert _spmm_case(gas, g, sg, F, torch.float32, True) <= TOL[torch.float32], (name, F)
 
 
-@pytest.mark.parametrize("F", [128, 256, 64, 8, 520, 9])
+@pytest.mark.parametrize("F", [128, 256, 64, 8, 520, 9, 2056])
 def test_spmm_bf16_gin(gas, graphs_small, F):
     cfg, g, sg = graphs_small["gin"]
     assert _spmm_case(gas, g, sg, F, torch.bfloat16, False, diag=1.0) <= TOL[torch.bfloat16]

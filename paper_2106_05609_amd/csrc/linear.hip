@@ -1492,6 +1492,10 @@ static gas_status run_linear(const char* who, const void* Z, int64_t ldz, int64_
     if (dt == GAS_F32) {
         const bool vec = aligned16(Z) && aligned16(W) && ldz % 4 == 0 && F_in % 4 == 0 && F_out % 4 == 0;
         a.push_idx = push.idx; a.push_hist = static_cast<char*>(push.hist); a.ld_push = push.ld_hist;
+        // a small batch in 128-row tiles would leave most compute units without a workgroup: 64 x 64 tiles then
+        // (the same products in the same order, so the same bits)
+        const int64_t tiles128 = ((n_rows + 127) / 128) * ((F_out + (F_out <= 64 ? 63 : 127)) / (F_out <= 64 ? 64 : 128));
+        if (tiles128 < 512) return launch_f32<64, 64>(a, vec, s);
         return F_out <= 64 ? launch_f32<128, 64>(a, vec, s) : launch_f32<128, 128>(a, vec, s);
     }
     const bool vec = aligned16(Z) && aligned16(W) && ldz % 8 == 0 && F_in % 8 == 0 && F_out % 8 == 0;

@@ -173,7 +173,8 @@ def test_spmm_empty_rows_and_empty_matrix(gas):
         gas.gas_plan_create(ptr, 4, 4)                   # nnz does not match ptr
 
 
-@pytest.mark.parametrize("dtype,F", [(torch.float32, 256), (torch.float32, 100), (torch.bfloat16, 256), (torch.float32, 6)])
+@pytest.mark.parametrize("dtype,F", [(torch.float32, 256), (torch.float32, 100), (torch.bfloat16, 256), (torch.float32, 6),
+                                     (torch.float32, 1028)])
 def test_spmm_t_parity(gas, graphs_small, dtype, F):
     for name in ("sbm", "powerlaw"):
         cfg, g, sg = graphs_small[name]
@@ -258,7 +259,8 @@ def test_mlp2_parity(gas, dtype, M, K, H, N):
 
 
 @pytest.mark.parametrize("name,dtype,F", [("powerlaw", torch.float32, 256), ("sbm", torch.float32, 100),
-                                           ("gin", torch.bfloat16, 256), ("powerlaw", torch.float32, 12)])
+                                           ("gin", torch.bfloat16, 256), ("powerlaw", torch.float32, 12),
+                                           ("sbm", torch.float32, 1100), ("gin", torch.bfloat16, 2056)])   # rows above 4096 B
 def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     cfg, g, sg = graphs_small[name]
     use_val = name != "gin"

@@ -26,6 +26,8 @@
 #endif
 
 #include <algorithm>
+#include <mutex>
+#include <string.h>
 #include <cstdlib>
 #include <vector>
 
@@ -731,8 +733,25 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
     const bool windowed = ind && window > 0 && n_heavy_rows > 0;
     if (windowed || (ind && xcd_mode == 2 && nnz > 0)) {
         h_ind.resize((size_t)nnz);
-        hipError_t e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        // through pinned chunks of the library's own staging buffer (a pageable destination takes four times as long)
+        static std::mutex stage_mutex;
+        static int32_t* stage = nullptr;
+        constexpr int64_t kStage = 16 << 20;                                // entries (64 MB), allocated on first use
+        std::lock_guard<std::mutex> lock(stage_mutex);
+        hipError_t e = hipSuccess;
+        if (!stage && hipHostMalloc(reinterpret_cast<void**>(&stage), kStage * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
+            stage = nullptr;
+            (void)hipGetLastError();                                         // no pinned memory: copy directly
+            e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
+            if (e == hipSuccess) e = hipStreamSynchronize(s);
+        } else {
+            for (int64_t k0 = 0; k0 < nnz && e == hipSuccess; k0 += kStage) {
+                const int64_t cnt = std::min<int64_t>(kStage, nnz - k0);
+                e = hipMemcpyAsync(stage, ind + k0, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost, s);
+                if (e == hipSuccess) e = hipStreamSynchronize(s);
+                if (e == hipSuccess) memcpy(h_ind.data() + k0, stage, sizeof(int32_t) * cnt);
+            }
+        }
         if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
         int64_t max_col = 0;
         for (int64_t r = 0; windowed && r < n_rows; ++r)
@@ -782,10 +801,16 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
                 int32_t c = b;
                 while (c < e) {
                     // negative indices (history rows of the in-place variant) order like their magnitudes
-                    auto key = [&](int32_t k) { const int64_t v = h_ind[k]; return (int32_t)((v >= 0 ? v : -1 - v) / window); };
-                    const int32_t w = key(c);
+                    auto mag = [&](int32_t k) { const int64_t v = h_ind[k]; return v >= 0 ? v : -1 - v; };
+                    const int32_t w = (int32_t)(mag(c) / window);
+                    const int64_t lo = (int64_t)w * window, hi = lo + window;      // the window of this chunk
+                    const int32_t limit = c + p->chunk < e ? c + p->chunk : e;
                     int32_t stop = c + 1;
-                    while (stop < e && stop - c < p->chunk && key(stop) == w) ++stop;
+                    while (stop < limit) {
+                        const int64_t v = mag(stop);
+                        if (v < lo || v >= hi) break;
+                        ++stop;
+                    }
                     chunk.push_back((int32_t)(chunk.size() / 3));
                     chunk.push_back(c);
                     chunk.push_back(stop);
@@ -799,13 +824,17 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
     p->n_heavy = (int64_t)heavy_row.size();
     p->n_chunks = (int64_t)chunk.size() / 3;
     if (!chunk_window.empty()) {
-        std::vector<int32_t> order((size_t)p->n_chunks);
-        for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
-        std::stable_sort(order.begin(), order.end(),
-                         [&](int32_t x, int32_t y) { return chunk_window[x] < chunk_window[y]; });
+        // counting sort by window; chunks of one window keep their row order
+        int32_t n_windows = 0;
+        for (int32_t w : chunk_window) n_windows = std::max(n_windows, w + 1);
+        std::vector<int64_t> first((size_t)n_windows + 1, 0);
+        for (int32_t w : chunk_window) ++first[(size_t)w + 1];
+        for (int32_t w = 0; w < n_windows; ++w) first[(size_t)w + 1] += first[w];
         std::vector<int32_t> sorted(chunk.size());
-        for (size_t i = 0; i < order.size(); ++i)
-            for (int q = 0; q < 3; ++q) sorted[3 * i + q] = chunk[3 * (size_t)order[i] + q];
+        for (size_t i = 0; i < chunk_window.size(); ++i) {
+            const size_t at = (size_t)first[chunk_window[i]]++;
+            for (int q = 0; q < 3; ++q) sorted[3 * at + q] = chunk[3 * i + q];
+        }
         chunk.swap(sorted);
     }
     if (!group.empty()) {
@@ -835,7 +864,7 @@ gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_row
             }
             p->xcd_ranges = seen > 0 && 10 * local >= 3 * seen;
         }
-        const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
+            const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
         p->n_groups = (int64_t)group.size() / 2;
         hipError_t e = hipMalloc(&p->d_group, bounds.size() * sizeof(int32_t));
         if (e == hipSuccess)

@@ -20,3 +20,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Worst per-row relative error each GPU parity test saw (rows measured on their own scale)."""
+    from tests import util
+    if not util.WORST_ROW_ERR:
+        return
+    terminalreporter.write_line("worst per-row relative error against the oracle, by test (largest first):")
+    for test, err in sorted(util.WORST_ROW_ERR.items(), key=lambda kv: -kv[1])[:25]:
+        terminalreporter.write_line(f"  {err:9.3e}  {test}")

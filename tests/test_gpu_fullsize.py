@@ -5,8 +5,10 @@ whole tensors of this size in seconds, so:
   - pull and push are checked on EVERY row, bit for bit, against a gather done
     with torch's own indexing, and on a sample against the oracle;
   - aggregation, transform and backward aggregation are checked on sampled
-    output rows (the longest rows, the first and last ones, random ones) that
-    the oracle computes one by one from the same inputs.
+    output rows (the longest rows, the shortest, the first and last ones and
+    several thousand random ones) that the oracle computes one by one from the
+    same inputs; every sampled row is measured on its own scale
+    (tests.util.node_rel_err), so a light row cannot hide behind a hub row.
 """
 import numpy as np
 import pytest
@@ -14,7 +16,7 @@ import torch
 
 from gas_inputs import configs, batches, rng
 from oracle import ops as oops
-from tests.util import to_np, max_rel_err
+from tests.util import to_np, node_rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -24,7 +26,7 @@ TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
 def _sample_rows(lengths: np.ndarray, n_random: int, seed: int) -> np.ndarray:
     n = lengths.size
     heavy = np.argsort(-lengths, kind="stable")[:24]
-    light = np.argsort(lengths, kind="stable")[:8]
+    light = np.argsort(lengths, kind="stable")[:64]
     r = np.random.default_rng(seed).choice(n, size=min(n, n_random), replace=False)
     return np.unique(np.concatenate([heavy, light, [0, n - 1], r]))
 
@@ -66,7 +68,7 @@ def _check_step(cfg_id):
 
     # ---- aggregation on sampled rows
     lengths = (sg.rowptr[1:] - sg.rowptr[:-1]).cpu().numpy()
-    rows = _sample_rows(lengths, 1500, 2)
+    rows = _sample_rows(lengths, 8000, 2)
     sub_ptr, sub_col, pos, cols = _sub_pattern(sg.rowptr, sg.col, rows)
     assert lengths[rows].max() == lengths.max()
     cols_dev = torch.from_numpy(cols).to(dev)
@@ -90,7 +92,7 @@ def _check_step(cfg_id):
         want_z = oops.spmm(sub_ptr, (sub_col + rows.size).astype(np.int32), None, xs, diag=ls.diag)
     else:
         want_z = oops.spmm(sub_ptr, sub_col, val, x_rows)
-    e = max_rel_err(to_np(ls.z[rows_dev]), want_z)
+    e = node_rel_err(to_np(ls.z[rows_dev]), want_z)
     assert e <= tol, ("spmm", e)
 
     # ---- transform on sampled rows (input: the library's own Z rows)
@@ -99,7 +101,7 @@ def _check_step(cfg_id):
         want_y = oops.mlp2(z_rows, to_np(ls.w1), to_np(ls.w2), relu_out=True)
     else:
         want_y = oops.linear(z_rows, to_np(ls.w), relu=True)
-    e = max_rel_err(to_np(ls.x_next[rows_dev]), want_y)
+    e = node_rel_err(to_np(ls.x_next[rows_dev]), want_y)
     assert e <= tol, ("linear", e)
 
     # ---- push: every in-batch row landed, bit for bit; nothing else was touched
@@ -113,7 +115,7 @@ def _check_step(cfg_id):
 
     # ---- backward aggregation on sampled columns u < nb: GX[u] = sum over the entries (v, u) of the CSR
     clen = (sg.colptr[1:nb + 1] - sg.colptr[:nb]).cpu().numpy()
-    us = _sample_rows(clen, 600, 3)
+    us = _sample_rows(clen, 4000, 3)
     t_ptr, t_row, t_pos, t_rows = _sub_pattern(sg.colptr, sg.row, us)
     # the CSC copy really lists the entries of the CSR: check a few columns by searching the CSR
     for u in us[:6]:
@@ -131,7 +133,7 @@ def _check_step(cfg_id):
         # CSC values are the CSR values of the same entries
         perm = sg.csc_perm[torch.from_numpy(t_pos).to(dev)].long()
         assert torch.equal(ls.bg.val[perm], ls.bg.val_t[torch.from_numpy(t_pos).to(dev)])
-    e = max_rel_err(to_np(ls.gx[us_dev]), want_gx)
+    e = node_rel_err(to_np(ls.gx[us_dev]), want_gx)
     assert e <= tol, ("spmm_t", e)
 
     # ---- the in-place form of the step (the one the benchmark's headline times): halo rows read from the history

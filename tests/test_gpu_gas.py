@@ -8,7 +8,7 @@ import torch
 
 from gas_inputs import configs, batches
 from oracle import model as omodel
-from tests.util import to_np, max_rel_err, oracle_model
+from tests.util import to_np, node_rel_err, oracle_model
 
 pytestmark = pytest.mark.gpu
 
@@ -49,13 +49,13 @@ def _run_both(wl, batch_ids, hist_init, sweeps=1, check_layers=True):
             torch.cuda.synchronize()
             if check_layers:
                 for l, (a, c) in enumerate(zip(layers_gpu, layers_cpu[:-1])):
-                    e = max_rel_err(to_np(a), c)
+                    e = node_rel_err(to_np(a), c)
                     assert e <= TOL[cfg.dtype], (cfg.name, sweep, b, "layer", l + 1, e)
-            e = max_rel_err(to_np(y_gpu), y_cpu)
+            e = node_rel_err(to_np(y_gpu), y_cpu)
             worst = max(worst, e)
             assert e <= TOL[cfg.dtype], (cfg.name, sweep, b, "output", e)
     for l, (a, c) in enumerate(zip(hs_gpu, hs_cpu)):
-        e = max_rel_err(to_np(a), c)
+        e = node_rel_err(to_np(a), c)
         assert e <= TOL[cfg.dtype], (cfg.name, "history", l, e)
     return worst, hs_gpu, y_gpu
 
@@ -66,7 +66,7 @@ def test_config0_tiny_gcn_two_sweeps_from_zero_history():
     # after one sweep the single history is exact, so sweep 2 equals the full-batch model
     om = oracle_model(wl)
     exact = omodel.full_batch_forward(om, to_np(wl.graph.rowptr), to_np(wl.graph.col), to_np(wl.x))
-    assert max_rel_err(to_np(hs_gpu[0]), exact[0]) <= 1e-5
+    assert node_rel_err(to_np(hs_gpu[0]), exact[0]) <= 1e-5
 
 
 def test_config1_mid_gcn_full_size_first_batch():
@@ -121,9 +121,9 @@ def test_fused_execution_matches_oracle(cfg_id, scale):
         y_gpu = executor.forward_batch_fused(gm, bg, x_dev, hs_gpu)
         y_cpu = omodel.gas_batch_forward(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
                                          to_np(wl.x), hs_cpu)
-        assert max_rel_err(to_np(y_gpu), y_cpu) <= TOL[cfg.dtype]
+        assert node_rel_err(to_np(y_gpu), y_cpu) <= TOL[cfg.dtype]
     for a, c in zip(hs_gpu, hs_cpu):
-        assert max_rel_err(to_np(a), c) <= TOL[cfg.dtype]
+        assert node_rel_err(to_np(a), c) <= TOL[cfg.dtype]
 
 
 def test_paper_overhead_workload_matches_oracle():
@@ -146,7 +146,7 @@ def test_paper_overhead_workload_matches_oracle():
     bg = executor.BatchGraph(nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=F, normalise=False)
     for fn in (executor.forward_batch, executor.forward_batch_fused):
         y = fn(gm, bg, d(x), [d(h).clone() for h in hist])
-        assert max_rel_err(to_np(y), want) <= 1e-5, fn.__name__
+        assert node_rel_err(to_np(y), want) <= 1e-5, fn.__name__
 
 
 @pytest.mark.parametrize("cfg_id,scale,dtype", [(1, 0.1, torch.float32), (2, 0.02, torch.float32), (1, 0.1, torch.bfloat16)])
@@ -177,9 +177,9 @@ def test_appnp_matches_oracle(cfg_id, scale, dtype, fused):
         y = executor.appnp_forward_batch(d(w1), d(w2), alpha, K, bg, d(x), hs_gpu, fused=fused)
         want = omodel.appnp_batch_forward(to_np(w1), to_np(w2), alpha, K, to_np(sg.n_id), to_np(sg.rowptr),
                                           to_np(sg.col), sg.nb, to_np(g.deg), to_np(x), hs_cpu)
-        assert max_rel_err(to_np(y), want) <= TOL[dtype], (b, max_rel_err(to_np(y), want))
+        assert node_rel_err(to_np(y), want) <= TOL[dtype], (b, node_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
-        assert max_rel_err(to_np(a), c) <= TOL[dtype]
+        assert node_rel_err(to_np(a), c) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("cfg_id,scale,dtype,f,f1", [(1, 0.1, torch.float32, 64, 32), (2, 0.01, torch.float32, 100, 28),
@@ -209,9 +209,9 @@ def test_pna_model_matches_oracle(cfg_id, scale, dtype, f, f1):
         y = executor.pna_forward_batch(ws_gpu, delta, bg, d(x), hs_gpu)
         want = omodel.pna_batch_forward(ws_cpu, delta, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x),
                                         hs_cpu)
-        assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
+        assert node_rel_err(to_np(y), want) <= tol, (b, node_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
-        assert max_rel_err(to_np(a), c) <= tol
+        assert node_rel_err(to_np(a), c) <= tol
 
 
 @pytest.mark.parametrize("cfg_id,scale,dtype,f", [(1, 0.1, torch.float32, 64), (2, 0.01, torch.float32, 100),
@@ -239,9 +239,9 @@ def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
         bg = executor.BatchGraph(sg.nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=f, normalise=False)
         y = executor.gat_forward_batch(ws_gpu, bg, d(x), hs_gpu)
         want = omodel.gat_batch_forward(ws_cpu, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x), hs_cpu)
-        assert max_rel_err(to_np(y), want) <= tol, (b, max_rel_err(to_np(y), want))
+        assert node_rel_err(to_np(y), want) <= tol, (b, node_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
-        assert max_rel_err(to_np(a), c) <= tol
+        assert node_rel_err(to_np(a), c) <= tol
 
 
 @pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (4, 0.001), (3, 0.1)])
@@ -277,7 +277,7 @@ def test_host_histories_with_concurrent_transfers(cfg_id, scale):
         if k < 2:
             y_cpu = omodel.gas_batch_forward(om, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(g.deg),
                                              to_np(wl.x), hs_cpu)
-            assert max_rel_err(to_np(y_host), y_cpu) <= TOL[cfg.dtype]
+            assert node_rel_err(to_np(y_host), y_cpu) <= TOL[cfg.dtype]
     pipe.join()
     torch.cuda.synchronize()
     for a, t in zip(hs_dev, pinned):

@@ -10,7 +10,7 @@ import torch
 
 from gas_inputs import configs, batches, rng
 from oracle import ops as oops
-from tests.util import to_np, max_rel_err
+from tests.util import to_np, node_rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -113,7 +113,7 @@ def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld
                      r=None if r is None else to_np(r)[:, :F], s_res=0.3 if res else 0.0,
                      out_dt=oops.F32 if out_dtype == torch.float32 else oops.BF16)
     got = to_np(z[:, :F])
-    err = max_rel_err(got, want)
+    err = node_rel_err(got, want)
     # run-to-run determinism: no atomics, fixed order
     z2 = torch.full_like(z, float("nan"))
     gas.gas_spmm(plan, *args[1:4], xd[:, :F], z2[:, :F], **kw)
@@ -187,7 +187,7 @@ def test_spmm_t_parity(gas, graphs_small, dtype, F):
             gx = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
             gas.gas_spmm_t(plan, dev(sg.colptr), dev(sg.row), dev(val_t), dev(gz), gx, diag=0.75)
             want = oops.spmm_t(to_np(sg.rowptr), to_np(sg.col), val, to_np(gz), n_out, diag=0.75)
-            assert max_rel_err(to_np(gx), want) <= TOL[dtype], (name, n_out)
+            assert node_rel_err(to_np(gx), want) <= TOL[dtype], (name, n_out)
 
 
 # ------------------------------------------------------------------ dense transform
@@ -201,12 +201,12 @@ def test_linear_fp32_parity(gas, M, K, N):
         y = torch.full((M, N), float("nan"), device="cuda")
         gas.gas_linear(dev(z), dev(w), y, bias=None if "bias" not in kw else dev(b), relu=kw.get("relu", False))
         want = oops.linear(to_np(z), to_np(w), bias=None if "bias" not in kw else to_np(b), relu=kw.get("relu", False))
-        assert max_rel_err(to_np(y), want) <= 1e-5, (M, K, N, kw)
+        assert node_rel_err(to_np(y), want) <= 1e-5, (M, K, N, kw)
     if K == N:
         y = torch.full((M, N), float("nan"), device="cuda")
         gas.gas_linear(dev(z), dev(w), y, c_identity=0.6, c_weight=0.4, relu=True)
         want = oops.linear(to_np(z), to_np(w), c_identity=0.6, c_weight=0.4, relu=True)
-        assert max_rel_err(to_np(y), want) <= 1e-5
+        assert node_rel_err(to_np(y), want) <= 1e-5
 
 
 def test_linear_strided_rows(gas):
@@ -215,7 +215,7 @@ def test_linear_strided_rows(gas):
     ybuf = torch.full((900, 64), float("nan"), device="cuda")
     gas.gas_linear(dev(zbuf)[:, :256], dev(w), ybuf[:700])
     want = oops.linear(to_np(zbuf)[:, :256], to_np(w))
-    assert max_rel_err(to_np(ybuf[:700]), want) <= 1e-5 and torch.isnan(ybuf[700:]).all()
+    assert node_rel_err(to_np(ybuf[:700]), want) <= 1e-5 and torch.isnan(ybuf[700:]).all()
 
 
 @pytest.mark.parametrize("M,K,N", [(1000, 256, 256), (4097, 128, 256), (300, 64, 64), (129, 256, 128), (257, 72, 200),
@@ -229,12 +229,12 @@ def test_linear_bf16_parity(gas, M, K, N):
         y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
         gas.gas_linear(dev(z), dev(w), y, bias=None if "bias" not in kw else dev(b), relu=kw.get("relu", False))
         want = oops.linear(to_np(z), to_np(w), bias=None if "bias" not in kw else to_np(b), relu=kw.get("relu", False))
-        assert max_rel_err(to_np(y), want) <= 2e-2, (M, K, N, kw)
+        assert node_rel_err(to_np(y), want) <= 2e-2, (M, K, N, kw)
     if K == N:
         y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
         gas.gas_linear(dev(z), dev(w), y, c_identity=0.6, c_weight=0.4, relu=True)
         want = oops.linear(to_np(z), to_np(w), c_identity=0.6, c_weight=0.4, relu=True)
-        assert max_rel_err(to_np(y), want) <= 2e-2
+        assert node_rel_err(to_np(y), want) <= 2e-2
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -252,7 +252,7 @@ def test_mlp2_parity(gas, dtype, M, K, H, N):
                      relu_out=relu_out)
         want = oops.mlp2(to_np(z), to_np(w1), to_np(w2), b1=to_np(b1) if bias else None,
                          b2=to_np(b2) if bias else None, relu_out=relu_out)
-        assert max_rel_err(to_np(y), want) <= TOL[dtype], (dtype, M, K, H, N, bias)
+        assert node_rel_err(to_np(y), want) <= TOL[dtype], (dtype, M, K, H, N, bias)
     with pytest.raises(gas.GasError):
         gas.gas_mlp2(dev(z), dev(rng.glorot_uniform(6, 355, K, 300, dtype=dtype)),
                      dev(rng.glorot_uniform(6, 356, 300, N, dtype=dtype)), y)      # hidden width above the limit
@@ -289,7 +289,7 @@ def test_spmm_hist_equals_pull_then_spmm(gas, graphs_small, name, dtype, F):
     # and against the oracle's pull + aggregation
     xo = np.concatenate([to_np(xb), oops.pull(to_np(hist), nid_np[nb:])])
     want = oops.spmm(to_np(sg.rowptr), col_np, val, xo, diag=diag)
-    assert max_rel_err(to_np(z), want) <= TOL[dtype]
+    assert node_rel_err(to_np(z), want) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -314,11 +314,11 @@ def test_mlp_that_keeps_its_hidden_activation(gas, dtype, M, K, H, N, push):
         return
     dt = oops.F32 if dtype == torch.float32 else oops.BF16
     want_h = oops.linear(to_np(z), to_np(w1), bias=to_np(b1), relu=True, out_dt=dt)
-    assert max_rel_err(to_np(h), want_h) <= TOL[dtype]
+    assert node_rel_err(to_np(h), want_h) <= TOL[dtype]
     # the second product on the hidden activation the library stored (a unit within rounding of zero may fall on
     # either side of the ReLU in two correct passes)
     want_y = oops.linear(to_np(h), to_np(w2), relu=True, out_dt=dt)
-    assert max_rel_err(to_np(y), want_y) <= TOL[dtype]
+    assert node_rel_err(to_np(y), want_y) <= TOL[dtype]
     want_table = to_np(table0).copy()
     if push:
         oops.push(to_np(y), to_np(idx), want_table)
@@ -348,7 +348,7 @@ def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name, monkeypatch
     assert np.array_equal(out[0].view(np.uint8), out[1].view(np.uint8))
     assert np.array_equal(out[0].view(np.uint8), out[2].view(np.uint8))
     want = oops.spmm(to_np(sg.rowptr), to_np(sg.col), to_np(val), to_np(x))
-    assert max_rel_err(out[1], want) <= 1e-5
+    assert node_rel_err(out[1], want) <= 1e-5
 
 
 @pytest.mark.parametrize("name,K,N,variant", [("sbm", 64, 64, "gcnii"), ("sbm", 128, 64, "gcn"), ("powerlaw", 100, 36, "gcn"),
@@ -388,7 +388,10 @@ def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, v
     gas.gas_spmm_linear(d_ptr, src, dval, dev(xb), dev(w), y, hist=dev(hist), r=None if r is None else dev(r),
                         bias=None if bias is None else dev(bias), relu=relu, push_idx=d_nid[:nb], push_hist=table,
                         **kw, **lin)
-    assert max_rel_err(to_np(y), want) <= 1e-5
+    # rows measured against the products summed for them: with N = 4 a ReLU can leave a row whose largest
+    # output is a hundredth of its terms
+    terms = (np.abs(z.astype(np.float64)) @ np.abs(to_np(w).astype(np.float64))).max(axis=1)
+    assert node_rel_err(to_np(y), want, scale=terms) <= 1e-5
     assert np.array_equal(to_np(table)[nid_np[:nb]], to_np(y))
     keep = np.ones(g.n, dtype=bool)
     keep[nid_np[:nb]] = False
@@ -478,7 +481,7 @@ def test_pna_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
         got = to_np(out[:, :9 * F])
         for j in range(9):
             blk = slice(j * F, (j + 1) * F)
-            assert max_rel_err(got[:, blk], want[:, blk]) <= TOL[dtype], (j, max_rel_err(got[:, blk], want[:, blk]))
+            assert node_rel_err(got[:, blk], want[:, blk]) <= TOL[dtype], (j, node_rel_err(got[:, blk], want[:, blk]))
         if add is None:
             assert np.array_equal(got[:, F:3 * F], want[:, F:3 * F])
     # a row without neighbours gives zeros; an empty problem is fine
@@ -505,7 +508,7 @@ def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
     z = torch.full((nb, F + ld_pad), float("nan"), dtype=dtype, device="cuda")
     gas.gas_gat_aggregate(dev(sg.rowptr), dev(sg.col), dev(p)[:, :F], dev(a_dst), dev(a_src), z[:, :F])
     want = oops.gat_aggregate(to_np(sg.rowptr), to_np(sg.col), to_np(p)[:, :F], to_np(a_dst), to_np(a_src))
-    assert max_rel_err(to_np(z[:, :F]), want) <= TOL[dtype], max_rel_err(to_np(z[:, :F]), want)
+    assert node_rel_err(to_np(z[:, :F]), want) <= TOL[dtype], node_rel_err(to_np(z[:, :F]), want)
     # same call again: same bits (entries are folded in index order)
     z2 = torch.full((nb, F + ld_pad), float("nan"), dtype=dtype, device="cuda")
     gas.gas_gat_aggregate(dev(sg.rowptr), dev(sg.col), dev(p)[:, :F], dev(a_dst), dev(a_src), z2[:, :F])

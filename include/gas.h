@@ -304,6 +304,25 @@ GAS_API gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void*
                                  float* dW, void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * gas_linear_bwd_weight for callers that cannot allocate or pass a workspace:
+ * code under HIP graph capture, tight serving or training loops, harnesses that
+ * forbid hipMalloc.  Same kernels, same slabs and the same bits as
+ * gas_linear_bwd_weight, with the slab partials kept in a static device array of
+ * the library (64 MiB on every GPU the library runs on, held until the process
+ * ends) instead of a caller's workspace.  Calls no hipMalloc, hipFree or other
+ * allocating routine.  Shapes whose partials exceed the array
+ * (gas_linear_bwd_weight_workspace(n_rows, F_in, F_out) > 64 MiB; at widths
+ * 256 x 256 that is above 1,048,576 rows) are rejected with GAS_ERR_ARG and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (two streams, two threads) race; calls on one
+ * stream are ordered and safe.  Every partial a call reads it has written
+ * itself, so nothing needs clearing between calls.
+ */
+GAS_API gas_status gas_linear_bwd_weight_static(const void* Z, int64_t ldz, const void* GP, int64_t ldgp,
+                                        int64_t n_rows, int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight,
+                                        float* dW, void* stream);
+
+/*
  * Loss of a mini-batch and the parameter update that close the loop body of
  * Algorithm 1 (the loss is taken over the in-batch nodes only, Section 1; the
  * paper's tasks are node classification; Section 3 names L2 regularisation).

@@ -17,7 +17,7 @@ EXPORTS = [
     "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
     "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
-    "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace",
+    "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_bwd_weight_static",
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
     "gas_pna_aggregate", "gas_gat_aggregate",
 ]
@@ -261,6 +261,18 @@ def gas_linear_bwd_weight(z, gp, dw, workspace, c_weight=1.0):
     _check(lib().gas_linear_bwd_weight(a, lda, b, ldb, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]),
                                        C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_float(c_weight), _ptr(dw),
                                        _ptr(workspace), C.c_int64(nbytes), _stream()))
+
+
+def gas_linear_bwd_weight_static(z, gp, dw, c_weight=1.0):
+    """gas_linear_bwd_weight with the slab partials in the library's static scratch array (no workspace)."""
+    a, lda = _mat(z)
+    b, ldb = _mat(gp)
+    if z.dtype != gp.dtype or z.shape[0] != gp.shape[0] or dw.dtype != torch.float32 or \
+            dw.shape != (z.shape[1], gp.shape[1]) or not dw.is_contiguous():
+        raise ValueError("gas_linear_bwd_weight_static: shapes or dtypes do not match")
+    _check(lib().gas_linear_bwd_weight_static(a, lda, b, ldb, C.c_int64(z.shape[0]), C.c_int32(z.shape[1]),
+                                              C.c_int32(gp.shape[1]), C.c_int(_dt(z)), C.c_float(c_weight),
+                                              _ptr(dw), _stream()))
 
 
 def gas_linear_push(z, w, y, idx, hist, bias=None, c_identity=0.0, c_weight=1.0, relu=False):

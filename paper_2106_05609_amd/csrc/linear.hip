@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include <mutex>
 
 namespace gas {
 namespace {
@@ -1121,6 +1122,33 @@ static int64_t dw_slab_rows(int64_t M, int K, int N) {
     return slab < 128 ? 128 : (slab > 4096 ? 4096 : slab);
 }
 
+// Slab partials for callers that can bring no workspace (gas_linear_bwd_weight_static): a zero-initialised array in
+// the code object, one copy per GPU at that GPU's own address.  In host code the array's name is only a handle for
+// the runtime; the address a kernel can use comes from hipGetSymbolAddress, asked once per device with that device
+// current, and is what the launches are given.
+constexpr int64_t kDwScratchBytes = 64ll << 20;
+static __device__ __align__(256) unsigned char dw_scratch[kDwScratchBytes];
+constexpr int kMaxDevices = 64;
+
+static gas_status dw_scratch_pointer(void** out) {
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {nullptr};
+    int dev = -1;
+    GAS_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(GAS_ERR_ARG, "gas_linear_bwd_weight_static: device %d", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(dw_scratch));
+        if (e != hipSuccess || !p)
+            return fail(GAS_ERR_HIP, "gas_linear_bwd_weight_static: no address for the scratch array on device %d: %s",
+                        dev, hipGetErrorString(e));
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return GAS_OK;
+}
+
 struct DwArgs {
     const char* Z;  int64_t ldz;
     const char* G;  int64_t ldg;
@@ -1558,9 +1586,10 @@ int64_t gas_linear_bwd_weight_workspace(int64_t n_rows, int32_t F_in, int32_t F_
     return ((n_rows + slab - 1) / slab) * (int64_t)F_in * F_out * (int64_t)sizeof(float);
 }
 
-gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
-                                 int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight, float* dW,
-                                 void* workspace, int64_t workspace_bytes, void* stream) {
+// Weight gradient with the slab partials in `workspace` (the caller's, or the library's static array).
+static gas_status run_dw(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
+                         int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight, float* dW,
+                         void* workspace, int64_t workspace_bytes, bool static_scratch, void* stream) {
     if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_linear_bwd_weight: unknown dtype %d", (int)dt);
     GAS_REQUIRE(n_rows >= 0 && F_in > 0 && F_out > 0, "gas_linear_bwd_weight: n_rows=%lld widths %d, %d",
                 (long long)n_rows, F_in, F_out);
@@ -1584,6 +1613,17 @@ gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int
     }
     GAS_REQUIRE(Z && GP, "gas_linear_bwd_weight: null pointer");
     GAS_REQUIRE(ldz >= F_in && ldgp >= F_out, "gas_linear_bwd_weight: row stride smaller than the row");
+    if (static_scratch) {
+        const int64_t need = gas_linear_bwd_weight_workspace(n_rows, F_in, F_out);
+        if (need > kDwScratchBytes)
+            return fail(GAS_ERR_ARG, "gas_linear_bwd_weight_static: the slab partials of this shape take %lld bytes, "
+                        "the library's static scratch array holds %lld; use gas_linear_bwd_weight with a workspace",
+                        (long long)need, (long long)kDwScratchBytes);
+        const gas_status st = dw_scratch_pointer(&workspace);
+        if (st != GAS_OK) return st;
+        workspace_bytes = kDwScratchBytes;
+        a.partial = static_cast<float*>(workspace);
+    }
     GAS_REQUIRE(workspace && workspace_bytes >= gas_linear_bwd_weight_workspace(n_rows, F_in, F_out),
                 "gas_linear_bwd_weight: workspace of %lld bytes needed, %lld given",
                 (long long)gas_linear_bwd_weight_workspace(n_rows, F_in, F_out), (long long)workspace_bytes);
@@ -1613,6 +1653,18 @@ gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int
     hipLaunchKernelGGL(dw_reduce_kernel, dim3(rblocks), dim3(256), 0, s, a);
     GAS_CHECK_HIP(hipGetLastError());
     return GAS_OK;
+}
+
+gas_status gas_linear_bwd_weight(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
+                                 int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight, float* dW,
+                                 void* workspace, int64_t workspace_bytes, void* stream) {
+    return run_dw(Z, ldz, GP, ldgp, n_rows, F_in, F_out, dt, c_weight, dW, workspace, workspace_bytes, false, stream);
+}
+
+gas_status gas_linear_bwd_weight_static(const void* Z, int64_t ldz, const void* GP, int64_t ldgp, int64_t n_rows,
+                                        int32_t F_in, int32_t F_out, gas_dtype dt, float c_weight, float* dW,
+                                        void* stream) {
+    return run_dw(Z, ldz, GP, ldgp, n_rows, F_in, F_out, dt, c_weight, dW, nullptr, 0, true, stream);
 }
 
 gas_status gas_relu_bwd(const void* GY, int64_t ldgy, const void* Y, int64_t ldy, int64_t n_rows, int32_t F,

@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""History tables in host memory (the paper's arrangement, Section 4): forward passes over consecutive
+"""History tables in host memory (the paper's arrangement, Section 5 "PyGAS"): forward passes over consecutive
 mini-batches of a benchmark configuration with
 
   hbm              the tables in device memory (executor.forward_batch), for reference;
@@ -18,7 +18,7 @@ import sys
 
 import torch
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
 

@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""The paper's synthetic runtime experiment (Section 5, "fast mini-batch
+"""The paper's synthetic runtime experiment (Section 6 "Experiments", "fast mini-batch
 execution"; the figure on runtime overhead versus inter-/intra-connectivity):
 a 4-layer GIN, a mini-batch of exactly 4,000 nodes each linked to 60 others
 inside the batch, and a varying number of out-of-batch nodes each linked to 60
@@ -27,7 +27,7 @@ import os
 
 import torch
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
 

@@ -13,25 +13,8 @@ import time
 
 import torch
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
-
-
-# Shapes of four rows of the paper's dataset-statistics table (nodes, undirected edges, features, classes): the
-# datasets its training-step runtimes are quoted on.  Only the counts are used; every record is synthetic.
-SHAPES = {"cora": (2_708, 5_278, 1_433, 7), "pubmed": (19_717, 44_324, 500, 3), "ppi": (56_944, 793_632, 50, 121),
-          "flickr": (89_250, 449_878, 500, 7)}
-
-
-def shaped_config(configs, name):
-    """Clustered synthetic graph (8 clusters, 85 % of the links inside them, 2 clusters per mini-batch) with the
-    counts of `name`; 4-layer GCN, hidden width 256 (the paper does not state it), classes padded to a multiple of 8."""
-    n, e, f, c = SHAPES[name]
-    cfg = configs.config(1)
-    cfg.name, cfg.n, cfg.n_blocks, cfg.blocks_per_batch = f"{name}-shaped-gcn4", n, 8, 2
-    cfg.widths = [(f + 3) // 4 * 4, 256, 256, 256, (c + 7) // 8 * 8]
-    cfg.graph = dict(kind="sbm_partners", mean_degree=2.0 * e / n, frac_intra=0.85)
-    return cfg
 
 
 def main():
@@ -40,9 +23,6 @@ def main():
     p.add_argument("--scale", type=float, default=1.0)
     p.add_argument("--epochs", type=int, default=2, help="timed epochs after one warm-up epoch")
     p.add_argument("--separate", action="store_true", help="pull the halo rows instead of reading them in place")
-    p.add_argument("--shape", choices=sorted(SHAPES), help="a 4-layer GCN on a synthetic graph with the node, edge, "
-                   "feature and class counts of one row of the paper's dataset table (the records are synthetic); "
-                   "overrides --config")
     p.add_argument("--graph", action="store_true", help="also replay every mini-batch's training step as a HIP graph")
     p.add_argument("--lr", type=float, default=0.0, help="step size (default: 0.01 for GCN; 1e-10 for GIN, whose unnormalised sums of N(0,1) features give logits of order 1e5)")
     args = p.parse_args()
@@ -53,7 +33,7 @@ def main():
     from gas_inputs import configs, batches
     gas.lib()
     dev = torch.device("cuda:0")
-    cfg = shaped_config(configs, args.shape) if args.shape else configs.config(args.config, args.scale)
+    cfg = configs.config(args.config, args.scale)
     lr = args.lr if args.lr > 0 else (1e-10 if cfg.op == "gin" else 0.01)
     fused = not args.separate
     t0 = time.time()
@@ -136,7 +116,7 @@ def main():
               f"(x{sec_eager / sec_graph:.2f}), weights and histories identical: {same}", file=sys.stderr, flush=True)
         if not same:
             sys.exit("bench_train.py: the replayed epochs left different weights or histories")
-    out = {"workload": f"{'shape ' + args.shape if args.shape else f'configs[{args.config}]'} {cfg.name}: one training epoch over {len(bgs)} mini-batches, {len(ws)} layers",
+    out = {"workload": f"configs[{args.config}] {cfg.name}: one training epoch over {len(bgs)} mini-batches, {len(ws)} layers",
            "epoch_s": round(sec, 4), "batches": len(bgs), "ms_per_training_step": round(sec / len(bgs) * 1e3, 4),
            "forward_edges_per_s": round(edges / sec, 1), "nodes_per_s": round(g.n / sec, 1),
            "mean_loss_per_epoch": [round(x, 5) for x in losses], "dtype": "f32" if cfg.dtype == torch.float32 else "bf16"}

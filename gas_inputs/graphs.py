@@ -237,7 +237,7 @@ def chung_lu_bfs_blocks(n: int, exponent: float, mean_degree: float, max_degree:
 
 
 def batch_with_outside_links(n_batch: int, n_outside: int, links: int, seed: int, device="cpu") -> Graph:
-    """The paper's synthetic overhead workload (Section 5, runtime analysis): a mini-batch of `n_batch` nodes,
+    """The paper's synthetic overhead workload (Section 6 "Experiments", runtime analysis): a mini-batch of `n_batch` nodes,
     each randomly linked to `links` other nodes of the batch, plus `n_outside` out-of-batch nodes each randomly
     linked to `links` nodes inside the batch.  Nodes 0..n_batch-1 are the batch (block 0), the rest block 1.
     "Linked to 60 other nodes" is read as an average degree of 60 inside the batch: every node draws links/2

@@ -98,25 +98,45 @@ GAS_API gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t 
                         const int32_t* n_id, const int32_t* deg, float* val, void* stream);
 
 /*
- * Schedule for one compressed sparse pattern (degree bins, chunk lists of the
- * heavy rows, partial-sum workspace).  Built once per batch subgraph and
- * reused by every layer and every epoch; one plan for the CSR, one for the CSC
- * copy.  ptr is a device pointer (int32[n_rows+1]); it is copied to the host
- * inside this call, which therefore waits for `stream`.  ind (device,
- * int32[nnz], each row ascending) may be NULL; when given it is used to cut
- * and order the chunks of heavy rows by column range (better cache reuse of
- * the gathered rows), and to see whether the pattern is clustered (most
- * entries of a row name rows near it, as in a batch of partition clusters):
- * then each of the eight XCDs is given one contiguous range of rows, so a
- * cluster is gathered into one L2 instead of eight.  It is copied to the
- * host as well.  Either the local
- * column ids or the source indices of gas_fuse_sources may be passed.  max_F
- * is the widest feature dimension the plan will be used with (sizes the
- * workspace).  A plan must not be used by two streams at the same time.
+ * Schedule for one compressed sparse pattern (groups of light rows, chunk
+ * lists of the heavy rows, partial-sum workspace).  Built once per batch
+ * subgraph (Algorithm 1 builds G_b once per batch) and reused by every layer
+ * and every epoch; one plan for the CSR, one for the CSC copy.  ptr is a device
+ * pointer (int32[n_rows+1]); ind (device, int32[nnz], each row ascending) may
+ * be NULL; when given it is used to cut and order the chunks of heavy rows by
+ * L2-sized windows of the rows they gather, and to see whether the pattern is clustered (most entries of a row
+ * name rows near it, as in a batch of partition clusters): then each of the
+ * eight XCDs is given one contiguous range of light rows, so a cluster is
+ * gathered into one L2 instead of eight.  Either the local column ids or the
+ * source indices of gas_fuse_sources may be passed.  Both arrays are read
+ * inside this call, which therefore waits for `stream`; ptr is validated
+ * (0 = ptr[0] <= ptr[r] <= ptr[r+1] <= ptr[n_rows] = nnz, else GAS_ERR_ARG).
+ * max_F is the widest feature dimension the plan will be used with (sizes the
+ * workspace and the windows).  A plan must not be used by two streams at the
+ * same time.
+ *
+ * gas_plan_create_opt takes the schedule's parameters explicitly (NULL or a
+ * zero field = the default): rows with more than heavy_threshold entries
+ * (512) are cut into chunks of at most `chunk` entries (256) that end at a
+ * window boundary once they hold min_chunk entries (32); window_rows = rows of
+ * the gathered table per window (default: 2 MiB worth of rows of max_F floats,
+ * rounded down to a power of two; -1 = no windows); xcd_ranges: 0 = decide
+ * from the pattern, 1 = always, 2 = never.  The parameters change which
+ * wavefront sums what, never the set of terms: results agree to rounding
+ * between parameter sets and are bit-identical for one set.
  */
 typedef struct gas_plan gas_plan;
+typedef struct {
+    int32_t heavy_threshold;
+    int32_t chunk;
+    int32_t min_chunk;
+    int32_t window_rows;
+    int32_t xcd_ranges;
+} gas_plan_options;
 GAS_API gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz,
                            int32_t max_F, void* stream, gas_plan** out);
+GAS_API gas_status gas_plan_create_opt(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz,
+                               int32_t max_F, const gas_plan_options* opt, void* stream, gas_plan** out);
 GAS_API void gas_plan_destroy(gas_plan* plan);
 
 /*
@@ -245,7 +265,7 @@ GAS_API gas_status gas_mlp2_keep(const void* Z, int64_t ldz, int64_t n_rows, int
  * One whole layer in one launch, for narrow layers (Algorithm 1's loop body
  * for the in-batch nodes: aggregate over G_b with both sources of Eq. 2,
  * transform, Push):
- *     Z[v, :] = s_agg * ( sum_k val[k] * S(src[k]) + diag * X[v, :] ) + s_res * R[v, :]
+ *     Z[v, :] = s_agg * sum_k val[k] * S(src[k]) + diag * X[v, :] + s_res * R[v, :]
  *     Y[v, :] = act( c_identity * Z[v, :] + c_weight * (Z W)[v, :] + bias )
  *     push_hist[push_idx[v], :] = Y[v, :]                (if push_idx != NULL)
  * with S(s) = X[s, :] for s >= 0 and hist[-1-s, :] for s < 0, exactly as in
@@ -421,7 +441,7 @@ GAS_API gas_status gas_row_distance_bwd(const void* A, int64_t lda, const void* 
 
 /*
  * Histories outside HBM (the paper keeps them in host memory and overlaps
- * the transfers with computation, Section 4): gas_pull and gas_push accept a
+ * the transfers with computation, Section 5 "PyGAS"): gas_pull and gas_push accept a
  * table in pinned host memory once its device-side address is known; the
  * copy kernel then moves the rows over the host link itself, with no staging
  * copy and no host thread, and overlaps with other work when launched on a

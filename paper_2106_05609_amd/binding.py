@@ -15,7 +15,7 @@ OK = 0
 EXPORTS = [
     "gas_last_error", "gas_version", "gas_validate_indices",
     "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
-    "gas_gcn_norm", "gas_plan_create", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
+    "gas_gcn_norm", "gas_plan_create", "gas_plan_create_opt", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_bwd_weight_static",
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
@@ -117,16 +117,27 @@ def gas_gcn_norm(ptr, ind, n_id, deg, val):
                               _ptr(n_id, torch.int32), _ptr(deg, torch.int32), _ptr(val, torch.float32), _stream()))
 
 
+class PlanOptions(C.Structure):
+    """gas_plan_options of the C ABI; a zero field means the default."""
+    _fields_ = [("heavy_threshold", C.c_int32), ("chunk", C.c_int32), ("min_chunk", C.c_int32),
+                ("window_rows", C.c_int32), ("xcd_ranges", C.c_int32)]
+
+
 class Plan:
     """Owner of a gas_plan handle."""
 
-    def __init__(self, ptr: torch.Tensor, nnz: int, max_F: int, n_rows=None, ind=None):
+    def __init__(self, ptr: torch.Tensor, nnz: int, max_F: int, n_rows=None, ind=None, options=None):
+        """options: dict with any of heavy_threshold, chunk, min_chunk, window_rows, xcd_ranges (gas_plan_options)."""
         self.n_rows = ptr.numel() - 1 if n_rows is None else n_rows
         self.handle = C.c_void_p(0)
         if ind is not None and ind.numel() < nnz:
             raise ValueError("gas_plan_create: ind is shorter than nnz")
-        _check(lib().gas_plan_create(_ptr(ptr, torch.int32), _ptr(ind, torch.int32), C.c_int64(self.n_rows),
-                                     C.c_int64(nnz), C.c_int32(max_F), _stream(), C.byref(self.handle)))
+        opt = None
+        if options:
+            opt = PlanOptions(**options)
+        _check(lib().gas_plan_create_opt(_ptr(ptr, torch.int32), _ptr(ind, torch.int32), C.c_int64(self.n_rows),
+                                         C.c_int64(nnz), C.c_int32(max_F), None if opt is None else C.byref(opt),
+                                         _stream(), C.byref(self.handle)))
 
     def close(self):
         if self.handle:
@@ -140,8 +151,8 @@ class Plan:
             pass
 
 
-def gas_plan_create(ptr, nnz, max_F, n_rows=None, ind=None) -> Plan:
-    return Plan(ptr, nnz, max_F, n_rows, ind)
+def gas_plan_create(ptr, nnz, max_F, n_rows=None, ind=None, options=None) -> Plan:
+    return Plan(ptr, nnz, max_F, n_rows, ind, options)
 
 
 def gas_plan_destroy(plan: Plan):

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void spmm_linear_f32_kernel(FusedArgs a) 
                     if (a.diag != 0.f) {
                         const f32x4 d = *reinterpret_cast<const f32x4*>(a.X + m * a.ldx + 4 * p);
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) z[c] = fmaf(a.s_agg * a.diag, d[c], z[c]);
+                        for (int c = 0; c < 4; ++c) z[c] = fmaf(a.diag, d[c], z[c]);
                     }
                     if (a.R) {
                         const f32x4 d = *reinterpret_cast<const f32x4*>(a.R + m * a.ldr + 4 * p);

@@ -15,26 +15,22 @@
 // Heavier rows (power-law hubs) are cut into chunks of at most `chunk` entries,
 // one wavefront per chunk (spmm_chunk_kernel), whose fp32 partial sums go to a
 // workspace and are added in a fixed order by spmm_heavy_reduce_kernel; the
-// light rows follow in spmm_rows_kernel.  The summation order is a function of
-// the plan alone, so results are bit-identical from run to run.
+// light rows follow in spmm_rows_kernel.  The chunks are cut and ordered by
+// L2-sized windows of the source rows (plan_host.h states the rules), so that
+// wavefronts running together gather from rows that fit the L2 of every XCD.
+// The summation order is a
+// function of the plan alone, so results are bit-identical from run to run.
 #include "common.h"
-
-#ifndef GAS_WAVES
-#define GAS_WAVES_ATTR
-#else
-#define GAS_WAVES_ATTR __attribute__((amdgpu_waves_per_eu(GAS_WAVES, GAS_WAVES)))
-#endif
+#include "plan_host.h"
 
 #include <algorithm>
-#include <mutex>
 #include <string.h>
-#include <cstdlib>
 #include <vector>
 
 struct gas_plan {
     int64_t n_rows = 0, nnz = 0;
     int32_t max_F = 0;
-    int32_t threshold = 0, chunk = 0, slices = 1;
+    int32_t threshold = 0, chunk = 0;
     int64_t n_heavy = 0, n_chunks = 0;
     int32_t* d_chunk = nullptr;        // [3 * n_chunks]: slot of the partial sum, begin, end (in processing order)
     int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
@@ -64,8 +60,6 @@ struct SpmmArgs {
     float diag, s_agg, s_res;
     int64_t n_rows, n_diag;
     int units;            // 16-byte units per row of X
-    int n_slices;         // the row is cut into n_slices equal feature slices, one per workgroup
-    int slice_units;      // units per slice
     int F;
     int threshold;
     const int32_t* chunk;       // plan lists
@@ -110,7 +104,7 @@ __device__ __forceinline__ float bcast_f(float v, int k) {
 // Sum of val[k] * X[ind[k], :] over k in [begin, end) for this lane's units.
 // Afterwards every team of the wavefront holds the full sum.
 template <int G, int UPT, int U, bool XBF>
-__device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int nunits, int begin, int end,
+__device__ __forceinline__ void accumulate(const SpmmArgs& a, int begin, int end,
                                            float (&acc)[UPT][Unit<XBF>::E]) {
     constexpr int S = kWave / G;
     constexpr int E = Unit<XBF>::E;
@@ -120,8 +114,9 @@ __device__ __forceinline__ void accumulate(const SpmmArgs& a, int unit0, int nun
     for (int p = 0; p < UPT; ++p)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[p][e] = 0.f;
-    const char* xb = a.X + (int64_t)(unit0 + tl) * 16;
-    const char* hb = a.H + (int64_t)(unit0 + tl) * 16;
+    const char* xb = a.X + (int64_t)tl * 16;
+    const char* hb = a.H + (int64_t)tl * 16;
+    const int nunits = a.units;
     for (int t = begin; t < end; t += kWave) {
         const int cnt = min(kWave, end - t);
         int my_c = 0;
@@ -366,10 +361,9 @@ __device__ __forceinline__ void light_group(const SpmmArgs& a, int64_t g) {
 
 // One chunk of a heavy row on the wave-per-row layout (rows of 64 vectors of VB bytes): every lane owns VB bytes
 // of the row, 8 gathers in flight per lane, the fp32 partial sum goes to the chunk's slot of the workspace.
-template <int VB, bool XBF>
+template <int VB, bool XBF, int U>
 __device__ __forceinline__ void chunk_wave_per_row(const SpmmArgs& a, int64_t c) {
     typedef typename VecOf<VB>::type V;
-    constexpr int U = 8;
     constexpr int E = LaneAcc<VB, XBF>::E;
     const int lane = threadIdx.x & 63;
     const int begin = a.chunk[3 * c + 1], end = a.chunk[3 * c + 2];
@@ -415,30 +409,28 @@ __device__ __forceinline__ void chunk_wave_per_row(const SpmmArgs& a, int64_t c)
 }
 
 // Chunks of heavy rows: one wavefront per chunk, partial sums to the workspace.
-// With n_slices > 1 a feature row is cut into equal slices and workgroup b
-// works on slice b % n_slices: consecutive workgroup ids go to different XCDs
-// (round robin), so with 8 slices every XCD keeps to one slice and the same L2
-// capacity holds 8x more rows of it.
+// Workgroups take the window-ordered list four chunks at a time.  At most
+// four wavefronts per SIMD: fewer chunks in flight keep the gathers of the
+// running chunks inside a narrower range of rows (measured: 2-4 % faster than
+// 5 or 8, 3 and fewer are slower).
 template <int G, int UPT, int U, bool XBF, int VB>
-__global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_chunk_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void spmm_chunk_kernel(SpmmArgs a) {
     constexpr int E = Unit<XBF>::E;
     const int lane = threadIdx.x & 63;
-    const int slice = blockIdx.x % a.n_slices;
-    const int64_t c = (int64_t)(blockIdx.x / a.n_slices) * 4 + (threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= a.n_chunks) return;
-    if constexpr (VB > 0) {                 // rows of 64 vectors, not sliced
-        chunk_wave_per_row<VB, XBF>(a, c);
+    if constexpr (VB > 0) {                 // rows of 64 vectors
+        chunk_wave_per_row<VB, XBF, U>(a, c);
         return;
     }
-    const int unit0 = slice * a.slice_units;
     float acc[UPT][E];
-    accumulate<G, UPT, U, XBF>(a, unit0, a.slice_units, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
+    accumulate<G, UPT, U, XBF>(a, a.chunk[3 * c + 1], a.chunk[3 * c + 2], acc);
     if (lane < G) {
 #pragma unroll
         for (int p = 0; p < UPT; ++p) {
             const int unit = lane + p * G;
-            if (unit < a.slice_units) {
-                float* dst = a.partial + (int64_t)a.chunk[3 * c] * a.F + (int64_t)(unit0 + unit) * E;
+            if (unit < a.units) {
+                float* dst = a.partial + (int64_t)a.chunk[3 * c] * a.F + (int64_t)unit * E;
 #pragma unroll
                 for (int q = 0; q < E / 4; ++q)
                     *reinterpret_cast<f32x4*>(dst + 4 * q) =
@@ -452,7 +444,7 @@ __global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_chunk_kernel(SpmmArgs
 // groups, one wavefront per row (rows of exactly 64 vectors of VB bytes);
 // VB == 0: one wavefront per row, teams of G lanes per neighbour.
 template <int G, int UPT, int U, bool XBF, bool ZBF, int VB>
-__global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_rows_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
     if constexpr (VB > 0) {
         // Workgroups go to the eight XCDs in turn and each XCD has its own L2: with xcd_ranges every XCD takes one
         // contiguous range of the groups (equal cost per range), so rows of one cluster of the partition gather
@@ -472,7 +464,7 @@ __global__ __launch_bounds__(256) GAS_WAVES_ATTR void spmm_rows_kernel(SpmmArgs 
         const int begin = a.ptr[row], end = a.ptr[row + 1];
         if (end - begin > a.threshold) return;       // heavy row: done by the chunk kernel
         float acc[UPT][E];
-        accumulate<G, UPT, U, XBF>(a, 0, a.units, begin, end, acc);
+        accumulate<G, UPT, U, XBF>(a, begin, end, acc);
         if (lane < G) {
 #pragma unroll
             for (int p = 0; p < UPT; ++p)
@@ -532,26 +524,19 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(SpmmArgs a) {
     }
 }
 
-int env_int(const char* name, int dflt, int lo, int hi);
-
 template <int G, int UPT, int U, bool XBF, int VB = 0>
 gas_status launch_chunks(const SpmmArgs& a, hipStream_t s) {
-    const int64_t blocks = ((a.n_chunks + 3) / 4) * (VB > 0 ? 1 : a.n_slices);
+    const int64_t blocks = (a.n_chunks + 3) / 4;
     if (blocks > 0x7FFFFFFFLL) return fail(GAS_ERR_ARG, "gas_spmm: too many workgroups for one launch");
-    // Unused dynamic LDS caps the workgroups per compute unit (bytes per workgroup; 33,000 -> 4 workgroups =
-    // 4 wavefronts per SIMD): fewer chunks in flight keep the gathers of the running chunks inside a narrower
-    // range of feature rows.  Measured on the power-law configuration: 4 per SIMD is 2-4 % faster than 5 or 8,
-    // 3 and fewer are slower.
-    static const int lds = env_int("GAS_SPMM_CHUNK_LDS", 33000, 0, 160 * 1024);
-    hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF, VB>), dim3((unsigned)blocks), dim3(256), lds, s, a);
+    hipLaunchKernelGGL((spmm_chunk_kernel<G, UPT, U, XBF, VB>), dim3((unsigned)blocks), dim3(256), 0, s, a);
     return GAS_OK;
 }
 
 template <bool XBF>
 gas_status dispatch_chunks(const SpmmArgs& a, hipStream_t s) {
-    const int u = a.slice_units;
-    if (a.n_slices == 1 && a.units == 64) return launch_chunks<64, 1, 8, XBF, 16>(a, s);
-    if (a.n_slices == 1 && a.units == 32) return launch_chunks<32, 1, 8, XBF, 8>(a, s);
+    const int u = a.units;
+    if (u == 64) return launch_chunks<64, 1, 8, XBF, 16>(a, s);
+    if (u == 32) return launch_chunks<32, 1, 8, XBF, 8>(a, s);
     if (u <= 8) return launch_chunks<8, 1, 8, XBF>(a, s);
     if (u <= 16) return launch_chunks<16, 1, 8, XBF>(a, s);
     if (u <= 32) return launch_chunks<32, 1, 8, XBF>(a, s);
@@ -639,9 +624,6 @@ gas_status run_spmm(const char* who, const gas_plan* plan, const int32_t* ptr, c
     a.diag = diag; a.s_agg = s_agg; a.s_res = s_res;
     a.n_rows = plan->n_rows; a.n_diag = n_diag;
     a.units = (F * xb) / 16; a.F = F;
-    a.n_slices = plan->slices;
-    while (a.n_slices > 1 && (a.units % a.n_slices != 0)) a.n_slices >>= 1;
-    a.slice_units = a.units / (a.n_slices > 0 ? a.n_slices : 1);
     a.threshold = plan->threshold;
     a.chunk = plan->d_chunk; a.n_chunks = plan->n_chunks;
     a.heavy = plan->d_heavy; a.n_heavy = plan->n_heavy;
@@ -674,13 +656,6 @@ __global__ __launch_bounds__(256) void fuse_sources_kernel(const int32_t* __rest
     src[k] = c < nb ? c : -1 - n_id[c];
 }
 
-int env_int(const char* name, int dflt, int lo, int hi) {
-    const char* e = getenv(name);
-    if (!e || !*e) return dflt;
-    const long v = strtol(e, nullptr, 10);
-    return (v < lo || v > hi) ? dflt : (int)v;
-}
-
 }  // namespace
 }  // namespace gas
 
@@ -688,214 +663,83 @@ using namespace gas;
 
 extern "C" {
 
-gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
-                           void* stream, gas_plan** out) {
+gas_status gas_plan_create_opt(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
+                               const gas_plan_options* opt, void* stream, gas_plan** out) {
     GAS_REQUIRE(out, "gas_plan_create: null output");
     *out = nullptr;
     GAS_REQUIRE(n_rows >= 0 && n_rows < 0x7FFFFFF0LL && nnz >= 0 && nnz < 0x7FFFFFF0LL && max_F > 0,
                 "gas_plan_create: n_rows=%lld nnz=%lld max_F=%d", (long long)n_rows, (long long)nnz, max_F);
     GAS_REQUIRE(ptr || n_rows == 0, "gas_plan_create: null row pointer array");
+    PlanParams pp;
+    pp.wshift = plan_default_wshift(max_F);
+    if (opt) {
+        GAS_REQUIRE(opt->heavy_threshold >= 0 && opt->chunk >= 0 && opt->min_chunk >= 0 && opt->window_rows >= -1 &&
+                    opt->xcd_ranges >= 0 && opt->xcd_ranges <= 2,
+                    "gas_plan_create: options out of range (threshold %d, chunk %d, min_chunk %d, window_rows %d, "
+                    "xcd_ranges %d)", opt->heavy_threshold, opt->chunk, opt->min_chunk, opt->window_rows, opt->xcd_ranges);
+        if (opt->heavy_threshold > 0) pp.threshold = opt->heavy_threshold;
+        if (opt->chunk > 0) pp.chunk = opt->chunk;
+        if (opt->min_chunk > 0) pp.min_chunk = opt->min_chunk;
+        if (opt->window_rows < 0) pp.wshift = -1;
+        else if (opt->window_rows > 0) {                 // rounded down to a power of two
+            pp.wshift = 0;
+            while ((2ll << pp.wshift) <= opt->window_rows) ++pp.wshift;
+        }
+        pp.xcd_mode = opt->xcd_ranges;
+    }
     hipStream_t s = (hipStream_t)stream;
     gas_plan* p = new gas_plan();
     p->n_rows = n_rows; p->nnz = nnz; p->max_F = max_F;
-    p->threshold = env_int("GAS_SPMM_HEAVY", 512, 1, 1 << 24);
-    p->chunk = env_int("GAS_SPMM_CHUNK", 256, 32, 1 << 24);
-    p->slices = env_int("GAS_SPMM_SLICES", 1, 1, 8);
-    if (p->slices & (p->slices - 1)) p->slices = 1;
+    p->threshold = pp.threshold; p->chunk = pp.chunk;
     (void)hipGetDevice(&p->device);
-    std::vector<int32_t> h_ptr((size_t)n_rows + 1, 0);
+    std::vector<int32_t> h_ptr((size_t)n_rows + 1, 0), h_ind;
+    hipError_t e = hipSuccess;
     if (n_rows > 0) {
-        hipError_t e = hipMemcpyAsync(h_ptr.data(), ptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost, s);
+        e = hipMemcpyAsync(h_ptr.data(), ptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ptr failed: %s", hipGetErrorString(e)); }
-        if (h_ptr[0] != 0 || h_ptr[n_rows] != nnz) {
+        const int64_t bad = plan_validate_ptr(h_ptr.data(), n_rows, nnz);
+        if (bad) {
             delete p;
-            return fail(GAS_ERR_ARG, "gas_plan_create: ptr[0]=%d ptr[n_rows]=%d do not match nnz=%lld", h_ptr[0],
-                        h_ptr[n_rows], (long long)nnz);
+            if (bad > n_rows)
+                return fail(GAS_ERR_ARG, "gas_plan_create: ptr[0]=%d ptr[n_rows]=%d do not match nnz=%lld", h_ptr[0],
+                            h_ptr[n_rows], (long long)nnz);
+            return fail(GAS_ERR_ARG, "gas_plan_create: ptr decreases or leaves [0, nnz] at row %lld", (long long)(bad - 1));
         }
     }
-    // Heavy rows are cut into chunks.  With the column indices at hand a chunk also ends where the (sorted)
-    // columns of the row cross a multiple of `window`, and the chunks are then processed window by window:
-    // wavefronts that run at the same time gather from the same range of feature rows, which therefore stay
-    // in the caches between their uses.  The partial sums keep their row-major slots, so the order in which
-    // a row's partials are added does not depend on the processing order.
-    // The window is at least GAS_SPMM_WINDOW rows (default 32768, 32 MB of 1 KiB rows; 0 turns windows off) and
-    // wide enough that an average heavy row keeps about 32 entries per window: narrower windows would shred
-    // the rows into tiny chunks whose partial sums cost more traffic than the reuse saves.
-    int64_t window = env_int("GAS_SPMM_WINDOW", 32768, 0, 1 << 30);
-    std::vector<int32_t> h_ind;
-    int64_t n_heavy_rows = 0, heavy_entries = 0;
-    for (int64_t r = 0; r < n_rows; ++r) {
-        const int64_t len = h_ptr[r + 1] - h_ptr[r];
-        if (len > p->threshold) { ++n_heavy_rows; heavy_entries += len; }
-    }
-    const int xcd_mode = env_int("GAS_SPMM_XCD", 2, 0, 2);       // 0 never, 1 always, 2 where the pattern is clustered
-    const bool windowed = ind && window > 0 && n_heavy_rows > 0;
-    if (windowed || (ind && xcd_mode == 2 && nnz > 0)) {
+    if (ind && nnz > 0) {
         h_ind.resize((size_t)nnz);
-        // through pinned chunks of the library's own staging buffer (a pageable destination takes four times as long)
-        static std::mutex stage_mutex;
-        static int32_t* stage = nullptr;
-        constexpr int64_t kStage = 16 << 20;                                // entries (64 MB), allocated on first use
-        std::lock_guard<std::mutex> lock(stage_mutex);
-        hipError_t e = hipSuccess;
-        if (!stage && hipHostMalloc(reinterpret_cast<void**>(&stage), kStage * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
-            stage = nullptr;
-            (void)hipGetLastError();                                         // no pinned memory: copy directly
-            e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
-            if (e == hipSuccess) e = hipStreamSynchronize(s);
-        } else {
-            for (int64_t k0 = 0; k0 < nnz && e == hipSuccess; k0 += kStage) {
-                const int64_t cnt = std::min<int64_t>(kStage, nnz - k0);
-                e = hipMemcpyAsync(stage, ind + k0, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost, s);
-                if (e == hipSuccess) e = hipStreamSynchronize(s);
-                if (e == hipSuccess) memcpy(h_ind.data() + k0, stage, sizeof(int32_t) * cnt);
-            }
-        }
+        e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
-        int64_t max_col = 0;
-        for (int64_t r = 0; windowed && r < n_rows; ++r)
-            if (h_ptr[r + 1] - h_ptr[r] > p->threshold) {      // rows are ascending: look at both ends
-                for (int32_t k : {h_ptr[r], h_ptr[r + 1] - 1}) {
-                    const int64_t v = h_ind[k] >= 0 ? h_ind[k] : -1 - (int64_t)h_ind[k];
-                    if (v > max_col) max_col = v;
-                }
-            }
-        if (windowed) {
-            const int64_t keep32 = (max_col + 1) * 32 / (heavy_entries / n_heavy_rows);
-            if (keep32 > window) window = keep32;
-        }
     }
-    std::vector<int32_t> chunk, heavy_row, heavy_first, group, chunk_window;
-    const bool grouping = env_int("GAS_SPMM_GROUPS", 1, 0, 1) != 0;
-    int64_t g_start = -1;          // first row of the open group, -1 if none
-    int32_t g_entries = 0;
-    auto close_group = [&](int64_t end_row) {
-        if (g_start >= 0) { group.push_back((int32_t)g_start); group.push_back((int32_t)end_row); }
-        g_start = -1; g_entries = 0;
+    PlanArrays pa;
+    build_plan_host(h_ptr.data(), h_ind.empty() ? nullptr : h_ind.data(), n_rows, nnz, pp, pa);
+    p->n_heavy = pa.n_heavy; p->n_chunks = pa.n_chunks; p->n_groups = pa.n_groups;
+    p->xcd_ranges = pa.xcd_ranges;
+    for (int x = 0; x < 9; ++x) p->xcd_start[x] = pa.xcd_start[x];
+    auto upload = [&](int32_t** dst, const std::vector<int32_t>& v) -> hipError_t {
+        if (v.empty()) return hipSuccess;
+        hipError_t r = hipMalloc(dst, v.size() * sizeof(int32_t));
+        if (r == hipSuccess) r = hipMemcpyAsync(*dst, v.data(), v.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        return r;
     };
-    for (int64_t r = 0; r < n_rows; ++r) {
-        const int32_t b = h_ptr[r], e = h_ptr[r + 1];
-        if (e < b) { delete p; return fail(GAS_ERR_ARG, "gas_plan_create: ptr decreases at row %lld", (long long)r); }
-        if (grouping) {
-            // groups are runs of consecutive light rows: <= 64 entries and <= 63 rows, or one row alone
-            const int32_t len = e - b;
-            if (len > p->threshold) {
-                close_group(r);
-            } else {
-                if (g_start >= 0 && (g_entries + len > 64 || r - g_start >= 63)) close_group(r);
-                if (g_start < 0) g_start = r;
-                g_entries += len;
-            }
-        }
-        if (e - b > p->threshold) {
-            heavy_row.push_back((int32_t)r);
-            heavy_first.push_back((int32_t)(chunk.size() / 3));
-            if (!windowed) {
-                for (int32_t c = b; c < e; c += p->chunk) {
-                    chunk.push_back((int32_t)(chunk.size() / 3));      // slot of the partial sum
-                    chunk.push_back(c);
-                    chunk.push_back(c + p->chunk < e ? c + p->chunk : e);
-                }
-            } else {
-                int32_t c = b;
-                while (c < e) {
-                    // negative indices (history rows of the in-place variant) order like their magnitudes
-                    auto mag = [&](int32_t k) { const int64_t v = h_ind[k]; return v >= 0 ? v : -1 - v; };
-                    const int32_t w = (int32_t)(mag(c) / window);
-                    const int64_t lo = (int64_t)w * window, hi = lo + window;      // the window of this chunk
-                    const int32_t limit = c + p->chunk < e ? c + p->chunk : e;
-                    int32_t stop = c + 1;
-                    while (stop < limit) {
-                        const int64_t v = mag(stop);
-                        if (v < lo || v >= hi) break;
-                        ++stop;
-                    }
-                    chunk.push_back((int32_t)(chunk.size() / 3));
-                    chunk.push_back(c);
-                    chunk.push_back(stop);
-                    chunk_window.push_back(w);
-                    c = stop;
-                }
-            }
-        }
-    }
-    close_group(n_rows);
-    p->n_heavy = (int64_t)heavy_row.size();
-    p->n_chunks = (int64_t)chunk.size() / 3;
-    if (!chunk_window.empty()) {
-        // counting sort by window; chunks of one window keep their row order
-        int32_t n_windows = 0;
-        for (int32_t w : chunk_window) n_windows = std::max(n_windows, w + 1);
-        std::vector<int64_t> first((size_t)n_windows + 1, 0);
-        for (int32_t w : chunk_window) ++first[(size_t)w + 1];
-        for (int32_t w = 0; w < n_windows; ++w) first[(size_t)w + 1] += first[w];
-        std::vector<int32_t> sorted(chunk.size());
-        for (size_t i = 0; i < chunk_window.size(); ++i) {
-            const size_t at = (size_t)first[chunk_window[i]]++;
-            for (int q = 0; q < 3; ++q) sorted[3 * at + q] = chunk[3 * i + q];
-        }
-        chunk.swap(sorted);
-    }
-    if (!group.empty()) {
-        // Ranges of groups of equal cost (entries gathered + rows written), one per XCD; used when the pattern is
-        // clustered: GAS_SPMM_XCD=1 always, 0 never, otherwise when at least 30 % of the entries of light rows name
-        // a row of their own range (a partition into clusters does that, a graph without communities stays near 0).
-        const int64_t ng = (int64_t)group.size() / 2;
-        std::vector<int64_t> cost((size_t)ng + 1, 0);
-        for (int64_t i = 0; i < ng; ++i)
-            cost[i + 1] = cost[i] + (h_ptr[group[2 * i + 1]] - h_ptr[group[2 * i]]) + (group[2 * i + 1] - group[2 * i]);
-        for (int x = 0; x <= 8; ++x) {
-            const int64_t target = cost[ng] * x / 8;
-            p->xcd_start[x] = x == 8 ? ng : std::lower_bound(cost.begin(), cost.end(), target) - cost.begin();
-        }
-        p->xcd_ranges = xcd_mode == 1;
-        if (xcd_mode == 2 && !h_ind.empty()) {
-            int64_t local = 0, seen = 0;
-            for (int x = 0; x < 8; ++x) {
-                if (p->xcd_start[x] >= p->xcd_start[x + 1]) continue;
-                const int64_t r0 = group[2 * p->xcd_start[x]], r1 = group[2 * (p->xcd_start[x + 1] - 1) + 1];
-                const int64_t step = std::max<int64_t>(1, (p->xcd_start[x + 1] - p->xcd_start[x]) / 4096);   // sample
-                for (int64_t i = p->xcd_start[x]; i < p->xcd_start[x + 1]; i += step)
-                    for (int32_t k = h_ptr[group[2 * i]]; k < h_ptr[group[2 * i + 1]]; ++k) {
-                        ++seen;
-                        local += h_ind[k] >= r0 && h_ind[k] < r1;
-                    }
-            }
-            p->xcd_ranges = seen > 0 && 10 * local >= 3 * seen;
-        }
-            const std::vector<int32_t>& bounds = group;      // [first row, end row) of every group
-        p->n_groups = (int64_t)group.size() / 2;
-        hipError_t e = hipMalloc(&p->d_group, bounds.size() * sizeof(int32_t));
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(p->d_group, bounds.data(), bounds.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) {
-            gas_plan_destroy(p);
-            return fail(GAS_ERR_NOMEM, "gas_plan_create: group list: %s", hipGetErrorString(e));
-        }
-    }
-    if (p->n_heavy > 0) {
-        heavy_first.push_back((int32_t)p->n_chunks);
-        heavy_row.insert(heavy_row.end(), heavy_first.begin(), heavy_first.end());
-        hipError_t e = hipMalloc(&p->d_chunk, chunk.size() * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(&p->d_heavy, heavy_row.size() * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(&p->d_partial, (size_t)p->n_chunks * max_F * sizeof(float));
-        if (e != hipSuccess) {
-            gas_plan_destroy(p);
-            return fail(GAS_ERR_NOMEM, "gas_plan_create: device allocation failed: %s", hipGetErrorString(e));
-        }
-        e = hipMemcpyAsync(p->d_chunk, chunk.data(), chunk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(p->d_heavy, heavy_row.data(), heavy_row.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) {
-            gas_plan_destroy(p);
-            return fail(GAS_ERR_HIP, "gas_plan_create: upload failed: %s", hipGetErrorString(e));
-        }
+    e = upload(&p->d_group, pa.group);
+    if (e == hipSuccess) e = upload(&p->d_chunk, pa.chunk);
+    if (e == hipSuccess) e = upload(&p->d_heavy, pa.heavy);
+    if (e == hipSuccess && p->n_chunks > 0) e = hipMalloc(&p->d_partial, (size_t)p->n_chunks * max_F * sizeof(float));
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        gas_plan_destroy(p);
+        return fail(GAS_ERR_NOMEM, "gas_plan_create: device allocation or upload failed: %s", hipGetErrorString(e));
     }
     *out = p;
     return GAS_OK;
+}
+
+gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
+                           void* stream, gas_plan** out) {
+    return gas_plan_create_opt(ptr, ind, n_rows, nnz, max_F, nullptr, stream, out);
 }
 
 void gas_plan_destroy(gas_plan* p) {

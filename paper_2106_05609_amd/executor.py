@@ -21,27 +21,46 @@ from . import binding as B
 class BatchGraph:
     """Device-side index structure of one batch subgraph plus its plans."""
 
-    def __init__(self, nb, n_id, rowptr, col, deg=None, colptr=None, row=None, max_F=256, normalise=True):
+    def __init__(self, nb, n_id, rowptr, col, deg=None, colptr=None, row=None, max_F=256, normalise=True, timed=False,
+                 plan_options=None):
+        """timed: wait for the device after each part of the per-batch set-up and keep its wall time in
+        self.setup_ms (plans, coefficients, fused source indices); the benchmark reports it."""
+        import time
+        self.setup_ms = {}
+
+        def part(name, fn):
+            if not timed:
+                return fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            out = fn()
+            torch.cuda.synchronize()
+            self.setup_ms[name] = round((time.perf_counter() - t0) * 1e3, 3)
+            return out
+
         self.nb, self.nv = int(nb), int(n_id.numel())
         self.n_id, self.rowptr, self.col = n_id, rowptr, col
         self.nnz = int(col.numel())
         self.max_row = int((rowptr[1:] - rowptr[:-1]).max().item()) if self.nb > 0 else 0
-        self.plan = B.gas_plan_create(rowptr, self.nnz, max_F, ind=col)
+        self.plan = part("plan_csr", lambda: B.gas_plan_create(rowptr, self.nnz, max_F, ind=col, options=plan_options))
         self.val = None
         if normalise:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
-            B.gas_gcn_norm(rowptr, col, n_id, deg, self.val)
+            part("gcn_norm_csr", lambda: B.gas_gcn_norm(rowptr, col, n_id, deg, self.val))
         self._src = None
         self._plan_t_all, self._max_F = None, max_F
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
         if colptr is not None:
             # backward over the in-batch columns only: histories are constants
-            self.plan_t = B.gas_plan_create(colptr[: self.nb + 1], int(colptr[self.nb].item()), max_F, n_rows=self.nb,
-                                              ind=row)
+            nnz_t = int(colptr[self.nb].item())
+            self.plan_t = part("plan_csc", lambda: B.gas_plan_create(colptr[: self.nb + 1], nnz_t, max_F,
+                                                                     n_rows=self.nb, ind=row, options=plan_options))
             if normalise:
                 self.val_t = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
-                B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t)
-
+                part("gcn_norm_csc", lambda: B.gas_gcn_norm(colptr, row, n_id, deg, self.val_t))
+        if timed:
+            part("fuse_sources", lambda: self.src)
+            self.setup_ms["total"] = round(sum(self.setup_ms.values()), 3)
 
     @property
     def plan_t_all(self):
@@ -221,7 +240,7 @@ def forward_batch(model: Model, bg: BatchGraph, x_feat, histories, do_push=True,
 
 
 class HostPipeline:
-    """Streams for histories kept in host memory (Section 4 of the paper: history access runs beside the
+    """Streams for histories kept in host memory (Section 5 "PyGAS" of the paper: history access runs beside the
     computation).  One stream carries the pulls, one the pushes, both at the default priority.  The mini-batch
     tensors the transfers touch belong to the pipeline: two sets, used by alternate batches, so that a batch can
     compute while the pushes of the one before still read its tensors.  Events: `table_pushed[l]`, the end of the
@@ -439,13 +458,13 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             grads[l - 1] = weight_grad(z, g, beta)
             B.gas_linear_bwd_input(g, model.weights[l - 1], gz, c_identity=1.0 - beta, c_weight=beta)
             if g_h0 is None:
-                g_h0 = torch.zeros((nv, gz.shape[1]), dtype=torch.float32, device=dev)
-            g_h0[:nb] += model.alpha * gz.float()        # small accumulation on the side (fp32), not a hot-path step
+                g_h0 = torch.zeros((nv, gz.shape[1]), dtype=dt, device=dev)
+            B.gas_axpy(g_h0[:nb], gz, g_h0[:nb], model.alpha)      # the initial residual's share: g_h0 += alpha * gz
         if l == 1:
             if model.op == "gcnii":
                 gx = torch.empty((nv, gz.shape[1]), dtype=dt, device=dev)
                 B.gas_spmm_t(bg.plan_t_all, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
-                g_h0 += gx.float()
+                B.gas_axpy(g_h0, gx, g_h0, 1.0)
             break
         gx = torch.empty((nb, gz.shape[1]), dtype=dt, device=dev)
         if model.op == "gin":
@@ -456,9 +475,8 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, gz, gx, s_agg=1.0 - model.alpha)
         g = gx
     if model.op == "gcnii":
-        gh0 = g_h0.to(dt)
-        gp = torch.empty_like(gh0)
-        B.gas_relu_bwd(gh0, h0, gp)
+        gp = torch.empty_like(g_h0)
+        B.gas_relu_bwd(g_h0, h0, gp)
         grads["w_in"] = weight_grad(x0, gp)
     return y, grads, {"x0": x0, "h0": h0, "layers": saved}
 
@@ -494,7 +512,7 @@ def layer_input(model: Model, l, bg: BatchGraph, kept, histories):
         return kept["h0"] if model.op == "gcnii" else kept["x0"]
     y = kept["layers"][l - 2][2]
     x = torch.empty((bg.nv, y.shape[1]), dtype=y.dtype, device=y.device)
-    x[:bg.nb].copy_(y)
+    B.gas_pull(y, None, x[:bg.nb], base=0, n=bg.nb)
     if bg.nv > bg.nb:
         B.gas_pull(histories[l - 2], bg.n_id[bg.nb:], x[bg.nb:])
     return x

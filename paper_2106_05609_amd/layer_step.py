@@ -1,5 +1,5 @@
-"""One middle-layer GAS step on one mini-batch, as the benchmark times it and
-the full-size parity tests check it: buffers are torch allocations, every
+"""One GAS layer step on one mini-batch, as the benchmark times it and the
+full-size parity tests check it: buffers are torch allocations, every
 operation is a C-ABI call.
 
     gas_pull    halo rows of the mini-batch tensor <- history table l
@@ -12,6 +12,15 @@ The in-place form of the same step is three calls: gas_spmm_hist (halo rows
 read from the history table by the aggregation itself), gas_linear_push /
 gas_mlp2_push (the transform stores each output row to its history slot as
 well), gas_spmm_t.
+
+Three kinds of layer (Algorithm 1 treats them differently):
+  "first"   the input is exact for every node of V_b: ALL rows of the
+            mini-batch tensor are gathered from the feature table (no history
+            is read); the output is pushed; no backward aggregation (features
+            take no gradient).  In place: only the in-batch rows are gathered,
+            the aggregation reads the other rows from the feature table.
+  "middle"  hidden width in and out, pull + push, backward aggregation.
+  "last"    no ReLU, nothing is pushed; backward aggregation.
 """
 import torch
 
@@ -19,46 +28,67 @@ from . import binding as B
 from . import executor
 
 NAMES = ["pull", "spmm", "linear", "push", "spmm_t"]
+KINDS = ("first", "middle", "last")
 
 
 class LayerStep:
-    def __init__(self, cfg, g, sg, rng, device):
+    def __init__(self, cfg, g, sg, rng, device, kind="middle", bg=None, plan_options=None):
         """cfg: benchmark configuration, g: graph, sg: batch subgraph (index tensors on `device`),
-        rng: the seeded generator module for the synthetic tensors."""
-        self.cfg, self.sg = cfg, sg
+        rng: the seeded generator module for the synthetic tensors, bg: the batch's plans if already built."""
+        assert kind in KINDS
+        self.cfg, self.sg, self.kind = cfg, sg, kind
         self.nb, self.nh, self.nv, self.nnz = sg.nb, sg.nh, sg.nv, sg.nnz
         self.nnz_t = int(sg.colptr[sg.nb].item())
-        F = self.F = cfg.widths[-2]
+        hidden = cfg.widths[-2]
+        self.F_in = cfg.widths[0] if kind == "first" else hidden
+        self.F_out = cfg.widths[-1] if kind == "last" else hidden
+        self.F = self.F_in
+        self.does_push = kind != "last"
+        self.does_spmm_t = kind != "first"
+        self.relu = kind != "last"
         dt = self.dt = cfg.dtype
         self.gin = cfg.op == "gin"
-        self.bg = executor.BatchGraph(sg.nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row, max_F=F,
-                                      normalise=not self.gin)
-        nb, nv = self.nb, self.nv
-        self.hist_in = rng.normal_matrix(cfg.seed, 200, cfg.n, F, device, dt)
-        self.hist_out = torch.zeros((cfg.n, F), dtype=dt, device=device)
-        self.x = rng.normal_matrix(cfg.seed, 210, nv, F, device, dt)     # rows 0..nb-1: fresh in-batch embeddings
-        self.x[nb:] = 0                                                  # halo rows arrive through gas_pull
-        self.z = torch.empty((nb, F), dtype=dt, device=device)
-        self.x_next = torch.empty((nv, F), dtype=dt, device=device)
-        self.gz = rng.normal_matrix(cfg.seed, 211, nb, F, device, dt)    # upstream gradient for the backward aggregation
-        self.gx = torch.empty((nb, F), dtype=dt, device=device)
-        if self.gin:
-            self.w1 = rng.glorot_uniform(cfg.seed, 102, F, cfg.gin_hidden, device, dt)
-            self.w2 = rng.glorot_uniform(cfg.seed, 103, cfg.gin_hidden, F, device, dt)
+        if bg is None:
+            bg = executor.BatchGraph(sg.nb, sg.n_id, sg.rowptr, sg.col, g.deg, sg.colptr, sg.row, max_F=max(cfg.widths),
+                                     normalise=not self.gin, timed=True, plan_options=plan_options)
+        self.bg = bg
+        nb, nv, Fi, Fo = self.nb, self.nv, self.F_in, self.F_out
+        # the table the rows outside the batch come from: the feature table for the first layer, else history l
+        self.hist_in = rng.normal_matrix(cfg.seed, 10 if kind == "first" else 200, cfg.n, Fi, device, dt)
+        self.hist_out = torch.zeros((cfg.n, Fo), dtype=dt, device=device) if self.does_push else None
+        if kind == "first":
+            self.x = torch.zeros((nv, Fi), dtype=dt, device=device)      # every row arrives through gas_pull
         else:
-            self.w = rng.glorot_uniform(cfg.seed, 101, F, F, device, dt)
-        self.h0 = rng.normal_matrix(cfg.seed, 212, nb, F, device, dt) if cfg.op == "gcnii" else None
+            self.x = rng.normal_matrix(cfg.seed, 210, nv, Fi, device, dt)    # rows 0..nb-1: fresh in-batch embeddings
+            self.x[nb:] = 0                                              # halo rows arrive through gas_pull
+        self.z = torch.empty((nb, Fi), dtype=dt, device=device)
+        self.x_next = torch.empty((nv if self.does_push else nb, Fo), dtype=dt, device=device)
+        if self.does_spmm_t:
+            self.gz = rng.normal_matrix(cfg.seed, 211, nb, Fi, device, dt)   # upstream gradient for the backward aggregation
+            self.gx = torch.empty((nb, Fi), dtype=dt, device=device)
+        else:
+            self.gz = self.gx = None
+        if self.gin:
+            self.w1 = rng.glorot_uniform(cfg.seed, 102, Fi, cfg.gin_hidden, device, dt)
+            self.w2 = rng.glorot_uniform(cfg.seed, 103, cfg.gin_hidden, Fo, device, dt)
+        else:
+            self.w = rng.glorot_uniform(cfg.seed, 101, Fi, Fo, device, dt)
+        self.h0 = rng.normal_matrix(cfg.seed, 212, nb, Fi, device, dt) if cfg.op == "gcnii" else None
         self.beta = executor.gcnii_beta(2)
         self.diag = (1.0 + cfg.gin_eps) if self.gin else 0.0
 
     def run(self, mark=None, skip_spmm_t=False, fused=False):
-        """fused: the aggregation reads the halo rows from the history table itself
+        """fused: the aggregation reads the rows outside the batch from their table itself
         (gas_spmm_hist) and the transform pushes its output rows (gas_linear_push /
-        gas_mlp2_push); the pull and push launches disappear."""
+        gas_mlp2_push); the push launch disappears, and the pull launch too (for the
+        first layer it shrinks to the in-batch rows)."""
         cfg, bg, nb = self.cfg, self.bg, self.nb
         mark = mark or (lambda i: None)
         mark(0)
-        if not fused:
+        if self.kind == "first":
+            n_pull = nb if fused else self.nv
+            B.gas_pull(self.hist_in, bg.n_id[:n_pull], self.x[:n_pull])
+        elif not fused:
             B.gas_pull(self.hist_in, bg.n_id[nb:], self.x[nb:])
         mark(1)
         if fused:
@@ -78,12 +108,12 @@ class LayerStep:
         else:
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, bg.val, self.x, self.z)
         mark(2)
-        self.transform(push=fused)
+        self.transform(push=fused and self.does_push)
         mark(3)
-        if not fused:
+        if not fused and self.does_push:
             B.gas_push(self.x_next[:nb], bg.n_id[:nb], self.hist_out)
         mark(4)
-        if not skip_spmm_t:
+        if self.does_spmm_t and not skip_spmm_t:
             B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, self.gz, self.gx, diag=self.diag)
         mark(5)
 
@@ -94,33 +124,36 @@ class LayerStep:
         y, idx = self.x_next[:nb], self.bg.n_id[:nb]
         if self.gin:
             if push:
-                B.gas_mlp2_push(self.z, self.w1, self.w2, y, idx, self.hist_out, relu_out=True)
+                B.gas_mlp2_push(self.z, self.w1, self.w2, y, idx, self.hist_out, relu_out=self.relu)
             else:
-                B.gas_mlp2(self.z, self.w1, self.w2, y, relu_out=True)
+                B.gas_mlp2(self.z, self.w1, self.w2, y, relu_out=self.relu)
             return
-        c_id, c_w = (1.0 - self.beta, self.beta) if cfg.op == "gcnii" else (0.0, 1.0)
+        gcnii = cfg.op == "gcnii" and self.F_in == self.F_out
+        c_id, c_w = (1.0 - self.beta, self.beta) if gcnii else (0.0, 1.0)
         if push:
-            B.gas_linear_push(self.z, self.w, y, idx, self.hist_out, c_identity=c_id, c_weight=c_w, relu=True)
+            B.gas_linear_push(self.z, self.w, y, idx, self.hist_out, c_identity=c_id, c_weight=c_w, relu=self.relu)
         else:
-            B.gas_linear(self.z, self.w, y, c_identity=c_id, c_weight=c_w, relu=True)
+            B.gas_linear(self.z, self.w, y, c_identity=c_id, c_weight=c_w, relu=self.relu)
 
     def algorithmic_bytes(self):
         """Bytes each call must move at least once (indices and values once, every
         needed feature row once, every output row once)."""
-        F, s = self.F, (4 if self.dt == torch.float32 else 2)
+        Fi, Fo, s = self.F_in, self.F_out, (4 if self.dt == torch.float32 else 2)
         nb, nh, nv, nnz, nnz_t = self.nb, self.nh, self.nv, self.nnz, self.nnz_t
         vb = 0 if self.gin else 4
+        hid = self.cfg.gin_hidden
+        n_pull = nv if self.kind == "first" else nh
         return {
-            "pull": nh * (2 * F * s + 4),
-            "spmm": nnz * (4 + vb) + (nb + 1) * 4 + nv * F * s + nb * F * s,
-            "linear": nb * 2 * F * s + F * F * s * (2 if self.gin else 1),
-            "push": nb * (2 * F * s + 4),
-            "push_in_epilogue": nb * (F * s + 4),       # the transform already holds the row: only the store is left
-            "spmm_t": nnz_t * (4 + vb) + (nb + 1) * 4 + nb * F * s + nb * F * s,
-            "spmm_no_reuse": nnz * (4 + vb) + (nb + 1) * 4 + nnz * F * s + nb * F * s,
+            "pull": n_pull * (2 * Fi * s + 4),
+            "pull_in_place": nb * (2 * Fi * s + 4) if self.kind == "first" else 0,
+            "spmm": nnz * (4 + vb) + (nb + 1) * 4 + nv * Fi * s + nb * Fi * s,
+            "linear": nb * (Fi + Fo) * s + ((Fi * hid + hid * Fo) if self.gin else Fi * Fo) * s,
+            "push": nb * (2 * Fo * s + 4) if self.does_push else 0,
+            "push_in_epilogue": nb * (Fo * s + 4) if self.does_push else 0,   # the transform holds the row: only the store is left
+            "spmm_t": (nnz_t * (4 + vb) + (nb + 1) * 4 + nb * Fi * s + nb * Fi * s) if self.does_spmm_t else 0,
+            "spmm_no_reuse": nnz * (4 + vb) + (nb + 1) * 4 + nnz * Fi * s + nb * Fi * s,
         }
 
-    def fused_algorithmic_bytes(self):
-        """The fused aggregation reads the same rows once (in-batch from X, halo
-        from the history table) and writes Z; no halo copy is written or re-read."""
-        return self.algorithmic_bytes()["spmm"]
+    def flops(self):
+        Fi, Fo, hid = self.F_in, self.F_out, self.cfg.gin_hidden
+        return 2.0 * self.nb * ((Fi * hid + hid * Fo) if self.gin else Fi * Fo)

@@ -43,27 +43,43 @@ def _sub_pattern(ptr_dev, ind_dev, rows: np.ndarray):
     return sub_ptr, inv.astype(np.int32), pos, cols
 
 
-def _check_step(cfg_id):
+def _check_config(cfg_id):
+    """The middle layer (the benchmark's headline), then the first layer (every row of V_b gathered from the
+    feature table, input width) and the last one (no ReLU, nothing pushed) on the same batch and plans."""
     from paper_2106_05609_amd.layer_step import LayerStep
     dev = torch.device("cuda:0")
     cfg = configs.config(cfg_id)
     g = configs.build_graph(cfg, device=dev)
     bl = batches.split(g, cfg.blocks_per_batch, cfg.seed)
     sg = batches.batch_subgraph(g, bl[0], cfg.self_loops)
-    ls = LayerStep(cfg, g, sg, rng, dev)
+    bg, mid = None, None
+    for kind in ("middle", "first", "last"):
+        ls = LayerStep(cfg, g, sg, rng, dev, kind=kind, bg=bg)
+        bg = ls.bg
+        _check_step(cfg, g, sg, ls, dev)
+        if kind == "middle":
+            mid = (ls.nb, ls.nnz, ls.F, ls.dt)
+        del ls
+        torch.cuda.empty_cache()
+    return mid
+
+
+def _check_step(cfg, g, sg, ls, dev):
     nb, nv, F, tol = ls.nb, ls.nv, ls.F, TOL[cfg.dtype]
     ls.run()
     ls.run()                                            # a second pass over the same buffers: same result
     torch.cuda.synchronize()
     n_id = sg.n_id.long()
 
-    # ---- pull: every halo row, bit for bit
+    # ---- pull: every pulled row, bit for bit (first layer: all of V_b from the feature table; else the halo rows)
     bits = torch.int32 if cfg.dtype == torch.float32 else torch.int16
-    want_halo = ls.hist_in[n_id[nb:]]
-    assert torch.equal(ls.x[nb:].view(bits), want_halo.view(bits))
-    samp = torch.from_numpy(np.random.default_rng(1).choice(ls.nh, 512, replace=False)).to(dev)
-    got = to_np(ls.x[nb:][samp])
-    table_rows = to_np(ls.hist_in[n_id[nb:][samp]])     # the rows the oracle's pull must return
+    p0 = 0 if ls.kind == "first" else nb
+    want_rows = ls.hist_in[n_id[p0:]]
+    assert torch.equal(ls.x[p0:].view(bits), want_rows.view(bits))
+    del want_rows
+    samp = torch.from_numpy(np.random.default_rng(1).choice(nv - p0, 512, replace=False)).to(dev)
+    got = to_np(ls.x[p0:][samp])
+    table_rows = to_np(ls.hist_in[n_id[p0:][samp]])     # the rows the oracle's pull must return
     assert np.array_equal(got, oops.pull(table_rows, np.arange(512, dtype=np.int32)))
 
     # ---- aggregation on sampled rows
@@ -93,26 +109,56 @@ def _check_step(cfg_id):
     else:
         want_z = oops.spmm(sub_ptr, sub_col, val, x_rows)
     e = node_rel_err(to_np(ls.z[rows_dev]), want_z)
-    assert e <= tol, ("spmm", e)
+    assert e <= tol, ("spmm", ls.kind, e)
 
     # ---- transform on sampled rows (input: the library's own Z rows)
     z_rows = to_np(ls.z[rows_dev])
     if ls.gin:
-        want_y = oops.mlp2(z_rows, to_np(ls.w1), to_np(ls.w2), relu_out=True)
+        want_y = oops.mlp2(z_rows, to_np(ls.w1), to_np(ls.w2), relu_out=ls.relu)
     else:
-        want_y = oops.linear(z_rows, to_np(ls.w), relu=True)
+        want_y = oops.linear(z_rows, to_np(ls.w), relu=ls.relu)
     e = node_rel_err(to_np(ls.x_next[rows_dev]), want_y)
-    assert e <= tol, ("linear", e)
+    assert e <= tol, ("linear", ls.kind, e)
 
     # ---- push: every in-batch row landed, bit for bit; nothing else was touched
-    assert torch.equal(ls.hist_out[n_id[:nb]].view(bits), ls.x_next[:nb].view(bits))
-    touched = torch.zeros(cfg.n, dtype=torch.bool, device=dev)
-    touched[n_id[:nb]] = True
-    assert int((ls.hist_out != 0).any(dim=1).logical_and(~touched).sum()) == 0
-    got = np.zeros((rows.size, F), dtype=want_y.dtype)
-    oops.push(to_np(ls.x_next[rows_dev]), np.arange(rows.size, dtype=np.int32), got)
-    assert np.array_equal(got, to_np(ls.hist_out[n_id[rows_dev]]))
+    if ls.does_push:
+        assert torch.equal(ls.hist_out[n_id[:nb]].view(bits), ls.x_next[:nb].view(bits))
+        touched = torch.zeros(cfg.n, dtype=torch.bool, device=dev)
+        touched[n_id[:nb]] = True
+        assert int((ls.hist_out != 0).any(dim=1).logical_and(~touched).sum()) == 0
+        got = np.zeros((rows.size, ls.F_out), dtype=want_y.dtype)
+        oops.push(to_np(ls.x_next[rows_dev]), np.arange(rows.size, dtype=np.int32), got)
+        assert np.array_equal(got, to_np(ls.hist_out[n_id[rows_dev]]))
 
+    if ls.does_spmm_t:
+        _check_backward_aggregation(cfg, sg, ls, dev, tol)
+
+    # ---- the in-place form of the step (the one the benchmark's headline times): rows from outside the batch read
+    # from their table by the aggregation, push in the transform's epilogue.  Same bits everywhere as the separate launches.
+    z_ref, y_ref = ls.z.clone(), ls.x_next[:nb].clone()
+    gx_ref = ls.gx.clone() if ls.does_spmm_t else None
+    hist_ref = ls.hist_out
+    if ls.does_push:
+        ls.hist_out = torch.zeros_like(hist_ref)
+    ls.z.fill_(float("nan"))
+    ls.x_next.fill_(float("nan"))
+    if ls.does_spmm_t:
+        ls.gx.fill_(float("nan"))
+    ls.x[nb:] = float("nan")                            # the in-place form must not read the halo copy
+    if ls.kind == "first":
+        ls.x[:nb] = float("nan")                        # ... and gathers the in-batch rows of the first layer itself
+    ls.run(fused=True)
+    torch.cuda.synchronize()
+    assert torch.equal(ls.z.view(bits), z_ref.view(bits))
+    assert torch.equal(ls.x_next[:nb].view(bits), y_ref.view(bits))
+    if ls.does_spmm_t:
+        assert torch.equal(ls.gx.view(bits), gx_ref.view(bits))
+    if ls.does_push:
+        assert torch.equal(ls.hist_out.view(bits), hist_ref.view(bits))
+
+
+def _check_backward_aggregation(cfg, sg, ls, dev, tol):
+    nb = ls.nb
     # ---- backward aggregation on sampled columns u < nb: GX[u] = sum over the entries (v, u) of the CSR
     clen = (sg.colptr[1:nb + 1] - sg.colptr[:nb]).cpu().numpy()
     us = _sample_rows(clen, 4000, 3)
@@ -134,31 +180,14 @@ def _check_step(cfg_id):
         perm = sg.csc_perm[torch.from_numpy(t_pos).to(dev)].long()
         assert torch.equal(ls.bg.val[perm], ls.bg.val_t[torch.from_numpy(t_pos).to(dev)])
     e = node_rel_err(to_np(ls.gx[us_dev]), want_gx)
-    assert e <= tol, ("spmm_t", e)
-
-    # ---- the in-place form of the step (the one the benchmark's headline times): halo rows read from the history
-    # table by the aggregation, push in the transform's epilogue.  Same bits everywhere as the five launches.
-    z_ref, y_ref, gx_ref = ls.z.clone(), ls.x_next[:nb].clone(), ls.gx.clone()
-    hist_ref = ls.hist_out
-    ls.hist_out = torch.zeros_like(hist_ref)
-    ls.z.fill_(float("nan"))
-    ls.x_next.fill_(float("nan"))
-    ls.gx.fill_(float("nan"))
-    ls.x[nb:] = float("nan")                            # the in-place form must not read the halo copy
-    ls.run(fused=True)
-    torch.cuda.synchronize()
-    assert torch.equal(ls.z.view(bits), z_ref.view(bits))
-    assert torch.equal(ls.x_next[:nb].view(bits), y_ref.view(bits))
-    assert torch.equal(ls.gx.view(bits), gx_ref.view(bits))
-    assert torch.equal(ls.hist_out.view(bits), hist_ref.view(bits))
-    return ls
+    assert e <= tol, ("spmm_t", ls.kind, e)
 
 
-def test_config2_full_size_layer_step():
-    ls = _check_step(2)
-    assert ls.nb == 600_000 and ls.nnz > 40_000_000 and ls.F == 256
+def test_config2_full_size_layer_steps():
+    nb, nnz, F, dt = _check_config(2)
+    assert nb == 600_000 and nnz > 40_000_000 and F == 256
 
 
-def test_config4_full_size_layer_step():
-    ls = _check_step(4)
-    assert ls.nb > 3_000_000 and ls.cfg.n == 50_000_000 and ls.dt == torch.bfloat16
+def test_config4_full_size_layer_steps():
+    nb, nnz, F, dt = _check_config(4)
+    assert nb > 3_000_000 and dt == torch.bfloat16

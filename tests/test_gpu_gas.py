@@ -127,7 +127,7 @@ def test_fused_execution_matches_oracle(cfg_id, scale):
 
 
 def test_paper_overhead_workload_matches_oracle():
-    """The paper's synthetic runtime workload (Section 5): 4-layer GIN, batch of 4,000 nodes x 60 links,
+    """The paper's synthetic runtime workload (Section 6 "Experiments", fast mini-batch execution): 4-layer GIN, batch of 4,000 nodes x 60 links,
     out-of-batch nodes x 60 links, at ratio 1; both history-access variants against the oracle."""
     from gas_inputs import graphs, rng
     from paper_2106_05609_amd import executor
@@ -247,7 +247,7 @@ def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
 @pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (4, 0.001), (3, 0.1)])
 def test_host_histories_with_concurrent_transfers(cfg_id, scale):
     """Histories in pinned host memory, pulled ahead and pushed behind the computation on their own streams
-    (Section 4): two sweeps over all batches give, bit for bit, the outputs and tables of the run with the
+    (Section 5 "PyGAS"): two sweeps over all batches give, bit for bit, the outputs and tables of the run with the
     tables in device memory, and the oracle's within tolerance."""
     from paper_2106_05609_amd import executor
     import paper_2106_05609_amd as gas

@@ -97,13 +97,13 @@ def test_gcn_norm_bit_exact(gas, graphs_small):
         assert np.array_equal(to_np(val_t), want[to_np(sg.csc_perm)])
 
 
-def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld_pad=0, out_dtype=None):
+def _spmm_case(gas, g, sg, F, dtype, use_val, diag=0.0, s_agg=1.0, res=False, ld_pad=0, out_dtype=None, options=None):
     x = rng.normal_matrix(2, 310, sg.nv, F + ld_pad, dtype=dtype)
     r = rng.normal_matrix(2, 311, sg.nb, F + ld_pad, dtype=dtype) if res else None
     val = oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg)) if use_val else None
     out_dtype = out_dtype or dtype
     z = torch.full((sg.nb, F + ld_pad), float("nan"), dtype=out_dtype, device="cuda")
-    plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col))
+    plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col), options=options)
     dval = None if val is None else dev(torch.from_numpy(val))
     xd, rd = dev(x), None if r is None else dev(r)
     args = (plan, dev(sg.rowptr), dev(sg.col), dval, xd[:, :F], z[:, :F])
@@ -135,25 +135,24 @@ def test_spmm_bf16_gin(gas, graphs_small, F):
     assert _spmm_case(gas, g, sg, F, torch.bfloat16, False, diag=1.1, out_dtype=torch.float32) <= 1e-5
 
 
-def test_spmm_epilogues_padding_and_heavy_rows(gas, graphs_small, monkeypatch):
+def test_spmm_epilogues_padding_and_heavy_rows(gas, graphs_small):
     cfg, g, sg = graphs_small["powerlaw"]
     deg = np.diff(to_np(sg.rowptr))
     assert deg.max() > 512 and deg.min() < 32          # both the chunked and the one-wavefront path run
     assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True, ld_pad=8) <= 1e-5
     assert _spmm_case(gas, g, sg, 64, torch.float32, False, diag=1.25) <= 1e-5
     # tiny thresholds: almost every row is cut into many chunks
-    monkeypatch.setenv("GAS_SPMM_HEAVY", "8")
-    monkeypatch.setenv("GAS_SPMM_CHUNK", "32")
-    assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True) <= 1e-5
-    assert _spmm_case(gas, g, sg, 128, torch.bfloat16, True, diag=0.5) <= 2e-2
-    assert _spmm_case(gas, g, sg, 20, torch.float32, True) <= 1e-5
-    # heavy rows cut at column-window boundaries and processed window by window
-    monkeypatch.setenv("GAS_SPMM_HEAVY", "64")
-    monkeypatch.setenv("GAS_SPMM_CHUNK", "64")
-    for window in ("1000", "37", "1000000"):
-        monkeypatch.setenv("GAS_SPMM_WINDOW", window)
-        assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True) <= 1e-5
-        assert _spmm_case(gas, g, sg, 256, torch.bfloat16, False, diag=1.0) <= 2e-2
+    tiny = dict(heavy_threshold=8, chunk=32)
+    assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True, options=tiny) <= 1e-5
+    assert _spmm_case(gas, g, sg, 128, torch.bfloat16, True, diag=0.5, options=tiny) <= 2e-2
+    assert _spmm_case(gas, g, sg, 20, torch.float32, True, options=tiny) <= 1e-5
+    # heavy rows cut at window boundaries (windows of 512, 32 and 2^20 rows, chunks that may shrink to one entry
+    # or must hold 16) and processed window by window, each XCD its own range; and no windows at all
+    for window, min_chunk in ((512, 1), (32, 16), (1 << 20, 8), (-1, 8)):
+        opt = dict(heavy_threshold=64, chunk=64, window_rows=window, min_chunk=min_chunk)
+        assert _spmm_case(gas, g, sg, 256, torch.float32, True, s_agg=0.9, res=True, options=opt) <= 1e-5
+        assert _spmm_case(gas, g, sg, 256, torch.bfloat16, False, diag=1.0, options=opt) <= 2e-2
+        assert _spmm_case(gas, g, sg, 100, torch.float32, True, options=opt) <= 1e-5
 
 
 def test_spmm_empty_rows_and_empty_matrix(gas):
@@ -331,16 +330,15 @@ def test_mlp_that_keeps_its_hidden_activation(gas, dtype, M, K, H, N, push):
 
 
 @pytest.mark.parametrize("name", ["sbm", "powerlaw"])
-def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name, monkeypatch):
+def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name):
     """Handing the light rows to the XCDs in contiguous ranges changes which workgroup does a row, not the sum."""
     cfg, g, sg = graphs_small[name]
     F = 256
     x = dev(rng.normal_matrix(10, 390, sg.nv, F))
     val = dev(torch.from_numpy(oops.gcn_norm(to_np(sg.rowptr), to_np(sg.col), to_np(sg.n_id), to_np(g.deg))))
     out = []
-    for mode in ("0", "1", "2"):
-        monkeypatch.setenv("GAS_SPMM_XCD", mode)
-        plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col))
+    for mode in (2, 1, 0):                             # never, always, decided from the pattern
+        plan = gas.gas_plan_create(dev(sg.rowptr), sg.nnz, F, ind=dev(sg.col), options=dict(xcd_ranges=mode))
         z = torch.full((sg.nb, F), float("nan"), device="cuda")
         gas.gas_spmm(plan, dev(sg.rowptr), dev(sg.col), val, x, z)
         out.append(to_np(z))
@@ -352,7 +350,8 @@ def test_spmm_xcd_ranges_give_the_same_bits(gas, graphs_small, name, monkeypatch
 
 
 @pytest.mark.parametrize("name,K,N,variant", [("sbm", 64, 64, "gcnii"), ("sbm", 128, 64, "gcn"), ("powerlaw", 100, 36, "gcn"),
-                                               ("powerlaw", 128, 128, "gcnii"), ("gin", 8, 4, "gin"), ("sbm", 64, 64, "plain")])
+                                               ("powerlaw", 128, 128, "gcnii"), ("gin", 8, 4, "gin"), ("sbm", 64, 64, "plain"),
+                                               ("gin", 64, 32, "all_terms")])
 def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, variant):
     """gas_spmm_linear: Eq. (2)'s aggregation with both sources, the transform and the Push in one launch, against
     the oracle's pull + aggregation + transform + push; rows that are not pushed keep their contents."""
@@ -369,6 +368,9 @@ def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, v
     if variant == "gcnii":
         r = rng.normal_matrix(9, 384, nb, K)
         kw.update(s_agg=0.9, s_res=0.1)
+    if variant == "all_terms":          # every term of the epilogue at once: the diagonal term is NOT scaled by s_agg
+        r = rng.normal_matrix(9, 384, nb, K)
+        kw.update(diag=0.75, s_agg=0.6, s_res=0.3)
     lin = dict(c_identity=0.7, c_weight=0.3) if variant == "gcnii" and K == N else {}
     relu = variant != "plain"
     # oracle: pull, aggregate, transform, push
@@ -393,6 +395,15 @@ def test_layer_in_one_launch_matches_the_oracle(gas, graphs_small, name, K, N, v
     terms = (np.abs(z.astype(np.float64)) @ np.abs(to_np(w).astype(np.float64))).max(axis=1)
     assert node_rel_err(to_np(y), want, scale=terms) <= 1e-5
     assert np.array_equal(to_np(table)[nid_np[:nb]], to_np(y))
+    if variant == "all_terms":
+        # the same layer as two calls (gas_spmm_hist, gas_linear) takes the same meaning of diag, s_agg and R
+        plan = gas.gas_plan_create(d_ptr, sg.nnz, K, ind=src)
+        z2 = torch.full((nb, K), float("nan"), device="cuda")
+        gas.gas_spmm_hist(plan, d_ptr, src, dval, dev(xb), dev(hist), z2, r=dev(r), **kw)
+        assert node_rel_err(to_np(z2), z) <= 1e-5
+        y2 = torch.full((nb, N), float("nan"), device="cuda")
+        gas.gas_linear(z2, dev(w), y2, relu=relu)
+        assert node_rel_err(to_np(y2), want, scale=terms) <= 1e-5
     keep = np.ones(g.n, dtype=bool)
     keep[nid_np[:nb]] = False
     assert np.array_equal(to_np(table)[keep], want_table[keep])

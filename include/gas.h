@@ -108,8 +108,9 @@ GAS_API gas_status gas_gcn_norm(const int32_t* ptr, const int32_t* ind, int64_t 
  * name rows near it, as in a batch of partition clusters): then each of the
  * eight XCDs is given one contiguous range of light rows, so a cluster is
  * gathered into one L2 instead of eight.  Either the local column ids or the
- * source indices of gas_fuse_sources may be passed.  Both arrays are read
- * inside this call, which therefore waits for `stream`; ptr is validated
+ * source indices of gas_fuse_sources may be passed.  The plan is built by
+ * kernels on `stream`; a few counters are read back, so the call waits for the
+ * stream (twice); ptr is validated
  * (0 = ptr[0] <= ptr[r] <= ptr[r+1] <= ptr[n_rows] = nnz, else GAS_ERR_ARG).
  * max_F is the widest feature dimension the plan will be used with (sizes the
  * workspace and the windows).  A plan must not be used by two streams at the
@@ -132,12 +133,25 @@ typedef struct {
     int32_t min_chunk;
     int32_t window_rows;
     int32_t xcd_ranges;
+    int32_t host_builder;   /* 1: build the plan on the host from copies of ptr and ind (slow; the reference the
+                               device builder is tested against: both give the same lists) */
 } gas_plan_options;
 GAS_API gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz,
                            int32_t max_F, void* stream, gas_plan** out);
 GAS_API gas_status gas_plan_create_opt(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz,
                                int32_t max_F, const gas_plan_options* opt, void* stream, gas_plan** out);
 GAS_API void gas_plan_destroy(gas_plan* plan);
+
+/*
+ * Inspection of a plan (tests, tools).  gas_plan_describe: info[0..15] = n_rows, nnz, number of groups of light
+ * rows, of heavy rows, of chunks, whether the XCD ranges are used, max_F, then the nine range boundaries (in
+ * groups).  gas_plan_copy_lists copies the plan's lists to HOST buffers (any may be NULL): group int32[2 * groups]
+ * (first and end row), heavy int32[2 * heavy + 1] (row ids, then the first chunk slot of each and the end), chunk
+ * int32[3 * chunks] (slot, first entry, end entry, in processing order); waits for `stream`.
+ */
+GAS_API gas_status gas_plan_describe(const gas_plan* plan, int64_t info[16]);
+GAS_API gas_status gas_plan_copy_lists(const gas_plan* plan, int32_t* group, int32_t* heavy, int32_t* chunk,
+                               void* stream);
 
 /*
  * Aggregation over the batch subgraph (Eq. 1 / Eq. 2 with the operators of the

@@ -15,7 +15,7 @@ OK = 0
 EXPORTS = [
     "gas_last_error", "gas_version", "gas_validate_indices",
     "gas_pull", "gas_push", "gas_host_table_pointer", "gas_pull_host", "gas_push_host",
-    "gas_gcn_norm", "gas_plan_create", "gas_plan_create_opt", "gas_plan_destroy", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
+    "gas_gcn_norm", "gas_plan_create", "gas_plan_create_opt", "gas_plan_destroy", "gas_plan_describe", "gas_plan_copy_lists", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_bwd_weight_static",
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
@@ -120,7 +120,7 @@ def gas_gcn_norm(ptr, ind, n_id, deg, val):
 class PlanOptions(C.Structure):
     """gas_plan_options of the C ABI; a zero field means the default."""
     _fields_ = [("heavy_threshold", C.c_int32), ("chunk", C.c_int32), ("min_chunk", C.c_int32),
-                ("window_rows", C.c_int32), ("xcd_ranges", C.c_int32)]
+                ("window_rows", C.c_int32), ("xcd_ranges", C.c_int32), ("host_builder", C.c_int32)]
 
 
 class Plan:
@@ -138,6 +138,25 @@ class Plan:
         _check(lib().gas_plan_create_opt(_ptr(ptr, torch.int32), _ptr(ind, torch.int32), C.c_int64(self.n_rows),
                                          C.c_int64(nnz), C.c_int32(max_F), None if opt is None else C.byref(opt),
                                          _stream(), C.byref(self.handle)))
+
+    def describe(self) -> dict:
+        info = (C.c_int64 * 16)()
+        _check(lib().gas_plan_describe(self.handle, info))
+        keys = ["n_rows", "nnz", "n_groups", "n_heavy", "n_chunks", "xcd_ranges", "max_F"]
+        d = {k: int(info[i]) for i, k in enumerate(keys)}
+        d["xcd_start"] = [int(info[7 + x]) for x in range(9)]
+        return d
+
+    def lists(self):
+        """(group, heavy, chunk) as numpy int32 arrays on the host."""
+        import numpy as np
+        d = self.describe()
+        group = np.zeros(2 * d["n_groups"], dtype=np.int32)
+        heavy = np.zeros(2 * d["n_heavy"] + 1 if d["n_heavy"] else 0, dtype=np.int32)
+        chunk = np.zeros(3 * d["n_chunks"], dtype=np.int32)
+        as_p = lambda a: a.ctypes.data_as(C.c_void_p) if a.size else None
+        _check(lib().gas_plan_copy_lists(self.handle, as_p(group), as_p(heavy), as_p(chunk), _stream()))
+        return group, heavy, chunk
 
     def close(self):
         if self.handle:

@@ -21,26 +21,11 @@
 // The summation order is a
 // function of the plan alone, so results are bit-identical from run to run.
 #include "common.h"
-#include "plan_host.h"
+#include "plan.h"
 
 #include <algorithm>
 #include <string.h>
 #include <vector>
-
-struct gas_plan {
-    int64_t n_rows = 0, nnz = 0;
-    int32_t max_F = 0;
-    int32_t threshold = 0, chunk = 0;
-    int64_t n_heavy = 0, n_chunks = 0;
-    int32_t* d_chunk = nullptr;        // [3 * n_chunks]: slot of the partial sum, begin, end (in processing order)
-    int32_t* d_heavy = nullptr;        // [n_heavy] row ids, then [n_heavy + 1] first chunk of each
-    float* d_partial = nullptr;        // [n_chunks, max_F]
-    int32_t* d_group = nullptr;        // [2 * n_groups] first and end row of every group of light rows
-    int64_t n_groups = 0;
-    int xcd_ranges = 0;                // light-row groups are handed out in one contiguous range per XCD
-    int64_t xcd_start[9] = {0};        // first group of every XCD's range (and the end), equal cost per range
-    int device = 0;
-};
 
 namespace gas {
 namespace {
@@ -662,94 +647,6 @@ __global__ __launch_bounds__(256) void fuse_sources_kernel(const int32_t* __rest
 using namespace gas;
 
 extern "C" {
-
-gas_status gas_plan_create_opt(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
-                               const gas_plan_options* opt, void* stream, gas_plan** out) {
-    GAS_REQUIRE(out, "gas_plan_create: null output");
-    *out = nullptr;
-    GAS_REQUIRE(n_rows >= 0 && n_rows < 0x7FFFFFF0LL && nnz >= 0 && nnz < 0x7FFFFFF0LL && max_F > 0,
-                "gas_plan_create: n_rows=%lld nnz=%lld max_F=%d", (long long)n_rows, (long long)nnz, max_F);
-    GAS_REQUIRE(ptr || n_rows == 0, "gas_plan_create: null row pointer array");
-    PlanParams pp;
-    pp.wshift = plan_default_wshift(max_F);
-    if (opt) {
-        GAS_REQUIRE(opt->heavy_threshold >= 0 && opt->chunk >= 0 && opt->min_chunk >= 0 && opt->window_rows >= -1 &&
-                    opt->xcd_ranges >= 0 && opt->xcd_ranges <= 2,
-                    "gas_plan_create: options out of range (threshold %d, chunk %d, min_chunk %d, window_rows %d, "
-                    "xcd_ranges %d)", opt->heavy_threshold, opt->chunk, opt->min_chunk, opt->window_rows, opt->xcd_ranges);
-        if (opt->heavy_threshold > 0) pp.threshold = opt->heavy_threshold;
-        if (opt->chunk > 0) pp.chunk = opt->chunk;
-        if (opt->min_chunk > 0) pp.min_chunk = opt->min_chunk;
-        if (opt->window_rows < 0) pp.wshift = -1;
-        else if (opt->window_rows > 0) {                 // rounded down to a power of two
-            pp.wshift = 0;
-            while ((2ll << pp.wshift) <= opt->window_rows) ++pp.wshift;
-        }
-        pp.xcd_mode = opt->xcd_ranges;
-    }
-    hipStream_t s = (hipStream_t)stream;
-    gas_plan* p = new gas_plan();
-    p->n_rows = n_rows; p->nnz = nnz; p->max_F = max_F;
-    p->threshold = pp.threshold; p->chunk = pp.chunk;
-    (void)hipGetDevice(&p->device);
-    std::vector<int32_t> h_ptr((size_t)n_rows + 1, 0), h_ind;
-    hipError_t e = hipSuccess;
-    if (n_rows > 0) {
-        e = hipMemcpyAsync(h_ptr.data(), ptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ptr failed: %s", hipGetErrorString(e)); }
-        const int64_t bad = plan_validate_ptr(h_ptr.data(), n_rows, nnz);
-        if (bad) {
-            delete p;
-            if (bad > n_rows)
-                return fail(GAS_ERR_ARG, "gas_plan_create: ptr[0]=%d ptr[n_rows]=%d do not match nnz=%lld", h_ptr[0],
-                            h_ptr[n_rows], (long long)nnz);
-            return fail(GAS_ERR_ARG, "gas_plan_create: ptr decreases or leaves [0, nnz] at row %lld", (long long)(bad - 1));
-        }
-    }
-    if (ind && nnz > 0) {
-        h_ind.resize((size_t)nnz);
-        e = hipMemcpyAsync(h_ind.data(), ind, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) { delete p; return fail(GAS_ERR_HIP, "gas_plan_create: copy of ind failed: %s", hipGetErrorString(e)); }
-    }
-    PlanArrays pa;
-    build_plan_host(h_ptr.data(), h_ind.empty() ? nullptr : h_ind.data(), n_rows, nnz, pp, pa);
-    p->n_heavy = pa.n_heavy; p->n_chunks = pa.n_chunks; p->n_groups = pa.n_groups;
-    p->xcd_ranges = pa.xcd_ranges;
-    for (int x = 0; x < 9; ++x) p->xcd_start[x] = pa.xcd_start[x];
-    auto upload = [&](int32_t** dst, const std::vector<int32_t>& v) -> hipError_t {
-        if (v.empty()) return hipSuccess;
-        hipError_t r = hipMalloc(dst, v.size() * sizeof(int32_t));
-        if (r == hipSuccess) r = hipMemcpyAsync(*dst, v.data(), v.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-        return r;
-    };
-    e = upload(&p->d_group, pa.group);
-    if (e == hipSuccess) e = upload(&p->d_chunk, pa.chunk);
-    if (e == hipSuccess) e = upload(&p->d_heavy, pa.heavy);
-    if (e == hipSuccess && p->n_chunks > 0) e = hipMalloc(&p->d_partial, (size_t)p->n_chunks * max_F * sizeof(float));
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e != hipSuccess) {
-        gas_plan_destroy(p);
-        return fail(GAS_ERR_NOMEM, "gas_plan_create: device allocation or upload failed: %s", hipGetErrorString(e));
-    }
-    *out = p;
-    return GAS_OK;
-}
-
-gas_status gas_plan_create(const int32_t* ptr, const int32_t* ind, int64_t n_rows, int64_t nnz, int32_t max_F,
-                           void* stream, gas_plan** out) {
-    return gas_plan_create_opt(ptr, ind, n_rows, nnz, max_F, nullptr, stream, out);
-}
-
-void gas_plan_destroy(gas_plan* p) {
-    if (!p) return;
-    if (p->d_chunk) (void)hipFree(p->d_chunk);
-    if (p->d_heavy) (void)hipFree(p->d_heavy);
-    if (p->d_partial) (void)hipFree(p->d_partial);
-    if (p->d_group) (void)hipFree(p->d_group);
-    delete p;
-}
 
 gas_status gas_spmm(const gas_plan* plan, const int32_t* rowptr, const int32_t* col, const float* val, float diag,
                     const void* X, int64_t ldx, gas_dtype dt_x, int32_t F, float s_agg, const void* R, int64_t ldr,

@@ -57,6 +57,9 @@ def parse():
     p.add_argument("--skip-spmm-t", action="store_true",
                    help="profiling aid: leave the backward aggregation out, so that the per-kernel averages of a "
                         "trace are those of the forward aggregation alone (the reported value is then not the metric)")
+    p.add_argument("--only-spmm-t", action="store_true",
+                   help="profiling aid: run the backward aggregation alone (its kernels share their names with the "
+                        "forward aggregation's; the reported value is then not the metric)")
     p.add_argument("--path", choices=["both", "separate", "in-place"], default="both",
                    help="separate: pull, aggregate, transform, push, backward aggregate as five launches; in-place: the "
                         "aggregation reads the halo rows from the history table itself (gas_spmm_hist, same result bit "
@@ -108,7 +111,8 @@ def measure(ls, args, fused):
     tag = "in-place" if fused else "separate"
 
     def step(ev=None):
-        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t, fused=fused)
+        ls.run(None if ev is None else (lambda i: ev[i].record()), skip_spmm_t=args.skip_spmm_t, fused=fused,
+               only_spmm_t=args.only_spmm_t)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -157,20 +161,20 @@ def measure(ls, args, fused):
     sk = "spmm_hist" if fused else "spmm"
     lk = "linear_alone" if fused else "linear"
     mfma_peak = 157.3 if ls.dt == torch.float32 else 2500.0        # dense MFMA TFLOP/s of the operand type
-    kern[lk]["TFLOPs"] = round(ls.flops() / (per["linear"] * 1e-3) / 1e12, 2)
+    kern[lk]["TFLOPs"] = round(ls.flops() / (max(per["linear"], 1e-6) * 1e-3) / 1e12, 2)
     kern[lk]["mfma_util"] = round(kern[lk]["TFLOPs"] / mfma_peak, 4)
     if fused and ls.does_push:
         kern["linear_push"] = {"ms": round(per["linear_push"], 4),
-                               "TFLOPs": round(ls.flops() / (per["linear_push"] * 1e-3) / 1e12, 2)}
-    kern[sk]["edges_per_s"] = round(ls.nnz / (per["spmm"] * 1e-3), 1)
-    kern[sk]["gathered_GBps"] = round(spmm_hi / (per["spmm"] * 1e-3) / 1e9, 1)
+                               "TFLOPs": round(ls.flops() / (max(per["linear_push"], 1e-6) * 1e-3) / 1e12, 2)}
+    kern[sk]["edges_per_s"] = round(ls.nnz / (max(per["spmm"], 1e-6) * 1e-3), 1)
+    kern[sk]["gathered_GBps"] = round(spmm_hi / (max(per["spmm"], 1e-6) * 1e-3) / 1e9, 1)
     # pull + aggregation + push, three ways:
     #  five_launch_literal  bytes of the three operations as separate launches / the time those launches take
     #  in_place_own_bytes   the in-place form's own, smaller byte count (no halo copy written and re-read, the
     #                       transform's output not re-read) / the time it needs for that work
     #  work_equivalent      the separate-launch byte count / the in-place form's time: not a bandwidth (the in-place
     #                       form moves no such bytes), only how fast the same work gets done
-    t3 = (per["pull"] + per["spmm"] + per["push"]) * 1e-3
+    t3 = max(per["pull"] + per["spmm"] + per["push"], 1e-6) * 1e-3
     lit = by["pull"] + by["spmm"] + by["push"]
     own = bytes_of["pull"] + by["spmm"] + bytes_of["push"]
     hbm = {}
@@ -259,7 +263,7 @@ def main():
     hm = head[form]
     per, by = hm["_per"], hm["_by"]
     fused_head = form == "in-place"
-    spmm_gbs = by["spmm"] / (per["spmm"] * 1e-3) / 1e9
+    spmm_gbs = by["spmm"] / (max(per["spmm"], 1e-6) * 1e-3) / 1e9
     traffic, traffic_src = load_traffic(head_id, args.scale)
     F = head["F"]
     hbm = dict(hm["hbm_pull_spmm_push"])
@@ -287,8 +291,8 @@ def main():
                      # what this machine reaches for a plain device copy, timed in this run, and the same call against it
                      "attainable": round(copy_gbs, 1), "frac_of_attainable": round(spmm_gbs / copy_gbs, 4),
                      "traffic": traffic, "traffic_source": traffic_src,
-                     "traffic_GBps": None if traffic is None else round(traffic / (per["spmm"] * 1e-3) / 1e9, 1),
-                     "gathered_GBps": round(by["spmm_no_reuse"] / (per["spmm"] * 1e-3) / 1e9, 1)},
+                     "traffic_GBps": None if traffic is None else round(traffic / (max(per["spmm"], 1e-6) * 1e-3) / 1e9, 1),
+                     "gathered_GBps": round(by["spmm_no_reuse"] / (max(per["spmm"], 1e-6) * 1e-3) / 1e9, 1)},
         "setup_ms": hrec.get("setup_ms"),
         "configs": per_cfg,
     }

@@ -445,6 +445,16 @@ GAS_API gas_status gas_row_distance(const void* A, int64_t lda, const void* B, i
                             int32_t F, gas_dtype dt, float* dist, float* dist_sum, void* stream);
 
 /*
+ * Row-wise inner products: dot[i] = sum_f A[i, f] * B[i, f] (fp32[n_rows], fp32 accumulation), and, if dot_sum is
+ * given (fp32[1]), their sum in a fixed order (double accumulation).  With A the gradient at a GIN layer's
+ * aggregated rows and B the layer's in-batch input rows, dot_sum is the gradient of that layer's eps (operator
+ * appendix, GIN: the self term is (1 + eps) h_v and eps is trainable, so dL/d eps = sum_v <dL/dZ_v, h_v>).
+ * A, B: [n_rows, F] of type dt.
+ */
+GAS_API gas_status gas_row_dot(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows,
+                       int32_t F, gas_dtype dt, float* dot, float* dot_sum, void* stream);
+
+/*
  * Gradient of the distance of Eq. (3): G[i, :] = scale * (A[i, :] - B[i, :]) / ||A[i, :] - B[i, :]||_2, zero where
  * the two rows are equal; this is d/dA of scale * sum_i ||A[i] - B[i]||_2, and d/dB is its negative.  A, B, G:
  * [n_rows, F] of type dt.  With it the regulariser's gradient with respect to a layer's weights is two passes of

@@ -318,6 +318,9 @@ def gas_batch_backward(model: Model, n_id, rowptr, col, nb, val, x0, h0, saved, 
             gh = ops.linear_bwd_input(g, w2, mask=h)
             grads[l - 1] = (ops.linear_bwd_weight(z, gh), dw2)
             gz = ops.linear_bwd_input(gh, w1)
+            # operator appendix, GIN: Z_v = (1 + eps) h_v + sum over N(v), eps trainable: dL/d eps = sum_v <GZ_v, h_v>
+            x_in = x0 if l == 1 else saved[l - 2][2]
+            grads.setdefault("eps", np.zeros(L, dtype=np.float64))[l - 1] = ops.row_dot(gz, x_in[:nb])[1]
         else:
             b = model.betas[l - 1]
             grads[l - 1] = ops.linear_bwd_weight(z, g, c_weight=b)
@@ -423,12 +426,15 @@ def pna_batch_forward(weights, delta, n_id, rowptr, col, nb, x_feat, histories, 
 
 
 # ----------------------------------------------------------------------------
-# GAT (paper, operator appendix), one head
+# GAT (paper, operator appendix); several heads are independent copies of the operator on column blocks
 # ----------------------------------------------------------------------------
-def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negative_slope=0.2, do_push=True):
-    """All layers of a one-head GAT for one mini-batch in the order of Algorithm 1; weights[l] = (W, a_dst, a_src).
+def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negative_slope=0.2, do_push=True, heads=1):
+    """All layers of a GAT for one mini-batch in the order of Algorithm 1; weights[l] = (W, a_dst, a_src).
     rowptr/col: the batch subgraph WITH self-loops (the sums run over N(v) and v).  Per layer: P = X W for every
-    node of V_b, attention-weighted aggregation for the in-batch rows, ReLU on all layers but the last."""
+    node of V_b, attention-weighted aggregation for the in-batch rows, ReLU on all layers but the last.
+    heads > 1 (the multi-head attention of the operator's source, which the paper's appendix states for one head):
+    the columns of W, a_dst and a_src are `heads` equal blocks, each block an attention head of its own with its
+    own coefficients alpha, and the layer's output is the heads side by side."""
     n_id = np.ascontiguousarray(n_id, dtype=np.int32)
     nv = n_id.size
     x = ops.pull(x_feat, n_id)
@@ -437,7 +443,11 @@ def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negativ
     for l in range(1, L + 1):
         w, a_dst, a_src = weights[l - 1]
         p = ops.linear(x, w)
-        y = ops.gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope, relu=l < L)
+        fh = p.shape[1] // heads
+        assert fh * heads == p.shape[1]
+        y = np.concatenate([ops.gat_aggregate(rowptr, col, p[:, h * fh:(h + 1) * fh], a_dst[h * fh:(h + 1) * fh],
+                                              a_src[h * fh:(h + 1) * fh], negative_slope, relu=l < L)
+                            for h in range(heads)], axis=1)
         if l == L:
             break
         if do_push:

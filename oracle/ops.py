@@ -277,6 +277,14 @@ def row_distance(a, b):
     return dist, float(total.value)
 
 
+def row_dot(a, b):
+    """(dot float32[n], their sum): dot[i] = sum_f a[i, f] * b[i, f], in float64."""
+    a64, b64 = to_f64(np.asarray(a)), to_f64(np.asarray(b))
+    assert a64.shape == b64.shape
+    rows = (a64 * b64).sum(axis=1)
+    return rows.astype(np.float32), float(rows.sum())
+
+
 def row_distance_bwd(a, b, scale=1.0) -> np.ndarray:
     """Gradient of scale * sum_i ||a[i] - b[i]||_2 with respect to a (that with respect to b is its negative):
     row i is scale * (a[i] - b[i]) / ||a[i] - b[i]||_2, and zero where the two rows are equal.  In a's type."""

@@ -18,7 +18,7 @@ EXPORTS = [
     "gas_gcn_norm", "gas_plan_create", "gas_plan_create_opt", "gas_plan_destroy", "gas_plan_describe", "gas_plan_copy_lists", "gas_spmm", "gas_spmm_hist", "gas_fuse_sources", "gas_spmm_t",
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_bwd_weight_static",
-    "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd",
+    "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd", "gas_row_dot",
     "gas_pna_aggregate", "gas_gat_aggregate",
 ]
 
@@ -458,6 +458,16 @@ def gas_axpy(x, e, y, alpha=1.0):
         raise ValueError("gas_axpy: shapes or dtypes do not match")
     _check(lib().gas_axpy(xp, ldx, ep, lde, C.c_int64(x.shape[0]), C.c_int32(x.shape[1]), C.c_int(_dt(x)),
                           C.c_float(alpha), yp, ldy, _stream()))
+
+
+def gas_row_dot(a, b, dot, dot_sum=None):
+    """dot[i] = <a[i], b[i]> (float32 [n]); dot_sum (float32 [1]) receives their sum in a fixed order."""
+    ap, lda = _mat(a)
+    bp, ldb = _mat(b)
+    if a.shape != b.shape or a.dtype != b.dtype or dot.dtype != torch.float32 or dot.numel() < a.shape[0]:
+        raise ValueError("gas_row_dot: shapes or dtypes do not match")
+    _check(lib().gas_row_dot(ap, lda, bp, ldb, C.c_int64(a.shape[0]), C.c_int32(a.shape[1]), C.c_int(_dt(a)),
+                             _ptr(dot), _ptr(dot_sum), _stream()))
 
 
 def gas_row_distance(a, b, dist, dist_sum=None):

@@ -239,6 +239,19 @@ __global__ __launch_bounds__(256) void row_distance_kernel(const char* A, int64_
     if (lane == 0) dist[row] = sqrtf(s);
 }
 
+// dot[m] = sum_f A[m, f] * B[m, f]: one wavefront per row, lanes stride over the row
+template <bool BF>
+__global__ __launch_bounds__(256) void row_dot_kernel(const char* A, int64_t lda, const char* B, int64_t ldb,
+                                                      int64_t M, int F, float* dot) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    float s = 0.f;
+    for (int f = lane; f < F; f += 64) s = fmaf(load_logit<BF>(A, row * lda + f), load_logit<BF>(B, row * ldb + f), s);
+    s = wave_sum(s);
+    if (lane == 0) dot[row] = s;
+}
+
 // G[m, :] = scale * (A[m, :] - B[m, :]) / || A[m, :] - B[m, :] ||_2 (zero where the rows are equal): one wavefront
 // per row, two passes over the row (the second one out of the cache)
 template <bool BF>
@@ -404,6 +417,31 @@ gas_status gas_row_distance(const void* A, int64_t lda, const void* B, int64_t l
     }
     if (dist_sum) {
         hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, dist, n_rows, dist_sum);
+        GAS_CHECK_HIP(hipGetLastError());
+    }
+    return GAS_OK;
+}
+
+gas_status gas_row_dot(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_rows, int32_t F,
+                       gas_dtype dt, float* dot, float* dot_sum, void* stream) {
+    if (!valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_row_dot: unknown dtype %d", (int)dt);
+    GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_row_dot: n_rows=%lld F=%d", (long long)n_rows, F);
+    hipStream_t s = (hipStream_t)stream;
+    if (n_rows > 0) {
+        GAS_REQUIRE(A && B && dot, "gas_row_dot: null pointer");
+        GAS_REQUIRE(lda >= F && ldb >= F, "gas_row_dot: row stride smaller than the row");
+        const int64_t blocks = (n_rows + 3) / 4;
+        GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_row_dot: too many rows for one launch");
+        if (dt == GAS_BF16)
+            hipLaunchKernelGGL(row_dot_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, dot);
+        else
+            hipLaunchKernelGGL(row_dot_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, F, dot);
+        GAS_CHECK_HIP(hipGetLastError());
+    }
+    if (dot_sum) {
+        hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, dot, n_rows, dot_sum);
         GAS_CHECK_HIP(hipGetLastError());
     }
     return GAS_OK;

@@ -453,6 +453,11 @@ def train_batch(model: Model, bg: BatchGraph, x_feat, histories, grad_out, do_pu
             B.gas_linear_bwd_input(g, w2, gh, mask=h)
             grads[l - 1] = (weight_grad(z, gh), dw2)
             B.gas_linear_bwd_input(gh, w1, gz)
+            # gradient of this layer's eps: sum over the in-batch nodes of <dL/dZ_v, h_v> (h = the layer's input)
+            if "eps" not in grads:
+                grads["eps"] = torch.zeros(L, dtype=torch.float32, device=dev)
+            x_in = x0 if l == 1 else saved[l - 2][2]
+            B.gas_row_dot(gz, x_in[:nb], torch.empty(nb, dtype=torch.float32, device=dev), grads["eps"][l - 1:l])
         else:
             beta = gcnii_beta(l)
             grads[l - 1] = weight_grad(z, g, beta)
@@ -628,11 +633,13 @@ def pna_forward_batch(weights, delta, bg: BatchGraph, x_feat, histories, do_push
     return y
 
 
-def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope=0.2, do_push=True):
-    """All layers of a one-head GAT (paper, operator appendix) for one mini-batch in the order of Algorithm 1;
+def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope=0.2, do_push=True, heads=1):
+    """All layers of a GAT (paper, operator appendix) for one mini-batch in the order of Algorithm 1;
     weights[l] = (W, a_dst, a_src); bg: the batch subgraph with self-loops.  Per layer: P = X W for every row of
     the mini-batch tensor (gas_linear), then scores, softmax and weighted sum in one pass (gas_gat_aggregate,
-    ReLU in its epilogue on all layers but the last), push, pull."""
+    ReLU in its epilogue on all layers but the last), push, pull.  heads > 1: the columns of W, a_dst and a_src are
+    `heads` equal blocks; one gas_gat_aggregate call per head on its block of columns of P (a strided view),
+    writing its block of the output."""
     dev, dt = x_feat.device, x_feat.dtype
     nb, nv = bg.nb, bg.nv
     x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
@@ -646,7 +653,13 @@ def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope
         B.gas_linear(x, w, p)
         x_next = torch.empty((nb if last else nv, w.shape[1]), dtype=dt, device=dev)
         y = x_next[:nb]
-        B.gas_gat_aggregate(bg.rowptr, bg.col, p, a_dst, a_src, y, negative_slope, relu=not last)
+        fh = w.shape[1] // heads
+        if fh * heads != w.shape[1]:
+            raise ValueError("gat_forward_batch: the layer width is not a multiple of the number of heads")
+        for h in range(heads):
+            cols = slice(h * fh, (h + 1) * fh)
+            B.gas_gat_aggregate(bg.rowptr, bg.col, p[:, cols], a_dst[cols], a_src[cols], y[:, cols], negative_slope,
+                                relu=not last)
         if last:
             break
         if do_push:

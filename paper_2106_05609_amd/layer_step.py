@@ -77,13 +77,20 @@ class LayerStep:
         self.beta = executor.gcnii_beta(2)
         self.diag = (1.0 + cfg.gin_eps) if self.gin else 0.0
 
-    def run(self, mark=None, skip_spmm_t=False, fused=False):
+    def run(self, mark=None, skip_spmm_t=False, fused=False, only_spmm_t=False):
         """fused: the aggregation reads the rows outside the batch from their table itself
         (gas_spmm_hist) and the transform pushes its output rows (gas_linear_push /
         gas_mlp2_push); the push launch disappears, and the pull launch too (for the
         first layer it shrinks to the in-batch rows)."""
         cfg, bg, nb = self.cfg, self.bg, self.nb
         mark = mark or (lambda i: None)
+        if only_spmm_t:                                  # profiling aid: the backward aggregation alone
+            for i in range(5):
+                mark(i)
+            if self.does_spmm_t:
+                B.gas_spmm_t(bg.plan_t, bg.colptr, bg.row, bg.val_t, self.gz, self.gx, diag=self.diag)
+            mark(5)
+            return
         mark(0)
         if self.kind == "first":
             n_pull = nb if fused else self.nv

@@ -127,6 +127,14 @@ def test_batch_backward_matches_oracle(cfg_id, scale, dtype, fused):
             assert max_rel_err(to_np(grads_gpu[l]), grads_cpu[l]) <= gtol, (l, max_rel_err(to_np(grads_gpu[l]), grads_cpu[l]))
     if cfg.op == "gcnii":
         assert max_rel_err(to_np(grads_gpu["w_in"]), grads_cpu["w_in"]) <= gtol
+    if cfg.op == "gin":
+        # gradient of every layer's eps: a sum over all in-batch rows and features, measured against the sum of
+        # the magnitudes of its terms (the signed sum can cancel to anything)
+        got, want = to_np(grads_gpu["eps"]).astype(np.float64), grads_cpu["eps"]
+        for l in range(om.n_layers):
+            x_in = to_np(kept["x0"]) if l == 0 else saved[l - 1][2]
+            gz_mag = np.abs(oops.to_f64(np.asarray(x_in[:sg.nb]))).max() * sg.nb * x_in.shape[1]
+            assert abs(got[l] - want[l]) <= gtol * max(abs(want[l]), 1e-6 * gz_mag), (l, got[l], want[l])
 
 
 @pytest.mark.parametrize("cfg_id,scale", [(1, 0.1), (4, 0.001)])

@@ -214,10 +214,12 @@ def test_pna_model_matches_oracle(cfg_id, scale, dtype, f, f1):
         assert node_rel_err(to_np(a), c) <= tol
 
 
-@pytest.mark.parametrize("cfg_id,scale,dtype,f", [(1, 0.1, torch.float32, 64), (2, 0.01, torch.float32, 100),
-                                                   (4, 0.0005, torch.bfloat16, 128)])
-def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
-    """Three one-head GAT layers (operator appendix) through the histories, two batches, against the oracle."""
+@pytest.mark.parametrize("cfg_id,scale,dtype,f,heads", [(1, 0.1, torch.float32, 64, 1), (2, 0.01, torch.float32, 100, 1),
+                                                         (4, 0.0005, torch.bfloat16, 128, 1), (1, 0.1, torch.float32, 64, 4),
+                                                         (4, 0.0005, torch.bfloat16, 128, 8), (2, 0.01, torch.float32, 100, 5)])
+def test_gat_model_matches_oracle(cfg_id, scale, dtype, f, heads):
+    """Three GAT layers (operator appendix; one head, or several heads on blocks of columns) through the histories,
+    two batches, against the oracle."""
     from gas_inputs import rng
     from paper_2106_05609_amd import executor
     cfg = configs.config(cfg_id, scale)
@@ -237,8 +239,9 @@ def test_gat_model_matches_oracle(cfg_id, scale, dtype, f):
     for b in (0, 1):
         sg = batches.batch_subgraph(g, bl[b], True)
         bg = executor.BatchGraph(sg.nb, d(sg.n_id), d(sg.rowptr), d(sg.col), None, None, None, max_F=f, normalise=False)
-        y = executor.gat_forward_batch(ws_gpu, bg, d(x), hs_gpu)
-        want = omodel.gat_batch_forward(ws_cpu, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x), hs_cpu)
+        y = executor.gat_forward_batch(ws_gpu, bg, d(x), hs_gpu, heads=heads)
+        want = omodel.gat_batch_forward(ws_cpu, to_np(sg.n_id), to_np(sg.rowptr), to_np(sg.col), sg.nb, to_np(x), hs_cpu,
+                                        heads=heads)
         assert node_rel_err(to_np(y), want) <= tol, (b, node_rel_err(to_np(y), want))
     for a, c in zip(hs_gpu, hs_cpu):
         assert node_rel_err(to_np(a), c) <= tol

@@ -254,6 +254,27 @@ def test_lipschitz_regulariser_matches_oracle(gas, op, dtype, layer):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("M,F,ld", [(1000, 256, 256), (333, 100, 104), (50, 7, 7), (0, 8, 8)])
+def test_row_dot_parity(gas, dtype, M, F, ld):
+    """gas_row_dot (the reduction behind the gradient of GIN's eps) against the oracle's float64 inner products."""
+    a = rng.normal_matrix(18, 1400, M, ld, dtype=dtype)
+    b = rng.normal_matrix(18, 1401, M, ld, dtype=dtype)
+    dot = torch.full((max(M, 1),), float("nan"), device="cuda")
+    total = torch.full((1,), float("nan"), device="cuda")
+    gas.gas_row_dot(a.to("cuda")[:, :F], b.to("cuda")[:, :F], dot, total)
+    if M == 0:
+        assert float(total) == 0.0
+        return
+    want, want_sum = oops.row_dot(to_np(a)[:, :F], to_np(b)[:, :F])
+    mag = (np.abs(oops.to_f64(to_np(a)[:, :F])) * np.abs(oops.to_f64(to_np(b)[:, :F]))).sum(axis=1)
+    assert (np.abs(to_np(dot[:M]) - want) <= 2e-6 * mag + 1e-30).all()
+    assert abs(float(total) - want_sum) <= 1e-6 * mag.sum()
+    d2, t2 = torch.empty_like(dot), torch.empty_like(total)
+    gas.gas_row_dot(a.to("cuda")[:, :F], b.to("cuda")[:, :F], d2, t2)
+    assert torch.equal(dot[:M], d2[:M]) and torch.equal(total, t2)              # fixed order
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,F,ld", [(1000, 256, 256), (333, 100, 104), (50, 7, 7), (0, 8, 8)])
 def test_row_distance_gradient_parity(gas, dtype, M, F, ld):
     a = rng.normal_matrix(16, 1300, M, ld, dtype=dtype)
     b = rng.normal_matrix(16, 1301, M, ld, dtype=dtype)

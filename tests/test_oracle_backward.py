@@ -45,6 +45,7 @@ def _torch_replica(wl, m, sg, n_id, rp, cl, hist, grad_out):
             a[v, w] = 1.0 if m.op == "gin" else 1.0 / np.sqrt((deg[n_id[v]] + 1.0) * (deg[n_id[w]] + 1.0))
     a = torch.from_numpy(a)
     params = {}
+    eps = [torch.tensor(float(m.gin_eps), dtype=torch.float64, requires_grad=True) for _ in m.weights]   # one per layer
     if m.op == "gin":
         ws = [(t(w1).requires_grad_(), t(w2).requires_grad_()) for w1, w2 in m.weights]
     else:
@@ -61,7 +62,7 @@ def _torch_replica(wl, m, sg, n_id, rp, cl, hist, grad_out):
         if m.op == "gcn":
             y = (a @ x) @ ws[l - 1]
         elif m.op == "gin":
-            z = (1.0 + m.gin_eps) * x[:nb] + a @ x
+            z = (1.0 + eps[l - 1]) * x[:nb] + a @ x
             y = torch.relu(z @ ws[l - 1][0]) @ ws[l - 1][1]
         else:
             z = (1.0 - m.alpha) * (a @ x) + m.alpha * h0[:nb]
@@ -77,6 +78,8 @@ def _torch_replica(wl, m, sg, n_id, rp, cl, hist, grad_out):
         grads[l] = (ws[l][0].grad.numpy(), ws[l][1].grad.numpy()) if m.op == "gin" else ws[l].grad.numpy()
     if m.op == "gcnii":
         grads["w_in"] = params["w_in"].grad.numpy()
+    if m.op == "gin":
+        grads["eps"] = np.array([float(e.grad) for e in eps])
     return y.detach().numpy(), grads
 
 
@@ -103,6 +106,10 @@ def test_batch_backward_matches_autograd(op):
             assert close(grads[l], grads_t[l]), l
     if op == "gcnii":
         assert close(grads["w_in"], grads_t["w_in"])
+    if op == "gin":
+        # the gradient of every layer's eps (the self term's weight is 1 + eps)
+        assert grads["eps"].shape == (m.n_layers,) and np.abs(grads_t["eps"]).min() > 0
+        assert np.abs(grads["eps"] - grads_t["eps"]).max() <= 2e-5 * np.abs(grads_t["eps"]).max()
     # the gradients of the lower layers are not all zero: the backward really reached them
     first = grads[0][0] if op == "gin" else grads[0]
     assert np.abs(first).max() > 1e-4

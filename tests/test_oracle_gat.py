@@ -93,3 +93,35 @@ def test_gat_model_whole_graph_equals_dense_layers():
     sg1, n_id1, rp1, cl1 = _sub(wl, wl.batches[0])
     y1 = omodel.gat_batch_forward(ws, n_id1, rp1, cl1, sg1.nb, x, [hist[0].copy()], do_push=False)
     assert np.abs(y1 - h.numpy()[n_id1[:sg1.nb]]).max() <= 5e-6 * np.abs(want).max()
+
+
+def test_multi_head_model_equals_dense_heads_in_float64():
+    """Four heads: every block of columns is an attention head of its own.  Written densely with torch in float64 as
+    one batched softmax over a [heads, n, n] score tensor (not as the oracle's loop over column slices)."""
+    from oracle import model as omodel
+    wl = _workload("gcn", n=160, layers=2, f=8)
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, torch.cat(wl.batches))
+    H, f = 4, [10, 12, 8]
+    x = to_np(rng.normal_matrix(53, 1020, g.n, f[0]))
+    ws = [(to_np(rng.glorot_uniform(53, 1021 + 3 * l, f[l], f[l + 1])), to_np(rng.normal(53, 1022 + 3 * l, 0, f[l + 1])),
+           to_np(rng.normal(53, 1023 + 3 * l, 0, f[l + 1]))) for l in range(2)]
+    y = omodel.gat_batch_forward(ws, n_id, rp, cl, sg.nb, x, [np.zeros((g.n, f[1]), np.float32)], heads=H)
+    mask = torch.zeros((g.n, g.n), dtype=torch.bool)
+    for v in range(sg.nb):
+        mask[n_id[v], n_id[cl[rp[v]:rp[v + 1]]]] = True
+    h = torch.from_numpy(f64(x))
+    for l, (w, a_dst, a_src) in enumerate(ws):
+        p = (h @ torch.from_numpy(f64(w))).view(g.n, H, -1).permute(1, 0, 2)                 # [H, n, f/H]
+        ad = torch.from_numpy(f64(a_dst)).view(H, 1, -1)
+        asr = torch.from_numpy(f64(a_src)).view(H, 1, -1)
+        e = torch.nn.functional.leaky_relu((p * ad).sum(-1)[:, :, None] + (p * asr).sum(-1)[:, None, :], 0.2)
+        alpha = torch.softmax(e.masked_fill(~mask[None], float("-inf")), dim=2)             # [H, n, n]
+        h = torch.bmm(alpha, p).permute(1, 0, 2).reshape(g.n, -1)
+        if l == 0:
+            h = torch.relu(h)
+    want = h.numpy()[n_id[:sg.nb]]
+    assert np.abs(y - want).max() <= 5e-6 * np.abs(want).max()
+    # and the heads really differ from one head over all columns
+    y1 = omodel.gat_batch_forward(ws, n_id, rp, cl, sg.nb, x, [np.zeros((g.n, f[1]), np.float32)], heads=1)
+    assert np.abs(y1 - y).max() > 1e-3 * np.abs(want).max()

@@ -398,6 +398,118 @@ void oracle_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_r
 }
 
 /*
+ * Backward of PNA's aggregation (chain rule on the aggregators of the operator appendix).  With, for a row v of d > 0
+ * entries and s = log(d + 1) / delta,
+ *     c_i[v, f] = G[v, i F + f] + s G[v, (3 + i) F + f] + G[v, (6 + i) F + f] / s     (i = mean, min, max),
+ * the gradient of the added term is c_0 + c_1 + c_2, and the gradient of X receives, from every entry k of row v,
+ * c_0 / d, plus c_1 where k is the FIRST entry of the row (in stored order) that attains the minimum of feature f,
+ * plus c_2 where it is the first that attains the maximum (the subgradient that follows the aggregator's own choice).
+ * GX has n_out rows (columns u < n_out of the pattern; entries into other columns are dropped, as for the sum
+ * aggregation's adjoint); Gadd [n_rows, F] may be NULL.  Written as a scatter over the rows in double.
+ */
+void oracle_pna_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows, int64_t n_out, const void* X,
+                              int64_t ldx, int dt, int32_t F, double delta, const void* G, int64_t ldg, void* GX,
+                              int64_t ldgx, void* Gadd, int64_t ldga) {
+    double* acc = (double*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)F, sizeof(double));
+    for (int64_t v = 0; v < n_rows; ++v) {
+        int64_t b = rowptr[v], e = rowptr[v + 1];
+        double d = (double)(e - b);
+        double s = log(d + 1.0) / delta;
+        for (int32_t f = 0; f < F; ++f) {
+            if (e == b) {
+                if (Gadd) store_elem(Gadd, v * ldga + f, dt, 0.0);
+                continue;
+            }
+            double c[3];
+            for (int i = 0; i < 3; ++i)
+                c[i] = load_elem(G, v * ldg + (int64_t)i * F + f, dt) + s * load_elem(G, v * ldg + (int64_t)(3 + i) * F + f, dt) +
+                       load_elem(G, v * ldg + (int64_t)(6 + i) * F + f, dt) / s;
+            int64_t kmin = b, kmax = b;
+            double mn = INFINITY, mx = -INFINITY;
+            for (int64_t k = b; k < e; ++k) {
+                double x = load_elem(X, (int64_t)col[k] * ldx + f, dt);
+                if (x < mn) { mn = x; kmin = k; }
+                if (x > mx) { mx = x; kmax = k; }
+            }
+            for (int64_t k = b; k < e; ++k)
+                if (col[k] < n_out) acc[(int64_t)col[k] * F + f] += c[0] / d;
+            if (col[kmin] < n_out) acc[(int64_t)col[kmin] * F + f] += c[1];
+            if (col[kmax] < n_out) acc[(int64_t)col[kmax] * F + f] += c[2];
+            if (Gadd) store_elem(Gadd, v * ldga + f, dt, c[0] + c[1] + c[2]);
+        }
+    }
+    for (int64_t u = 0; u < n_out; ++u)
+        for (int32_t f = 0; f < F; ++f) store_elem(GX, u * ldgx + f, dt, acc[u * F + f]);
+    free(acc);
+}
+
+/*
+ * Backward of GAT's aggregation (chain rule on the operator appendix's equations; GZ is the gradient at the weighted
+ * sum BEFORE any activation).  Per row v with scores t_k = a_dst . P[v] + a_src . P[col k], e_k = LeakyReLU(t_k),
+ * alpha = softmax(e):
+ *     dalpha_k = GZ[v] . P[col k],   de_k = alpha_k (dalpha_k - sum_j alpha_j dalpha_j),   dt_k = de_k * LeakyReLU'(t_k),
+ *     GP[col k] += alpha_k GZ[v] + dt_k a_src,    GP[v] += (sum_k dt_k) a_dst,
+ *     Ga_dst += (sum_k dt_k) P[v],                Ga_src += sum_k dt_k P[col k].
+ * GP has n_out rows (rows u < n_out of P); Ga_dst, Ga_src: fp32 [F], over ALL entries.
+ */
+void oracle_gat_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows, int64_t n_out, const void* P,
+                              int64_t ldp, int dt, int32_t F, const void* a_dst, const void* a_src,
+                              double negative_slope, const void* GZ, int64_t ldgz, void* GP, int64_t ldgp,
+                              float* Ga_dst, float* Ga_src) {
+    double* acc = (double*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)F, sizeof(double));
+    double* gd = (double*)calloc((size_t)F, sizeof(double));
+    double* gs = (double*)calloc((size_t)F, sizeof(double));
+    for (int64_t v = 0; v < n_rows; ++v) {
+        int64_t b = rowptr[v], e = rowptr[v + 1], n = e - b;
+        if (n == 0) continue;
+        double* t = (double*)malloc(sizeof(double) * (size_t)n * 3);
+        double *alpha = t + n, *dal = t + 2 * n;
+        double sv = 0.0, mx = -INFINITY;
+        for (int32_t f = 0; f < F; ++f) sv += load_elem(a_dst, f, dt) * load_elem(P, v * ldp + f, dt);
+        for (int64_t k = 0; k < n; ++k) {
+            double sw = 0.0, da = 0.0;
+            for (int32_t f = 0; f < F; ++f) {
+                double p = load_elem(P, (int64_t)col[b + k] * ldp + f, dt);
+                sw += load_elem(a_src, f, dt) * p;
+                da += load_elem(GZ, v * ldgz + f, dt) * p;
+            }
+            t[k] = sv + sw;
+            dal[k] = da;
+            double ek = t[k] > 0.0 ? t[k] : negative_slope * t[k];
+            if (ek > mx) mx = ek;
+        }
+        double den = 0.0;
+        for (int64_t k = 0; k < n; ++k) {
+            double ek = t[k] > 0.0 ? t[k] : negative_slope * t[k];
+            alpha[k] = exp(ek - mx);
+            den += alpha[k];
+        }
+        double mean_da = 0.0;
+        for (int64_t k = 0; k < n; ++k) { alpha[k] /= den; mean_da += alpha[k] * dal[k]; }
+        double sum_dt = 0.0;
+        for (int64_t k = 0; k < n; ++k) {
+            double dtk = alpha[k] * (dal[k] - mean_da) * (t[k] > 0.0 ? 1.0 : negative_slope);
+            sum_dt += dtk;
+            int64_t c = col[b + k];
+            for (int32_t f = 0; f < F; ++f) {
+                double p = load_elem(P, c * ldp + f, dt);
+                gs[f] += dtk * p;
+                if (c < n_out) acc[c * F + f] += alpha[k] * load_elem(GZ, v * ldgz + f, dt) + dtk * load_elem(a_src, f, dt);
+            }
+        }
+        for (int32_t f = 0; f < F; ++f) {
+            gd[f] += sum_dt * load_elem(P, v * ldp + f, dt);
+            if (v < n_out) acc[v * F + f] += sum_dt * load_elem(a_dst, f, dt);
+        }
+        free(t);
+    }
+    for (int64_t u = 0; u < n_out; ++u)
+        for (int32_t f = 0; f < F; ++f) store_elem(GP, u * ldgp + f, dt, acc[u * F + f]);
+    for (int32_t f = 0; f < F; ++f) { Ga_dst[f] = (float)gd[f]; Ga_src[f] = (float)gs[f]; }
+    free(acc); free(gd); free(gs);
+}
+
+/*
  * Pieces of the auxiliary loss of the paper's Eq. (3), L_reg = || f(h) - f(h + eps) ||: the perturbed input
  * Y = X + alpha E (E holds the drawn perturbations, one row per node) and the Euclidean distance between the
  * rows of two layer outputs, dist[i] = || A[i, :] - B[i, :] ||_2, with its sum over the rows in double.

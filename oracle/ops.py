@@ -241,6 +241,38 @@ def pna_aggregate(rowptr, col, x, delta, add=None) -> np.ndarray:
     return out
 
 
+def pna_aggregate_bwd(rowptr, col, x, delta, g, n_out, want_add=True):
+    """Backward of pna_aggregate: (GX [n_out, F], Gadd [n_rows, F] or None) from G [n_rows, 9F]."""
+    rowptr, col = _i32(rowptr), _i32(col)
+    x, ldx = _rows(x)
+    g, ldg = _rows(g)
+    n_rows, f = rowptr.size - 1, x.shape[1]
+    assert g.dtype == x.dtype and g.shape == (n_rows, 9 * f)
+    gx = np.empty((n_out, f), dtype=x.dtype)
+    gadd = np.empty((n_rows, f), dtype=x.dtype) if want_add else None
+    lib().oracle_pna_aggregate_bwd(_p(rowptr), _p(col), C.c_int64(n_rows), C.c_int64(n_out), _p(x), C.c_int64(ldx),
+                                   C.c_int(_dt(x)), C.c_int32(f), C.c_double(delta), _p(g), C.c_int64(ldg), _p(gx),
+                                   C.c_int64(f), _p(gadd), C.c_int64(f))
+    return gx, gadd
+
+
+def gat_aggregate_bwd(rowptr, col, p, a_dst, a_src, gz, n_out, negative_slope=0.2):
+    """Backward of gat_aggregate (gz: gradient at the weighted sum before any activation):
+    (GP [n_out, F] in p's type, Ga_dst float32[F], Ga_src float32[F])."""
+    rowptr, col = _i32(rowptr), _i32(col)
+    p, ldp = _rows(p)
+    gz, ldgz = _rows(gz)
+    n_rows, f = rowptr.size - 1, p.shape[1]
+    a_dst, a_src = np.ascontiguousarray(a_dst), np.ascontiguousarray(a_src)
+    assert a_dst.dtype == p.dtype == a_src.dtype == gz.dtype and gz.shape == (n_rows, f)
+    gp = np.empty((n_out, f), dtype=p.dtype)
+    gd, gs = np.empty(f, dtype=np.float32), np.empty(f, dtype=np.float32)
+    lib().oracle_gat_aggregate_bwd(_p(rowptr), _p(col), C.c_int64(n_rows), C.c_int64(n_out), _p(p), C.c_int64(ldp),
+                                   C.c_int(_dt(p)), C.c_int32(f), _p(a_dst), _p(a_src), C.c_double(negative_slope),
+                                   _p(gz), C.c_int64(ldgz), _p(gp), C.c_int64(f), _p(gd), _p(gs))
+    return gp, gd, gs
+
+
 def gat_aggregate(rowptr, col, p, a_dst, a_src, negative_slope=0.2, relu=False) -> np.ndarray:
     """Z[v] = sum_k softmax_k(LeakyReLU(a_dst.P[v] + a_src.P[col k])) P[col k] over the entries of row v."""
     rowptr, col = _i32(rowptr), _i32(col)

@@ -125,3 +125,30 @@ def test_multi_head_model_equals_dense_heads_in_float64():
     # and the heads really differ from one head over all columns
     y1 = omodel.gat_batch_forward(ws, n_id, rp, cl, sg.nb, x, [np.zeros((g.n, f[1]), np.float32)], heads=1)
     assert np.abs(y1 - y).max() > 1e-3 * np.abs(want).max()
+
+
+def test_backward_matches_float64_autograd():
+    """oracle_gat_aggregate_bwd (gradients of P, a_dst, a_src) against torch autograd on the dense float64
+    re-statement of the aggregation; all rows of P and the in-batch rows only; negative slope 0.2 and 1."""
+    sg, rp, cl, p, a_dst, a_src = _case(f=7)
+    gz = to_np(rng.normal_matrix(51, 1003, sg.nb, 7))
+    mask = torch.zeros((sg.nb, sg.nv), dtype=torch.bool)
+    for v in range(sg.nb):
+        mask[v, cl[rp[v]:rp[v + 1]]] = True
+    for slope in (0.2, 1.0):
+        pp = torch.from_numpy(f64(p)).requires_grad_()
+        ad = torch.from_numpy(f64(a_dst)).requires_grad_()
+        asr = torch.from_numpy(f64(a_src)).requires_grad_()
+        e = torch.nn.functional.leaky_relu((pp[:sg.nb] @ ad)[:, None] + (pp @ asr)[None, :], slope)
+        z = torch.softmax(e.masked_fill(~mask, float("-inf")), dim=1) @ pp
+        (z * torch.from_numpy(f64(gz))).sum().backward()
+        gp, gd, gs = ops.gat_aggregate_bwd(rp, cl, p, a_dst, a_src, gz, sg.nv, slope)
+        scale = np.abs(asr.grad.numpy()).max()
+        for got, want in ((gp, pp.grad.numpy()), (gd, ad.grad.numpy()), (gs, asr.grad.numpy())):
+            # with slope 1 the receiving node's score shifts a whole row: a_dst's gradient is zero up to rounding
+            assert np.abs(got - want).max() <= 2e-6 * max(np.abs(want).max(), 1e-6 * scale), slope
+        if slope == 1.0:
+            assert np.abs(gd).max() <= 1e-9 * scale
+        gp_b, gd_b, gs_b = ops.gat_aggregate_bwd(rp, cl, p, a_dst, a_src, gz, sg.nb, slope)
+        assert np.array_equal(gp_b, gp[:sg.nb]) and np.array_equal(gd_b, gd) and np.array_equal(gs_b, gs)
+    assert np.abs(pp.grad.numpy()[sg.nb:]).max() > 0

@@ -140,3 +140,48 @@ def test_pna_whole_graph_batch_needs_no_history():
     order = np.argsort(n_id[:sg.nb])
     full_rows = a[order][n_id1[:sg1.nb]]
     assert np.abs(y1 - full_rows).max() <= 5e-6 * np.abs(full_rows).max()
+
+
+def test_backward_matches_float64_autograd_and_the_first_extreme_takes_the_gradient():
+    """oracle_pna_aggregate_bwd against torch autograd on a dense re-statement of the nine blocks (masked mean,
+    amin, amax; continuous data, so no ties), for all columns and for the in-batch columns only; then a tie:
+    the first entry of the row that attains the extreme receives its gradient."""
+    import torch
+    wl = _workload("gin", n=300, layers=2, f=8)
+    g = wl.graph
+    sg, n_id, rp, cl = _sub(wl, wl.batches[2])
+    f = 6
+    x = to_np(rng.normal_matrix(42, 910, sg.nv, f))
+    q = to_np(rng.normal_matrix(42, 911, sg.nb, f))
+    gout = to_np(rng.normal_matrix(42, 912, sg.nb, 9 * f))
+    delta = float(np.log(to_np(g.deg).astype(np.float64) + 1.0).mean())
+    a = torch.from_numpy(_dense(rp, cl, sg.nb, sg.nv))
+    d = a.sum(dim=1).double()
+    has = d > 0
+    xt = torch.from_numpy(f64(x)).requires_grad_()
+    qt = torch.from_numpy(f64(q)).requires_grad_()
+    mean = (a.double() @ xt) / d.clamp(min=1)[:, None]
+    mn = torch.where(a[:, :, None], xt[None], torch.tensor(float("inf"), dtype=torch.float64)).amin(dim=1)
+    mx = torch.where(a[:, :, None], xt[None], torch.tensor(float("-inf"), dtype=torch.float64)).amax(dim=1)
+    s = (torch.log(d + 1.0) / delta)[:, None]
+    agg = [torch.where(has[:, None], t + qt, torch.zeros_like(qt)) for t in (mean, mn, mx)]
+    out = torch.cat(agg + [torch.where(has[:, None], s * t, torch.zeros_like(t)) for t in agg] +
+                    [torch.where(has[:, None], t / s.clamp(min=1e-30), torch.zeros_like(t)) for t in agg], dim=1)
+    fwd = ops.pna_aggregate(rp, cl, x, delta, add=q)
+    assert np.abs(fwd - out.detach().numpy()).max() <= 1e-6 * np.abs(fwd).max()       # the same function
+    (out * torch.from_numpy(f64(gout))).sum().backward()
+    gx, gadd = ops.pna_aggregate_bwd(rp, cl, x, delta, gout, sg.nv)
+    want_x, want_q = xt.grad.numpy(), qt.grad.numpy()
+    assert np.abs(gx - want_x).max() <= 1e-6 * np.abs(want_x).max()
+    assert np.abs(gadd - want_q).max() <= 1e-6 * np.abs(want_q).max()
+    assert np.abs(want_x[sg.nb:]).max() > 0                                           # halo columns do get gradient
+    gx_b, none = ops.pna_aggregate_bwd(rp, cl, x, delta, gout, sg.nb, want_add=False)
+    assert none is None and np.array_equal(gx_b, gx[:sg.nb])
+    # a tie: two neighbours with the same value in feature 0; the first in stored order takes min and max gradient
+    rp2 = np.array([0, 3], dtype=np.int32)
+    cl2 = np.array([2, 0, 1], dtype=np.int32)
+    x2 = np.array([[5.0], [7.0], [5.0]], dtype=np.float32)                            # entries: x[2]=5, x[0]=5, x[1]=7
+    g2 = np.zeros((1, 9), dtype=np.float32)
+    g2[0, 1] = 1.0                                                                    # gradient on the min block only
+    gx2, _ = ops.pna_aggregate_bwd(rp2, cl2, x2, 1.0, g2, 3)
+    assert gx2[:, 0].tolist() == [0.0, 0.0, 1.0]                                      # column 2 is the first entry with 5

@@ -432,6 +432,41 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
                              void* Z, int64_t ldz, void* stream);
 
 /*
+ * Backward passes of the two aggregations above (chain rule on the equations of the operator appendix), without
+ * atomics: a pass over the rows of the pattern leaves per-row / per-entry factors in `workspace`, a pass over the
+ * columns (the CSC copy: colptr int32[n_cols+1], row int32[nnz], and csc_pos int32[nnz] = the position of every CSC
+ * entry in the CSR arrays) sums each column's contributions in stored order.  n_out <= n_cols output rows are
+ * written (the in-batch nodes when histories are constants, or all of V_b).  workspace: device memory of at least
+ * gas_*_bwd_workspace(...) bytes, caller-owned, contents undefined afterwards.
+ *
+ * gas_pna_aggregate_bwd: G [n_rows, 9 F] is the gradient of gas_pna_aggregate's output.  With s and d as there and
+ *     c_i = G[v, i F + f] + s G[v, (3+i) F + f] + G[v, (6+i) F + f] / s   (i = mean, min, max; rows with entries),
+ * Gadd[v] = c_0 + c_1 + c_2 (optional, [n_rows, F]) and GX[u] receives from every entry (v, u): c_0 / d, plus c_1
+ * where the entry is the FIRST of row v (in stored order) attaining the minimum of that feature, plus c_2 for the
+ * maximum.  colptr needs n_out + 1 entries.
+ *
+ * gas_gat_aggregate_bwd: GZ [n_rows, F] is the gradient at the weighted sum BEFORE any activation (apply
+ * gas_relu_bwd first when the forward call had relu set).  Per row v, with t_k, alpha_k as in gas_gat_aggregate:
+ *     dalpha_k = GZ[v] . P[col k],  dt_k = alpha_k (dalpha_k - sum_j alpha_j dalpha_j) LeakyReLU'(t_k),
+ *     GP[col k] += alpha_k GZ[v] + dt_k a_src,   GP[v] += (sum_k dt_k) a_dst,
+ *     Ga_dst = sum_v (sum_k dt_k) P[v],          Ga_src = sum over all entries of dt_k P[col k]   (fp32 [F]).
+ * n_cols = rows of P = columns of the pattern (the column pass runs over all of them: Ga_src needs every entry).
+ */
+GAS_API int64_t gas_pna_aggregate_bwd_workspace(int64_t n_rows, int32_t F);
+GAS_API gas_status gas_pna_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+                                 const int32_t* colptr, const int32_t* row, const int32_t* csc_pos, int64_t n_out,
+                                 const void* X, int64_t ldx, gas_dtype dt, int32_t F, float delta,
+                                 const void* G, int64_t ldg, void* GX, int64_t ldgx, void* Gadd, int64_t ldga,
+                                 void* workspace, int64_t workspace_bytes, void* stream);
+GAS_API int64_t gas_gat_aggregate_bwd_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, int32_t F);
+GAS_API gas_status gas_gat_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+                                 const int32_t* colptr, const int32_t* row, const int32_t* csc_pos, int64_t n_cols,
+                                 int64_t n_out, int64_t nnz, const void* P, int64_t ldp, gas_dtype dt, int32_t F,
+                                 const void* a_dst, const void* a_src, float negative_slope,
+                                 const void* GZ, int64_t ldgz, void* GP, int64_t ldgp, float* Ga_dst, float* Ga_src,
+                                 void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Pieces of the auxiliary loss of Eq. (3), || f(h) - f(h + eps) ||, which is
  * a second forward pass of a layer on a perturbed input:
  * gas_axpy:          Y = X + alpha E, element-wise over [n_rows, F] of type dt

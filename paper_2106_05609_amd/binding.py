@@ -19,7 +19,8 @@ EXPORTS = [
     "gas_linear", "gas_mlp2", "gas_linear_push", "gas_mlp2_push", "gas_mlp2_keep", "gas_spmm_linear",
     "gas_relu_bwd", "gas_linear_bwd_input", "gas_linear_bwd_weight", "gas_linear_bwd_weight_workspace", "gas_linear_bwd_weight_static",
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd", "gas_row_dot",
-    "gas_pna_aggregate", "gas_gat_aggregate",
+    "gas_pna_aggregate", "gas_gat_aggregate", "gas_pna_aggregate_bwd", "gas_gat_aggregate_bwd",
+    "gas_pna_aggregate_bwd_workspace", "gas_gat_aggregate_bwd_workspace",
 ]
 
 _lib = None
@@ -43,8 +44,10 @@ def lib():
         L.gas_version.restype = C.c_int
         L.gas_plan_destroy.restype = None
         L.gas_linear_bwd_weight_workspace.restype = C.c_int64
+        L.gas_pna_aggregate_bwd_workspace.restype = C.c_int64
+        L.gas_gat_aggregate_bwd_workspace.restype = C.c_int64
         for name in EXPORTS:
-            if name not in ("gas_last_error", "gas_version", "gas_plan_destroy", "gas_linear_bwd_weight_workspace"):
+            if name not in ("gas_last_error", "gas_version", "gas_plan_destroy") and not name.endswith("_workspace"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -512,3 +515,40 @@ class HostTable:
 
     def stride(self, i):
         return self.tensor.stride(i)
+
+
+def gas_pna_aggregate_bwd(rowptr, col, colptr, row, csc_pos, x, g, gx, delta, gadd=None):
+    """Backward of gas_pna_aggregate: gx [n_out, F] (n_out = gx.shape[0] columns of the pattern), gadd [n_rows, F]."""
+    xp, ldx = _mat(x)
+    gp, ldg = _mat(g)
+    op, ldo = _mat(gx)
+    ap, lda = (C.c_void_p(0), C.c_int64(0)) if gadd is None else _mat(gadd)
+    n_rows, F = rowptr.numel() - 1, x.shape[1]
+    if g.shape != (n_rows, 9 * F) or gx.shape[1] != F or g.dtype != x.dtype or gx.dtype != x.dtype:
+        raise ValueError("gas_pna_aggregate_bwd: shapes or dtypes do not match")
+    nbytes = int(lib().gas_pna_aggregate_bwd_workspace(C.c_int64(n_rows), C.c_int32(F)))
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x.device)
+    _check(lib().gas_pna_aggregate_bwd(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
+                                       _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(csc_pos, torch.int32),
+                                       C.c_int64(gx.shape[0]), xp, ldx, C.c_int(_dt(x)), C.c_int32(F), C.c_float(delta),
+                                       gp, ldg, op, ldo, ap, lda, _ptr(ws), C.c_int64(nbytes), _stream()))
+
+
+def gas_gat_aggregate_bwd(rowptr, col, colptr, row, csc_pos, p, a_dst, a_src, gz, gp_out, ga_dst, ga_src,
+                          negative_slope=0.2):
+    """Backward of gas_gat_aggregate (gz: gradient before any activation): gp_out [n_out, F] rows of P's gradient,
+    ga_dst / ga_src float32 [F]."""
+    pp, ldp = _mat(p)
+    zp, ldz = _mat(gz)
+    op, ldo = _mat(gp_out)
+    n_rows, n_cols, F, nnz = rowptr.numel() - 1, p.shape[0], p.shape[1], col.numel()
+    if gz.shape != (n_rows, F) or gp_out.shape[1] != F or colptr.numel() != n_cols + 1 or gz.dtype != p.dtype or \
+            gp_out.dtype != p.dtype or ga_dst.dtype != torch.float32 or ga_src.dtype != torch.float32:
+        raise ValueError("gas_gat_aggregate_bwd: shapes or dtypes do not match")
+    nbytes = int(lib().gas_gat_aggregate_bwd_workspace(C.c_int64(n_rows), C.c_int64(n_cols), C.c_int64(nnz), C.c_int32(F)))
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=p.device)
+    _check(lib().gas_gat_aggregate_bwd(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
+                                       _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(csc_pos, torch.int32),
+                                       C.c_int64(n_cols), C.c_int64(gp_out.shape[0]), C.c_int64(nnz), pp, ldp,
+                                       C.c_int(_dt(p)), C.c_int32(F), _ptr(a_dst), _ptr(a_src), C.c_float(negative_slope),
+                                       zp, ldz, op, ldo, _ptr(ga_dst), _ptr(ga_src), _ptr(ws), C.c_int64(nbytes), _stream()))

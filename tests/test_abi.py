@@ -108,7 +108,8 @@ def test_every_entry_point_rejects_bad_arguments_without_launching():
 
 def test_a_zero_count_is_a_no_op():
     """n = 0 (an empty batch, an empty halo) succeeds without touching any pointer; the weight gradient and the
-    squared norm are the exceptions, since an empty sum still has to be written (a zero matrix, a zero)."""
+    squared norm are the exceptions, since an empty sum still has to be written (a zero matrix, a zero), and so are
+    the backward aggregations, whose output rows (n_out of them) exist without any row of the pattern."""
     L = binding.lib()
     for name, params in _signatures().items():
         if any("gas_plan" in p for p in params):
@@ -118,4 +119,5 @@ def test_a_zero_count_is_a_no_op():
         fn = getattr(L, name)
         fn.restype = ctypes.c_int
         st = fn(*_args(params, None, 0, 0))
-        assert st == (-1 if name in ("gas_linear_bwd_weight", "gas_linear_bwd_weight_static", "gas_sq_norm") else 0), name
+        assert st == (-1 if name in ("gas_linear_bwd_weight", "gas_linear_bwd_weight_static", "gas_sq_norm",
+                                  "gas_pna_aggregate_bwd", "gas_gat_aggregate_bwd") else 0), name

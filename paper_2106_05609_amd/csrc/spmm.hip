@@ -186,7 +186,7 @@ __device__ __forceinline__ void epilogue(const SpmmArgs& a, int64_t row, int uni
     }
 }
 
-// ---- wave-per-row path for rows of exactly 64 vectors of VB bytes (1 KiB or 512 B)
+// ---- wave-per-row path for rows of exactly 64 vectors of VB bytes (1 KiB, 512 B or 256 B)
 // Short rows are the common case on power-law graphs, and one wavefront per row
 // pays three dependent memory latencies (row pointers, indices, feature rows)
 // for a handful of gathers.  Here consecutive light rows are bundled at plan
@@ -200,6 +200,8 @@ __device__ __forceinline__ void epilogue(const SpmmArgs& a, int64_t row, int uni
 template <int VB> struct VecOf;
 template <> struct VecOf<16> { typedef u32x4 type; };
 template <> struct VecOf<8> { typedef u32x2 type; };
+typedef uint32_t u32x1 __attribute__((ext_vector_type(1)));
+template <> struct VecOf<4> { typedef u32x1 type; };
 
 template <int VB, bool XBF>
 struct LaneAcc {
@@ -388,8 +390,10 @@ __device__ __forceinline__ void chunk_wave_per_row(const SpmmArgs& a, int64_t c)
         *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc.v[4], acc.v[5], acc.v[6], acc.v[7]};
     } else if constexpr (E == 4) {
         *reinterpret_cast<f32x4*>(dst) = f32x4{acc.v[0], acc.v[1], acc.v[2], acc.v[3]};
-    } else {
+    } else if constexpr (E == 2) {
         *reinterpret_cast<u32x2*>(dst) = u32x2{__float_as_uint(acc.v[0]), __float_as_uint(acc.v[1])};
+    } else {
+        *dst = acc.v[0];
     }
 }
 
@@ -522,6 +526,7 @@ gas_status dispatch_chunks(const SpmmArgs& a, hipStream_t s) {
     const int u = a.units;
     if (u == 64) return launch_chunks<64, 1, 8, XBF, 16>(a, s);
     if (u == 32) return launch_chunks<32, 1, 8, XBF, 8>(a, s);
+    if (u == 16) return launch_chunks<16, 1, 8, XBF, 4>(a, s);
     if (u <= 8) return launch_chunks<8, 1, 8, XBF>(a, s);
     if (u <= 16) return launch_chunks<16, 1, 8, XBF>(a, s);
     if (u <= 32) return launch_chunks<32, 1, 8, XBF>(a, s);
@@ -557,9 +562,10 @@ gas_status dispatch_units(const SpmmArgs& a, hipStream_t s) {
                            0, s, a);
     }
     gas_status st;
-    // rows of exactly 1 KiB or 512 B: grouped wave-per-row path
+    // rows of exactly 1 KiB, 512 B or 256 B: grouped wave-per-row path
     if (a.group && u == 64) st = launch_rows<64, 1, 8, XBF, ZBF, 16>(a, s);
     else if (a.group && u == 32) st = launch_rows<32, 1, 4, XBF, ZBF, 8>(a, s);
+    else if (a.group && u == 16) st = launch_rows<16, 1, 4, XBF, ZBF, 4>(a, s);
     else if (u <= 8) st = launch_rows<8, 1, 2, XBF, ZBF>(a, s);
     else if (u <= 16) st = launch_rows<16, 1, 4, XBF, ZBF>(a, s);
     else if (u <= 32) st = launch_rows<32, 1, 4, XBF, ZBF>(a, s);

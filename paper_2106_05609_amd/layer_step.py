@@ -32,9 +32,14 @@ KINDS = ("first", "middle", "last")
 
 
 class LayerStep:
-    def __init__(self, cfg, g, sg, rng, device, kind="middle", bg=None, plan_options=None):
+    def __init__(self, cfg, g, sg, rng, device, kind="middle", bg=None, plan_options=None, tables_in=None, table_out=None,
+                 pools=None):
         """cfg: benchmark configuration, g: graph, sg: batch subgraph (index tensors on `device`),
-        rng: the seeded generator module for the synthetic tensors, bg: the batch's plans if already built."""
+        rng: the seeded generator module for the synthetic tensors, bg: the batch's plans if already built.
+        tables_in: tensors [N, F_in] allocated by the caller beforehand, every one of which is filled with the table
+        the layer gathers from (place_table then keeps the one the gathers run fastest on); table_out: likewise a
+        caller-allocated [N, F_out] tensor for the table the layer pushes to; pools: two caller-allocated byte
+        buffers the two mini-batch tensors are carved from (same reason: memory allocated early)."""
         assert kind in KINDS
         self.cfg, self.sg, self.kind = cfg, sg, kind
         self.nb, self.nh, self.nv, self.nnz = sg.nb, sg.nh, sg.nv, sg.nnz
@@ -55,14 +60,34 @@ class LayerStep:
         nb, nv, Fi, Fo = self.nb, self.nv, self.F_in, self.F_out
         # the table the rows outside the batch come from: the feature table for the first layer, else history l
         self.hist_in = rng.normal_matrix(cfg.seed, 10 if kind == "first" else 200, cfg.n, Fi, device, dt)
-        self.hist_out = torch.zeros((cfg.n, Fo), dtype=dt, device=device) if self.does_push else None
+        self.candidates = []
+        if tables_in:
+            for t in tables_in:
+                assert t.shape == self.hist_in.shape and t.dtype == dt
+                B.gas_pull(self.hist_in, None, t, base=0, n=t.shape[0])       # the library's own contiguous copy
+            self.candidates = list(tables_in)
+            self.hist_in = tables_in[0]
+        self.hist_out = None
+        if self.does_push:
+            self.hist_out = table_out.zero_() if table_out is not None else torch.zeros((cfg.n, Fo), dtype=dt, device=device)
+        def carve(pool, rows, cols):
+            if pool is None:
+                return torch.empty((rows, cols), dtype=dt, device=device)
+            nbytes = rows * cols * (4 if dt == torch.float32 else 2)
+            assert pool.numel() >= nbytes, "pool too small for the mini-batch tensor"
+            return pool[:nbytes].view(dt).view(rows, cols)
+
+        px, pxn = pools if pools else (None, None)
+        self.x = carve(px, nv, Fi)
         if kind == "first":
-            self.x = torch.zeros((nv, Fi), dtype=dt, device=device)      # every row arrives through gas_pull
+            self.x.zero_()                                               # every row arrives through gas_pull
         else:
-            self.x = rng.normal_matrix(cfg.seed, 210, nv, Fi, device, dt)    # rows 0..nb-1: fresh in-batch embeddings
+            fresh = rng.normal_matrix(cfg.seed, 210, nb, Fi, device, dt)
+            self.x[:nb] = fresh                                          # rows 0..nb-1: fresh in-batch embeddings
             self.x[nb:] = 0                                              # halo rows arrive through gas_pull
+            del fresh
         self.z = torch.empty((nb, Fi), dtype=dt, device=device)
-        self.x_next = torch.empty((nv if self.does_push else nb, Fo), dtype=dt, device=device)
+        self.x_next = carve(pxn, nv if self.does_push else nb, Fo)
         if self.does_spmm_t:
             self.gz = rng.normal_matrix(cfg.seed, 211, nb, Fi, device, dt)   # upstream gradient for the backward aggregation
             self.gx = torch.empty((nb, Fi), dtype=dt, device=device)
@@ -76,6 +101,51 @@ class LayerStep:
         self.h0 = rng.normal_matrix(cfg.seed, 212, nb, Fi, device, dt) if cfg.op == "gcnii" else None
         self.beta = executor.gcnii_beta(2)
         self.diag = (1.0 + cfg.gin_eps) if self.gin else 0.0
+
+    def place_table(self, candidates=3, reps=3):
+        """Where the driver puts a table of tens of gigabytes changes the time of the random gathers from it by up to
+        10 % (same data, same process, same box; see profiles/): a training run allocates its history tables once,
+        so it can afford to try a few allocations and keep the best.  Times the in-place aggregation on every
+        candidate table (the ones the caller allocated beforehand, else `candidates - 1` further copies allocated
+        here), keeps the fastest and drops the others.  Returns the per-candidate times in ms (the kept one first)."""
+        bg, nb = self.bg, self.nb
+
+        def time_on(table):
+            self.hist_in = table
+            for _ in range(2):
+                self._aggregate_in_place()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record()
+            for _ in range(reps):
+                self._aggregate_in_place()
+            ev[1].record()
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) / reps
+
+        if self.kind == "first":
+            B.gas_pull(self.hist_in, bg.n_id[:nb], self.x[:nb])
+        tables = list(self.candidates) if self.candidates else [self.hist_in]
+        while len(tables) < candidates:
+            t = torch.empty_like(self.hist_in)
+            B.gas_pull(self.hist_in, None, t, base=0, n=t.shape[0])
+            tables.append(t)
+        times = [time_on(t) for t in tables]
+        best = min(range(len(tables)), key=lambda i: times[i])
+        self.hist_in = tables[best]
+        self.candidates = [tables[best]]
+        del tables
+        torch.cuda.empty_cache()
+        return [round(times[best], 4)] + [round(t, 4) for i, t in enumerate(times) if i != best]
+
+    def _aggregate_in_place(self):
+        cfg, bg, xb = self.cfg, self.bg, self.x[:self.nb]
+        if self.gin:
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, xb, self.hist_in, self.z, diag=self.diag)
+        elif cfg.op == "gcnii":
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z, s_agg=1.0 - cfg.alpha,
+                            r=self.h0, s_res=cfg.alpha)
+        else:
+            B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z)
 
     def run(self, mark=None, skip_spmm_t=False, fused=False, only_spmm_t=False):
         """fused: the aggregation reads the rows outside the batch from their table itself
@@ -99,14 +169,7 @@ class LayerStep:
             B.gas_pull(self.hist_in, bg.n_id[nb:], self.x[nb:])
         mark(1)
         if fused:
-            xb = self.x[:nb]
-            if self.gin:
-                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, None, xb, self.hist_in, self.z, diag=self.diag)
-            elif cfg.op == "gcnii":
-                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z, s_agg=1.0 - cfg.alpha,
-                                r=self.h0, s_res=cfg.alpha)
-            else:
-                B.gas_spmm_hist(bg.plan, bg.rowptr, bg.src, bg.val, xb, self.hist_in, self.z)
+            self._aggregate_in_place()
         elif self.gin:
             B.gas_spmm(bg.plan, bg.rowptr, bg.col, None, self.x, self.z, diag=self.diag)
         elif cfg.op == "gcnii":

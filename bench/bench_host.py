@@ -7,7 +7,11 @@ mini-batches of a benchmark configuration with
   host-concurrent  the same tables, every layer's halo rows pulled ahead on one stream and every layer's output
                    pushed behind the computation on another (executor.forward_batch_host).
 
-All three give the same bits (tests/test_gpu_gas.py).  Before the sweeps the host link itself is measured with
+With --disk DIR a fourth variant keeps the tables in files under DIR (executor.forward_batch_disk: host threads
+gather the rows into pinned buffers, copies run beside the computation), and the file path itself is measured with
+the same 100,000 rows.
+
+All give the same bits (tests/test_gpu_gas.py, tests/test_gpu_disk.py).  Before the sweeps the host link itself is measured with
 100,000 rows of 1 KiB each way: a pull alone, a push alone, and both at once on two streams (and, for comparison,
 the copy engines moving the same contiguous bytes both ways at once).  One JSON line on stdout, a table on stderr.
 """
@@ -28,6 +32,9 @@ def main():
     p.add_argument("--scale", type=float, default=1.0)
     p.add_argument("--batches", type=int, default=4, help="consecutive mini-batches per sweep")
     p.add_argument("--reps", type=int, default=5, help="timed sweeps")
+    p.add_argument("--disk", default=None, help="directory for history tables kept in files (adds the disk variant)")
+    p.add_argument("--io-threads", type=int, default=8)
+    p.add_argument("--disk-calls", action="store_true", help="pread / pwrite instead of the mapped file")
     args = p.parse_args()
     if not torch.cuda.is_available():
         sys.exit("bench_host.py: no GPU visible")
@@ -103,6 +110,33 @@ def main():
     print(f"host link, {gb:.3f} GB each way: pull {link['pull_ms']} ms, push {link['push_ms']} ms, both at once "
           f"{link['pull_and_push_ms']} ms ({2 * gb / link['pull_and_push_ms'] * 1e3:.1f} GB/s); copy engines both ways "
           f"{link['copy_engines_both_ways_ms']} ms", file=sys.stderr, flush=True)
+    disk, dpipe = None, None
+    if args.disk:
+        import time
+        os.makedirs(args.disk, exist_ok=True)
+        probe = gas.DiskTable(os.path.join(args.disk, "probe.bin"), n_link, 256, torch.float32, create=True,
+                              io_threads=args.io_threads, calls=args.disk_calls)
+        rows_host = rows.cpu()
+
+        def wall(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            return (time.perf_counter() - t0) / reps * 1e3
+        link["disk_push_ms"] = round(wall(lambda: probe.wait(probe.push(d_out, rows_host))), 3)
+        link["disk_pull_ms"] = round(wall(lambda: probe.wait(probe.pull(rows_host, d_in))), 3)
+        link["disk_push_range_ms"] = round(wall(lambda: probe.wait(probe.push(d_out, None, base=0))), 3)
+        link["disk_pull_range_ms"] = round(wall(lambda: probe.wait(probe.pull(None, d_in, base=0))), 3)
+        print(f"file path, {gb:.3f} GB: scattered rows pull {link['disk_pull_ms']} ms, push {link['disk_push_ms']} ms; "
+              f"one range pull {link['disk_pull_range_ms']} ms, push {link['disk_push_range_ms']} ms "
+              f"({args.io_threads} I/O threads)", file=sys.stderr, flush=True)
+        probe.close()
+        os.remove(os.path.join(args.disk, "probe.bin"))
+        disk = [gas.DiskTable(os.path.join(args.disk, f"hist{l}.bin"), g.n, w, dt, create=True,
+                              io_threads=args.io_threads, calls=args.disk_calls) for l, w in enumerate(hw)]
+        dpipe = executor.DiskPipeline()
     del t_in, t_out, d_in, d_out
 
     def sweep(kind):
@@ -111,28 +145,38 @@ def main():
                 executor.forward_batch(model, bg, x, hbm)
             elif kind == "host-serial":
                 executor.forward_batch(model, bg, x, host)
+            elif kind == "disk":
+                executor.forward_batch_disk(model, bg, x, disk, dpipe)
             else:
                 executor.forward_batch_host(model, bg, x, host, pipe)
         if kind == "host-concurrent":
             pipe.join()
+        if kind == "disk":
+            dpipe.join()
 
     out = {"config": cfg.name, "host_link": link, "batches": len(bgs), "layers": L, "history_tables": len(hw),
            "rows_pulled_per_sweep": halo, "rows_pushed_per_sweep": inb, "host_link_GB_per_sweep": round(moved / 1e9, 3),
            "ms_per_batch": {}}
-    for kind in ("hbm", "host-serial", "host-concurrent"):
+    for kind in ("hbm", "host-serial", "host-concurrent") + (("disk",) if disk else ()):
+        import time
         for _ in range(2):
             sweep(kind)
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
+        t0 = time.perf_counter()                    # the disk variant waits on the host, so wall time for all
         for _ in range(args.reps):
             sweep(kind)
-        b.record()
         torch.cuda.synchronize()
-        t = a.elapsed_time(b) / args.reps / len(bgs)
+        t = (time.perf_counter() - t0) * 1e3 / args.reps / len(bgs)
         out["ms_per_batch"][kind] = round(t, 4)
         print(f"{kind:16s} {t:9.3f} ms per batch", file=sys.stderr, flush=True)
     same = all(torch.equal(a.cpu(), h.tensor) for a, h in zip(hbm, host))
+    if disk:
+        for a, t in zip(hbm, disk):
+            back = torch.empty(a.shape, dtype=a.dtype)
+            t.read_rows(back)
+            same = same and torch.equal(a.cpu(), back)
+            t.close()
+            os.remove(t.path)
     out["tables_identical"] = same
     rate = 2 * gb / link["pull_and_push_ms"] * 1e3          # GB/s with both directions busy
     out["link_bound_ms_per_batch"] = round(moved / len(bgs) / 1e6 / rate, 3)

@@ -52,7 +52,8 @@ typedef enum {
     GAS_ERR_DTYPE = -2,  /* unknown or unsupported dtype combination */
     GAS_ERR_RANGE = -4,  /* gas_validate_indices found an index out of range */
     GAS_ERR_HIP = -5,    /* a HIP runtime call failed */
-    GAS_ERR_NOMEM = -6   /* device allocation for a plan failed */
+    GAS_ERR_NOMEM = -6,  /* device allocation for a plan failed */
+    GAS_ERR_IO = -7      /* a file of a history table on disk could not be opened, sized, read or written */
 } gas_status;
 
 /* Message of the last failure on this thread (static storage, never NULL). */
@@ -519,6 +520,74 @@ GAS_API gas_status gas_pull_host(const void* hist, int64_t n_hist_rows, int64_t 
 GAS_API gas_status gas_push_host(const void* src, int64_t ld_src, const int32_t* idx, int64_t base,
                          int64_t n, int32_t F, gas_dtype dt,
                          void* hist, int64_t n_hist_rows, int64_t ld_hist, void* stream);
+
+/*
+ * Histories on disk (the paper's "Conclusion and Future Work" names disk
+ * storage as the tier behind host memory; the transfers follow the scheme of
+ * its Section 5 "PyGAS": rows are gathered into pinned buffers by host
+ * threads, copied beside the computation, and a layer waits only for its
+ * own rows).  A gas_disk_table is a file of n_rows x F elements of type dt,
+ * row after row, nothing else in it (rows never written read as zeros), with
+ * I/O threads, two pinned staging buffers, a copy stream at the default
+ * priority and one worker thread that runs the table's transfers in the
+ * order they were queued.
+ *
+ * gas_disk_open:  flags: GAS_DISK_CREATE makes (or empties) the file and
+ *                 sizes it; without it the file must exist with exactly the
+ *                 table's size.  The host threads reach the file through a
+ *                 shared mapping (copies into and out of the page cache, no
+ *                 system call per row); then nobody may shrink the file
+ *                 while the table is open, and a failing storage device
+ *                 ends the process with a signal.  GAS_DISK_CALLS uses
+ *                 pread / pwrite instead: slower for scattered rows, every
+ *                 failure a GAS_ERR_IO.  io_threads 0 = 8; staging_bytes 0 =
+ *                 32 MiB per buffer (allocated at the first transfer).
+ *                 HOST pointers.
+ * gas_disk_pull:  dst[i, 0:F] = table[r(i), 0:F] with r(i) as in gas_pull;
+ *                 idx is a HOST array (copied before the call returns), dst
+ *                 DEVICE memory [n, F], row stride ld_dst.  Returns at once
+ *                 with a ticket; the transfer starts after the work queued
+ *                 on `stream` so far has finished (so it may overwrite rows
+ *                 that work still reads) and is complete, rows in dst, when
+ *                 gas_disk_wait(ticket) returns.
+ * gas_disk_push:  table[r(i), 0:F] = src[i, 0:F], src DEVICE memory, read
+ *                 after the work queued on `stream` so far; src must stay
+ *                 unchanged until gas_disk_wait(ticket) returns.  Duplicate
+ *                 rows in idx: one of the values is kept.
+ * gas_disk_wait:  blocks the calling thread until the transfer with that
+ *                 ticket (and all queued before it) has finished; ticket 0 =
+ *                 everything queued so far.  Returns the first failure of
+ *                 any transfer of the table (GAS_ERR_IO, GAS_ERR_HIP), which
+ *                 is kept: later calls report it too and later transfers are
+ *                 dropped.
+ * gas_disk_read_rows / gas_disk_write_rows: the same row moves between the
+ *                 file and HOST memory, done by the calling thread after
+ *                 everything queued has finished (initialising a table,
+ *                 reading results back).
+ * gas_disk_sync:  waits like gas_disk_wait(0) and flushes the file's data to
+ *                 the storage device.
+ * gas_disk_close: finishes queued transfers, frees everything; the file
+ *                 stays.  A NULL table is allowed.
+ * Indices and ranges are checked before anything is queued (GAS_ERR_RANGE).
+ * One thread at a time may call into a given table; different tables are
+ * independent.  All of a table's device transfers use the device that was
+ * current at its first pull or push.  Pure data movement: bit-exact.
+ */
+typedef struct gas_disk_table gas_disk_table;
+enum { GAS_DISK_CREATE = 1, GAS_DISK_CALLS = 2 };
+GAS_API gas_status gas_disk_open(const char* path, int64_t n_rows, int32_t F, gas_dtype dt, int32_t flags,
+                         int32_t io_threads, int64_t staging_bytes, gas_disk_table** table);
+GAS_API gas_status gas_disk_close(gas_disk_table* table);
+GAS_API gas_status gas_disk_pull(gas_disk_table* table, const int32_t* idx, int64_t base, int64_t n,
+                         void* dst, int64_t ld_dst, void* stream, int64_t* ticket);
+GAS_API gas_status gas_disk_push(gas_disk_table* table, const int32_t* idx, int64_t base, int64_t n,
+                         const void* src, int64_t ld_src, void* stream, int64_t* ticket);
+GAS_API gas_status gas_disk_wait(gas_disk_table* table, int64_t ticket);
+GAS_API gas_status gas_disk_read_rows(gas_disk_table* table, const int32_t* idx, int64_t base, int64_t n,
+                              void* dst, int64_t ld_dst);
+GAS_API gas_status gas_disk_write_rows(gas_disk_table* table, const int32_t* idx, int64_t base, int64_t n,
+                               const void* src, int64_t ld_src);
+GAS_API gas_status gas_disk_sync(gas_disk_table* table);
 
 /*
  * Debug helper: GAS_ERR_RANGE if any idx[i] is outside [0, limit).  Copies a

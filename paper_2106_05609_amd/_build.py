@@ -40,7 +40,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         for src, p in procs:
             if p.wait() != 0:
                 raise RuntimeError(f"hipcc failed on {src}")
-        subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+        subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB] + objs)
     return LIB
 
 

@@ -21,6 +21,8 @@ EXPORTS = [
     "gas_softmax_xent", "gas_sgd_step", "gas_sq_norm", "gas_sgd_step_clipped", "gas_axpy", "gas_row_distance", "gas_row_distance_bwd", "gas_row_dot",
     "gas_pna_aggregate", "gas_gat_aggregate", "gas_pna_aggregate_bwd", "gas_gat_aggregate_bwd",
     "gas_pna_aggregate_bwd_workspace", "gas_gat_aggregate_bwd_workspace",
+    "gas_disk_open", "gas_disk_close", "gas_disk_pull", "gas_disk_push", "gas_disk_wait", "gas_disk_read_rows",
+    "gas_disk_write_rows", "gas_disk_sync",
 ]
 
 _lib = None
@@ -515,6 +517,90 @@ class HostTable:
 
     def stride(self, i):
         return self.tensor.stride(i)
+
+
+class DiskTable:
+    """A history table in a file (gas_disk_* of the C ABI).  Index lists are int32 tensors or arrays in HOST memory;
+    pull and push return a ticket and run beside the caller, wait(ticket) blocks until that transfer is complete.
+    The tensors of a transfer are kept alive here until it has been waited for."""
+
+    def __init__(self, path, n_rows, width, dtype, create=True, io_threads=0, staging_bytes=0, calls=False):
+        self.shape, self.dtype, self.path = (int(n_rows), int(width)), dtype, path
+        self._code = _dt(torch.empty(0, dtype=dtype))
+        self._h = C.c_void_p(0)
+        self._held = {}
+        _check(lib().gas_disk_open(os.fsencode(path), C.c_int64(n_rows), C.c_int32(width), C.c_int(self._code),
+                                   C.c_int32((1 if create else 0) | (2 if calls else 0)), C.c_int32(io_threads),
+                                   C.c_int64(staging_bytes),
+                                   C.byref(self._h)))
+
+    def _idx(self, idx):
+        if idx is None:
+            return None, C.c_void_p(0)
+        t = torch.as_tensor(idx)
+        if t.is_cuda or t.dtype != torch.int32 or t.dim() != 1 or not t.is_contiguous():
+            raise ValueError("DiskTable: idx must be a contiguous 1-D int32 tensor in host memory")
+        return t, C.c_void_p(t.data_ptr())
+
+    def _rows(self, t, n, device):
+        if t.dtype != self.dtype or t.dim() != 2 or t.shape[1] != self.shape[1] or t.shape[0] < n \
+                or t.is_cuda != device:
+            raise ValueError("DiskTable: rows do not match the table")
+        return _mat(t)
+
+    def _transfer(self, fn, idx, base, n, rows):
+        it, ip = self._idx(idx)
+        n = (it.numel() if it is not None else rows.shape[0]) if n is None else n
+        rp, ld = self._rows(rows, n, True)
+        ticket = C.c_int64(0)
+        _check(fn(self._h, ip, C.c_int64(base), C.c_int64(n), rp, ld, _stream(), C.byref(ticket)))
+        self._held[ticket.value] = rows
+        return ticket.value
+
+    def pull(self, idx, dst, base=0, n=None) -> int:
+        """dst[i] = table[idx[i]] (or table[base + i]); starts after the current stream's work so far."""
+        return self._transfer(lib().gas_disk_pull, idx, base, n, dst)
+
+    def push(self, src, idx, base=0, n=None) -> int:
+        """table[idx[i]] = src[i] (or table[base + i]); reads src after the current stream's work so far."""
+        return self._transfer(lib().gas_disk_push, idx, base, n, src)
+
+    def wait(self, ticket=0):
+        try:
+            _check(lib().gas_disk_wait(self._h, C.c_int64(ticket)))
+        finally:
+            for k in [k for k in self._held if ticket <= 0 or k <= ticket]:
+                del self._held[k]
+
+    def read_rows(self, dst, idx=None, base=0, n=None):
+        it, ip = self._idx(idx)
+        n = (it.numel() if it is not None else dst.shape[0]) if n is None else n
+        rp, ld = self._rows(dst, n, False)
+        _check(lib().gas_disk_read_rows(self._h, ip, C.c_int64(base), C.c_int64(n), rp, ld))
+        self._held.clear()
+
+    def write_rows(self, src, idx=None, base=0, n=None):
+        it, ip = self._idx(idx)
+        n = (it.numel() if it is not None else src.shape[0]) if n is None else n
+        rp, ld = self._rows(src, n, False)
+        _check(lib().gas_disk_write_rows(self._h, ip, C.c_int64(base), C.c_int64(n), rp, ld))
+        self._held.clear()
+
+    def sync(self):
+        _check(lib().gas_disk_sync(self._h))
+        self._held.clear()
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, C.c_void_p(0)
+            self._held.clear()
+            _check(lib().gas_disk_close(h))
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def gas_pna_aggregate_bwd(rowptr, col, colptr, row, csc_pos, x, g, gx, delta, gadd=None):

@@ -48,6 +48,7 @@ class BatchGraph:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
             part("gcn_norm_csr", lambda: B.gas_gcn_norm(rowptr, col, n_id, deg, self.val))
         self._src = None
+        self._n_id_host = None
         self._plan_t_all, self._max_F = None, max_F
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
         if colptr is not None:
@@ -69,6 +70,13 @@ class BatchGraph:
         if self._plan_t_all is None:
             self._plan_t_all = B.gas_plan_create(self.colptr, self.nnz, self._max_F, ind=self.row)
         return self._plan_t_all
+
+    @property
+    def n_id_host(self):
+        """The node ids in host memory (index lists of tables on disk are read by host threads)."""
+        if self._n_id_host is None:
+            self._n_id_host = self.n_id.cpu()
+        return self._n_id_host
 
     @property
     def src(self):
@@ -337,6 +345,75 @@ def forward_batch_host(model: Model, bg: BatchGraph, x_feat, histories, pipe: Ho
     pipe.set_read[turn].record(cur)
     if do_push and L > 1:
         pipe.set_pushed[turn] = pipe.table_pushed[L - 2]
+    return y
+
+
+class DiskPipeline:
+    """Mini-batch tensors for histories kept on disk (binding.DiskTable): two sets, used by alternate batches, so
+    that a batch can compute while the pushes of the one before still read its tensors; `pushing[i]` lists the
+    (table, ticket) pairs of the pushes that read set i."""
+
+    def __init__(self):
+        self.turn = 0
+        self.pushing = [[], []]
+        self._buffers = {}
+
+    def buffer(self, l, rows, width, dtype, device):
+        key = (self.turn, l, width, dtype)
+        t = self._buffers.get(key)
+        if t is None or t.shape[0] < rows:
+            t = self._buffers[key] = torch.empty((rows, width), dtype=dtype, device=device)
+        return t[:rows]
+
+    def settle(self, turn):
+        """Wait for the pushes that still read the tensors of set `turn`."""
+        for table, ticket in self.pushing[turn]:
+            table.wait(ticket)
+        self.pushing[turn] = []
+
+    def join(self):
+        self.settle(0)
+        self.settle(1)
+
+
+def forward_batch_disk(model: Model, bg: BatchGraph, x_feat, tables, pipe: DiskPipeline, do_push=True):
+    """forward_batch for history tables on disk (the tier the paper's "Conclusion and Future Work" names; transfer
+    scheme of its Section 5 "PyGAS").  The halo rows of every layer are requested at the start of the batch (they
+    were pushed by earlier batches; each table runs its transfers in the order queued, so a pull sees the pushes
+    queued before it), a layer waits for its own halo rows only, and each layer's output goes to its table while
+    the next layer computes.  Same bits as forward_batch.  The caller calls pipe.join() before it reads the tables."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    L = model.n_layers
+    turn = pipe.turn = pipe.turn ^ 1
+    pipe.settle(turn)
+    ids = bg.n_id_host
+    xs = [None] + [pipe.buffer(l, nv, model.out_width(l - 1), dt, dev) for l in range(1, L)]
+    pulled = [None] * L
+    if nv > nb:
+        # the transfer starts after the work queued so far, which includes the last readers of this set
+        for l in range(1, L):
+            pulled[l] = tables[l - 1].pull(ids[nb:], xs[l][nb:])
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    h0 = None
+    if model.op == "gcnii":
+        h0 = torch.empty((nv, model.w_in.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x, model.w_in, h0, relu=True)
+        x = h0
+    y = None
+    for l in range(1, L + 1):
+        last = l == L
+        z = torch.empty((nb, x.shape[1]), dtype=dt, device=dev)
+        y = torch.empty((nb, model.out_width(l - 1)), dtype=dt, device=dev) if last else xs[l][:nb]
+        if l > 1 and pulled[l - 1] is not None:
+            tables[l - 2].wait(pulled[l - 1])
+        _aggregate_transform(model, l, bg, x, h0, z, y)
+        if last:
+            break
+        if do_push:
+            pipe.pushing[turn].append((tables[l - 1], tables[l - 1].push(y, ids[:nb])))
+        x = xs[l]
     return y
 
 

@@ -458,6 +458,107 @@ def gat_batch_forward(weights, n_id, rowptr, col, nb, x_feat, histories, negativ
     return y
 
 
+def _next_input(y, nb, n_id, history):
+    x = np.empty((n_id.size, y.shape[1]), dtype=y.dtype)
+    x[:nb] = y
+    x[nb:] = ops.pull(history, n_id[nb:])
+    return x
+
+
+def pna_batch_train(weights, delta, n_id, rowptr, col, nb, x_feat, histories, grad_out, do_push=True):
+    """pna_batch_forward with the activations kept, then the chain rule backwards (operator appendix, PNA; histories
+    are constants, so only in-batch rows pass gradient to the layer below).  A layer computes, for the mini-batch
+    tensor X [nv, F]:  P = X W1b (every node as a neighbour),  Q = X[:nb] W1a (the receiving node's part),
+    A9 = the nine scaled aggregations of P, each plus Q,  Y = act([X[:nb] | A9] W2).  P of a halo row depends on W1b
+    although the row itself is a constant, so W1b's gradient sums over all nv rows.
+    Returns (Y_L, grads) with grads[l] = (dW1 [2F, F1], dW2) as float32."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    x = ops.pull(x_feat, n_id)
+    L = len(weights)
+    kept = []
+    y = None
+    for l in range(1, L + 1):
+        w1, w2 = weights[l - 1]
+        f = x.shape[1]
+        p = ops.linear(x, np.ascontiguousarray(w1[f:]))
+        q = ops.linear(np.ascontiguousarray(x[:nb]), np.ascontiguousarray(w1[:f]))
+        cat = np.concatenate([x[:nb], ops.pna_aggregate(rowptr, col, p, delta, add=q)], axis=1)
+        y = ops.linear(cat, w2, relu=l < L)
+        kept.append((x, p, cat, y))
+        if l == L:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        x = _next_input(y, nb, n_id, histories[l - 1])
+    grads = {}
+    g = np.ascontiguousarray(grad_out)
+    for l in range(L, 0, -1):
+        w1, w2 = weights[l - 1]
+        x, p, cat, yl = kept[l - 1]
+        f = x.shape[1]
+        w1a, w1b = np.ascontiguousarray(w1[:f]), np.ascontiguousarray(w1[f:])
+        if l != L:
+            g = ops.relu_bwd(g, yl)
+        dw2 = ops.linear_bwd_weight(cat, g)
+        gcat = ops.linear_bwd_input(g, w2)
+        gp, gq = ops.pna_aggregate_bwd(rowptr, col, p, delta, np.ascontiguousarray(gcat[:, f:]), nv)
+        xb = np.ascontiguousarray(x[:nb])
+        grads[l - 1] = (np.concatenate([ops.linear_bwd_weight(xb, gq), ops.linear_bwd_weight(x, gp)], axis=0), dw2)
+        if l == 1:
+            break
+        # dL/dX[:nb]: the copy of h_v in the concatenation, the neighbour part, the receiving-node part
+        g = ops.axpy(np.ascontiguousarray(gcat[:, :f]), ops.linear_bwd_input(np.ascontiguousarray(gp[:nb]), w1b), 1.0)
+        g = ops.axpy(g, ops.linear_bwd_input(gq, w1a), 1.0)
+    return y, grads
+
+
+def gat_batch_train(weights, n_id, rowptr, col, nb, x_feat, histories, grad_out, negative_slope=0.2, do_push=True,
+                    heads=1):
+    """gat_batch_forward with the activations kept, then the chain rule backwards (operator appendix, GAT; histories
+    are constants).  P = X W is computed for every node of V_b, so W's gradient sums over all nv rows of the
+    gradient of P; only the in-batch rows pass gradient on to the layer below.
+    Returns (Y_L, grads) with grads[l] = (dW, d a_dst, d a_src) as float32."""
+    n_id = np.ascontiguousarray(n_id, dtype=np.int32)
+    nv = n_id.size
+    x = ops.pull(x_feat, n_id)
+    L = len(weights)
+    kept = []
+    y = None
+
+    def blocks(width):
+        fh = width // heads
+        assert fh * heads == width
+        return [slice(h * fh, (h + 1) * fh) for h in range(heads)]
+    for l in range(1, L + 1):
+        w, a_dst, a_src = weights[l - 1]
+        p = ops.linear(x, w)
+        y = np.concatenate([ops.gat_aggregate(rowptr, col, p[:, c], a_dst[c], a_src[c], negative_slope, relu=l < L)
+                            for c in blocks(p.shape[1])], axis=1)
+        kept.append((x, p, y))
+        if l == L:
+            break
+        if do_push:
+            ops.push(y, n_id[:nb], histories[l - 1])
+        x = _next_input(y, nb, n_id, histories[l - 1])
+    grads = {}
+    g = np.ascontiguousarray(grad_out)
+    for l in range(L, 0, -1):
+        w, a_dst, a_src = weights[l - 1]
+        x, p, yl = kept[l - 1]
+        if l != L:
+            g = ops.relu_bwd(g, yl)
+        parts = [ops.gat_aggregate_bwd(rowptr, col, np.ascontiguousarray(p[:, c]), a_dst[c], a_src[c],
+                                       np.ascontiguousarray(g[:, c]), nv, negative_slope) for c in blocks(p.shape[1])]
+        gp = np.concatenate([t[0] for t in parts], axis=1)
+        grads[l - 1] = (ops.linear_bwd_weight(x, gp), np.concatenate([t[1] for t in parts]),
+                        np.concatenate([t[2] for t in parts]))
+        if l == 1:
+            break
+        g = ops.linear_bwd_input(np.ascontiguousarray(gp[:nb]), w)
+    return y, grads
+
+
 # ----------------------------------------------------------------------------
 # local Lipschitz regulariser (paper, Eq. 3)
 # ----------------------------------------------------------------------------

@@ -465,15 +465,9 @@ def _next_input(y, nb, n_id, history):
     return x
 
 
-def pna_batch_train(weights, delta, n_id, rowptr, col, nb, x_feat, histories, grad_out, do_push=True):
-    """pna_batch_forward with the activations kept, then the chain rule backwards (operator appendix, PNA; histories
-    are constants, so only in-batch rows pass gradient to the layer below).  A layer computes, for the mini-batch
-    tensor X [nv, F]:  P = X W1b (every node as a neighbour),  Q = X[:nb] W1a (the receiving node's part),
-    A9 = the nine scaled aggregations of P, each plus Q,  Y = act([X[:nb] | A9] W2).  P of a halo row depends on W1b
-    although the row itself is a constant, so W1b's gradient sums over all nv rows.
-    Returns (Y_L, grads) with grads[l] = (dW1 [2F, F1], dW2) as float32."""
+def pna_batch_forward_kept(weights, delta, n_id, rowptr, col, nb, x_feat, histories, do_push=True):
+    """pna_batch_forward with what the backward pass reads kept: per layer (X, P, [X[:nb] | A9], Y)."""
     n_id = np.ascontiguousarray(n_id, dtype=np.int32)
-    nv = n_id.size
     x = ops.pull(x_feat, n_id)
     L = len(weights)
     kept = []
@@ -491,12 +485,23 @@ def pna_batch_train(weights, delta, n_id, rowptr, col, nb, x_feat, histories, gr
         if do_push:
             ops.push(y, n_id[:nb], histories[l - 1])
         x = _next_input(y, nb, n_id, histories[l - 1])
+    return y, kept
+
+
+def pna_batch_backward(weights, delta, rowptr, col, nb, kept, grad_out):
+    """The chain rule backwards through PNA layers from kept activations (operator appendix, PNA; histories are
+    constants, so only in-batch rows pass gradient to the layer below).  A layer computed, for the mini-batch
+    tensor X [nv, F]:  P = X W1b (every node as a neighbour),  Q = X[:nb] W1a (the receiving node's part),
+    A9 = the nine scaled aggregations of P, each plus Q,  Y = act([X[:nb] | A9] W2).  P of a halo row depends on W1b
+    although the row itself is a constant, so W1b's gradient sums over all nv rows.
+    Returns grads[l] = (dW1 [2F, F1], dW2) as float32."""
+    L = len(weights)
     grads = {}
     g = np.ascontiguousarray(grad_out)
     for l in range(L, 0, -1):
         w1, w2 = weights[l - 1]
         x, p, cat, yl = kept[l - 1]
-        f = x.shape[1]
+        f, nv = x.shape[1], x.shape[0]
         w1a, w1b = np.ascontiguousarray(w1[:f]), np.ascontiguousarray(w1[f:])
         if l != L:
             g = ops.relu_bwd(g, yl)
@@ -510,53 +515,73 @@ def pna_batch_train(weights, delta, n_id, rowptr, col, nb, x_feat, histories, gr
         # dL/dX[:nb]: the copy of h_v in the concatenation, the neighbour part, the receiving-node part
         g = ops.axpy(np.ascontiguousarray(gcat[:, :f]), ops.linear_bwd_input(np.ascontiguousarray(gp[:nb]), w1b), 1.0)
         g = ops.axpy(g, ops.linear_bwd_input(gq, w1a), 1.0)
-    return y, grads
+    return grads
 
 
-def gat_batch_train(weights, n_id, rowptr, col, nb, x_feat, histories, grad_out, negative_slope=0.2, do_push=True,
-                    heads=1):
-    """gat_batch_forward with the activations kept, then the chain rule backwards (operator appendix, GAT; histories
-    are constants).  P = X W is computed for every node of V_b, so W's gradient sums over all nv rows of the
-    gradient of P; only the in-batch rows pass gradient on to the layer below.
-    Returns (Y_L, grads) with grads[l] = (dW, d a_dst, d a_src) as float32."""
+def pna_batch_train(weights, delta, n_id, rowptr, col, nb, x_feat, histories, grad_out, do_push=True):
+    """Forward with kept activations, then the backward pass: (Y_L, grads)."""
+    y, kept = pna_batch_forward_kept(weights, delta, n_id, rowptr, col, nb, x_feat, histories, do_push)
+    return y, pna_batch_backward(weights, delta, rowptr, col, nb, kept, grad_out)
+
+
+def _head_blocks(width, heads):
+    fh = width // heads
+    assert fh * heads == width
+    return [slice(h * fh, (h + 1) * fh) for h in range(heads)]
+
+
+def gat_batch_forward_kept(weights, n_id, rowptr, col, nb, x_feat, histories, negative_slope=0.2, do_push=True, heads=1):
+    """gat_batch_forward with what the backward pass reads kept: per layer (X, P, Y)."""
     n_id = np.ascontiguousarray(n_id, dtype=np.int32)
-    nv = n_id.size
     x = ops.pull(x_feat, n_id)
     L = len(weights)
     kept = []
     y = None
-
-    def blocks(width):
-        fh = width // heads
-        assert fh * heads == width
-        return [slice(h * fh, (h + 1) * fh) for h in range(heads)]
     for l in range(1, L + 1):
         w, a_dst, a_src = weights[l - 1]
         p = ops.linear(x, w)
         y = np.concatenate([ops.gat_aggregate(rowptr, col, p[:, c], a_dst[c], a_src[c], negative_slope, relu=l < L)
-                            for c in blocks(p.shape[1])], axis=1)
+                            for c in _head_blocks(p.shape[1], heads)], axis=1)
         kept.append((x, p, y))
         if l == L:
             break
         if do_push:
             ops.push(y, n_id[:nb], histories[l - 1])
         x = _next_input(y, nb, n_id, histories[l - 1])
+    return y, kept
+
+
+def gat_batch_backward(weights, rowptr, col, nb, kept, grad_out, negative_slope=0.2, heads=1):
+    """The chain rule backwards through GAT layers from kept activations (operator appendix, GAT; histories are
+    constants).  P = X W is computed for every node of V_b, so W's gradient sums over all nv rows of the gradient
+    of P; only the in-batch rows pass gradient on to the layer below.
+    Returns grads[l] = (dW, d a_dst, d a_src) as float32."""
+    L = len(weights)
     grads = {}
     g = np.ascontiguousarray(grad_out)
     for l in range(L, 0, -1):
         w, a_dst, a_src = weights[l - 1]
         x, p, yl = kept[l - 1]
+        nv = x.shape[0]
         if l != L:
             g = ops.relu_bwd(g, yl)
         parts = [ops.gat_aggregate_bwd(rowptr, col, np.ascontiguousarray(p[:, c]), a_dst[c], a_src[c],
-                                       np.ascontiguousarray(g[:, c]), nv, negative_slope) for c in blocks(p.shape[1])]
+                                       np.ascontiguousarray(g[:, c]), nv, negative_slope)
+                 for c in _head_blocks(p.shape[1], heads)]
         gp = np.concatenate([t[0] for t in parts], axis=1)
         grads[l - 1] = (ops.linear_bwd_weight(x, gp), np.concatenate([t[1] for t in parts]),
                         np.concatenate([t[2] for t in parts]))
         if l == 1:
             break
         g = ops.linear_bwd_input(np.ascontiguousarray(gp[:nb]), w)
-    return y, grads
+    return grads
+
+
+def gat_batch_train(weights, n_id, rowptr, col, nb, x_feat, histories, grad_out, negative_slope=0.2, do_push=True,
+                    heads=1):
+    """Forward with kept activations, then the backward pass: (Y_L, grads)."""
+    y, kept = gat_batch_forward_kept(weights, n_id, rowptr, col, nb, x_feat, histories, negative_slope, do_push, heads)
+    return y, gat_batch_backward(weights, rowptr, col, nb, kept, grad_out, negative_slope, heads)
 
 
 # ----------------------------------------------------------------------------

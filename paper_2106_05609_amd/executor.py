@@ -22,7 +22,7 @@ class BatchGraph:
     """Device-side index structure of one batch subgraph plus its plans."""
 
     def __init__(self, nb, n_id, rowptr, col, deg=None, colptr=None, row=None, max_F=256, normalise=True, timed=False,
-                 plan_options=None):
+                 plan_options=None, csc_pos=None):
         """timed: wait for the device after each part of the per-batch set-up and keep its wall time in
         self.setup_ms (plans, coefficients, fused source indices); the benchmark reports it."""
         import time
@@ -48,6 +48,7 @@ class BatchGraph:
             self.val = torch.empty(self.nnz, dtype=torch.float32, device=col.device)
             part("gcn_norm_csr", lambda: B.gas_gcn_norm(rowptr, col, n_id, deg, self.val))
         self._src = None
+        self.csc_pos = csc_pos       # int32[nnz]: position of every CSC entry in the CSR arrays (PNA / GAT backward)
         self._n_id_host = None
         self._plan_t_all, self._max_F = None, max_F
         self.colptr, self.row, self.val_t, self.plan_t = colptr, row, None, None
@@ -745,6 +746,152 @@ def gat_forward_batch(weights, bg: BatchGraph, x_feat, histories, negative_slope
             B.gas_pull(histories[l - 1], bg.n_id[nb:], x_next[nb:])
         x = x_next
     return y
+
+
+def _weight_grad(zz, gg, dw=None):
+    if dw is None:
+        dw = torch.empty((zz.shape[1], gg.shape[1]), dtype=torch.float32, device=zz.device)
+    ws = torch.empty(max(1, B.gas_linear_bwd_weight_workspace(zz.shape[0], zz.shape[1], gg.shape[1])),
+                     dtype=torch.uint8, device=zz.device)
+    B.gas_linear_bwd_weight(zz, gg, dw, ws)
+    return dw
+
+
+def _next_input(y_rows, bg: BatchGraph, history, do_push):
+    """Push the in-batch rows (already in rows 0..nb-1 of the next mini-batch tensor) and pull its halo rows."""
+    if do_push:
+        B.gas_push(y_rows[:bg.nb], bg.n_id[:bg.nb], history)
+    if bg.nv > bg.nb:
+        B.gas_pull(history, bg.n_id[bg.nb:], y_rows[bg.nb:])
+
+
+def pna_train_batch(weights, delta, bg: BatchGraph, x_feat, histories, grad_out, do_push=True):
+    """pna_forward_batch with the activations kept, then the backward pass (operator appendix, PNA; histories are
+    constants, so only in-batch rows pass gradient to the layer below, while the neighbour half of W1 takes gradient
+    through every row of V_b).  bg needs the CSC copy with csc_pos.  grad_out: dLoss/dY_L [nb, F_L] or a function of
+    Y_L.  Returns (Y_L, grads, kept) with grads[l] = (dW1 [2F, F1], dW2), float32, and kept[l] = the stored
+    activations (X, P, [X[:nb] | A9], Y) the backward pass read.  Every step is a gas_* call."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    L = len(weights)
+    kept = []
+    y = None
+    for l in range(1, L + 1):
+        w1, w2 = weights[l - 1]
+        last = l == L
+        f, f1 = x.shape[1], w1.shape[1]
+        p = torch.empty((nv, f1), dtype=dt, device=dev)
+        B.gas_linear(x, w1[f:], p)
+        q = torch.empty((nb, f1), dtype=dt, device=dev)
+        B.gas_linear(x[:nb], w1[:f], q)
+        cat = torch.empty((nb, f + 9 * f1), dtype=dt, device=dev)
+        B.gas_pull(x, None, cat[:, :f], base=0, n=nb)
+        B.gas_pna_aggregate(bg.rowptr, bg.col, p, cat[:, f:], delta, add=q)
+        x_next = torch.empty((nb if last else nv, w2.shape[1]), dtype=dt, device=dev)
+        y = x_next[:nb]
+        B.gas_linear(cat, w2, y, relu=not last)
+        kept.append((x, p, cat, y))
+        if last:
+            break
+        _next_input(x_next, bg, histories[l - 1], do_push)
+        x = x_next
+    grads = {}
+    g = grad_out(y) if callable(grad_out) else grad_out
+    for l in range(L, 0, -1):
+        w1, w2 = weights[l - 1]
+        x, p, cat, yl = kept[l - 1]
+        f, f1 = x.shape[1], w1.shape[1]
+        if l != L:
+            gm = torch.empty_like(g)
+            B.gas_relu_bwd(g, yl, gm)
+            g = gm
+        dw2 = _weight_grad(cat, g)
+        gcat = torch.empty_like(cat)
+        B.gas_linear_bwd_input(g, w2, gcat)
+        gp = torch.empty((nv, f1), dtype=dt, device=dev)
+        gq = torch.empty((nb, f1), dtype=dt, device=dev)
+        B.gas_pna_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, bg.csc_pos, p, gcat[:, f:], gp, delta, gadd=gq)
+        dw1 = torch.empty((2 * f, f1), dtype=torch.float32, device=dev)
+        _weight_grad(x[:nb], gq, dw1[:f])
+        _weight_grad(x, gp, dw1[f:])
+        grads[l - 1] = (dw1, dw2)
+        if l == 1:
+            break
+        # dL/dX[:nb] = the copy of h_v in the concatenation + the neighbour part + the receiving-node part
+        gx = torch.empty((nb, f), dtype=dt, device=dev)
+        B.gas_linear_bwd_input(gp[:nb], w1[f:], gx)
+        B.gas_axpy(gcat[:, :f], gx, gx, 1.0)
+        t = torch.empty((nb, f), dtype=dt, device=dev)
+        B.gas_linear_bwd_input(gq, w1[:f], t)
+        B.gas_axpy(gx, t, gx, 1.0)
+        g = gx
+    return y, grads, kept
+
+
+def gat_train_batch(weights, bg: BatchGraph, x_feat, histories, grad_out, negative_slope=0.2, do_push=True, heads=1):
+    """gat_forward_batch with the activations kept, then the backward pass (operator appendix, GAT).  P = X W is
+    computed for every node of V_b, so W takes gradient through all nv rows of P's gradient; only in-batch rows pass
+    gradient to the layer below.  bg: the batch subgraph with self-loops and the CSC copy with csc_pos.
+    Returns (Y_L, grads, kept) with grads[l] = (dW, d a_dst, d a_src), float32, and kept[l] = (X, P, Y).  Every
+    step is a gas_* call."""
+    dev, dt = x_feat.device, x_feat.dtype
+    nb, nv = bg.nb, bg.nv
+    x = torch.empty((nv, x_feat.shape[1]), dtype=dt, device=dev)
+    B.gas_pull(x_feat, bg.n_id, x)
+    L = len(weights)
+    kept = []
+    y = None
+
+    def blocks(width):
+        fh = width // heads
+        if fh * heads != width:
+            raise ValueError("gat_train_batch: the layer width is not a multiple of the number of heads")
+        return [slice(h * fh, (h + 1) * fh) for h in range(heads)]
+    for l in range(1, L + 1):
+        w, a_dst, a_src = weights[l - 1]
+        last = l == L
+        p = torch.empty((nv, w.shape[1]), dtype=dt, device=dev)
+        B.gas_linear(x, w, p)
+        x_next = torch.empty((nb if last else nv, w.shape[1]), dtype=dt, device=dev)
+        y = x_next[:nb]
+        for c in blocks(w.shape[1]):
+            B.gas_gat_aggregate(bg.rowptr, bg.col, p[:, c], a_dst[c], a_src[c], y[:, c], negative_slope, relu=not last)
+        kept.append((x, p, y))
+        if last:
+            break
+        _next_input(x_next, bg, histories[l - 1], do_push)
+        x = x_next
+    grads = {}
+    g = grad_out(y) if callable(grad_out) else grad_out
+    for l in range(L, 0, -1):
+        w, a_dst, a_src = weights[l - 1]
+        x, p, yl = kept[l - 1]
+        if l != L:
+            gm = torch.empty_like(g)
+            B.gas_relu_bwd(g, yl, gm)
+            g = gm
+        gp = torch.empty_like(p)
+        gd = torch.empty(w.shape[1], dtype=torch.float32, device=dev)
+        gs = torch.empty(w.shape[1], dtype=torch.float32, device=dev)
+        for c in blocks(w.shape[1]):
+            B.gas_gat_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, bg.csc_pos, p[:, c], a_dst[c], a_src[c],
+                                    g[:, c], gp[:, c], gd[c], gs[c], negative_slope)
+        grads[l - 1] = (_weight_grad(x, gp), gd, gs)
+        if l == 1:
+            break
+        gx = torch.empty((nb, w.shape[0]), dtype=dt, device=dev)
+        B.gas_linear_bwd_input(gp[:nb], w, gx)
+        g = gx
+    return y, grads, kept
+
+
+def sgd_update(weights, grads, lr, weight_decay=0.0):
+    """gas_sgd_step on every tensor of a list of per-layer weight tuples (PNA, GAT) with the matching gradients."""
+    for l, ws in enumerate(weights):
+        for w, dw in zip(ws, grads[l]):
+            B.gas_sgd_step(w, dw, lr, weight_decay)
 
 
 def layer_forward(model: Model, l, bg: BatchGraph, x, h0=None, y=None):

@@ -9,6 +9,7 @@
           copy kernel itself), alone and on a second stream beside the aggregation.
   gat     GAT's aggregation (same appendix, one head): scores, softmax over the row's entries and the weighted
           sum in one pass over the gathered rows.
+  pna_bwd, gat_bwd   the backward passes of the two aggregations, gradients for every row of V_b.
 
 One JSON line on stdout, a table on stderr.  Bytes are algorithmic (indices and coefficients once, every needed
 feature row once, every output row once)."""
@@ -101,6 +102,26 @@ def main():
                             "gathered_GBps": round(nnz * F * s / t / 1e6, 1)}
     print(f"gat_aggr   {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s  (gathers {nnz * F * s / t / 1e6:.0f} GB/s)",
           file=sys.stderr, flush=True)
+    # backward of the two aggregations, gradients for every row of V_b (what a training pass needs: the weights that
+    # multiply neighbour rows take gradient through halo rows too)
+    csc_pos = sg.csc_perm.to(torch.int32)
+    gx = torch.empty((nv, F), dtype=dt, device=dev)
+    g9 = out9                                                    # any values will do as the output gradient
+    gadd = torch.empty((nb, F), dtype=dt, device=dev)
+    plan_t = bg.plan_t_all
+    t = timed(lambda: gas.gas_pna_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, csc_pos, x, g9, gx, delta,
+                                                gadd=gadd, plan_t=plan_t), args.reps)
+    nbytes = nnz * 12 + (nb + nv + 2) * 4 + nv * F * s + 9 * nb * F * s + nv * F * s + nb * F * s
+    out["pna_aggregate_bwd"] = {"ms": round(t, 4), "alg_GB": round(nbytes / 1e9, 3), "GBps": round(nbytes / t / 1e6, 1)}
+    print(f"pna_bwd    {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s", file=sys.stderr, flush=True)
+    del g9, out9, gadd
+    gd, gs = torch.empty(F, device=dev), torch.empty(F, device=dev)
+    t = timed(lambda: gas.gas_gat_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, csc_pos, x, a_dst, a_src, y, gx,
+                                                gd, gs, 0.2, plan_t=plan_t), args.reps)
+    nbytes = nnz * 12 + (nb + nv + 2) * 4 + nv * F * s + nb * F * s + nv * F * s
+    out["gat_aggregate_bwd"] = {"ms": round(t, 4), "alg_GB": round(nbytes / 1e9, 3), "GBps": round(nbytes / t / 1e6, 1)}
+    print(f"gat_bwd    {t:8.3f} ms  {nbytes / 1e9:7.3f} GB  {nbytes / t / 1e6:8.1f} GB/s", file=sys.stderr, flush=True)
+    del gx
     if args.host_rows > 0:
         hr = min(args.host_rows, cfg.n)
         table = gas.HostTable(torch.zeros((hr, F), dtype=dt).pin_memory())

@@ -439,6 +439,13 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
  * entry in the CSR arrays) sums each column's contributions in stored order.  n_out <= n_cols output rows are
  * written (the in-batch nodes when histories are constants, or all of V_b).  workspace: device memory of at least
  * gas_*_bwd_workspace(...) bytes, caller-owned, contents undefined afterwards.
+ * plan_t: a plan of the CSC copy for exactly the n_out output rows, gas_plan_create(colptr, colptr[n_out], max_F >= F,
+ * n_out, row), or NULL.  With it, and rows of at most 64 pieces of 16 bytes that are 16-byte aligned, the row pass
+ * gathers like the forward call and the sum of whole rows over a column's entries is taken by gas_spmm_t's kernels
+ * (which rounds it to the storage type before the remaining terms are added: one more rounding for bf16).  Without
+ * it, or for other shapes, plain kernels run: one wavefront per row and per column, one entry at a time; slow, and
+ * the definition the fast path is tested against.  Fixed summation order either way (not the same order: the two
+ * paths agree to rounding).
  *
  * gas_pna_aggregate_bwd: G [n_rows, 9 F] is the gradient of gas_pna_aggregate's output.  With s and d as there and
  *     c_i = G[v, i F + f] + s G[v, (3+i) F + f] + G[v, (6+i) F + f] / s   (i = mean, min, max; rows with entries),
@@ -453,14 +460,14 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
  *     Ga_dst = sum_v (sum_k dt_k) P[v],          Ga_src = sum over all entries of dt_k P[col k]   (fp32 [F]).
  * n_cols = rows of P = columns of the pattern (the column pass runs over all of them: Ga_src needs every entry).
  */
-GAS_API int64_t gas_pna_aggregate_bwd_workspace(int64_t n_rows, int32_t F);
-GAS_API gas_status gas_pna_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
-                                 const int32_t* colptr, const int32_t* row, const int32_t* csc_pos, int64_t n_out,
+GAS_API int64_t gas_pna_aggregate_bwd_workspace(int64_t n_rows, int64_t nnz, int32_t F);
+GAS_API gas_status gas_pna_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+                                 int64_t nnz, const int32_t* colptr, const int32_t* row, const int32_t* csc_pos, int64_t n_out,
                                  const void* X, int64_t ldx, gas_dtype dt, int32_t F, float delta,
                                  const void* G, int64_t ldg, void* GX, int64_t ldgx, void* Gadd, int64_t ldga,
                                  void* workspace, int64_t workspace_bytes, void* stream);
 GAS_API int64_t gas_gat_aggregate_bwd_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, int32_t F);
-GAS_API gas_status gas_gat_aggregate_bwd(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
+GAS_API gas_status gas_gat_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, const int32_t* col, int64_t n_rows,
                                  const int32_t* colptr, const int32_t* row, const int32_t* csc_pos, int64_t n_cols,
                                  int64_t n_out, int64_t nnz, const void* P, int64_t ldp, gas_dtype dt, int32_t F,
                                  const void* a_dst, const void* a_src, float negative_slope,

@@ -603,8 +603,9 @@ class DiskTable:
             pass
 
 
-def gas_pna_aggregate_bwd(rowptr, col, colptr, row, csc_pos, x, g, gx, delta, gadd=None):
-    """Backward of gas_pna_aggregate: gx [n_out, F] (n_out = gx.shape[0] columns of the pattern), gadd [n_rows, F]."""
+def gas_pna_aggregate_bwd(rowptr, col, colptr, row, csc_pos, x, g, gx, delta, gadd=None, plan_t=None):
+    """Backward of gas_pna_aggregate: gx [n_out, F] (n_out = gx.shape[0] columns of the pattern), gadd [n_rows, F].
+    plan_t: a Plan of the CSC copy for those n_out columns (fast path), or None (plain kernels)."""
     xp, ldx = _mat(x)
     gp, ldg = _mat(g)
     op, ldo = _mat(gx)
@@ -612,18 +613,20 @@ def gas_pna_aggregate_bwd(rowptr, col, colptr, row, csc_pos, x, g, gx, delta, ga
     n_rows, F = rowptr.numel() - 1, x.shape[1]
     if g.shape != (n_rows, 9 * F) or gx.shape[1] != F or g.dtype != x.dtype or gx.dtype != x.dtype:
         raise ValueError("gas_pna_aggregate_bwd: shapes or dtypes do not match")
-    nbytes = int(lib().gas_pna_aggregate_bwd_workspace(C.c_int64(n_rows), C.c_int32(F)))
+    nnz = col.numel()
+    nbytes = int(lib().gas_pna_aggregate_bwd_workspace(C.c_int64(n_rows), C.c_int64(nnz), C.c_int32(F)))
     ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x.device)
-    _check(lib().gas_pna_aggregate_bwd(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
-                                       _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(csc_pos, torch.int32),
+    _check(lib().gas_pna_aggregate_bwd(plan_t.handle if plan_t is not None else C.c_void_p(0),
+                                       _ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
+                                       C.c_int64(nnz), _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(csc_pos, torch.int32),
                                        C.c_int64(gx.shape[0]), xp, ldx, C.c_int(_dt(x)), C.c_int32(F), C.c_float(delta),
                                        gp, ldg, op, ldo, ap, lda, _ptr(ws), C.c_int64(nbytes), _stream()))
 
 
 def gas_gat_aggregate_bwd(rowptr, col, colptr, row, csc_pos, p, a_dst, a_src, gz, gp_out, ga_dst, ga_src,
-                          negative_slope=0.2):
+                          negative_slope=0.2, plan_t=None):
     """Backward of gas_gat_aggregate (gz: gradient before any activation): gp_out [n_out, F] rows of P's gradient,
-    ga_dst / ga_src float32 [F]."""
+    ga_dst / ga_src float32 [F].  plan_t: a Plan of the CSC copy for those n_out columns (fast path), or None."""
     pp, ldp = _mat(p)
     zp, ldz = _mat(gz)
     op, ldo = _mat(gp_out)
@@ -633,7 +636,8 @@ def gas_gat_aggregate_bwd(rowptr, col, colptr, row, csc_pos, p, a_dst, a_src, gz
         raise ValueError("gas_gat_aggregate_bwd: shapes or dtypes do not match")
     nbytes = int(lib().gas_gat_aggregate_bwd_workspace(C.c_int64(n_rows), C.c_int64(n_cols), C.c_int64(nnz), C.c_int32(F)))
     ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=p.device)
-    _check(lib().gas_gat_aggregate_bwd(_ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
+    _check(lib().gas_gat_aggregate_bwd(plan_t.handle if plan_t is not None else C.c_void_p(0),
+                                       _ptr(rowptr, torch.int32), _ptr(col, torch.int32), C.c_int64(n_rows),
                                        _ptr(colptr, torch.int32), _ptr(row, torch.int32), _ptr(csc_pos, torch.int32),
                                        C.c_int64(n_cols), C.c_int64(gp_out.shape[0]), C.c_int64(nnz), pp, ldp,
                                        C.c_int(_dt(p)), C.c_int32(F), _ptr(a_dst), _ptr(a_src), C.c_float(negative_slope),

@@ -1,7 +1,7 @@
 // PNA's neighbourhood aggregation (paper, operator appendix): mean, min and max over the neighbours of every
 // in-batch node in ONE pass over the gathered rows, times the degree scalers 1, s and 1/s.  HBM-bound like the
 // sum aggregation; three aggregators from one gather cost a third of three separate calls.
-#include "common.h"
+#include "wave.h"
 
 namespace gas {
 namespace {
@@ -15,24 +15,6 @@ struct PnaArgs {
     int F;
     float inv_delta;
 };
-
-template <bool BF> struct Elems { static constexpr int E = BF ? 8 : 4; };
-
-template <bool BF>
-__device__ __forceinline__ void unpack(const u32x4& r, float (&x)[Elems<BF>::E]) {
-    if constexpr (BF) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(r[i]); x[2 * i + 1] = bf16_hi(r[i]); }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(r[i]);
-    }
-}
-template <bool BF>
-__device__ __forceinline__ u32x4 pack(const float (&x)[Elems<BF>::E]) {
-    if constexpr (BF) return u32x4{pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])};
-    else return u32x4{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
-}
 
 // One wavefront per row of the batch subgraph; lane l owns the 16-byte piece l (+64, +128, ...) of the feature
 // row.  Neighbour indices are read 64 at a time and broadcast; gathers are issued sixteen at a time and folded in

@@ -1,0 +1,62 @@
+// Helpers shared by the one-wavefront-per-row kernels (PNA and GAT aggregations and their backward passes):
+// reductions over the 64 lanes and the 16-byte piece of a feature row that a lane owns.
+#pragma once
+#include "common.h"
+
+namespace gas {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Eight lane reductions at once: at each of the first three steps a lane keeps one half of its values, adds
+// the partner's copy of that half and hands over the other half, so 4 + 2 + 1 exchanges leave one partial sum per
+// lane; three more steps finish it, and the eight totals are read back from the lanes that hold them.  Ten
+// exchanges instead of forty-eight.  Value j ends up in the lanes whose bits 5..3 spell j.
+__device__ __forceinline__ void wave_sum8(float (&s)[8]) {
+    const int lane = threadIdx.x & 63;
+    float t4[4], t2[2];
+    const bool h5 = lane & 32, h4 = lane & 16, h3 = lane & 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float keep = h5 ? s[j + 4] : s[j], send = h5 ? s[j] : s[j + 4];
+        t4[j] = keep + __shfl_xor(send, 32);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float keep = h4 ? t4[j + 2] : t4[j], send = h4 ? t4[j] : t4[j + 2];
+        t2[j] = keep + __shfl_xor(send, 16);
+    }
+    float t = (h3 ? t2[1] : t2[0]) + __shfl_xor(h3 ? t2[0] : t2[1], 8);
+    t += __shfl_xor(t, 4);
+    t += __shfl_xor(t, 2);
+    t += __shfl_xor(t, 1);
+    // lane bits (5, 4, 3) = (j >> 2 & 1, j >> 1 & 1, j & 1): value j sits in lanes 32 (j>>2&1) + 16 (j>>1&1) + 8 (j&1)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        s[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t),
+                                                                  32 * ((j >> 2) & 1) + 16 * ((j >> 1) & 1) + 8 * (j & 1)));
+}
+
+// elements in a 16-byte piece
+template <bool BF> struct Elems { static constexpr int E = BF ? 8 : 4; };
+
+template <bool BF>
+__device__ __forceinline__ void unpack(const u32x4& r, float (&x)[Elems<BF>::E]) {
+    if constexpr (BF) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(r[i]); x[2 * i + 1] = bf16_hi(r[i]); }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(r[i]);
+    }
+}
+template <bool BF>
+__device__ __forceinline__ u32x4 pack(const float (&x)[Elems<BF>::E]) {
+    if constexpr (BF) return u32x4{pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])};
+    else return u32x4{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+}
+
+}  // namespace gas

@@ -812,7 +812,8 @@ def pna_train_batch(weights, delta, bg: BatchGraph, x_feat, histories, grad_out,
         B.gas_linear_bwd_input(g, w2, gcat)
         gp = torch.empty((nv, f1), dtype=dt, device=dev)
         gq = torch.empty((nb, f1), dtype=dt, device=dev)
-        B.gas_pna_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, bg.csc_pos, p, gcat[:, f:], gp, delta, gadd=gq)
+        B.gas_pna_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, bg.csc_pos, p, gcat[:, f:], gp, delta, gadd=gq,
+                                plan_t=bg.plan_t_all)
         dw1 = torch.empty((2 * f, f1), dtype=torch.float32, device=dev)
         _weight_grad(x[:nb], gq, dw1[:f])
         _weight_grad(x, gp, dw1[f:])
@@ -877,7 +878,7 @@ def gat_train_batch(weights, bg: BatchGraph, x_feat, histories, grad_out, negati
         gs = torch.empty(w.shape[1], dtype=torch.float32, device=dev)
         for c in blocks(w.shape[1]):
             B.gas_gat_aggregate_bwd(bg.rowptr, bg.col, bg.colptr, bg.row, bg.csc_pos, p[:, c], a_dst[c], a_src[c],
-                                    g[:, c], gp[:, c], gd[c], gs[c], negative_slope)
+                                    g[:, c], gp[:, c], gd[c], gs[c], negative_slope, plan_t=bg.plan_t_all)
         grads[l - 1] = (_weight_grad(x, gp), gd, gs)
         if l == 1:
             break

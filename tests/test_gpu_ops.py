@@ -558,10 +558,14 @@ def test_pull_push_with_a_history_table_in_pinned_host_memory(gas, dtype):
 
 
 @pytest.mark.parametrize("name,dtype,F", [("sbm", torch.float32, 8), ("powerlaw", torch.float32, 100), ("gin", torch.bfloat16, 128),
-                                          ("powerlaw", torch.float32, 7), ("gin", torch.float32, 520)])
+                                          ("powerlaw", torch.float32, 7), ("gin", torch.float32, 520),
+                                          ("sbm", torch.float32, 256), ("sbm", torch.bfloat16, 512),
+                                          ("powerlaw", torch.float32, 256), ("powerlaw", torch.bfloat16, 256)])
 def test_pna_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     """gas_pna_aggregate_bwd against the oracle (itself pinned to float64 autograd): gradient of the gathered rows
-    for all columns of the pattern and for the in-batch columns only, gradient of the added term."""
+    for all columns of the pattern and for the in-batch columns only, gradient of the added term.  The graphs have
+    rows of one entry (which then wins every feature: lists longer than a wavefront) and rows above 512 entries
+    (items counted and placed in several goes)."""
     cfg, g, sg = graphs_small[name]
     nb, nv = sg.nb, sg.nv
     x = rng.normal_matrix(12, 960, nv, F, dtype=dtype)
@@ -569,22 +573,30 @@ def test_pna_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     delta = float(torch.log(g.deg.double() + 1.0).mean())
     d = lambda t: t.to("cuda")
     want_x, want_add = oops.pna_aggregate_bwd(to_np(sg.rowptr), to_np(sg.col), to_np(x), delta, to_np(gout), nv)
-    for n_out in (nv, nb):
-        gx = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
-        gadd = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
-        gas.gas_pna_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr)[: n_out + 1], d(sg.row), d(sg.csc_perm).int(),
-                                  d(x), d(gout), gx, delta, gadd=gadd)
-        assert node_rel_err(to_np(gx), want_x[:n_out]) <= TOL[dtype], (n_out, node_rel_err(to_np(gx), want_x[:n_out]))
-        assert node_rel_err(to_np(gadd), want_add) <= TOL[dtype]
-    gx2 = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
-    gas.gas_pna_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr)[: nb + 1], d(sg.row), d(sg.csc_perm).int(), d(x), d(gout),
-                              gx2, delta)
-    assert torch.equal(gx2.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
-                       gx.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))       # fixed order
+    bits = lambda t: t.view(torch.int16 if dtype == torch.bfloat16 else torch.int32)
+    for fast in (False, True):
+        # fast: with a plan of the CSC copy (rows gathered like the forward call, the mean's share taken by the
+        # backward aggregation's kernels, minima and maxima as per-entry item lists); widths it does not take fall
+        # back to the plain kernels, which is checked too
+        for n_out in (nv, nb):
+            plan_t = gas.gas_plan_create(d(sg.colptr)[: n_out + 1], int(sg.colptr[n_out]), F, n_rows=n_out, ind=d(sg.row)) \
+                if fast else None
+            gx = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
+            gadd = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
+            gas.gas_pna_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr)[: n_out + 1], d(sg.row), d(sg.csc_perm).int(),
+                                      d(x), d(gout), gx, delta, gadd=gadd, plan_t=plan_t)
+            assert node_rel_err(to_np(gx), want_x[:n_out]) <= TOL[dtype], (fast, n_out, node_rel_err(to_np(gx), want_x[:n_out]))
+            assert node_rel_err(to_np(gadd), want_add) <= TOL[dtype]
+            gx2 = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
+            gas.gas_pna_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr)[: n_out + 1], d(sg.row), d(sg.csc_perm).int(),
+                                      d(x), d(gout), gx2, delta, plan_t=plan_t)
+            assert torch.equal(bits(gx2), bits(gx))                                            # fixed order
 
 
 @pytest.mark.parametrize("name,dtype,F", [("sbm", torch.float32, 8), ("powerlaw", torch.float32, 100), ("sbm", torch.bfloat16, 128),
-                                          ("powerlaw", torch.float32, 7), ("sbm", torch.float32, 520)])
+                                          ("powerlaw", torch.float32, 7), ("sbm", torch.float32, 520),
+                                          ("powerlaw", torch.float32, 256), ("powerlaw", torch.bfloat16, 256),
+                                          ("gin", torch.bfloat16, 512)])
 def test_gat_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     """gas_gat_aggregate_bwd against the oracle (pinned to float64 autograd): gradients of P (all rows / in-batch
     rows) and of the two halves of the attention vector."""
@@ -601,6 +613,8 @@ def test_gat_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     # dalpha_k = GZ[v] . P[col k]; the error of dt_k is relative to the products summed for dalpha_k (at most
     # ||GZ[v]|| ||P[col k]||), not to the difference, and dt_k a_src is a term of output row col k.  So row u is
     # measured against max(its own largest entry, sum over its entries of alpha_k ||GZ[v]|| ||P[u]|| max|a_src|).
+    # An in-batch row v also receives (sum_k dt_k) a_dst, a sum over its own row's entries that cancels (it is
+    # exactly zero for slope 1): its error is relative to sum_k alpha_k ||GZ[v]|| ||P[col k]|| max|a_dst|.
     rp, cl = to_np(sg.rowptr), to_np(sg.col)
     rows = np.repeat(np.arange(nb), np.diff(rp))
     p64 = oops.to_f64(to_np(p))
@@ -610,14 +624,23 @@ def test_gat_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     assert np.diff(rp).min() > 0                       # the pattern carries the self-loops: no empty rows
     weight = alpha * np.linalg.norm(oops.to_f64(to_np(gz)), axis=1)[rows] * np.linalg.norm(p64, axis=1)[cl]
     terms = np.bincount(cl, weights=weight, minlength=nv) * np.abs(oops.to_f64(to_np(a_src))).max()
-    for n_out in (nv, nb):
-        gp = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
-        gd = torch.full((F,), float("nan"), device="cuda")
-        gs = torch.full((F,), float("nan"), device="cuda")
-        gas.gas_gat_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr), d(sg.row), d(sg.csc_perm).int(), d(p), d(a_dst),
-                                  d(a_src), d(gz), gp, gd, gs, 0.2)
-        assert node_rel_err(to_np(gp), want_p[:n_out], scale=terms[:n_out]) <= TOL[dtype], \
-            (n_out, node_rel_err(to_np(gp), want_p[:n_out], scale=terms[:n_out]))
-        # the two vector gradients are sums over all entries: against the size of the larger of the two
-        scale = max(np.abs(want_d).max(), np.abs(want_s).max())
-        assert np.abs(to_np(gd) - want_d).max() <= TOL[dtype] * scale and np.abs(to_np(gs) - want_s).max() <= TOL[dtype] * scale
+    terms[:nb] += np.add.reduceat(weight, rp[:-1]) * np.abs(oops.to_f64(to_np(a_dst))).max()
+    for fast in (False, True):
+        for n_out in (nv, nb):
+            plan_t = gas.gas_plan_create(d(sg.colptr)[: n_out + 1], int(sg.colptr[n_out]), F, n_rows=n_out, ind=d(sg.row)) \
+                if fast else None
+            gp = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
+            gd = torch.full((F,), float("nan"), device="cuda")
+            gs = torch.full((F,), float("nan"), device="cuda")
+            gas.gas_gat_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr), d(sg.row), d(sg.csc_perm).int(), d(p), d(a_dst),
+                                      d(a_src), d(gz), gp, gd, gs, 0.2, plan_t=plan_t)
+            assert node_rel_err(to_np(gp), want_p[:n_out], scale=terms[:n_out]) <= TOL[dtype], \
+                (fast, n_out, node_rel_err(to_np(gp), want_p[:n_out], scale=terms[:n_out]))
+            # the two vector gradients are sums over all entries: against the size of the larger of the two
+            scale = max(np.abs(want_d).max(), np.abs(want_s).max())
+            assert np.abs(to_np(gd) - want_d).max() <= TOL[dtype] * scale and np.abs(to_np(gs) - want_s).max() <= TOL[dtype] * scale
+            gp2 = torch.full((n_out, F), float("nan"), dtype=dtype, device="cuda")
+            gas.gas_gat_aggregate_bwd(d(sg.rowptr), d(sg.col), d(sg.colptr), d(sg.row), d(sg.csc_perm).int(), d(p), d(a_dst),
+                                      d(a_src), d(gz), gp2, gd, gs, 0.2, plan_t=plan_t)
+            assert torch.equal(gp.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                               gp2.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))     # fixed order

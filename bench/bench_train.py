@@ -27,6 +27,7 @@ def main():
     p.add_argument("--separate", action="store_true", help="pull the halo rows instead of reading them in place")
     p.add_argument("--graph", action="store_true", help="also replay every mini-batch's training step as a HIP graph")
     p.add_argument("--op", default=None, choices=["pna", "gat"], help="train this operator instead of the configuration's")
+    p.add_argument("--heads", type=int, default=4, help="attention heads of --op gat")
     p.add_argument("--lr", type=float, default=0.0, help="step size (default: 0.01 for GCN; 1e-10 for GIN, whose unnormalised sums of N(0,1) features give logits of order 1e5)")
     args = p.parse_args()
     if not torch.cuda.is_available():
@@ -91,7 +92,7 @@ def main():
                 if args.op == "pna":
                     _, grads, _ = executor.pna_train_batch(ws, delta, bg, wl.x, hist, loss_grad)
                 else:
-                    _, grads, _ = executor.gat_train_batch(ws, bg, wl.x, hist, loss_grad, heads=4)
+                    _, grads, _ = executor.gat_train_batch(ws, bg, wl.x, hist, loss_grad, heads=args.heads)
                 executor.sgd_update(ws, grads, lr)
             else:
                 loss_sum, _, _, _ = executor.train_step(gm, bg, wl.x, hist, lab_b, lr, n_labelled=n_lab, fused=fused)

@@ -35,6 +35,7 @@ def main():
     p = argparse.ArgumentParser()
     p.add_argument("--config", type=int, default=2)
     p.add_argument("--slots", type=int, default=3584, help="feature rows per L2 (3.5 MB of 1 KiB rows)")
+    p.add_argument("--stats-only", action="store_true", help="only the popularity of the gathered rows")
     args = p.parse_args()
     if not torch.cuda.is_available():
         sys.exit("l2_model.py: no GPU visible (the graph and the plan are built on the device)")
@@ -74,6 +75,15 @@ def main():
         light = np.stack([ptr[group[0::2]], ptr[group[1::2]]], 1)
         return light, chunk[:, 1:3].copy()
 
+    # how much reuse the batch offers at all
+    count = np.bincount(col, minlength=int(col.max()) + 1)
+    used = count[count > 0]
+    by_count = np.sort(used)[::-1].cumsum() / col.size
+    print(f"{col.size} entries name {used.size} rows; used once: {(used == 1).sum()}, twice: {(used == 2).sum()}; share of "
+          "the entries held by the most popular rows: " +
+          ", ".join(f"{k}: {100 * by_count[min(k, used.size) - 1]:.1f} %" for k in (4096, 8192, 32768, 131072, 262144)))
+    if args.stats_only:
+        return
     light, chunks = lists()
     partial_gb = len(chunks) * F * 4 * 2 / 1e9                       # written once, read once by the reduction
     print(f"configs[{args.config}] {cfg.name}, first batch, width {F}: {len(chunks)} chunks of heavy rows "
@@ -93,7 +103,6 @@ def main():
         it, xs = in_turn(chunks, P)
         print(f"heavy rows, units of {P} chunks dealt to the XCDs in turn: {model(it, xs):.1f} GB + {partial_gb:.1f} GB")
     # light rows with the gathers of unpopular rows kept from displacing the K most popular ones
-    count = np.bincount(col, minlength=int(col.max()) + 1)
     rank = np.empty(count.size, dtype=np.int64)
     rank[np.argsort(-count, kind="stable")] = np.arange(count.size)
     it, xs = in_turn(light, 4)

@@ -252,6 +252,49 @@ __global__ __launch_bounds__(256) void row_dot_kernel(const char* A, int64_t lda
     if (lane == 0) dot[row] = s;
 }
 
+// The same for rows of 16-byte pieces (both strides and bases 16-byte aligned): a team of G = 2^g lanes per row,
+// a piece per lane and turn, four rows of every team in flight; the team's lanes are added in a fixed tree.
+template <bool BF>
+__global__ __launch_bounds__(256) void row_dot_vec_kernel(const char* A, int64_t lda, const char* B, int64_t ldb,
+                                                          int64_t M, int pieces, int g_log2, float* dot) {
+    constexpr int E = BF ? 8 : 4, EB = BF ? 2 : 4, R = 4;
+    const int G = 1 << g_log2;
+    const int team = threadIdx.x >> g_log2, tl = threadIdx.x & (G - 1);
+    const int teams = 256 >> g_log2;
+    const int64_t r0 = ((int64_t)blockIdx.x * teams + team) * R;
+    float s[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) s[j] = 0.f;
+    for (int p = tl; p < pieces; p += G) {
+        u32x4 a[R], b[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            a[j] = u32x4{0u, 0u, 0u, 0u};
+            b[j] = u32x4{0u, 0u, 0u, 0u};
+            if (r0 + j < M) {
+                a[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(A + ((r0 + j) * lda + (int64_t)p * E) * EB));
+                b[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(B + ((r0 + j) * ldb + (int64_t)p * E) * EB));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (BF) {
+                    s[j] = fmaf(bf16_lo(a[j][i]), bf16_lo(b[j][i]), s[j]);
+                    s[j] = fmaf(bf16_hi(a[j][i]), bf16_hi(b[j][i]), s[j]);
+                } else {
+                    s[j] = fmaf(__uint_as_float(a[j][i]), __uint_as_float(b[j][i]), s[j]);
+                }
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        for (int o = G >> 1; o > 0; o >>= 1) s[j] += __shfl_xor(s[j], o);
+        if (tl == 0 && r0 + j < M) dot[r0 + j] = s[j];
+    }
+}
+
 // G[m, :] = scale * (A[m, :] - B[m, :]) / || A[m, :] - B[m, :] ||_2 (zero where the rows are equal): one wavefront
 // per row, two passes over the row (the second one out of the cache)
 template <bool BF>
@@ -430,6 +473,27 @@ gas_status gas_row_dot(const void* A, int64_t lda, const void* B, int64_t ldb, i
     if (n_rows > 0) {
         GAS_REQUIRE(A && B && dot, "gas_row_dot: null pointer");
         GAS_REQUIRE(lda >= F && ldb >= F, "gas_row_dot: row stride smaller than the row");
+        const int e = dt == GAS_BF16 ? 8 : 4;
+        if (F % e == 0 && lda % e == 0 && ldb % e == 0 && aligned16(A) && aligned16(B)) {
+            const int pieces = F / e;
+            int g_log2 = 0;
+            while ((1 << g_log2) < pieces && g_log2 < 6) ++g_log2;
+            const int64_t rows_per_block = (256 >> g_log2) * 4;
+            const int64_t vblocks = (n_rows + rows_per_block - 1) / rows_per_block;
+            GAS_REQUIRE(vblocks <= 0x7FFFFFFFLL, "gas_row_dot: too many rows for one launch");
+            if (dt == GAS_BF16)
+                hipLaunchKernelGGL(row_dot_vec_kernel<true>, dim3((unsigned)vblocks), dim3(256), 0, s,
+                                   static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, pieces, g_log2, dot);
+            else
+                hipLaunchKernelGGL(row_dot_vec_kernel<false>, dim3((unsigned)vblocks), dim3(256), 0, s,
+                                   static_cast<const char*>(A), lda, static_cast<const char*>(B), ldb, n_rows, pieces, g_log2, dot);
+            GAS_CHECK_HIP(hipGetLastError());
+            if (dot_sum) {
+                hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(1024), 0, s, dot, n_rows, dot_sum);
+                GAS_CHECK_HIP(hipGetLastError());
+            }
+            return GAS_OK;
+        }
         const int64_t blocks = (n_rows + 3) / 4;
         GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_row_dot: too many rows for one launch");
         if (dt == GAS_BF16)

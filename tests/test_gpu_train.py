@@ -253,7 +253,8 @@ def test_lipschitz_regulariser_matches_oracle(gas, op, dtype, layer):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("M,F,ld", [(1000, 256, 256), (333, 100, 104), (50, 7, 7), (0, 8, 8)])
+@pytest.mark.parametrize("M,F,ld", [(1000, 256, 256), (333, 100, 104), (50, 7, 7), (0, 8, 8), (4099, 512, 512), (777, 64, 72),
+                                    (129, 520, 520), (65, 8, 8), (1, 16, 16)])
 def test_row_dot_parity(gas, dtype, M, F, ld):
     """gas_row_dot (the reduction behind the gradient of GIN's eps) against the oracle's float64 inner products."""
     a = rng.normal_matrix(18, 1400, M, ld, dtype=dtype)

@@ -434,7 +434,7 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
 
 /*
  * Backward passes of the two aggregations above (chain rule on the equations of the operator appendix), without
- * atomics: a pass over the rows of the pattern leaves per-row / per-entry factors in `workspace`, a pass over the
+ * floating-point atomics: a pass over the rows of the pattern leaves per-row / per-entry factors in `workspace`, a pass over the
  * columns (the CSC copy: colptr int32[n_cols+1], row int32[nnz], and csc_pos int32[nnz] = the position of every CSC
  * entry in the CSR arrays) sums each column's contributions in stored order.  n_out <= n_cols output rows are
  * written (the in-batch nodes when histories are constants, or all of V_b).  workspace: device memory of at least
@@ -445,7 +445,7 @@ GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, 
  * (which rounds it to the storage type before the remaining terms are added: one more rounding for bf16).  Without
  * it, or for other shapes, plain kernels run: one wavefront per row and per column, one entry at a time; slow, and
  * the definition the fast path is tested against.  Fixed summation order either way (not the same order: the two
- * paths agree to rounding).
+ * paths agree to rounding).  The plan's partial-sum workspace is in use during the call, as in gas_spmm_t.
  *
  * gas_pna_aggregate_bwd: G [n_rows, 9 F] is the gradient of gas_pna_aggregate's output.  With s and d as there and
  *     c_i = G[v, i F + f] + s G[v, (3+i) F + f] + G[v, (6+i) F + f] / s   (i = mean, min, max; rows with entries),

@@ -547,7 +547,9 @@ GAS_API gas_status gas_push_host(const void* src, int64_t ld_src, const int32_t*
  *                 while the table is open, and a failing storage device
  *                 ends the process with a signal.  GAS_DISK_CALLS uses
  *                 pread / pwrite instead: slower for scattered rows, every
- *                 failure a GAS_ERR_IO.  io_threads 0 = 8; staging_bytes 0 =
+ *                 failure a GAS_ERR_IO.  io_threads (at most 16, 0 = 8): how
+ *                 many of the process's I/O threads a transfer of this table
+ *                 uses (one pool serves all tables); staging_bytes 0 =
  *                 32 MiB per buffer (allocated at the first transfer).
  *                 HOST pointers.
  * gas_disk_pull:  dst[i, 0:F] = table[r(i), 0:F] with r(i) as in gas_pull;

@@ -3,7 +3,8 @@
 // gathers rows into pinned buffers, copies run beside the computation, and a layer waits only for its own rows).
 //
 // A gas_disk_table is a raw row-major file of n_rows x F elements plus
-//   * a pool of I/O threads that move rows between the file and a buffer: through a shared mapping of the file (plain
+//   * I/O threads (one pool for all tables of the process; a table uses as many of them as it was opened with, one
+//     table's burst at a time) that move rows between the file and a buffer: through a shared mapping of the file (plain
 //     copies into and out of the page cache: no system call and no file lock per row, which scattered 1 KiB rows
 //     need), or, on request, with pread / pwrite, runs of consecutive rows in one call (errors then come back as
 //     status codes instead of signals),
@@ -32,7 +33,7 @@
 
 namespace {
 
-// n_threads workers that run one range function at a time over [0, n) in equal parts.
+// n_threads workers that run one range function at a time over [0, n) in `parts` equal parts (the caller takes part 0).
 class IoPool {
 public:
     explicit IoPool(int n_threads) : n_(std::max(1, n_threads)) {
@@ -49,12 +50,13 @@ public:
     }
     int size() const { return n_; }
     // fn(part, begin, end) for each part; returns when all parts are done.  One caller at a time.
-    void run(int64_t n, const std::function<void(int, int64_t, int64_t)>& fn) {
+    void run(int64_t n, int parts, const std::function<void(int, int64_t, int64_t)>& fn) {
         if (n <= 0) return;
         {
             std::lock_guard<std::mutex> g(m_);
             fn_ = &fn;
             total_ = n;
+            parts_ = std::max(1, std::min(parts, n_));
             pending_ = n_ - 1;
             ++epoch_;
         }
@@ -67,7 +69,8 @@ public:
 
 private:
     void part(int t) {
-        const int64_t per = (total_ + n_ - 1) / n_;
+        if (t >= parts_) return;
+        const int64_t per = (total_ + parts_ - 1) / parts_;
         const int64_t b = std::min<int64_t>(total_, per * t), e = std::min<int64_t>(total_, b + per);
         if (b < e) (*fn_)(t, b, e);
     }
@@ -94,6 +97,7 @@ private:
     std::condition_variable cv_, done_;
     const std::function<void(int, int64_t, int64_t)>* fn_ = nullptr;
     int64_t total_ = 0;
+    int parts_ = 1;
     int pending_ = 0;
     uint64_t epoch_ = 0;
     bool stop_ = false;
@@ -121,7 +125,7 @@ struct gas_disk_table {
     gas_dtype dt = GAS_F32;
     int64_t row_bytes = 0;
     int64_t staging_rows = 0;
-    IoPool* pool = nullptr;
+    int io_threads = 8;
     // device side, set up by the worker at the first transfer
     int device = -1;
     bool device_ready = false;
@@ -142,6 +146,15 @@ struct gas_disk_table {
 namespace {
 
 using gas::fail;
+
+// The process's I/O threads, started at the first transfer of any table and never stopped (they sleep between
+// bursts).  One burst at a time: tables take turns for the file copies and overlap them with each other's DMA.
+constexpr int kPoolThreads = 16;
+std::mutex pool_mutex;
+IoPool* shared_pool() {
+    static IoPool* pool = new IoPool(kPoolThreads);
+    return pool;
+}
 
 // Rows [b, e) of the list (idx or base + i) between the file and `buf` (row i of the list at buf + (i - origin) *
 // row_bytes).  Runs of consecutive file rows take one call.  Returns 0 or errno.
@@ -183,8 +196,9 @@ int io_rows(const gas_disk_table* t, bool write, const int32_t* idx, int64_t bas
 
 int io_parallel(gas_disk_table* t, bool write, const int32_t* idx, int64_t base, int64_t origin, int64_t b, int64_t e,
                 char* buf) {
-    std::vector<int> err((size_t)t->pool->size(), 0);
-    t->pool->run(e - b, [&](int part, int64_t pb, int64_t pe) {
+    std::vector<int> err((size_t)kPoolThreads, 0);
+    std::lock_guard<std::mutex> g(pool_mutex);
+    shared_pool()->run(e - b, t->io_threads, [&](int part, int64_t pb, int64_t pe) {
         err[(size_t)part] = io_rows(t, write, idx, base, origin, b + pb, b + pe, buf);
     });
     for (int v : err)
@@ -383,8 +397,9 @@ gas_status host_rows(gas_disk_table* t, bool write, const char* who, const int32
     if (pitch == t->row_bytes) {
         e = io_parallel(t, write, idx, base, 0, 0, n, (char*)rows);
     } else {                       // strided host rows: one row per call
-        std::vector<int> err((size_t)t->pool->size(), 0);
-        t->pool->run(n, [&](int part, int64_t b, int64_t e2) {
+        std::vector<int> err((size_t)kPoolThreads, 0);
+        std::lock_guard<std::mutex> g(pool_mutex);
+        shared_pool()->run(n, t->io_threads, [&](int part, int64_t b, int64_t e2) {
             for (int64_t i = b; i < e2 && !err[(size_t)part]; ++i)
                 err[(size_t)part] = io_rows(t, write, idx, base, i, i, i + 1, (char*)rows + i * pitch);
         });
@@ -406,7 +421,8 @@ gas_status gas_disk_open(const char* path, int64_t n_rows, int32_t F, gas_dtype 
     const bool create = flags & GAS_DISK_CREATE;
     if (!gas::valid_dtype(dt)) return fail(GAS_ERR_DTYPE, "gas_disk_open: unknown dtype %d", (int)dt);
     GAS_REQUIRE(n_rows >= 0 && F > 0, "gas_disk_open: n_rows=%lld F=%d", (long long)n_rows, F);
-    GAS_REQUIRE(io_threads >= 0 && io_threads <= 64, "gas_disk_open: io_threads=%d not in [0, 64]", io_threads);
+    GAS_REQUIRE(io_threads >= 0 && io_threads <= kPoolThreads, "gas_disk_open: io_threads=%d not in [0, %d]", io_threads,
+                kPoolThreads);
     GAS_REQUIRE(staging_bytes >= 0 && staging_bytes <= (1ll << 32), "gas_disk_open: staging_bytes=%lld not in [0, 4 GiB]",
                 (long long)staging_bytes);
     const int64_t row_bytes = (int64_t)F * gas::elem_bytes(dt);
@@ -452,7 +468,7 @@ gas_status gas_disk_open(const char* path, int64_t n_rows, int32_t F, gas_dtype 
     t->row_bytes = row_bytes;
     const int64_t sb_bytes = staging_bytes > 0 ? staging_bytes : (32ll << 20);
     t->staging_rows = std::max<int64_t>(1, sb_bytes / row_bytes);
-    t->pool = new IoPool(io_threads > 0 ? io_threads : 8);
+    t->io_threads = io_threads > 0 ? io_threads : 8;
     t->worker = std::thread(worker_loop, t);
     *out = t;
     return GAS_OK;
@@ -476,7 +492,6 @@ gas_status gas_disk_close(gas_disk_table* t) {
         }
         (void)hipStreamDestroy(t->copy_stream);
     }
-    delete t->pool;
     if (t->map) (void)munmap(t->map, (size_t)t->map_bytes);
     if (close(t->fd) != 0 && st == GAS_OK) st = fail(GAS_ERR_IO, "gas_disk_close: %s", strerror(errno));
     delete t;

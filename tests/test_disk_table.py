@@ -128,7 +128,7 @@ def test_bad_open_arguments():
     import ctypes as C
     h = C.c_void_p(0)
     for args in ((b"/tmp/x", 4, 4, 0, 4, 0, 0), (b"/tmp/x", -1, 4, 0, 1, 0, 0), (b"/tmp/x", 4, 0, 0, 1, 0, 0), (b"/tmp/x", 4, 4, 9, 1, 0, 0),
-                 (b"/tmp/x", 4, 4, 0, 1, 65, 0), (b"/tmp/x", 4, 4, 0, 1, 0, -5)):
+                 (b"/tmp/x", 4, 4, 0, 1, 17, 0), (b"/tmp/x", 4, 4, 0, 1, 0, -5)):
         st = L.gas_disk_open(args[0], C.c_int64(args[1]), C.c_int32(args[2]), C.c_int(args[3]), C.c_int32(args[4]),
                              C.c_int32(args[5]), C.c_int64(args[6]), C.byref(h))
         assert st in (-1, -2) and not h.value

@@ -408,8 +408,10 @@ GAS_API gas_status gas_sgd_step_clipped(void* W, int64_t n, gas_dtype dt, const 
  * s = log(d_v + 1) / delta, d_v = rowptr[v+1] - rowptr[v]; delta > 0 is the
  * mean of log(deg + 1) over the graph.  Rows without entries give zeros.
  * rowptr int32[n_rows+1], col int32[nnz] in range of X's rows; X, add, out of
- * type dt (device), out must not alias them.  Deterministic (entries folded
- * in index order).
+ * type dt (device), out must not alias them.  Deterministic: which lane folds
+ * which entry depends on the row's length and on F alone (rows of at most 64
+ * pieces of 16 bytes are shared by teams of lanes, rows above 2,048 entries by
+ * the wavefronts of a workgroup, folded in a fixed order).
  */
 GAS_API gas_status gas_pna_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows,
                              const void* X, int64_t ldx, gas_dtype dt, int32_t F,
@@ -424,7 +426,9 @@ GAS_API gas_status gas_pna_aggregate(const int32_t* rowptr, const int32_t* col, 
  * P = H W [n_cols, F] computed beforehand (rows 0..n_rows-1 are the in-batch
  * nodes); a_dst, a_src: the two halves of the attention vector, [F] of type
  * dt.  Scores, softmax and the weighted sum take one pass over the gathered
- * rows (fp32 arithmetic, entries folded in index order: deterministic).
+ * rows (fp32 arithmetic; running maxima and sums kept per team of lanes, and
+ * per wavefront for rows above 2,048 entries, merged in a fixed order that
+ * depends on the row's length and on F alone: deterministic).
  * Rows without entries give zeros.  F <= 1024.  Z must not alias P.
  */
 GAS_API gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* col, int64_t n_rows,

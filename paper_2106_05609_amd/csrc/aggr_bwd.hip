@@ -127,12 +127,15 @@ struct PnaFastArgs {
     float inv_delta;
 };
 
-template <bool BF>
+// G: lanes that hold a row (at least its number of pieces).  With G < 64 the wavefront's S = 64 / G teams each hold
+// the row and take the entries in turn while gathering (team t the entries t, t + S, ...); their winners are
+// merged before the rest, which the lanes of team 0 do as lanes 0 .. G - 1 of the wavefront.
+template <bool BF, int G>
 __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
-    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 16;
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, S = 64 / G, U = 16 / (S > 2 ? 2 : 1);
     __shared__ uint32_t cnt[2][kPnaChunk];
     const int64_t v = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x, team = lane / G, tl = lane % G;
     const int b = a.rowptr[v], e = a.rowptr[v + 1];
     const int d = e - b;
     const bool on = lane * E < a.F;
@@ -148,24 +151,29 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
     int kmn[E], kmx[E];
 #pragma unroll
     for (int i = 0; i < E; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; kmn[i] = b; kmx[i] = b; }
+    const bool gon = tl * E < a.F;
     for (int k0 = b; k0 < e; k0 += 64) {
         const int n64 = min(64, e - k0);
         const int mine = lane < n64 ? a.col[k0 + lane] : 0;
-        for (int j0 = 0; j0 < n64; j0 += U) {
+        for (int j0 = 0; j0 < n64; j0 += U * S) {
             u32x4 r[U];
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                const int c = __builtin_amdgcn_readlane(mine, (j0 + j) & 63);
+                const int kk = j0 + j * S + team;
+                int c;
+                if constexpr (S == 1) c = __builtin_amdgcn_readlane(mine, kk & 63);
+                else c = __shfl(mine, kk & 63);
                 r[j] = u32x4{0u, 0u, 0u, 0u};
-                if (on && j0 + j < n64)
-                    r[j] = *reinterpret_cast<const u32x4*>(a.X + ((int64_t)c * a.ldx + (int64_t)lane * E) * EB);
+                if (gon && kk < n64)
+                    r[j] = *reinterpret_cast<const u32x4*>(a.X + ((int64_t)c * a.ldx + (int64_t)tl * E) * EB);
             }
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                if (j0 + j < n64) {
+                const int kk = j0 + j * S + team;
+                if (kk < n64) {
                     float x[E];
                     unpack<BF>(r[j], x);
-                    const int k = k0 + j0 + j;
+                    const int k = k0 + kk;
 #pragma unroll
                     for (int i = 0; i < E; ++i) {
                         if (x[i] < mn[i]) { mn[i] = x[i]; kmn[i] = k; }      // strict: the first entry that attains it
@@ -173,6 +181,17 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
                     }
                 }
             }
+        }
+    }
+    // the teams' winners merged: the smaller (larger) value, and of equal values the earlier entry
+#pragma unroll
+    for (int o = G; o < 64; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            const float xn = __shfl_xor(mn[i], o), xx = __shfl_xor(mx[i], o);
+            const int kn = __shfl_xor(kmn[i], o), kx = __shfl_xor(kmx[i], o);
+            if (xn < mn[i] || (xn == mn[i] && kn < kmn[i])) { mn[i] = xn; kmn[i] = kn; }
+            if (xx > mx[i] || (xx == mx[i] && kx < kmx[i])) { mx[i] = xx; kmx[i] = kx; }
         }
     }
     // the three block gradients folded with their scalers
@@ -478,23 +497,24 @@ __global__ __launch_bounds__(64) void gat_bwd_cols_kernel(GatBwdArgs a) {
 }
 
 // ---- fast path: rows of at most 64 pieces of 16 bytes
-// Row v, as gat_bwd_rows_kernel, with the gathers of the forward kernel: eight neighbour rows in flight, both dot
-// products of an entry (with a_src for the score, with GZ[v] for the gradient of its attention weight) reduced
-// over the lanes eight entries at a time.
-template <bool BF>
+// Row v, as gat_bwd_rows_kernel, with the gathers of the forward kernel: eight neighbour rows in flight per lane,
+// both dot products of an entry (with a_src for the score, with GZ[v] for the gradient of its attention weight)
+// reduced over the lanes eight entries at a time.  A row of at most G < 64 pieces is held by each of the
+// wavefront's S = 64 / G teams of G lanes, which take the entries in turn (team t the entries t, t + S, ...).
+template <bool BF, int G>
 __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
-    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 8;
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 8, S = 64 / G;
     const int64_t v = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x, team = lane / G, tl = lane % G;
     const int b = a.rowptr[v], e = a.rowptr[v + 1];
     if (e == b) {
         if (lane == 0) a.csum[v] = 0.f;
         return;
     }
-    const bool on = lane * E < a.F;
+    const bool on = tl * E < a.F;
     auto piece = [&](const char* base, int64_t row_elems) {
         u32x4 t = {0u, 0u, 0u, 0u};
-        if (on) t = *reinterpret_cast<const u32x4*>(base + (row_elems + (int64_t)lane * E) * EB);
+        if (on) t = *reinterpret_cast<const u32x4*>(base + (row_elems + (int64_t)tl * E) * EB);
         return t;
     };
     float ar[E], gz[E], x[E], ad[E];
@@ -505,19 +525,22 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
     float sv = 0.f;
 #pragma unroll
     for (int i = 0; i < E; ++i) sv += ad[i] * x[i];
-    sv = wave_sum(sv);
+    sv = team_sum<G>(sv);
     float mx = -INFINITY;
     for (int k0 = b; k0 < e; k0 += 64) {
         const int cnt = min(64, e - k0);
         const int mine = lane < cnt ? a.col[k0 + lane] : 0;
-        for (int j0 = 0; j0 < cnt; j0 += U) {
+        for (int j0 = 0; j0 < cnt; j0 += U * S) {
             u32x4 r[U];
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                const int c = __builtin_amdgcn_readlane(mine, (j0 + j) & 63);
+                const int kk = j0 + j * S + team;
+                int c;
+                if constexpr (S == 1) c = __builtin_amdgcn_readlane(mine, kk & 63);
+                else c = __shfl(mine, kk & 63);
                 r[j] = u32x4{0u, 0u, 0u, 0u};
-                if (on && j0 + j < cnt)
-                    r[j] = *reinterpret_cast<const u32x4*>(a.P + ((int64_t)c * a.ldp + (int64_t)lane * E) * EB);
+                if (on && kk < cnt)
+                    r[j] = *reinterpret_cast<const u32x4*>(a.P + ((int64_t)c * a.ldp + (int64_t)tl * E) * EB);
             }
             float sw[U], da[U];
 #pragma unroll
@@ -531,19 +554,28 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
                     da[j] = fmaf(gz[i], x[i], da[j]);
                 }
             }
-            wave_sum8(sw);
-            wave_sum8(da);
+            team_sum8<G>(sw);
+            team_sum8<G>(da);
+            // Entry j0 + i of the block is stored by lane j0 + i, the lane that reads it in the loops below, so no lane
+            // ever reads another lane's store; its two sums are with team i % S, in slot i / S.
+            const int mine_i = lane - j0;
+            float my_t = 0.f, my_da = 0.f;
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                if (j0 + j < cnt) {
-                    const float t = sv + sw[j];
-                    mx = fmaxf(mx, t > 0.f ? t : a.slope * t);
-                    // the lane that reads entry k in the loops below is the one that stores it here
-                    if (lane == ((j0 + j) & 63)) { a.alpha[k0 + j0 + j] = t; a.dt[k0 + j0 + j] = da[j]; }
+                float tj = sv + sw[j], dj = da[j];
+                if (j * S + team < cnt - j0) mx = fmaxf(mx, tj > 0.f ? tj : a.slope * tj);
+                if constexpr (S > 1) {
+                    const int src = (mine_i & (S - 1)) * G;
+                    tj = __shfl(tj, src);
+                    dj = __shfl(dj, src);
                 }
+                if (mine_i >= j * S && mine_i < (j + 1) * S) { my_t = tj; my_da = dj; }
             }
+            if (mine_i >= 0 && mine_i < U * S && lane < cnt) { a.alpha[k0 + lane] = my_t; a.dt[k0 + lane] = my_da; }
         }
     }
+#pragma unroll
+    for (int o = G; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     float den = 0.f;
     for (int k = b + lane; k < e; k += 64) {
         const float t = a.alpha[k];
@@ -792,8 +824,17 @@ gas_status gas_pna_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
         a.items_v = reinterpret_cast<float*>(w); w += align_up(n_rows * 2 * (int64_t)F * 4);
         a.ent = reinterpret_cast<uint2*>(w);
         a.F = F; a.inv_delta = 1.f / delta;
-        if (bf) hipLaunchKernelGGL(pna_bwd_rows_vec_kernel<true>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
-        else hipLaunchKernelGGL(pna_bwd_rows_vec_kernel<false>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
+        const dim3 grid((unsigned)n_rows), block(64);
+        const int pieces = F / (bf ? 8 : 4);
+        if (bf) {
+            if (pieces <= 16) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 16>), grid, block, 0, s, a);
+            else if (pieces <= 32) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 32>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 64>), grid, block, 0, s, a);
+        } else {
+            if (pieces <= 16) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 16>), grid, block, 0, s, a);
+            else if (pieces <= 32) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 32>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 64>), grid, block, 0, s, a);
+        }
         GAS_CHECK_HIP(hipGetLastError());
         // the mean's share: GX[u] = sum over the entries (v, u) of C0[v]
         const gas_status st = gas_spmm_t(plan_t, colptr, row, nullptr, 0.f, 1.f, 0, a.C0, F, dt, F, GX, ldgx, dt, stream);
@@ -873,8 +914,17 @@ gas_status gas_gat_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
     const bool vec = vec_rows(dt, F, {P, GZ, GP, a_dst, a_src}, {ldp, ldgz, ldgp});
     if (plan_t && n_out > 0 && vec) {
         if (n_rows > 0) {
-            if (bf) hipLaunchKernelGGL(gat_bwd_rows_vec_kernel<true>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
-            else hipLaunchKernelGGL(gat_bwd_rows_vec_kernel<false>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
+            const dim3 grid((unsigned)n_rows), block(64);
+            const int pieces = F / (bf ? 8 : 4);
+            if (bf) {
+                if (pieces <= 16) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 16>), grid, block, 0, s, a);
+                else if (pieces <= 32) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 32>), grid, block, 0, s, a);
+                else hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 64>), grid, block, 0, s, a);
+            } else {
+                if (pieces <= 16) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 16>), grid, block, 0, s, a);
+                else if (pieces <= 32) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 32>), grid, block, 0, s, a);
+                else hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 64>), grid, block, 0, s, a);
+            }
         }
         GAS_REQUIRE(plan_t->nnz <= nnz, "gas_gat_aggregate_bwd: the plan has %lld entries, the pattern %lld",
                     (long long)plan_t->nnz, (long long)nnz);

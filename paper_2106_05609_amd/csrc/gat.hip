@@ -19,49 +19,70 @@ struct GatArgs {
     int relu;                                     // ReLU on the output row
 };
 
-// Rows of at most 64 pieces of 16 bytes: lane l owns piece l.  Entries are taken U at a time: gathers, scores
-// (one lane reduction each), one rescale of the running sums to the block's maximum, then the weighted adds in
-// index order.
-template <bool BF>
-__global__ __launch_bounds__(64) void gat_rows_kernel(GatArgs a) {
-    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 8;   // U = 8: wave_sum8 reduces one block of scores
-    const int64_t v = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int b = a.rowptr[v], e = a.rowptr[v + 1];
-    const bool on = lane * E < a.F;
-    char* zrow = a.Z + (v * a.ldz + (int64_t)lane * E) * EB;
-    if (e == b) {
-        if (on) *reinterpret_cast<u32x4*>(zrow) = u32x4{0u, 0u, 0u, 0u};
-        return;
-    }
+// Rows of at most 64 pieces of 16 bytes, G = 16, 32 or 64 lanes per row (at least the number of pieces).  A
+// wavefront's S = 64 / G teams of G lanes each hold the whole row and take the entries in turn (team t the entries
+// t, t + S, ... of every block of 64), eight at a time per team: gathers, scores (one reduction over the team's
+// lanes for all eight), one rescale of the running sums to the new maximum, then the weighted adds.  Every team
+// keeps its own running maximum and sums, and the teams' states are merged pair by pair at the end.  A row of
+// more than kLongRow entries is shared by the kLongWaves wavefronts of a workgroup in the same way, block of 64
+// entries by block, and their states are merged in wavefront order.  Which lane takes which entry depends on the
+// row's length and the width alone, so the result is the same bits on every run.
+constexpr int kLongRow = 2048;
+constexpr int kLongWaves = 8;
+constexpr int kLongBlocks = 2048;                     // workgroups of the long-row kernel
+
+// running softmax state of one lane: maximum m, sum of weights l, weighted sum acc of its piece
+template <int E>
+__device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[E], float mo, float lo, const float (&acco)[E]) {
+    const float mm = fmaxf(m, mo);
+    // a state that has seen no entry has m = -inf and zero sums
+    const float s1 = m > -INFINITY ? expf(m - mm) : 0.f, s2 = mo > -INFINITY ? expf(mo - mm) : 0.f;
+    l = l * s1 + lo * s2;
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = acc[i] * s1 + acco[i] * s2;
+    m = mm;
+}
+
+// The entries of the blocks first, first + stride, ... of row v = [b, e), b < e: afterwards every team of the
+// wavefront holds the merged state of all of them.
+template <bool BF, int G>
+__device__ __forceinline__ void gat_gather(const GatArgs& a, int64_t v, int b, int e, int first, int stride,
+                                           float& m, float& l, float (&acc)[Elems<BF>::E]) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 8, S = 64 / G;
+    const int lane = threadIdx.x & 63, team = lane / G, tl = lane % G;
+    const bool on = tl * E < a.F;
     float ad[E], ar[E], x[E];
     u32x4 t = {0u, 0u, 0u, 0u};
-    if (on) t = *reinterpret_cast<const u32x4*>(a.a_dst + (int64_t)lane * E * EB);
+    if (on) t = *reinterpret_cast<const u32x4*>(a.a_dst + (int64_t)tl * E * EB);
     unpack<BF>(t, ad);
     t = u32x4{0u, 0u, 0u, 0u};
-    if (on) t = *reinterpret_cast<const u32x4*>(a.a_src + (int64_t)lane * E * EB);
+    if (on) t = *reinterpret_cast<const u32x4*>(a.a_src + (int64_t)tl * E * EB);
     unpack<BF>(t, ar);
     t = u32x4{0u, 0u, 0u, 0u};
-    if (on) t = *reinterpret_cast<const u32x4*>(a.P + (v * a.ldp + (int64_t)lane * E) * EB);
+    if (on) t = *reinterpret_cast<const u32x4*>(a.P + (v * a.ldp + (int64_t)tl * E) * EB);
     unpack<BF>(t, x);
     float sv = 0.f;
 #pragma unroll
     for (int i = 0; i < E; ++i) sv += ad[i] * x[i];
-    sv = wave_sum(sv);
-    float m = -INFINITY, l = 0.f, acc[E];
+    sv = team_sum<G>(sv);
+    m = -INFINITY;
+    l = 0.f;
 #pragma unroll
     for (int i = 0; i < E; ++i) acc[i] = 0.f;
-    for (int k0 = b; k0 < e; k0 += 64) {
+    for (int k0 = b + 64 * first; k0 < e; k0 += 64 * stride) {
         const int cnt = min(64, e - k0);
         const int mine = lane < cnt ? a.col[k0 + lane] : 0;
-        for (int j0 = 0; j0 < cnt; j0 += U) {
+        for (int j0 = 0; j0 < cnt; j0 += U * S) {
             u32x4 r[U];
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                const int c = __builtin_amdgcn_readlane(mine, (j0 + j) & 63);
+                const int kk = j0 + j * S + team;
+                int c;
+                if constexpr (S == 1) c = __builtin_amdgcn_readlane(mine, kk & 63);
+                else c = __shfl(mine, kk & 63);
                 r[j] = u32x4{0u, 0u, 0u, 0u};
-                if (on && j0 + j < cnt)
-                    r[j] = *reinterpret_cast<const u32x4*>(a.P + ((int64_t)c * a.ldp + (int64_t)lane * E) * EB);
+                if (on && kk < cnt)
+                    r[j] = *reinterpret_cast<const u32x4*>(a.P + ((int64_t)c * a.ldp + (int64_t)tl * E) * EB);
             }
             float sc[U], mb = m;
 #pragma unroll
@@ -71,40 +92,129 @@ __global__ __launch_bounds__(64) void gat_rows_kernel(GatArgs a) {
 #pragma unroll
                 for (int i = 0; i < E; ++i) sc[j] += ar[i] * x[i];
             }
-            wave_sum8(sc);
+            team_sum8<G>(sc);
 #pragma unroll
             for (int j = 0; j < U; ++j) {
                 float s = sc[j] + sv;
                 s = s > 0.f ? s : a.slope * s;
-                sc[j] = j0 + j < cnt ? s : -INFINITY;
+                sc[j] = j0 + j * S + team < cnt ? s : -INFINITY;
                 mb = fmaxf(mb, sc[j]);
             }
-            const float scale = expf(m - mb);         // m = -inf at the start: scale 0 on sums that are 0
-            l *= scale;
+            if (mb > -INFINITY) {                         // a team may have had no entry of its own yet
+                const float scale = expf(m - mb);         // m = -inf at the start: scale 0 on sums that are 0
+                l *= scale;
 #pragma unroll
-            for (int i = 0; i < E; ++i) acc[i] *= scale;
+                for (int i = 0; i < E; ++i) acc[i] *= scale;
 #pragma unroll
-            for (int j = 0; j < U; ++j) {
-                const float p = expf(sc[j] - mb);     // 0 for the padding entries
-                l += p;
-                unpack<BF>(r[j], x);
+                for (int j = 0; j < U; ++j) {
+                    const float p = expf(sc[j] - mb);     // 0 for the padding entries
+                    l += p;
+                    unpack<BF>(r[j], x);
 #pragma unroll
-                for (int i = 0; i < E; ++i) acc[i] += p * x[i];
+                    for (int i = 0; i < E; ++i) acc[i] += p * x[i];
+                }
+                m = mb;
             }
-            m = mb;
         }
     }
-    if (!on) return;
+    // both partners of an exchange compute the same merged state
+#pragma unroll
+    for (int o = G; o < 64; o <<= 1) {
+        const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
+        float acco[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) acco[i] = __shfl_xor(acc[i], o);
+        merge_state<E>(m, l, acc, mo, lo, acco);
+    }
+}
+
+template <bool BF, int G>
+__device__ __forceinline__ void gat_finish(const GatArgs& a, int64_t v, float l, float (&acc)[Elems<BF>::E]) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4;
+    const int lane = threadIdx.x & 63;
+    if (lane >= G || lane * E >= a.F) return;         // team 0 stores
     const float inv = 1.f / l;
 #pragma unroll
     for (int i = 0; i < E; ++i) {
         acc[i] *= inv;
         if (a.relu) acc[i] = fmaxf(acc[i], 0.f);
     }
-    u32x4 o;
-    if constexpr (BF) o = u32x4{pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]), pack_bf16(acc[6], acc[7])};
-    else o = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-    __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(zrow));
+    __builtin_nontemporal_store(pack<BF>(acc), reinterpret_cast<u32x4*>(a.Z + (v * a.ldz + (int64_t)lane * E) * EB));
+}
+
+// one wavefront per row; long rows are left to gat_long_rows_kernel
+template <bool BF, int G>
+__global__ __launch_bounds__(64) void gat_rows_kernel(GatArgs a) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4;
+    const int64_t v = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int b = a.rowptr[v], e = a.rowptr[v + 1];
+    if (e == b) {
+        if (lane < G && lane * E < a.F)
+            *reinterpret_cast<u32x4*>(a.Z + (v * a.ldz + (int64_t)lane * E) * EB) = u32x4{0u, 0u, 0u, 0u};
+        return;
+    }
+    if (e - b > kLongRow) return;
+    float m, l, acc[E];
+    gat_gather<BF, G>(a, v, b, e, 0, 1, m, l, acc);
+    gat_finish<BF, G>(a, v, l, acc);
+}
+
+// Workgroup w looks at the rows w, w + gridDim.x, ... (512 of them at a time), and every row of more than kLongRow
+// entries among them is gathered by all its wavefronts together.
+template <bool BF, int G>
+__global__ __launch_bounds__(64 * kLongWaves) void gat_long_rows_kernel(GatArgs a) {
+    constexpr int E = Elems<BF>::E, T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    __shared__ float red[kLongWaves][E + 2][64];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t r0 = blockIdx.x; r0 < a.n_rows; r0 += (int64_t)T * gridDim.x) {
+        if (threadIdx.x == 0) n_queued = 0;
+        __syncthreads();
+        const int64_t r = r0 + (int64_t)threadIdx.x * gridDim.x;
+        if (r < a.n_rows && a.rowptr[r + 1] - a.rowptr[r] > kLongRow) queue[atomicAdd(&n_queued, 1)] = (int)r;
+        __syncthreads();
+        const int nq = n_queued;
+        for (int q = 0; q < nq; ++q) {
+            const int64_t v = queue[q];
+            const int b = a.rowptr[v], e = a.rowptr[v + 1];
+            float m, l, acc[E];
+            gat_gather<BF, G>(a, v, b, e, w, kLongWaves, m, l, acc);
+            if (w > 0) {
+                red[w][E][lane] = m;
+                red[w][E + 1][lane] = l;
+#pragma unroll
+                for (int i = 0; i < E; ++i) red[w][i][lane] = acc[i];
+            }
+            __syncthreads();
+            if (w == 0) {
+                for (int o = 1; o < kLongWaves; ++o) {
+                    float acco[E];
+#pragma unroll
+                    for (int i = 0; i < E; ++i) acco[i] = red[o][i][lane];
+                    merge_state<E>(m, l, acc, red[o][E][lane], red[o][E + 1][lane], acco);
+                }
+                gat_finish<BF, G>(a, v, l, acc);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <bool BF, int G>
+void launch_rows(const GatArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((gat_rows_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
+    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    hipLaunchKernelGGL((gat_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
+}
+
+template <bool BF>
+void launch_vec(const GatArgs& a, hipStream_t s) {
+    const int pieces = a.F / Elems<BF>::E;            // at most 64
+    if (pieces <= 16) launch_rows<BF, 16>(a, s);
+    else if (pieces <= 32) launch_rows<BF, 32>(a, s);
+    else launch_rows<BF, 64>(a, s);
 }
 
 // any alignment, widths up to 64 * NE: lane l owns elements l, l + 64, ...; one entry at a time
@@ -195,8 +305,8 @@ extern "C" gas_status gas_gat_aggregate(const int32_t* rowptr, const int32_t* co
     const bool vec = F % e == 0 && F <= 64 * e && ldp % e == 0 && ldz % e == 0 && aligned16(P) && aligned16(Z) &&
                      aligned16(a_dst) && aligned16(a_src);
     if (vec) {
-        if (dt == GAS_BF16) hipLaunchKernelGGL(gat_rows_kernel<true>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
-        else hipLaunchKernelGGL(gat_rows_kernel<false>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
+        if (dt == GAS_BF16) launch_vec<true>(a, s);
+        else launch_vec<false>(a, s);
         GAS_CHECK_HIP(hipGetLastError());
         return GAS_OK;
     }

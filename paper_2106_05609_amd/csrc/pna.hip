@@ -16,11 +16,161 @@ struct PnaArgs {
     float inv_delta;
 };
 
-// One wavefront per row of the batch subgraph; lane l owns the 16-byte piece l (+64, +128, ...) of the feature
-// row.  Neighbour indices are read 64 at a time and broadcast; gathers are issued sixteen at a time and folded in
-// index order, so the result does not depend on timing.
-template <bool BF>
+// Rows of at most 64 pieces of 16 bytes, G = 16, 32 or 64 lanes per row (at least the number of pieces).  A
+// wavefront's S = 64 / G teams of G lanes each hold the whole row and take the entries in turn (team t the entries
+// t, t + S, ... of every block of 64), 16 or 32 gathers in flight per wavefront step; the teams' sums, minima and
+// maxima are folded pair by pair afterwards.  A row of more than kLongRow entries is shared by the kLongWaves
+// wavefronts of a workgroup in the same way, block of 64 entries by block, and their results are folded in
+// wavefront order.  Which lane adds which entry depends on the row's length and the width alone, so the order of
+// every sum is fixed.
+constexpr int kLongRow = 2048;
+constexpr int kLongWaves = 8;
+constexpr int kLongBlocks = 2048;                     // workgroups of the long-row kernel
+
+template <bool BF, int G>
+__device__ __forceinline__ void pna_gather(const PnaArgs& a, int b, int e, int first, int stride,
+                                           float (&sum)[Elems<BF>::E], float (&mn)[Elems<BF>::E], float (&mx)[Elems<BF>::E]) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, S = 64 / G, U = S == 1 ? 16 : 32 / S;
+    const int lane = threadIdx.x & 63, team = lane / G, tl = lane % G;
+    const bool on = tl * E < a.F;
+#pragma unroll
+    for (int i = 0; i < E; ++i) { sum[i] = 0.f; mn[i] = INFINITY; mx[i] = -INFINITY; }
+    for (int k0 = b + 64 * first; k0 < e; k0 += 64 * stride) {
+        const int cnt = min(64, e - k0);
+        const int mine = lane < cnt ? a.col[k0 + lane] : 0;
+        for (int j0 = 0; j0 < cnt; j0 += U * S) {
+            u32x4 r[U];
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                const int kk = j0 + j * S + team;
+                int c;
+                if constexpr (S == 1) c = __builtin_amdgcn_readlane(mine, kk & 63);
+                else c = __shfl(mine, kk & 63);
+                r[j] = u32x4{0u, 0u, 0u, 0u};
+                if (on && kk < cnt)
+                    r[j] = *reinterpret_cast<const u32x4*>(a.X + ((int64_t)c * a.ldx + (int64_t)tl * E) * EB);
+            }
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                if (j0 + j * S + team < cnt) {
+                    float x[E];
+                    unpack<BF>(r[j], x);
+#pragma unroll
+                    for (int i = 0; i < E; ++i) {
+                        sum[i] += x[i];
+                        mn[i] = fminf(mn[i], x[i]);
+                        mx[i] = fmaxf(mx[i], x[i]);
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int o = G; o < 64; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            sum[i] += __shfl_xor(sum[i], o);
+            mn[i] = fminf(mn[i], __shfl_xor(mn[i], o));
+            mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], o));
+        }
+    }
+}
+
+// The nine output blocks of row v from its folded sums; every team of the wavefront holds them, and team t stores
+// the blocks of the aggregators j with j % S == t.
+template <bool BF, int G>
+__device__ __forceinline__ void pna_finish(const PnaArgs& a, int64_t v, int n_entries, const float (&sum)[Elems<BF>::E],
+                                           const float (&mn)[Elems<BF>::E], const float (&mx)[Elems<BF>::E]) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, S = 64 / G;
+    const int lane = threadIdx.x & 63, team = lane / G, tl = lane % G;
+    if (tl * E >= a.F) return;
+    const bool any = n_entries > 0;
+    const float d = (float)n_entries;
+    const float s = logf(d + 1.f) * a.inv_delta;
+    float q[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) q[i] = 0.f;
+    if (a.add && any) unpack<BF>(*reinterpret_cast<const u32x4*>(a.add + (v * a.ldadd + (int64_t)tl * E) * EB), q);
+    float agg[3][E];
+    const float inv_d = any ? 1.f / d : 0.f;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+        agg[0][i] = any ? sum[i] * inv_d + q[i] : 0.f;
+        agg[1][i] = any ? mn[i] + q[i] : 0.f;
+        agg[2][i] = any ? mx[i] + q[i] : 0.f;
+    }
+    const float inv_s = any ? 1.f / s : 0.f;
+    char* o = a.out + (v * a.ldout + (int64_t)tl * E) * EB;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        if (j % S != team) continue;
+        float t1[E], t2[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) { t1[i] = s * agg[j][i]; t2[i] = agg[j][i] * inv_s; }
+        __builtin_nontemporal_store(pack<BF>(agg[j]), reinterpret_cast<u32x4*>(o + (int64_t)j * a.F * EB));
+        __builtin_nontemporal_store(pack<BF>(t1), reinterpret_cast<u32x4*>(o + (int64_t)(3 + j) * a.F * EB));
+        __builtin_nontemporal_store(pack<BF>(t2), reinterpret_cast<u32x4*>(o + (int64_t)(6 + j) * a.F * EB));
+    }
+}
+
+// one wavefront per row; long rows are left to pna_long_rows_kernel
+template <bool BF, int G>
 __global__ __launch_bounds__(64) void pna_rows_kernel(PnaArgs a) {
+    constexpr int E = Elems<BF>::E;
+    const int64_t v = blockIdx.x;
+    const int b = a.rowptr[v], e = a.rowptr[v + 1];
+    if (e - b > kLongRow) return;
+    float sum[E], mn[E], mx[E];
+    pna_gather<BF, G>(a, b, e, 0, 1, sum, mn, mx);
+    pna_finish<BF, G>(a, v, e - b, sum, mn, mx);
+}
+
+// Workgroup w looks at the rows w, w + gridDim.x, ... (512 of them at a time), and every row of more than kLongRow
+// entries among them is gathered by all its wavefronts together.
+template <bool BF, int G>
+__global__ __launch_bounds__(64 * kLongWaves) void pna_long_rows_kernel(PnaArgs a) {
+    constexpr int E = Elems<BF>::E, T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    __shared__ float red[kLongWaves][3][E][64];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t r0 = blockIdx.x; r0 < a.n_rows; r0 += (int64_t)T * gridDim.x) {
+        if (threadIdx.x == 0) n_queued = 0;
+        __syncthreads();
+        const int64_t r = r0 + (int64_t)threadIdx.x * gridDim.x;
+        if (r < a.n_rows && a.rowptr[r + 1] - a.rowptr[r] > kLongRow) queue[atomicAdd(&n_queued, 1)] = (int)r;
+        __syncthreads();
+        const int nq = n_queued;
+        for (int q = 0; q < nq; ++q) {
+            const int64_t v = queue[q];
+            const int b = a.rowptr[v], e = a.rowptr[v + 1];
+            float sum[E], mn[E], mx[E];
+            pna_gather<BF, G>(a, b, e, w, kLongWaves, sum, mn, mx);
+            if (w > 0) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) { red[w][0][i][lane] = sum[i]; red[w][1][i][lane] = mn[i]; red[w][2][i][lane] = mx[i]; }
+            }
+            __syncthreads();
+            if (w == 0) {
+                for (int o = 1; o < kLongWaves; ++o) {
+#pragma unroll
+                    for (int i = 0; i < E; ++i) {
+                        sum[i] += red[o][0][i][lane];
+                        mn[i] = fminf(mn[i], red[o][1][i][lane]);
+                        mx[i] = fmaxf(mx[i], red[o][2][i][lane]);
+                    }
+                }
+                pna_finish<BF, G>(a, v, e - b, sum, mn, mx);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// rows of more than 64 pieces: one wavefront per row; lane l owns the pieces l, l + 64, ... and the row's entries
+// are walked once per 64 pieces
+template <bool BF>
+__global__ __launch_bounds__(64) void pna_wide_rows_kernel(PnaArgs a) {
     constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4;
     constexpr int U = 16;                             // gathers in flight per lane
     const int64_t v = blockIdx.x;
@@ -92,6 +242,22 @@ __global__ __launch_bounds__(64) void pna_rows_kernel(PnaArgs a) {
     }
 }
 
+template <bool BF, int G>
+void launch_rows(const PnaArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((pna_rows_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
+    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    hipLaunchKernelGGL((pna_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
+}
+
+template <bool BF>
+void launch_vec(const PnaArgs& a, hipStream_t s) {
+    const int pieces = a.F / Elems<BF>::E;
+    if (pieces <= 16) launch_rows<BF, 16>(a, s);
+    else if (pieces <= 32) launch_rows<BF, 32>(a, s);
+    else if (pieces <= 64) launch_rows<BF, 64>(a, s);
+    else hipLaunchKernelGGL(pna_wide_rows_kernel<BF>, dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
+}
+
 // any width and alignment: one thread per (row, feature)
 template <bool BF>
 __global__ __launch_bounds__(256) void pna_generic_kernel(PnaArgs a) {
@@ -151,8 +317,8 @@ extern "C" gas_status gas_pna_aggregate(const int32_t* rowptr, const int32_t* co
     const bool vec = F % e == 0 && ldx % e == 0 && ldout % e == 0 && (!add || ldadd % e == 0) && aligned16(X) &&
                      aligned16(out) && (!add || aligned16(add));
     if (vec) {
-        if (dt == GAS_BF16) hipLaunchKernelGGL(pna_rows_kernel<true>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
-        else hipLaunchKernelGGL(pna_rows_kernel<false>, dim3((unsigned)n_rows), dim3(64), 0, s, a);
+        if (dt == GAS_BF16) launch_vec<true>(a, s);
+        else launch_vec<false>(a, s);
     } else {
         const int64_t blocks = (n_rows * F + 255) / 256;
         GAS_REQUIRE(blocks <= 0x7FFFFFFFLL, "gas_pna_aggregate: problem too large for the element-wise path");

@@ -40,6 +40,45 @@ __device__ __forceinline__ void wave_sum8(float (&s)[8]) {
                                                                   32 * ((j >> 2) & 1) + 16 * ((j >> 1) & 1) + 8 * (j & 1)));
 }
 
+// Sum over the G lanes of a team: the wavefront's aligned groups of G lanes, G a power of two.
+template <int G>
+__device__ __forceinline__ float team_sum(float v) {
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// wave_sum8 inside every team of G = 16 or 32 lanes (G = 64: wave_sum8 itself): the same halving exchanges on the team's three upper lane
+// bits, the remaining steps on the lower ones, and every lane reads the eight totals back from its own team.
+template <int G>
+__device__ __forceinline__ void team_sum8(float (&s)[8]) {
+    static_assert(G == 16 || G == 32 || G == 64, "teams of 16, 32 or 64 lanes");
+    if constexpr (G == 64) {
+        wave_sum8(s);
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    float t4[4], t2[2];
+    const bool ha = lane & (G / 2), hb = lane & (G / 4), hc = lane & (G / 8);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float keep = ha ? s[j + 4] : s[j], send = ha ? s[j] : s[j + 4];
+        t4[j] = keep + __shfl_xor(send, G / 2);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float keep = hb ? t4[j + 2] : t4[j], send = hb ? t4[j] : t4[j + 2];
+        t2[j] = keep + __shfl_xor(send, G / 4);
+    }
+    float t = (hc ? t2[1] : t2[0]) + __shfl_xor(hc ? t2[0] : t2[1], G / 8);
+#pragma unroll
+    for (int o = G / 16; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    const int base = lane & ~(G - 1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        s[j] = __shfl(t, base + (G / 2) * ((j >> 2) & 1) + (G / 4) * ((j >> 1) & 1) + (G / 8) * (j & 1));
+}
+
 // elements in a 16-byte piece
 template <bool BF> struct Elems { static constexpr int E = BF ? 8 : 4; };
 

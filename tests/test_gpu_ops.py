@@ -508,7 +508,7 @@ def test_pna_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("name,F,ld_pad", [("powerlaw", 256, 0), ("sbm", 64, 8), ("powerlaw", 100, 0), ("sbm", 7, 0),
-                                           ("powerlaw", 520, 0), ("gin", 128, 0)])
+                                           ("powerlaw", 520, 0), ("gin", 128, 0), ("sbm", 512, 0), ("powerlaw", 32, 0)])
 def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
     """GAT's scores, softmax and weighted sum in one pass (operator appendix) against the oracle's three-step form."""
     cfg, g, sg = graphs_small[name]
@@ -533,6 +533,48 @@ def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
     assert not to_np(out[0]).any() and not torch.isnan(out.float()).any()
     with pytest.raises(gas.GasError):
         gas.gas_gat_aggregate(ptr, col, out, dev(a_dst), dev(a_src), out)
+
+
+def _pattern_with_long_rows(seed, nv):
+    """Rows around the length above which a workgroup shares a row (2,048 entries), beside short and empty ones."""
+    lengths = [0, 1, 3000, 2049, 2048, 5003, 70, 2047, 0, 4096, 9, 2113]
+    gen = np.random.default_rng(seed)
+    ptr = np.zeros(len(lengths) + 1, dtype=np.int32)
+    ptr[1:] = np.cumsum(lengths)
+    col = gen.integers(0, nv, size=int(ptr[-1]), dtype=np.int32)
+    return ptr, col
+
+
+@pytest.mark.parametrize("dtype,F", [(torch.float32, 256), (torch.bfloat16, 256), (torch.bfloat16, 64), (torch.float32, 128),
+                                     (torch.float32, 32), (torch.bfloat16, 512)])
+def test_pna_and_gat_aggregate_rows_shared_by_a_workgroup(gas, dtype, F):
+    """Rows above 2,048 entries are gathered by the eight wavefronts of a workgroup and merged in wavefront order:
+    same results as the oracle for every width class (16, 32 and 64 lanes per row), and the same bits twice."""
+    nv = 6000
+    ptr, col = _pattern_with_long_rows(41, nv)
+    nb = ptr.size - 1
+    x = rng.normal_matrix(13, 970, nv, F, dtype=dtype)
+    q = rng.normal_matrix(13, 971, nb, F, dtype=dtype)
+    d_ptr, d_col = dev(torch.from_numpy(ptr)), dev(torch.from_numpy(col))
+    out = torch.full((nb, 9 * F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_pna_aggregate(d_ptr, d_col, dev(x), out, 1.3, add=dev(q))
+    want = oops.pna_aggregate(ptr, col, to_np(x), 1.3, add=to_np(q))
+    got = to_np(out)
+    for j in range(9):
+        blk = slice(j * F, (j + 1) * F)
+        assert node_rel_err(got[:, blk], want[:, blk]) <= TOL[dtype], (j, node_rel_err(got[:, blk], want[:, blk]))
+    out2 = torch.full((nb, 9 * F), float("nan"), dtype=dtype, device="cuda")
+    gas.gas_pna_aggregate(d_ptr, d_col, dev(x), out2, 1.3)
+    assert np.array_equal(to_np(out2)[:, F:3 * F], oops.pna_aggregate(ptr, col, to_np(x), 1.3)[:, F:3 * F])   # min, max: exact
+    a_dst = rng.normal(13, 972, 0, F, dtype=dtype) * 0.3
+    a_src = rng.normal(13, 973, 0, F, dtype=dtype) * 0.3
+    z = [torch.full((nb, F), float("nan"), dtype=dtype, device="cuda") for _ in range(2)]
+    for t in z:
+        gas.gas_gat_aggregate(d_ptr, d_col, dev(x), dev(a_dst), dev(a_src), t)
+    want = oops.gat_aggregate(ptr, col, to_np(x), to_np(a_dst), to_np(a_src))
+    assert node_rel_err(to_np(z[0]), want) <= TOL[dtype], node_rel_err(to_np(z[0]), want)
+    bits = torch.int32 if dtype == torch.float32 else torch.int16
+    assert torch.equal(z[0].view(bits), z[1].view(bits))
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])

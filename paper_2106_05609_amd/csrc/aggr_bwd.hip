@@ -127,32 +127,25 @@ struct PnaFastArgs {
     float inv_delta;
 };
 
-// G: lanes that hold a row (at least its number of pieces).  With G < 64 the wavefront's S = 64 / G teams each hold
-// the row and take the entries in turn while gathering (team t the entries t, t + S, ...); their winners are
-// merged before the rest, which the lanes of team 0 do as lanes 0 .. G - 1 of the wavefront.
-template <bool BF, int G>
-__global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
+// Row v = [b, e), b < e.  G: lanes that hold a row (at least its number of pieces).  With G < 64 the wavefront's
+// S = 64 / G teams each hold the row and take the entries in turn while gathering (team t the entries t, t + S, ...);
+// their winners are merged before the rest, which the lanes of team 0 do as lanes 0 .. G - 1 of the wavefront.
+// W = 1: one wavefront has the whole row.  W = kLongWaves: the wavefronts of a workgroup gather the row's blocks of
+// 64 entries in turn (wavefront w the blocks w, w + W, ...), their winners are merged through LDS (redv, redk:
+// W x E x 64 values each), and wavefront 0 does the rest while the others wait at its barriers.
+template <bool BF, int G, int W>
+__device__ __forceinline__ void pna_bwd_row(const PnaFastArgs& a, int64_t v, int b, int e, uint32_t (*cnt)[kPnaChunk],
+                                            float* redv, int* redk) {
     constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, S = 64 / G, U = 16 / (S > 2 ? 2 : 1);
-    __shared__ uint32_t cnt[2][kPnaChunk];
-    const int64_t v = blockIdx.x;
-    const int lane = threadIdx.x, team = lane / G, tl = lane % G;
-    const int b = a.rowptr[v], e = a.rowptr[v + 1];
+    const int lane = threadIdx.x & 63, team = lane / G, tl = lane % G;
+    const int w = W == 1 ? 0 : (int)(threadIdx.x >> 6);
     const int d = e - b;
-    const bool on = lane * E < a.F;
-    char* c0row = a.C0 + (v * a.F + (int64_t)lane * E) * EB;
-    if (d == 0) {
-        if (on) {
-            *reinterpret_cast<u32x4*>(c0row) = u32x4{0u, 0u, 0u, 0u};
-            if (a.Gadd) *reinterpret_cast<u32x4*>(a.Gadd + (v * a.ldga + (int64_t)lane * E) * EB) = u32x4{0u, 0u, 0u, 0u};
-        }
-        return;
-    }
     float mn[E], mx[E];
     int kmn[E], kmx[E];
 #pragma unroll
     for (int i = 0; i < E; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; kmn[i] = b; kmx[i] = b; }
     const bool gon = tl * E < a.F;
-    for (int k0 = b; k0 < e; k0 += 64) {
+    for (int k0 = b + 64 * w; k0 < e; k0 += 64 * W) {
         const int n64 = min(64, e - k0);
         const int mine = lane < n64 ? a.col[k0 + lane] : 0;
         for (int j0 = 0; j0 < n64; j0 += U * S) {
@@ -194,6 +187,42 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
             if (xx > mx[i] || (xx == mx[i] && kx < kmx[i])) { mx[i] = xx; kmx[i] = kx; }
         }
     }
+    if constexpr (W > 1) {                            // the wavefronts' winners, by the same rule: minima, then maxima
+        if (w > 0) {
+#pragma unroll
+            for (int i = 0; i < E; ++i) { redv[(w * E + i) * 64 + lane] = mn[i]; redk[(w * E + i) * 64 + lane] = kmn[i]; }
+        }
+        __syncthreads();
+        if (w == 0) {
+            for (int o = 1; o < W; ++o) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    const float xn = redv[(o * E + i) * 64 + lane];
+                    const int kn = redk[(o * E + i) * 64 + lane];
+                    if (xn < mn[i] || (xn == mn[i] && kn < kmn[i])) { mn[i] = xn; kmn[i] = kn; }
+                }
+            }
+        }
+        __syncthreads();
+        if (w > 0) {
+#pragma unroll
+            for (int i = 0; i < E; ++i) { redv[(w * E + i) * 64 + lane] = mx[i]; redk[(w * E + i) * 64 + lane] = kmx[i]; }
+        }
+        __syncthreads();
+        if (w == 0) {
+            for (int o = 1; o < W; ++o) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    const float xx = redv[(o * E + i) * 64 + lane];
+                    const int kx = redk[(o * E + i) * 64 + lane];
+                    if (xx > mx[i] || (xx == mx[i] && kx < kmx[i])) { mx[i] = xx; kmx[i] = kx; }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const bool active = w == 0;                       // from here on the other wavefronts only keep the barriers
+    const bool on = active && lane * E < a.F;
     // the three block gradients folded with their scalers
     const float df = (float)d;
     const float s = logf(df + 1.f) * a.inv_delta;
@@ -212,7 +241,7 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
         float t[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) t[i] = cc[0][i] / df;
-        *reinterpret_cast<u32x4*>(c0row) = pack<BF>(t);
+        *reinterpret_cast<u32x4*>(a.C0 + (v * a.F + (int64_t)lane * E) * EB) = pack<BF>(t);
         if (a.Gadd) {
 #pragma unroll
             for (int i = 0; i < E; ++i) t[i] = cc[0][i] + cc[1][i] + cc[2][i];
@@ -230,7 +259,8 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
     uint32_t base0 = 0, base1 = 0;
     for (int c0 = 0; c0 < d; c0 += kPnaChunk) {
         const int n = min(kPnaChunk, d - c0);
-        for (int t = lane; t < 2 * kPnaChunk; t += 64) (&cnt[0][0])[t] = 0u;
+        if (active)
+            for (int t = lane; t < 2 * kPnaChunk; t += 64) (&cnt[0][0])[t] = 0u;
         __syncthreads();
         int r0[E], r1[E];
 #pragma unroll
@@ -240,32 +270,34 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
             r1[i] = (on && p1 >= 0 && p1 < n) ? (int)atomicAdd(&cnt[1][p1], 1u) : -1;
         }
         __syncthreads();
-        uint32_t c[2][8], tot0 = 0, tot1 = 0;
+        if (active) {
+            uint32_t c[2][8], tot0 = 0, tot1 = 0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            c[0][t] = cnt[0][lane * 8 + t];
-            c[1][t] = cnt[1][lane * 8 + t];
-            tot0 += c[0][t];
-            tot1 += c[1][t];
-        }
-        uint32_t inc0 = tot0, inc1 = tot1;
+            for (int t = 0; t < 8; ++t) {
+                c[0][t] = cnt[0][lane * 8 + t];
+                c[1][t] = cnt[1][lane * 8 + t];
+                tot0 += c[0][t];
+                tot1 += c[1][t];
+            }
+            uint32_t inc0 = tot0, inc1 = tot1;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t t0 = __shfl_up(inc0, o), t1 = __shfl_up(inc1, o);
-            if (lane >= o) { inc0 += t0; inc1 += t1; }
-        }
-        uint32_t ex0 = base0 + inc0 - tot0, ex1 = base1 + inc1 - tot1;
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t t0 = __shfl_up(inc0, o), t1 = __shfl_up(inc1, o);
+                if (lane >= o) { inc0 += t0; inc1 += t1; }
+            }
+            uint32_t ex0 = base0 + inc0 - tot0, ex1 = base1 + inc1 - tot1;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int slot = lane * 8 + t;
-            if (slot < n) a.ent[(int64_t)b + c0 + slot] = uint2{ex0 | (c[0][t] << 16), ex1 | (c[1][t] << 16)};
-            cnt[0][slot] = ex0;
-            cnt[1][slot] = ex1;
-            ex0 += c[0][t];
-            ex1 += c[1][t];
+            for (int t = 0; t < 8; ++t) {
+                const int slot = lane * 8 + t;
+                if (slot < n) a.ent[(int64_t)b + c0 + slot] = uint2{ex0 | (c[0][t] << 16), ex1 | (c[1][t] << 16)};
+                cnt[0][slot] = ex0;
+                cnt[1][slot] = ex1;
+                ex0 += c[0][t];
+                ex1 += c[1][t];
+            }
+            base0 += __shfl(inc0, 63);
+            base1 += __shfl(inc1, 63);
         }
-        base0 += __shfl(inc0, 63);
-        base1 += __shfl(inc1, 63);
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < E; ++i) {
@@ -282,6 +314,49 @@ __global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
         }
         __syncthreads();
     }
+}
+
+// one wavefront per row; long rows are left to pna_bwd_long_rows_kernel
+template <bool BF, int G>
+__global__ __launch_bounds__(64) void pna_bwd_rows_vec_kernel(PnaFastArgs a) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4;
+    __shared__ uint32_t cnt[2][kPnaChunk];
+    const int64_t v = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int b = a.rowptr[v], e = a.rowptr[v + 1];
+    if (e == b) {
+        if (lane * E < a.F) {
+            *reinterpret_cast<u32x4*>(a.C0 + (v * a.F + (int64_t)lane * E) * EB) = u32x4{0u, 0u, 0u, 0u};
+            if (a.Gadd) *reinterpret_cast<u32x4*>(a.Gadd + (v * a.ldga + (int64_t)lane * E) * EB) = u32x4{0u, 0u, 0u, 0u};
+        }
+        return;
+    }
+    if (e - b > kLongRow) return;
+    pna_bwd_row<BF, G, 1>(a, v, b, e, cnt, nullptr, nullptr);
+}
+
+template <bool BF, int G>
+__global__ __launch_bounds__(64 * kLongWaves) void pna_bwd_long_rows_kernel(PnaFastArgs a) {
+    constexpr int E = Elems<BF>::E, T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    __shared__ uint32_t cnt[2][kPnaChunk];
+    __shared__ float redv[kLongWaves * E * 64];
+    __shared__ int redk[kLongWaves * E * 64];
+    for (int64_t r0 = blockIdx.x; r0 < a.n_rows; r0 += (int64_t)T * gridDim.x) {
+        const int nq = queue_long_rows(a.rowptr, a.n_rows, r0, queue, &n_queued);
+        for (int q = 0; q < nq; ++q) {
+            const int64_t v = queue[q];
+            pna_bwd_row<BF, G, kLongWaves>(a, v, a.rowptr[v], a.rowptr[v + 1], cnt, redv, redk);   // ends with a barrier
+        }
+    }
+}
+
+template <bool BF, int G>
+void launch_pna_bwd_rows(const PnaFastArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
+    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    hipLaunchKernelGGL((pna_bwd_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 
 // The items of the entries [b, e) of one column, added to its sums `acc` by the wavefront: the records of 64
@@ -497,20 +572,19 @@ __global__ __launch_bounds__(64) void gat_bwd_cols_kernel(GatBwdArgs a) {
 }
 
 // ---- fast path: rows of at most 64 pieces of 16 bytes
-// Row v, as gat_bwd_rows_kernel, with the gathers of the forward kernel: eight neighbour rows in flight per lane,
-// both dot products of an entry (with a_src for the score, with GZ[v] for the gradient of its attention weight)
-// reduced over the lanes eight entries at a time.  A row of at most G < 64 pieces is held by each of the
-// wavefront's S = 64 / G teams of G lanes, which take the entries in turn (team t the entries t, t + S, ...).
-template <bool BF, int G>
-__global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
+// Row v = [b, e), b < e, as gat_bwd_rows_kernel, with the gathers of the forward kernel: eight neighbour rows in
+// flight per lane, both dot products of an entry (with a_src for the score, with GZ[v] for the gradient of its
+// attention weight) reduced over the lanes eight entries at a time.  A row of at most G < 64 pieces is held by each
+// of the wavefront's S = 64 / G teams of G lanes, which take the entries in turn (team t the entries t, t + S, ...).
+// W = 1: one wavefront has the whole row.  W = kLongWaves: the wavefronts of a workgroup take the row's blocks of 64
+// entries in turn (wavefront w the blocks w, w + W, ...) and meet for the row's maximum and its three sums, which
+// are added in wavefront order; `red` is their W floats of LDS.  Either way entry k is stored and read again by
+// one and the same lane, so no lane ever reads another lane's store.
+template <bool BF, int G, int W>
+__device__ __forceinline__ void gat_bwd_row(const GatBwdArgs& a, int64_t v, int b, int e, float* red) {
     constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, U = 8, S = 64 / G;
-    const int64_t v = blockIdx.x;
-    const int lane = threadIdx.x, team = lane / G, tl = lane % G;
-    const int b = a.rowptr[v], e = a.rowptr[v + 1];
-    if (e == b) {
-        if (lane == 0) a.csum[v] = 0.f;
-        return;
-    }
+    const int lane = threadIdx.x & 63, team = lane / G, tl = lane % G;
+    const int first = W == 1 ? 0 : (int)(threadIdx.x >> 6);
     const bool on = tl * E < a.F;
     auto piece = [&](const char* base, int64_t row_elems) {
         u32x4 t = {0u, 0u, 0u, 0u};
@@ -527,7 +601,7 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
     for (int i = 0; i < E; ++i) sv += ad[i] * x[i];
     sv = team_sum<G>(sv);
     float mx = -INFINITY;
-    for (int k0 = b; k0 < e; k0 += 64) {
+    for (int k0 = b + 64 * first; k0 < e; k0 += 64 * W) {
         const int cnt = min(64, e - k0);
         const int mine = lane < cnt ? a.col[k0 + lane] : 0;
         for (int j0 = 0; j0 < cnt; j0 += U * S) {
@@ -556,8 +630,7 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
             }
             team_sum8<G>(sw);
             team_sum8<G>(da);
-            // Entry j0 + i of the block is stored by lane j0 + i, the lane that reads it in the loops below, so no lane
-            // ever reads another lane's store; its two sums are with team i % S, in slot i / S.
+            // entry j0 + i of the block is stored by lane j0 + i; its two sums are with team i % S, in slot i / S
             const int mine_i = lane - j0;
             float my_t = 0.f, my_da = 0.f;
 #pragma unroll
@@ -576,20 +649,21 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
     }
 #pragma unroll
     for (int o = G; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    mx = across_waves<W, true>(mx, red);
     float den = 0.f;
-    for (int k = b + lane; k < e; k += 64) {
+    for (int k = b + 64 * first + lane; k < e; k += 64 * W) {
         const float t = a.alpha[k];
         den += expf((t > 0.f ? t : a.slope * t) - mx);
     }
-    den = wave_sum(den);
+    den = across_waves<W, false>(wave_sum(den), red);
     float mean_da = 0.f;
-    for (int k = b + lane; k < e; k += 64) {
+    for (int k = b + 64 * first + lane; k < e; k += 64 * W) {
         const float t = a.alpha[k];
         mean_da += expf((t > 0.f ? t : a.slope * t) - mx) / den * a.dt[k];
     }
-    mean_da = wave_sum(mean_da);
+    mean_da = across_waves<W, false>(wave_sum(mean_da), red);
     float sum_dt = 0.f;
-    for (int k = b + lane; k < e; k += 64) {
+    for (int k = b + 64 * first + lane; k < e; k += 64 * W) {
         const float t = a.alpha[k];
         const float al = expf((t > 0.f ? t : a.slope * t) - mx) / den;
         const float dtk = al * (a.dt[k] - mean_da) * (t > 0.f ? 1.f : a.slope);
@@ -597,8 +671,43 @@ __global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
         a.dt[k] = dtk;
         sum_dt += dtk;
     }
-    sum_dt = wave_sum(sum_dt);
-    if (lane == 0) a.csum[v] = sum_dt;
+    sum_dt = across_waves<W, false>(wave_sum(sum_dt), red);
+    if (threadIdx.x == 0) a.csum[v] = sum_dt;
+}
+
+// one wavefront per row; long rows are left to gat_bwd_long_rows_kernel
+template <bool BF, int G>
+__global__ __launch_bounds__(64) void gat_bwd_rows_vec_kernel(GatBwdArgs a) {
+    const int64_t v = blockIdx.x;
+    const int b = a.rowptr[v], e = a.rowptr[v + 1];
+    if (e == b) {
+        if (threadIdx.x == 0) a.csum[v] = 0.f;
+        return;
+    }
+    if (e - b > kLongRow) return;
+    gat_bwd_row<BF, G, 1>(a, v, b, e, nullptr);
+}
+
+template <bool BF, int G>
+__global__ __launch_bounds__(64 * kLongWaves) void gat_bwd_long_rows_kernel(GatBwdArgs a) {
+    constexpr int T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    __shared__ float red[kLongWaves];
+    for (int64_t r0 = blockIdx.x; r0 < a.n_rows; r0 += (int64_t)T * gridDim.x) {
+        const int nq = queue_long_rows(a.rowptr, a.n_rows, r0, queue, &n_queued);
+        for (int q = 0; q < nq; ++q) {
+            const int64_t v = queue[q];
+            gat_bwd_row<BF, G, kLongWaves>(a, v, a.rowptr[v], a.rowptr[v + 1], red);   // ends with a barrier
+        }
+    }
+}
+
+template <bool BF, int G>
+void launch_gat_bwd_rows(const GatBwdArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
+    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    hipLaunchKernelGGL((gat_bwd_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 
 // The attention weights and the score gradients in the order of the CSC copy: the coefficients of the backward
@@ -824,16 +933,15 @@ gas_status gas_pna_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
         a.items_v = reinterpret_cast<float*>(w); w += align_up(n_rows * 2 * (int64_t)F * 4);
         a.ent = reinterpret_cast<uint2*>(w);
         a.F = F; a.inv_delta = 1.f / delta;
-        const dim3 grid((unsigned)n_rows), block(64);
         const int pieces = F / (bf ? 8 : 4);
         if (bf) {
-            if (pieces <= 16) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 16>), grid, block, 0, s, a);
-            else if (pieces <= 32) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 32>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<true, 64>), grid, block, 0, s, a);
+            if (pieces <= 16) launch_pna_bwd_rows<true, 16>(a, s);
+            else if (pieces <= 32) launch_pna_bwd_rows<true, 32>(a, s);
+            else launch_pna_bwd_rows<true, 64>(a, s);
         } else {
-            if (pieces <= 16) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 16>), grid, block, 0, s, a);
-            else if (pieces <= 32) hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 32>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<false, 64>), grid, block, 0, s, a);
+            if (pieces <= 16) launch_pna_bwd_rows<false, 16>(a, s);
+            else if (pieces <= 32) launch_pna_bwd_rows<false, 32>(a, s);
+            else launch_pna_bwd_rows<false, 64>(a, s);
         }
         GAS_CHECK_HIP(hipGetLastError());
         // the mean's share: GX[u] = sum over the entries (v, u) of C0[v]
@@ -914,16 +1022,15 @@ gas_status gas_gat_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
     const bool vec = vec_rows(dt, F, {P, GZ, GP, a_dst, a_src}, {ldp, ldgz, ldgp});
     if (plan_t && n_out > 0 && vec) {
         if (n_rows > 0) {
-            const dim3 grid((unsigned)n_rows), block(64);
             const int pieces = F / (bf ? 8 : 4);
             if (bf) {
-                if (pieces <= 16) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 16>), grid, block, 0, s, a);
-                else if (pieces <= 32) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 32>), grid, block, 0, s, a);
-                else hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<true, 64>), grid, block, 0, s, a);
+                if (pieces <= 16) launch_gat_bwd_rows<true, 16>(a, s);
+                else if (pieces <= 32) launch_gat_bwd_rows<true, 32>(a, s);
+                else launch_gat_bwd_rows<true, 64>(a, s);
             } else {
-                if (pieces <= 16) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 16>), grid, block, 0, s, a);
-                else if (pieces <= 32) hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 32>), grid, block, 0, s, a);
-                else hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<false, 64>), grid, block, 0, s, a);
+                if (pieces <= 16) launch_gat_bwd_rows<false, 16>(a, s);
+                else if (pieces <= 32) launch_gat_bwd_rows<false, 32>(a, s);
+                else launch_gat_bwd_rows<false, 64>(a, s);
             }
         }
         GAS_REQUIRE(plan_t->nnz <= nnz, "gas_gat_aggregate_bwd: the plan has %lld entries, the pattern %lld",

@@ -23,9 +23,6 @@ struct PnaArgs {
 // wavefronts of a workgroup in the same way, block of 64 entries by block, and their results are folded in
 // wavefront order.  Which lane adds which entry depends on the row's length and the width alone, so the order of
 // every sum is fixed.
-constexpr int kLongRow = 2048;
-constexpr int kLongWaves = 8;
-constexpr int kLongBlocks = 2048;                     // workgroups of the long-row kernel
 
 template <bool BF, int G>
 __device__ __forceinline__ void pna_gather(const PnaArgs& a, int b, int e, int first, int stride,
@@ -135,12 +132,7 @@ __global__ __launch_bounds__(64 * kLongWaves) void pna_long_rows_kernel(PnaArgs 
     __shared__ float red[kLongWaves][3][E][64];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int64_t r0 = blockIdx.x; r0 < a.n_rows; r0 += (int64_t)T * gridDim.x) {
-        if (threadIdx.x == 0) n_queued = 0;
-        __syncthreads();
-        const int64_t r = r0 + (int64_t)threadIdx.x * gridDim.x;
-        if (r < a.n_rows && a.rowptr[r + 1] - a.rowptr[r] > kLongRow) queue[atomicAdd(&n_queued, 1)] = (int)r;
-        __syncthreads();
-        const int nq = n_queued;
+        const int nq = queue_long_rows(a.rowptr, a.n_rows, r0, queue, &n_queued);
         for (int q = 0; q < nq; ++q) {
             const int64_t v = queue[q];
             const int b = a.rowptr[v], e = a.rowptr[v + 1];

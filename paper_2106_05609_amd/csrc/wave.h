@@ -79,6 +79,40 @@ __device__ __forceinline__ void team_sum8(float (&s)[8]) {
         s[j] = __shfl(t, base + (G / 2) * ((j >> 2) & 1) + (G / 4) * ((j >> 1) & 1) + (G / 8) * (j & 1));
 }
 
+// ---- rows too long for one wavefront
+// The one-wavefront-per-row kernels leave a row of more than kLongRow entries to a second launch of kLongBlocks
+// workgroups of kLongWaves wavefronts, which take the row's blocks of 64 entries in turn: a hub row of 17,000
+// entries is thousands of dependent steps for one wavefront, which the whole launch would wait for.
+constexpr int kLongRow = 2048;
+constexpr int kLongWaves = 8;
+constexpr int kLongBlocks = 2048;
+
+// Workgroup w of such a launch looks at the rows w, w + gridDim.x, ..., blockDim.x of them per call (r0 = w, then
+// + blockDim.x * gridDim.x): the long ones among them are left in queue[0 .. return value).  Called by every thread
+// of the workgroup; every long row the caller then works on ends with a barrier.
+__device__ __forceinline__ int queue_long_rows(const int32_t* rowptr, int64_t n_rows, int64_t r0, int* queue, int* n_queued) {
+    if (threadIdx.x == 0) *n_queued = 0;
+    __syncthreads();
+    const int64_t r = r0 + (int64_t)threadIdx.x * gridDim.x;
+    if (r < n_rows && rowptr[r + 1] - rowptr[r] > kLongRow) queue[atomicAdd(n_queued, 1)] = (int)r;
+    __syncthreads();
+    return *n_queued;
+}
+
+// A value that is the same in all lanes of a wavefront, summed (or its maximum taken) over the W wavefronts of
+// the workgroup in wavefront order; every thread of the workgroup calls it.
+template <int W, bool MAX>
+__device__ __forceinline__ float across_waves(float x, float* red) {
+    if constexpr (W == 1) return x;
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int o = 1; o < W; ++o) r = MAX ? fmaxf(r, red[o]) : r + red[o];
+    __syncthreads();
+    return r;
+}
+
 // elements in a 16-byte piece
 template <bool BF> struct Elems { static constexpr int E = BF ? 8 : 4; };
 

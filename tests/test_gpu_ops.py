@@ -535,9 +535,11 @@ def test_gat_aggregate_parity(gas, graphs_small, dtype, name, F, ld_pad):
         gas.gas_gat_aggregate(ptr, col, out, dev(a_dst), dev(a_src), out)
 
 
-def _pattern_with_long_rows(seed, nv):
+def _pattern_with_long_rows(seed, nv, empty_rows=True):
     """Rows around the length above which a workgroup shares a row (2,048 entries), beside short and empty ones."""
     lengths = [0, 1, 3000, 2049, 2048, 5003, 70, 2047, 0, 4096, 9, 2113]
+    if not empty_rows:
+        lengths = [n for n in lengths if n > 0]
     gen = np.random.default_rng(seed)
     ptr = np.zeros(len(lengths) + 1, dtype=np.int32)
     ptr[1:] = np.cumsum(lengths)
@@ -575,6 +577,54 @@ def test_pna_and_gat_aggregate_rows_shared_by_a_workgroup(gas, dtype, F):
     assert node_rel_err(to_np(z[0]), want) <= TOL[dtype], node_rel_err(to_np(z[0]), want)
     bits = torch.int32 if dtype == torch.float32 else torch.int16
     assert torch.equal(z[0].view(bits), z[1].view(bits))
+
+
+@pytest.mark.parametrize("dtype,F", [(torch.float32, 256), (torch.bfloat16, 256), (torch.bfloat16, 64), (torch.float32, 128)])
+def test_pna_and_gat_backward_rows_shared_by_a_workgroup(gas, dtype, F):
+    """The row passes of the two backward aggregations on rows above 2,048 entries (gathered by the eight wavefronts
+    of a workgroup; winners, maxima and sums merged in wavefront order): against the oracle, and the same bits twice."""
+    nv = 6000
+    ptr, col = _pattern_with_long_rows(43, nv, empty_rows=False)
+    nb, nnz = ptr.size - 1, int(ptr[-1])
+    order = np.argsort(col, kind="stable")
+    rows = np.repeat(np.arange(nb, dtype=np.int32), np.diff(ptr))
+    colptr = np.zeros(nv + 1, dtype=np.int32)
+    colptr[1:] = np.cumsum(np.bincount(col, minlength=nv))
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+    d_ptr, d_col, d_colptr, d_row, d_pos = d(ptr), d(col), d(colptr), d(rows[order]), d(order.astype(np.int32))
+    plan_t = gas.gas_plan_create(d_colptr, nnz, F, n_rows=nv, ind=d_row)
+    bits = torch.int32 if dtype == torch.float32 else torch.int16
+    x = rng.normal_matrix(14, 980, nv, F, dtype=dtype)
+    gout = rng.normal_matrix(14, 981, nb, 9 * F, dtype=dtype)
+    want_x, want_add = oops.pna_aggregate_bwd(ptr, col, to_np(x), 1.3, to_np(gout), nv)
+    res = []
+    for _ in range(2):
+        gx = torch.full((nv, F), float("nan"), dtype=dtype, device="cuda")
+        gadd = torch.full((nb, F), float("nan"), dtype=dtype, device="cuda")
+        gas.gas_pna_aggregate_bwd(d_ptr, d_col, d_colptr, d_row, d_pos, x.to("cuda"), gout.to("cuda"), gx, 1.3, gadd=gadd,
+                                  plan_t=plan_t)
+        res.append(gx)
+    assert node_rel_err(to_np(res[0]), want_x) <= TOL[dtype], node_rel_err(to_np(res[0]), want_x)
+    assert node_rel_err(to_np(gadd), want_add) <= TOL[dtype]
+    assert torch.equal(res[0].view(bits), res[1].view(bits))
+    p = rng.normal_matrix(14, 982, nv, F, dtype=dtype) * 0.5
+    a_dst = rng.normal(14, 983, 0, F, dtype=dtype) * 0.3
+    a_src = rng.normal(14, 984, 0, F, dtype=dtype) * 0.3
+    gz = rng.normal_matrix(14, 985, nb, F, dtype=dtype)
+    want_p, want_d, want_s = oops.gat_aggregate_bwd(ptr, col, to_np(p), to_np(a_dst), to_np(a_src), to_np(gz), nv, 0.2)
+    terms = _gat_bwd_row_scale(ptr, col, to_np(p), to_np(a_dst), to_np(a_src), to_np(gz), nb, nv)
+    res = []
+    for _ in range(2):
+        gp = torch.full((nv, F), float("nan"), dtype=dtype, device="cuda")
+        gd = torch.full((F,), float("nan"), device="cuda")
+        gs = torch.full((F,), float("nan"), device="cuda")
+        gas.gas_gat_aggregate_bwd(d_ptr, d_col, d_colptr, d_row, d_pos, p.to("cuda"), a_dst.to("cuda"), a_src.to("cuda"),
+                                  gz.to("cuda"), gp, gd, gs, 0.2, plan_t=plan_t)
+        res.append(gp)
+    assert node_rel_err(to_np(res[0]), want_p, scale=terms) <= TOL[dtype], node_rel_err(to_np(res[0]), want_p, scale=terms)
+    scale = max(np.abs(want_d).max(), np.abs(want_s).max())
+    assert np.abs(to_np(gd) - want_d).max() <= TOL[dtype] * scale and np.abs(to_np(gs) - want_s).max() <= TOL[dtype] * scale
+    assert torch.equal(res[0].view(bits), res[1].view(bits))
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -635,6 +685,22 @@ def test_pna_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
             assert torch.equal(bits(gx2), bits(gx))                                            # fixed order
 
 
+def _gat_bwd_row_scale(rp, cl, p, a_dst, a_src, gz, nb, nv):
+    """Per-row scale of the rounding errors of GAT's backward pass (see test_gat_aggregate_backward_parity): for
+    output row u, the sum over its entries of alpha_k ||GZ[v]|| ||P[u]|| max|a_src|, plus for an in-batch row the sum
+    over its own row's entries of alpha_k ||GZ[v]|| ||P[col k]|| max|a_dst|."""
+    rows = np.repeat(np.arange(nb), np.diff(rp))
+    p64 = oops.to_f64(p)
+    t = (p64[:nb] @ oops.to_f64(a_dst))[rows] + (p64 @ oops.to_f64(a_src))[cl]
+    ex = np.exp(np.where(t > 0, t, 0.2 * t) - np.maximum.reduceat(np.where(t > 0, t, 0.2 * t), rp[:-1])[rows])
+    alpha = ex / np.add.reduceat(ex, rp[:-1])[rows]
+    assert np.diff(rp).min() > 0                       # no empty rows (reduceat)
+    weight = alpha * np.linalg.norm(oops.to_f64(gz), axis=1)[rows] * np.linalg.norm(p64, axis=1)[cl]
+    terms = np.bincount(cl, weights=weight, minlength=nv) * np.abs(oops.to_f64(a_src)).max()
+    terms[:nb] += np.add.reduceat(weight, rp[:-1]) * np.abs(oops.to_f64(a_dst)).max()
+    return terms
+
+
 @pytest.mark.parametrize("name,dtype,F", [("sbm", torch.float32, 8), ("powerlaw", torch.float32, 100), ("sbm", torch.bfloat16, 128),
                                           ("powerlaw", torch.float32, 7), ("sbm", torch.float32, 520),
                                           ("powerlaw", torch.float32, 256), ("powerlaw", torch.bfloat16, 256),
@@ -657,16 +723,7 @@ def test_gat_aggregate_backward_parity(gas, graphs_small, name, dtype, F):
     # measured against max(its own largest entry, sum over its entries of alpha_k ||GZ[v]|| ||P[u]|| max|a_src|).
     # An in-batch row v also receives (sum_k dt_k) a_dst, a sum over its own row's entries that cancels (it is
     # exactly zero for slope 1): its error is relative to sum_k alpha_k ||GZ[v]|| ||P[col k]|| max|a_dst|.
-    rp, cl = to_np(sg.rowptr), to_np(sg.col)
-    rows = np.repeat(np.arange(nb), np.diff(rp))
-    p64 = oops.to_f64(to_np(p))
-    t = (p64[:nb] @ oops.to_f64(to_np(a_dst)))[rows] + (p64 @ oops.to_f64(to_np(a_src)))[cl]
-    ex = np.exp(np.where(t > 0, t, 0.2 * t) - np.maximum.reduceat(np.where(t > 0, t, 0.2 * t), rp[:-1])[rows])
-    alpha = ex / np.add.reduceat(ex, rp[:-1])[rows]
-    assert np.diff(rp).min() > 0                       # the pattern carries the self-loops: no empty rows
-    weight = alpha * np.linalg.norm(oops.to_f64(to_np(gz)), axis=1)[rows] * np.linalg.norm(p64, axis=1)[cl]
-    terms = np.bincount(cl, weights=weight, minlength=nv) * np.abs(oops.to_f64(to_np(a_src))).max()
-    terms[:nb] += np.add.reduceat(weight, rp[:-1]) * np.abs(oops.to_f64(to_np(a_dst))).max()
+    terms = _gat_bwd_row_scale(to_np(sg.rowptr), to_np(sg.col), to_np(p), to_np(a_dst), to_np(a_src), to_np(gz), nb, nv)
     for fast in (False, True):
         for n_out in (nv, nb):
             plan_t = gas.gas_plan_create(d(sg.colptr)[: n_out + 1], int(sg.colptr[n_out]), F, n_rows=n_out, ind=d(sg.row)) \

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(64 * kLongWaves) void pna_bwd_long_rows_kernel(PnaF
 template <bool BF, int G>
 void launch_pna_bwd_rows(const PnaFastArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((pna_bwd_rows_vec_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
-    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    const unsigned blocks = long_row_blocks(a.n_rows);
     hipLaunchKernelGGL((pna_bwd_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 
@@ -706,7 +706,7 @@ __global__ __launch_bounds__(64 * kLongWaves) void gat_bwd_long_rows_kernel(GatB
 template <bool BF, int G>
 void launch_gat_bwd_rows(const GatBwdArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((gat_bwd_rows_vec_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
-    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    const unsigned blocks = long_row_blocks(a.n_rows);
     hipLaunchKernelGGL((gat_bwd_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 

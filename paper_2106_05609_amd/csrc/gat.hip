@@ -197,7 +197,7 @@ __global__ __launch_bounds__(64 * kLongWaves) void gat_long_rows_kernel(GatArgs 
 template <bool BF, int G>
 void launch_rows(const GatArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((gat_rows_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
-    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    const unsigned blocks = long_row_blocks(a.n_rows);
     hipLaunchKernelGGL((gat_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 

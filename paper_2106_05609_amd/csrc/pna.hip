@@ -237,7 +237,7 @@ __global__ __launch_bounds__(64) void pna_wide_rows_kernel(PnaArgs a) {
 template <bool BF, int G>
 void launch_rows(const PnaArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((pna_rows_kernel<BF, G>), dim3((unsigned)a.n_rows), dim3(64), 0, s, a);
-    const unsigned blocks = (unsigned)(a.n_rows < kLongBlocks ? a.n_rows : kLongBlocks);
+    const unsigned blocks = long_row_blocks(a.n_rows);
     hipLaunchKernelGGL((pna_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 

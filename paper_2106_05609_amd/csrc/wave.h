@@ -85,7 +85,8 @@ __device__ __forceinline__ void team_sum8(float (&s)[8]) {
 // entries is thousands of dependent steps for one wavefront, which the whole launch would wait for.
 constexpr int kLongRow = 2048;
 constexpr int kLongWaves = 8;
-constexpr int kLongBlocks = 2048;
+constexpr int kLongBlocks = 2048;                     // 512, 8,192 and 32,768 were measured slower
+inline unsigned long_row_blocks(int64_t n_rows) { return (unsigned)(n_rows < kLongBlocks ? n_rows : kLongBlocks); }
 
 // Workgroup w of such a launch looks at the rows w, w + gridDim.x, ..., blockDim.x of them per call (r0 = w, then
 // + blockDim.x * gridDim.x): the long ones among them are left in queue[0 .. return value).  Called by every thread

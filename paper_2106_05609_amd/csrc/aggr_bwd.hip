@@ -420,7 +420,9 @@ __device__ __forceinline__ void add_items_of_column(const PnaFastArgs& a, int b,
 
 // Column u, after the backward aggregation has left the mean's share in GX[u]: one wavefront per column.  (Four
 // columns per wavefront, sixteen lanes each walking its column's entries one by one, was measured slower on both
-// benchmark batches: the eight entries in flight per column matter more than the idle lanes.)
+// benchmark batches: the eight entries in flight per column matter more than the idle lanes.  So was one wavefront
+// walking the contiguous entries of 2, 3, 4 or 8 consecutive columns as one list with one set of sums per column:
+// fewer wavefronts, each with a longer chain of dependent steps.)
 template <bool BF>
 __global__ __launch_bounds__(64) void pna_bwd_winners_kernel(PnaFastArgs a) {
     constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4;

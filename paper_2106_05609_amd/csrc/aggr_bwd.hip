@@ -725,28 +725,49 @@ __global__ __launch_bounds__(256) void permute_entries_kernel(const float* __res
 }
 
 // tsum[u] = the column's total of dt.  A wavefront takes 64 consecutive columns, whose terms are contiguous: a lane
-// adds the terms of its own column in stored order when there are at most 64 of them; a longer column is summed by
-// the whole wavefront (lanes stride over its terms, then a fixed reduction over the lanes).
+// adds the terms of its own column in stored order when there are at most 64 of them.  Longer columns are left to
+// column_totals_long_kernel: hub columns sit next to each other, and sixty-four of them in one wavefront's share,
+// summed one after the other, were most of this step's time.
+constexpr int kLongColumn = 64;
+
 __global__ __launch_bounds__(256) void column_totals_kernel(const int32_t* __restrict__ colptr, const float* __restrict__ dt_t,
                                                             int64_t n_cols, float* __restrict__ tsum) {
-    const int lane = threadIdx.x & 63;
-    const int64_t u = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64 + lane;
-    int b = 0, e = 0;
-    if (u < n_cols) { b = colptr[u]; e = colptr[u + 1]; }
+    const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (u >= n_cols) return;
+    const int b = colptr[u], e = colptr[u + 1];
+    if (e - b > kLongColumn) return;
     float ts = 0.f;
-    if (e - b <= 64)
-        for (int q = b; q < e; ++q) ts += dt_t[q];
-    unsigned long long longer = __ballot(e - b > 64);
-    while (longer) {
-        const int l = __builtin_ctzll(longer);
-        longer &= longer - 1;
-        const int bl = __shfl(b, l), el = __shfl(e, l);
-        float p = 0.f;
-        for (int q = bl + lane; q < el; q += 64) p += dt_t[q];
-        p = wave_sum(p);
-        if (lane == l) ts = p;
+    for (int q = b; q < e; q += 8) {                  // eight loads in flight, added in stored order
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = q + j < e ? dt_t[q + j] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ts += x[j];
     }
-    if (u < n_cols) tsum[u] = ts;
+    tsum[u] = ts;
+}
+
+// The columns of more than kLongColumn terms, found as the long rows are: one wavefront per column, lanes stride over
+// its terms, then a fixed reduction over the lanes.
+__global__ __launch_bounds__(64 * kLongWaves) void column_totals_long_kernel(const int32_t* __restrict__ colptr,
+                                                                             const float* __restrict__ dt_t, int64_t n_cols,
+                                                                             float* __restrict__ tsum) {
+    constexpr int T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t r0 = blockIdx.x; r0 < n_cols; r0 += (int64_t)T * gridDim.x) {
+        const int nq = queue_long_rows(colptr, n_cols, r0, queue, &n_queued, kLongColumn);
+        for (int q = w; q < nq; q += kLongWaves) {
+            const int64_t u = queue[q];
+            const int b = colptr[u], e = colptr[u + 1];
+            float p = 0.f;
+            for (int t = b + lane; t < e; t += 64) p += dt_t[t];
+            p = wave_sum(p);
+            if (lane == 0) tsum[u] = p;
+        }
+        __syncthreads();
+    }
 }
 
 // GP[u] += tsum[u] a_src + csum[u] a_dst after the backward aggregation has left sum_k alpha_k GZ[row k] in GP[u]:
@@ -1042,6 +1063,8 @@ gas_status gas_gat_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
                                csc_pos, nnz, val_t, dt_t);
         hipLaunchKernelGGL(column_totals_kernel, dim3((unsigned)((n_cols + 255) / 256)), dim3(256), 0, s, colptr, dt_t, n_cols,
                            a.tsum);
+        hipLaunchKernelGGL(column_totals_long_kernel, dim3(long_row_blocks(n_cols)), dim3(64 * kLongWaves), 0, s, colptr, dt_t,
+                           n_cols, a.tsum);
         GAS_CHECK_HIP(hipGetLastError());
         // GP[u] = sum over the entries (v, u) of alpha GZ[v]: the backward aggregation with the attention weights
         // as coefficients, in the order of the CSC copy; then the two rank-one terms

@@ -90,12 +90,13 @@ inline unsigned long_row_blocks(int64_t n_rows) { return (unsigned)(n_rows < kLo
 
 // Workgroup w of such a launch looks at the rows w, w + gridDim.x, ..., blockDim.x of them per call (r0 = w, then
 // + blockDim.x * gridDim.x): the long ones among them are left in queue[0 .. return value).  Called by every thread
-// of the workgroup; every long row the caller then works on ends with a barrier.
-__device__ __forceinline__ int queue_long_rows(const int32_t* rowptr, int64_t n_rows, int64_t r0, int* queue, int* n_queued) {
+// of the workgroup; the caller passes a barrier between its last use of the queue and the next call.
+__device__ __forceinline__ int queue_long_rows(const int32_t* rowptr, int64_t n_rows, int64_t r0, int* queue, int* n_queued,
+                                               int longer_than = kLongRow) {
     if (threadIdx.x == 0) *n_queued = 0;
     __syncthreads();
     const int64_t r = r0 + (int64_t)threadIdx.x * gridDim.x;
-    if (r < n_rows && rowptr[r + 1] - rowptr[r] > kLongRow) queue[atomicAdd(n_queued, 1)] = (int)r;
+    if (r < n_rows && rowptr[r + 1] - rowptr[r] > longer_than) queue[atomicAdd(n_queued, 1)] = (int)r;
     __syncthreads();
     return *n_queued;
 }

@@ -359,14 +359,15 @@ void launch_pna_bwd_rows(const PnaFastArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((pna_bwd_long_rows_kernel<BF, G>), dim3(blocks), dim3(64 * kLongWaves), 0, s, a);
 }
 
-// The items of the entries [b, e) of one column, added to its sums `acc` by the wavefront: the records of 64
-// entries are read at once, the items of eight entries are in flight at a time, and they are added entry after
-// entry, minima before maxima.
-__device__ __forceinline__ void add_items_of_column(const PnaFastArgs& a, int b, int e, float* acc) {
+// The items of the entries [b, e) of one column (of its blocks of 64 entries first, first + stride, ...), added to
+// the sums `acc` by the wavefront: the records of 64 entries are read at once, the items of eight entries are in
+// flight at a time, and they are added entry after entry, minima before maxima.
+__device__ __forceinline__ void add_items_of_column(const PnaFastArgs& a, int b, int e, float* acc, int first = 0,
+                                                    int stride = 1) {
     constexpr int U = 8;
     const int lane = threadIdx.x & 63;
     const int64_t F2 = 2 * (int64_t)a.F;
-    for (int q0 = b; q0 < e; q0 += 64) {
+    for (int q0 = b + 64 * first; q0 < e; q0 += 64 * stride) {
         const int n64 = min(64, e - q0);
         int myv = 0;
         uint32_t rx = 0u, ry = 0u;
@@ -418,6 +419,10 @@ __device__ __forceinline__ void add_items_of_column(const PnaFastArgs& a, int b,
     }
 }
 
+// A column of more than kLongWinners entries is shared by the wavefronts of a workgroup (a hub column of 17,000
+// entries is 2,000 dependent steps for one wavefront).
+constexpr int kLongWinners = 512;
+
 // Column u, after the backward aggregation has left the mean's share in GX[u]: one wavefront per column.  (Four
 // columns per wavefront, sixteen lanes each walking its column's entries one by one, was measured slower on both
 // benchmark batches: the eight entries in flight per column matter more than the idle lanes.  So was one wavefront
@@ -431,6 +436,7 @@ __global__ __launch_bounds__(64) void pna_bwd_winners_kernel(PnaFastArgs a) {
     const int lane = threadIdx.x;
     const int b = a.colptr[u], e = a.colptr[u + 1];
     if (b == e) return;                              // the aggregation wrote zeros and nothing is added
+    if (e - b > kLongWinners) return;                // pna_bwd_winners_long_kernel
     const bool on = lane * E < a.F;
     char* gx = a.GX + (u * a.ldgx + (int64_t)lane * E) * EB;
     if (on) {
@@ -447,6 +453,38 @@ __global__ __launch_bounds__(64) void pna_bwd_winners_kernel(PnaFastArgs a) {
 #pragma unroll
         for (int i = 0; i < E; ++i) g[i] = acc[lane * E + i];
         *reinterpret_cast<u32x4*>(gx) = pack<BF>(g);
+    }
+}
+
+// Columns of more than kLongWinners entries, found as the long rows are: the wavefronts of the workgroup take the
+// column's blocks of 64 entries in turn, each with sums of its own in LDS (F floats per wavefront), which are then
+// added to the column's row of GX in wavefront order.
+template <bool BF>
+__global__ __launch_bounds__(64 * kLongWaves) void pna_bwd_winners_long_kernel(PnaFastArgs a) {
+    constexpr int E = Elems<BF>::E, EB = BF ? 2 : 4, T = 64 * kLongWaves;
+    __shared__ int queue[T];
+    __shared__ int n_queued;
+    extern __shared__ float sums[];                  // [kLongWaves][F]
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float* mine = sums + w * a.F;
+    for (int64_t r0 = blockIdx.x; r0 < a.n_out; r0 += (int64_t)T * gridDim.x) {
+        const int nq = queue_long_rows(a.colptr, a.n_out, r0, queue, &n_queued, kLongWinners);
+        for (int q = 0; q < nq; ++q) {
+            const int64_t u = queue[q];
+            for (int t = lane; t < a.F; t += 64) mine[t] = 0.f;
+            add_items_of_column(a, a.colptr[u], a.colptr[u + 1], mine, w, kLongWaves);
+            __syncthreads();
+            if (w == 0 && lane * E < a.F) {
+                char* gx = a.GX + (u * a.ldgx + (int64_t)lane * E) * EB;
+                float g[E];
+                unpack<BF>(*reinterpret_cast<const u32x4*>(gx), g);
+                for (int o = 0; o < kLongWaves; ++o)
+#pragma unroll
+                    for (int i = 0; i < E; ++i) g[i] += sums[o * a.F + lane * E + i];
+                *reinterpret_cast<u32x4*>(gx) = pack<BF>(g);
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -972,6 +1010,9 @@ gas_status gas_pna_aggregate_bwd(const gas_plan* plan_t, const int32_t* rowptr, 
         if (st != GAS_OK) return st;
         if (bf) hipLaunchKernelGGL(pna_bwd_winners_kernel<true>, dim3((unsigned)n_out), dim3(64), 0, s, a);
         else hipLaunchKernelGGL(pna_bwd_winners_kernel<false>, dim3((unsigned)n_out), dim3(64), 0, s, a);
+        const size_t sums_bytes = (size_t)kLongWaves * F * 4;
+        if (bf) hipLaunchKernelGGL(pna_bwd_winners_long_kernel<true>, dim3(long_row_blocks(n_out)), dim3(64 * kLongWaves), sums_bytes, s, a);
+        else hipLaunchKernelGGL(pna_bwd_winners_long_kernel<false>, dim3(long_row_blocks(n_out)), dim3(64 * kLongWaves), sums_bytes, s, a);
         GAS_CHECK_HIP(hipGetLastError());
         return GAS_OK;
     }
